@@ -1,0 +1,117 @@
+"""Seeded synthetic inputs and the benchmark configurations.
+
+This module only draws numbers and names shapes.  It holds none of the method's
+arithmetic and is the one module that both the HIP path's callers (tests,
+bench) and the CPU oracle's callers may import.
+
+The paper measured on MNIST / CIFAR-10 networks (Sec. IV); homomorphic cost does
+not depend on the data, so uniform values mod p with the paper's shapes stand in
+for the trained weights and images.
+"""
+from dataclasses import dataclass
+
+import numpy as np
+
+# Parameter set of Sec. IV ("Evaluation"): n = 2048 slots, 60-bit q, 20-bit p.
+# p is the largest prime below 2^20 with p = 1 (mod 2n); q is the largest prime
+# below 2^60 with q = 1 (mod 2n * p), so that (q-1)/p is an integer.
+N = 2048
+P = 1032193
+Q = 1152921500113727489
+GADGET_BITS = 20           # key-switching digits of 20 bits -> 3 digits
+SIGMA = 3.2
+
+
+@dataclass(frozen=True)
+class Params:
+    n: int = N
+    q: int = Q
+    p: int = P
+    gadget_bits: int = GADGET_BITS
+
+
+DEFAULT = Params()
+
+
+@dataclass(frozen=True)
+class FcShape:
+    name: str
+    n_o: int
+    n_i: int
+    batch: int
+
+
+@dataclass(frozen=True)
+class ConvShape:
+    name: str
+    c_o: int
+    c_i: int
+    k_h: int
+    k_w: int
+    u_h: int
+    u_w: int
+    batch: int
+
+    @property
+    def tuple(self):
+        return (self.c_o, self.c_i, self.k_h, self.k_w, self.u_h, self.u_w)
+
+
+# the five benchmark configurations
+FC_16x128 = FcShape("fc_16x128_b1", 16, 128, 1)
+FC_128x1024 = FcShape("fc_128x1024_b64", 128, 1024, 64)
+FC_1000x2048 = FcShape("fc_1000x2048_b64", 1000, 2048, 64)
+CONV_16x16_128_3x3 = ConvShape("conv_16x16x128_3x3x128_b16", 128, 128, 3, 3, 16, 16, 16)
+
+
+def uniform_mod(p, shape, seed):
+    """Uniform integers in [0,p) as uint64, from numpy's PCG64 seeded with ``seed``."""
+    return np.random.default_rng(seed).integers(0, p, size=shape, dtype=np.uint64)
+
+
+def fc_inputs(shape, p=P, seed=0):
+    """W (n_o x n_i), x (batch x n_i), r (batch x n_o), all uniform mod p."""
+    W = uniform_mod(p, (shape.n_o, shape.n_i), [seed, 1])
+    x = uniform_mod(p, (shape.batch, shape.n_i), [seed, 2])
+    r = uniform_mod(p, (shape.batch, shape.n_o), [seed, 3])
+    return W, x, r
+
+
+def conv_inputs(shape, p=P, seed=0):
+    """K (c_o x c_i x k_h x k_w), x (batch x c_i x u_h x u_w), r (batch x c_o x u_h x u_w)."""
+    K = uniform_mod(p, (shape.c_o, shape.c_i, shape.k_h, shape.k_w), [seed, 1])
+    x = uniform_mod(p, (shape.batch, shape.c_i, shape.u_h, shape.u_w), [seed, 2])
+    r = uniform_mod(p, (shape.batch, shape.c_o, shape.u_h, shape.u_w), [seed, 3])
+    return K, x, r
+
+
+def find_prime_below(limit, modulus):
+    """Largest prime below ``limit`` that is 1 modulo ``modulus`` (test parameter sets)."""
+    k = (limit - 2) // modulus
+    while k > 0 and not _is_prime(k * modulus + 1):
+        k -= 1
+    return k * modulus + 1
+
+
+def _is_prime(v):
+    if v < 2:
+        return False
+    small = (2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37)
+    for s in small:
+        if v % s == 0:
+            return v == s
+    d, r = v - 1, 0
+    while d % 2 == 0:
+        d //= 2
+        r += 1
+    for a in small:      # deterministic for v < 3.3e24
+        x = pow(a, d, v)
+        if x in (1, v - 1):
+            continue
+        for _ in range(r - 1):
+            x = x * x % v
+            if x == v - 1:
+                break
+        else:
+            return False
+    return True
