@@ -1,0 +1,190 @@
+/*
+ * gala.h -- C ABI of the MI355X-native GALA linear-layer library.
+ *
+ * GALA (arXiv 2105.01827) evaluates the linear layers of a neural network on
+ * packed-BFV ciphertexts held by a server: plaintext-weight x ciphertext
+ * matrix-vector products with row-wise weight encoding fused with share
+ * generation (Sec. III-A(3)) and convolutions with kernel grouping
+ * (Sec. III-B(3)), as sequences of the homomorphic operations Add, ScMult and
+ * Perm of Sec. II-C(1).
+ *
+ * Conventions
+ *  - Every function returns 0 on success or a negative gala_status; nothing
+ *    throws or aborts across this boundary.
+ *  - "host" pointers are ordinary CPU memory.  "device" pointers are HIP device
+ *    memory on the device that was current when the context was created; they
+ *    stay owned by the caller.  Handles (gala_ctx, gala_sk, gala_gk, plans) are
+ *    created and destroyed by the library and own whatever device memory they
+ *    need (allocated at creation time, never inside he_fc / he_conv / rotate).
+ *  - A residue is a uint64_t in [0,q).  The INTERCHANGE form of a ciphertext is
+ *    2n residues: the coefficients of c0 then of c1, natural order.  The
+ *    INTERNAL device form is also 2n uint64_t per ciphertext but is private
+ *    (evaluation domain, permuted order); convert with gala_ct_import/export.
+ *  - A slot vector is n values mod p, laid out as two rows of n/2: slot
+ *    (h,k) = index h*n/2 + k holds the plaintext polynomial's value at
+ *    zeta^(+-3^k), zeta the smallest primitive 2n-th root of unity mod p.
+ *  - Streams are hipStream_t passed as void* (NULL = the default stream).
+ *    Device work is enqueued on that stream and not waited for.
+ */
+#ifndef GALA_H
+#define GALA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GALA_OK = 0,
+    GALA_EARG = -1,      /* null pointer, bad size, bad parameter set          */
+    GALA_ESHAPE = -2,    /* layer shape not supported by one ciphertext block  */
+    GALA_ENOKEY = -3,    /* a needed Galois key is missing / plan not bound    */
+    GALA_ENOMEM = -4,    /* host or device allocation failed, workspace small  */
+    GALA_EHIP = -5       /* a HIP call failed                                   */
+} gala_status;
+
+/* BFV parameters of Sec. II-C(1) / Sec. IV: n slots (power of two, 8..2048),
+ * ciphertext prime q (2^40 <= q < 2^61, q = 1 mod 2n), plaintext prime p
+ * (p = 1 mod 2n, p < 2^31, p < q), key-switching digit width gadget_bits
+ * (digits = ceil(bitlen(q-1)/gadget_bits) <= 32).  The error distribution is the
+ * discrete Gaussian with sigma = 3.2 cut at +-19; the secret is ternary. */
+typedef struct {
+    int32_t n;
+    int32_t gadget_bits;
+    uint64_t q;
+    uint64_t p;
+} gala_params;
+
+/* One slot rotation: both rows rotate left by step (0 <= step < n/2); the two
+ * rows are exchanged when swap = 1.  It is the Galois map X -> X^((-1)^swap 3^step). */
+typedef struct {
+    int32_t swap;
+    int32_t step;
+} gala_rot;
+
+/* Homomorphic operations executed by one call, in the paper's vocabulary.  A
+ * full Perm is one DecPerm plus one HstPerm on a ciphertext of its own;
+ * decperm_in / hstperm_in count the hoisted rotations of the convolution's
+ * input ciphertexts (Sec. III-B). */
+typedef struct {
+    int64_t perm, decperm_in, hstperm_in, scmult, add;
+} gala_opcount;
+
+typedef struct gala_ctx gala_ctx;
+typedef struct gala_sk gala_sk;
+typedef struct gala_gk gala_gk;
+typedef struct gala_fc_plan gala_fc_plan;
+typedef struct gala_conv_plan gala_conv_plan;
+
+/* ---- context ------------------------------------------------------------ */
+/* Validates the parameters, finds the roots of unity and uploads the transform
+ * tables to the current HIP device. */
+int gala_ctx_create(const gala_params *params, gala_ctx **out);
+void gala_ctx_destroy(gala_ctx *ctx);
+/* Number of key-switching digits and delta = floor(q/p) of the context. */
+int gala_ctx_ndigits(const gala_ctx *ctx);
+uint64_t gala_ctx_delta(const gala_ctx *ctx);
+/* The 38 thresholds floor(2^64 * P[X <= -19+i]) of the error sampler (host). */
+const uint64_t *gala_gauss_cdf(void);
+
+/* ---- keys (client side, host; Sec. II-C(1)) ------------------------------- */
+/* Ternary secret drawn from the seeded generator. */
+int gala_keygen(const gala_ctx *ctx, uint64_t seed, gala_sk **out);
+void gala_sk_destroy(gala_sk *sk);
+/* Copies the secret as n residues mod q (1, 0, q-1) to host memory. */
+int gala_sk_export(const gala_ctx *ctx, const gala_sk *sk, uint64_t *s_host);
+/* Key-switching keys for the given rotations (duplicates and the identity are
+ * ignored), sampled on the host from `seed` and kept on the device. */
+int gala_galois_keygen(gala_ctx *ctx, const gala_sk *sk, const gala_rot *rots, int nrots, uint64_t seed,
+                       gala_gk **out);
+void gala_gk_destroy(gala_gk *gk);
+/* Interchange form of one key: ndigits x (b_j, a_j) polynomials, coefficient
+ * domain, to host memory (ndigits*2*n words).  Returns GALA_ENOKEY if absent.
+ * Synchronises the device. */
+int gala_gk_export(gala_ctx *ctx, const gala_gk *gk, gala_rot rot, uint64_t *ksk_host);
+
+/* ---- plaintext encoding, encryption, decryption (host) -------------------- */
+int gala_encode(const gala_ctx *ctx, const uint64_t *slots /* n */, uint64_t *poly_p /* n, mod p */);
+int gala_decode(const gala_ctx *ctx, const uint64_t *poly_p, uint64_t *slots);
+/* Symmetric-key encryption ct = (-a s + e + delta*m, a) of a slot vector, in
+ * interchange form (2n words, host). */
+int gala_encrypt(const gala_ctx *ctx, const gala_sk *sk, const uint64_t *slots, uint64_t seed, uint64_t *ct_host);
+/* slots = decode(round(p (c0 + c1 s) / q) mod p); ct in interchange form (host). */
+int gala_decrypt(const gala_ctx *ctx, const gala_sk *sk, const uint64_t *ct_host, uint64_t *slots);
+
+/* ---- interchange <-> internal form (device, asynchronous) ----------------- */
+/* count ciphertexts of 2n words each; src and dst are device pointers and may
+ * be the same buffer. */
+int gala_ct_import(const gala_ctx *ctx, void *stream, const uint64_t *ct_coeff_dev, int count, uint64_t *ct_dev);
+int gala_ct_export(const gala_ctx *ctx, void *stream, const uint64_t *ct_dev, int count, uint64_t *ct_coeff_dev);
+
+/* ---- Perm: one slot rotation per ciphertext (Sec. II-C(1)) ----------------- */
+/* ct_out[i] = Perm_rot(ct_in[i]) for i < count, internal form, device.  A Perm
+ * is a DecPerm (inverse transform of c1, base-2^gadget_bits digits, forward
+ * transforms) followed by a HstPerm (automorphism of c0 and of every digit,
+ * inner product with the key).  ct_out must not overlap ct_in. */
+int gala_rotate(const gala_ctx *ctx, void *stream, const gala_gk *gk, const uint64_t *ct_in, int count,
+                gala_rot rot, uint64_t *ct_out);
+
+/* ---- he_fc: row-encoding-share-RaS matrix-vector product (Sec. III-A(3)) --- */
+/* "encode-rowwise" (offline): W is n_o x n_i row-major on the host, entries
+ * mod p.  n_o and n_i are padded to powers of two; supported in one block:
+ * n_i <= n/2 with n_o <= n, or n/2 < n_i <= n with n_o <= n/2.  The plan
+ * holds G = max(1, n_i n_o / n) encoded weight plaintexts on the device. */
+int gala_fc_plan_create(gala_ctx *ctx, const uint64_t *W, int n_o, int n_i, gala_fc_plan **out);
+void gala_fc_plan_destroy(gala_fc_plan *plan);
+/* G of the plan (ScMult count per input); the plan needs rotations by 1..G-1. */
+int gala_fc_plan_G(const gala_fc_plan *plan);
+/* Writes the G-1 rotations the plan needs (rots may be NULL to query *nrots). */
+int gala_fc_plan_rotations(const gala_fc_plan *plan, gala_rot *rots, int *nrots);
+/* Resolves the plan's rotations against a key set (offline; GALA_ENOKEY if one is missing). */
+int gala_fc_plan_bind(gala_fc_plan *plan, const gala_gk *gk);
+/* Client side: slot vector holding n/n_i copies of x (host). */
+int gala_fc_pack_input(const gala_fc_plan *plan, const uint64_t *x /* n_i */, uint64_t *slots /* n */);
+/* The plaintext rotate-and-sum both parties apply to their share (host):
+ * out[t] = sum of the slots that hold partial sums of output t, mod p. */
+int gala_fc_unpack_share(const gala_fc_plan *plan, const uint64_t *slots /* n */, uint64_t *out /* n_o */);
+/* Bytes of device workspace gala_he_fc needs for a batch. */
+size_t gala_he_fc_workspace(const gala_fc_plan *plan, int batch);
+/* ct_out[b] = sum_g Perm_g(ScMult(ct_in[b], w_g)) - r'_b for b < batch, where r'_b
+ * is the full-length random vector whose plaintext rotate-and-sum is r[b]
+ * (every slot but the first of each output's group is drawn from the generator
+ * keyed by mask_seed and b).  ct_in/ct_out: batch x 2n, internal form, device;
+ * r: batch x n_o values mod p, device.  counts (host, may be NULL) receives the
+ * operations executed.  Asynchronous on `stream`. */
+int gala_he_fc(const gala_ctx *ctx, void *stream, const gala_fc_plan *plan, const uint64_t *ct_in, int batch,
+               const uint64_t *r, uint64_t mask_seed, uint64_t *ct_out, void *workspace, size_t workspace_bytes,
+               gala_opcount *counts);
+
+/* ---- he_conv: kernel-grouping convolution (Sec. III-B(3)) ------------------ */
+/* K is c_o x c_i x k_h x k_w row-major on the host, entries mod p; the image
+ * is u_h x u_w per channel; stride 1, zero "same" padding, odd k_h and k_w.
+ * c_n = n / T channels share a ciphertext, T the power of two >= u_h*u_w
+ * (T <= n/2); channel counts are padded to multiples of c_n. */
+int gala_conv_plan_create(gala_ctx *ctx, const uint64_t *K, int c_o, int c_i, int k_h, int k_w, int u_h, int u_w,
+                          gala_conv_plan **out);
+void gala_conv_plan_destroy(gala_conv_plan *plan);
+/* geometry[0..4] = T, c_n, input ciphertexts per image, output ciphertexts, taps. */
+int gala_conv_plan_geometry(const gala_conv_plan *plan, int32_t *geometry);
+int gala_conv_plan_rotations(const gala_conv_plan *plan, gala_rot *rots, int *nrots);
+int gala_conv_plan_bind(gala_conv_plan *plan, const gala_gk *gk);
+/* Client side: x is c_i x u_h x u_w; slots receives (input ciphertexts) x n values. */
+int gala_conv_pack_input(const gala_conv_plan *plan, const uint64_t *x, uint64_t *slots);
+/* Gathers the real outputs of output ciphertext O from its decrypted slots into out (c_o x u_h x u_w). */
+int gala_conv_unpack_share(const gala_conv_plan *plan, int O, const uint64_t *slots, uint64_t *out);
+size_t gala_he_conv_workspace(const gala_conv_plan *plan, int batch);
+/* For each input b: one DecPerm per input ciphertext and one HstPerm per
+ * non-central tap; per output block and kernel order the ScMults are added
+ * first, then each sum is rotated once and added (first-Add-second-Perm); the
+ * mask r[b] (c_o x u_h x u_w, device) is subtracted, pad slots masked from the
+ * generator.  ct_in: batch x n_in x 2n; ct_out: batch x n_out x 2n; internal form. */
+int gala_he_conv(const gala_ctx *ctx, void *stream, const gala_conv_plan *plan, const uint64_t *ct_in, int batch,
+                 const uint64_t *r, uint64_t mask_seed, uint64_t *ct_out, void *workspace, size_t workspace_bytes,
+                 gala_opcount *counts);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GALA_H */

@@ -1,0 +1,334 @@
+"""Thin ctypes binding of the C ABI declared in ``include/gala.h``.
+
+Argument marshalling only: every step of the layers runs inside
+``libgala_hip.so``.  PyTorch is used by callers for device memory and streams;
+this module takes any object with ``data_ptr()`` (or a raw integer address) for
+device pointers and numpy ``uint64`` arrays for host pointers.  The library
+must be present: there is no fallback path.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgala_hip.so")
+
+GALA_OK, GALA_EARG, GALA_ESHAPE, GALA_ENOKEY, GALA_ENOMEM, GALA_EHIP = 0, -1, -2, -3, -4, -5
+_NAMES = {GALA_EARG: "GALA_EARG (bad argument)", GALA_ESHAPE: "GALA_ESHAPE (shape not supported)",
+          GALA_ENOKEY: "GALA_ENOKEY (Galois key missing or plan not bound)",
+          GALA_ENOMEM: "GALA_ENOMEM (allocation failed or workspace too small)",
+          GALA_EHIP: "GALA_EHIP (HIP call failed or no device)"}
+
+
+class GalaError(RuntimeError):
+    def __init__(self, code, where):
+        super().__init__(f"{where}: {_NAMES.get(code, code)}")
+        self.code = code
+
+
+class Params(C.Structure):
+    _fields_ = [("n", C.c_int32), ("gadget_bits", C.c_int32), ("q", C.c_uint64), ("p", C.c_uint64)]
+
+
+class Rot(C.Structure):
+    _fields_ = [("swap", C.c_int32), ("step", C.c_int32)]
+
+
+class OpCount(C.Structure):
+    _fields_ = [("perm", C.c_int64), ("decperm_in", C.c_int64), ("hstperm_in", C.c_int64),
+                ("scmult", C.c_int64), ("add", C.c_int64)]
+
+    def as_dict(self):
+        return {k: int(getattr(self, k)) for k, _ in self._fields_}
+
+
+_VP, _U64P, _I = C.c_void_p, C.c_void_p, C.c_int
+# name -> (restype, argtypes); the list mirrors include/gala.h one to one
+SIGNATURES = {
+    "gala_ctx_create": (_I, [C.POINTER(Params), C.POINTER(_VP)]),
+    "gala_ctx_destroy": (None, [_VP]),
+    "gala_ctx_ndigits": (_I, [_VP]),
+    "gala_ctx_delta": (C.c_uint64, [_VP]),
+    "gala_gauss_cdf": (C.POINTER(C.c_uint64), []),
+    "gala_keygen": (_I, [_VP, C.c_uint64, C.POINTER(_VP)]),
+    "gala_sk_destroy": (None, [_VP]),
+    "gala_sk_export": (_I, [_VP, _VP, _U64P]),
+    "gala_galois_keygen": (_I, [_VP, _VP, C.POINTER(Rot), _I, C.c_uint64, C.POINTER(_VP)]),
+    "gala_gk_destroy": (None, [_VP]),
+    "gala_gk_export": (_I, [_VP, _VP, Rot, _U64P]),
+    "gala_encode": (_I, [_VP, _U64P, _U64P]),
+    "gala_decode": (_I, [_VP, _U64P, _U64P]),
+    "gala_encrypt": (_I, [_VP, _VP, _U64P, C.c_uint64, _U64P]),
+    "gala_decrypt": (_I, [_VP, _VP, _U64P, _U64P]),
+    "gala_ct_import": (_I, [_VP, _VP, _U64P, _I, _U64P]),
+    "gala_ct_export": (_I, [_VP, _VP, _U64P, _I, _U64P]),
+    "gala_rotate": (_I, [_VP, _VP, _VP, _U64P, _I, Rot, _U64P]),
+    "gala_fc_plan_create": (_I, [_VP, _U64P, _I, _I, C.POINTER(_VP)]),
+    "gala_fc_plan_destroy": (None, [_VP]),
+    "gala_fc_plan_G": (_I, [_VP]),
+    "gala_fc_plan_rotations": (_I, [_VP, C.POINTER(Rot), C.POINTER(_I)]),
+    "gala_fc_plan_bind": (_I, [_VP, _VP]),
+    "gala_fc_pack_input": (_I, [_VP, _U64P, _U64P]),
+    "gala_fc_unpack_share": (_I, [_VP, _U64P, _U64P]),
+    "gala_he_fc_workspace": (C.c_size_t, [_VP, _I]),
+    "gala_he_fc": (_I, [_VP, _VP, _VP, _U64P, _I, _U64P, C.c_uint64, _U64P, _VP, C.c_size_t, C.POINTER(OpCount)]),
+    "gala_conv_plan_create": (_I, [_VP, _U64P, _I, _I, _I, _I, _I, _I, C.POINTER(_VP)]),
+    "gala_conv_plan_destroy": (None, [_VP]),
+    "gala_conv_plan_geometry": (_I, [_VP, C.POINTER(C.c_int32)]),
+    "gala_conv_plan_rotations": (_I, [_VP, C.POINTER(Rot), C.POINTER(_I)]),
+    "gala_conv_plan_bind": (_I, [_VP, _VP]),
+    "gala_conv_pack_input": (_I, [_VP, _U64P, _U64P]),
+    "gala_conv_unpack_share": (_I, [_VP, _I, _U64P, _U64P]),
+    "gala_he_conv_workspace": (C.c_size_t, [_VP, _I]),
+    "gala_he_conv": (_I, [_VP, _VP, _VP, _U64P, _I, _U64P, C.c_uint64, _U64P, _VP, C.c_size_t, C.POINTER(OpCount)]),
+}
+
+_lib = None
+
+
+def load():
+    """Load libgala_hip.so (built by ``paper_2105_01827_amd.build``); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2105_01827_amd.build` "
+                              "(there is no CPU fallback for the HIP path)")
+        lib = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            f = getattr(lib, name)
+            f.restype, f.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def _check(code, where):
+    if code != GALA_OK:
+        raise GalaError(code, where)
+
+
+def _host(a):
+    a = np.ascontiguousarray(np.asarray(a, dtype=np.uint64))
+    return a, a.ctypes.data_as(C.c_void_p)
+
+
+def _dev(t):
+    """Address of a device buffer: a torch tensor (uint64/int64 storage) or an int."""
+    return C.c_void_p(t if isinstance(t, int) else t.data_ptr())
+
+
+def _stream(s):
+    if s is None:
+        return None
+    return C.c_void_p(s if isinstance(s, int) else s.cuda_stream)
+
+
+def _rots(rots):
+    arr = (Rot * max(1, len(rots)))()
+    for i, (swap, step) in enumerate(rots):
+        arr[i].swap, arr[i].step = int(swap), int(step)
+    return arr
+
+
+class Context:
+    """gala_ctx: one BFV parameter set; device tables live on the current HIP device."""
+
+    def __init__(self, n, q, p, gadget_bits):
+        self.lib = load()
+        self.n, self.q, self.p, self.gadget_bits = n, q, p, gadget_bits
+        par = Params(n, gadget_bits, q, p)
+        h = C.c_void_p()
+        _check(self.lib.gala_ctx_create(C.byref(par), C.byref(h)), "gala_ctx_create")
+        self.h = h
+        self.ndigits = self.lib.gala_ctx_ndigits(h)
+        self.delta = int(self.lib.gala_ctx_delta(h))
+        self.ksk_words = self.ndigits * 2 * n
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.gala_ctx_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+    def gauss_cdf(self):
+        ptr = self.lib.gala_gauss_cdf()
+        return [int(ptr[i]) for i in range(38)]
+
+    # ---- client side (host)
+    def keygen(self, seed):
+        return SecretKey(self, seed)
+
+    def encode(self, slots):
+        s, sp = _host(slots); out = np.empty(self.n, np.uint64)
+        _check(self.lib.gala_encode(self.h, sp, out.ctypes.data_as(C.c_void_p)), "gala_encode"); return out
+
+    def decode(self, poly_p):
+        a, ap = _host(poly_p); out = np.empty(self.n, np.uint64)
+        _check(self.lib.gala_decode(self.h, ap, out.ctypes.data_as(C.c_void_p)), "gala_decode"); return out
+
+    def encrypt(self, sk, slots, seed):
+        s, sp = _host(slots); ct = np.empty(2 * self.n, np.uint64)
+        _check(self.lib.gala_encrypt(self.h, sk.h, sp, seed, ct.ctypes.data_as(C.c_void_p)), "gala_encrypt"); return ct
+
+    def decrypt(self, sk, ct):
+        c, cp = _host(ct); out = np.empty(self.n, np.uint64)
+        _check(self.lib.gala_decrypt(self.h, sk.h, cp, out.ctypes.data_as(C.c_void_p)), "gala_decrypt"); return out
+
+    def galois_keygen(self, sk, rots, seed):
+        return GaloisKeys(self, sk, rots, seed)
+
+    # ---- device side
+    def ct_import(self, src_dev, count, dst_dev, stream=None):
+        _check(self.lib.gala_ct_import(self.h, _stream(stream), _dev(src_dev), count, _dev(dst_dev)), "gala_ct_import")
+
+    def ct_export(self, src_dev, count, dst_dev, stream=None):
+        _check(self.lib.gala_ct_export(self.h, _stream(stream), _dev(src_dev), count, _dev(dst_dev)), "gala_ct_export")
+
+    def rotate(self, gk, ct_in, count, rot, ct_out, stream=None):
+        _check(self.lib.gala_rotate(self.h, _stream(stream), gk.h, _dev(ct_in), count, Rot(*rot), _dev(ct_out)),
+               "gala_rotate")
+
+    def fc_plan(self, W):
+        return FcPlan(self, W)
+
+    def conv_plan(self, K, u_h, u_w):
+        return ConvPlan(self, K, u_h, u_w)
+
+
+class SecretKey:
+    def __init__(self, ctx, seed):
+        self.ctx = ctx
+        h = C.c_void_p()
+        _check(ctx.lib.gala_keygen(ctx.h, seed, C.byref(h)), "gala_keygen")
+        self.h = h
+
+    def export(self):
+        out = np.empty(self.ctx.n, np.uint64)
+        _check(self.ctx.lib.gala_sk_export(self.ctx.h, self.h, out.ctypes.data_as(C.c_void_p)), "gala_sk_export")
+        return out
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            self.ctx.lib.gala_sk_destroy(self.h)
+            self.h = None
+
+
+class GaloisKeys:
+    def __init__(self, ctx, sk, rots, seed):
+        self.ctx = ctx
+        h = C.c_void_p()
+        _check(ctx.lib.gala_galois_keygen(ctx.h, sk.h, _rots(rots), len(rots), seed, C.byref(h)), "gala_galois_keygen")
+        self.h = h
+
+    def export(self, rot):
+        out = np.empty(self.ctx.ksk_words, np.uint64)
+        _check(self.ctx.lib.gala_gk_export(self.ctx.h, self.h, Rot(*rot), out.ctypes.data_as(C.c_void_p)),
+               "gala_gk_export")
+        return out
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            self.ctx.lib.gala_gk_destroy(self.h)
+            self.h = None
+
+
+class FcPlan:
+    """gala_fc_plan: the row-wise encoded weights of one FC layer."""
+
+    def __init__(self, ctx, W):
+        self.ctx = ctx
+        W, wp = _host(W)
+        self.n_o, self.n_i = W.shape
+        h = C.c_void_p()
+        _check(ctx.lib.gala_fc_plan_create(ctx.h, wp, self.n_o, self.n_i, C.byref(h)), "gala_fc_plan_create")
+        self.h = h
+        self.G = ctx.lib.gala_fc_plan_G(h)
+
+    def rotations(self):
+        n = C.c_int()
+        _check(self.ctx.lib.gala_fc_plan_rotations(self.h, None, C.byref(n)), "gala_fc_plan_rotations")
+        arr = (Rot * max(1, n.value))()
+        _check(self.ctx.lib.gala_fc_plan_rotations(self.h, arr, C.byref(n)), "gala_fc_plan_rotations")
+        return [(arr[i].swap, arr[i].step) for i in range(n.value)]
+
+    def bind(self, gk):
+        _check(self.ctx.lib.gala_fc_plan_bind(self.h, gk.h), "gala_fc_plan_bind")
+        self._gk = gk
+
+    def pack_input(self, x):
+        x, xp = _host(x); out = np.empty(self.ctx.n, np.uint64)
+        _check(self.ctx.lib.gala_fc_pack_input(self.h, xp, out.ctypes.data_as(C.c_void_p)), "gala_fc_pack_input")
+        return out
+
+    def unpack_share(self, slots):
+        s, sp = _host(slots); out = np.empty(self.n_o, np.uint64)
+        _check(self.ctx.lib.gala_fc_unpack_share(self.h, sp, out.ctypes.data_as(C.c_void_p)), "gala_fc_unpack_share")
+        return out
+
+    def workspace_bytes(self, batch):
+        return int(self.ctx.lib.gala_he_fc_workspace(self.h, batch))
+
+    def he_fc(self, ct_in, batch, r, mask_seed, ct_out, workspace, workspace_bytes, stream=None):
+        cnt = OpCount()
+        _check(self.ctx.lib.gala_he_fc(self.ctx.h, _stream(stream), self.h, _dev(ct_in), batch, _dev(r), mask_seed,
+                                       _dev(ct_out), _dev(workspace), workspace_bytes, C.byref(cnt)), "gala_he_fc")
+        return cnt.as_dict()
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            self.ctx.lib.gala_fc_plan_destroy(self.h)
+            self.h = None
+
+
+class ConvPlan:
+    """gala_conv_plan: the kernel-grouping encoding of one convolution layer."""
+
+    def __init__(self, ctx, K, u_h, u_w):
+        self.ctx = ctx
+        K, kp = _host(K)
+        self.c_o, self.c_i, self.k_h, self.k_w = K.shape
+        self.u_h, self.u_w = u_h, u_w
+        h = C.c_void_p()
+        _check(ctx.lib.gala_conv_plan_create(ctx.h, kp, self.c_o, self.c_i, self.k_h, self.k_w, u_h, u_w, C.byref(h)),
+               "gala_conv_plan_create")
+        self.h = h
+        g = (C.c_int32 * 5)()
+        _check(ctx.lib.gala_conv_plan_geometry(h, g), "gala_conv_plan_geometry")
+        self.T, self.cn, self.nin, self.nout, self.ntap = (int(v) for v in g)
+
+    def rotations(self):
+        n = C.c_int()
+        _check(self.ctx.lib.gala_conv_plan_rotations(self.h, None, C.byref(n)), "gala_conv_plan_rotations")
+        arr = (Rot * max(1, n.value))()
+        _check(self.ctx.lib.gala_conv_plan_rotations(self.h, arr, C.byref(n)), "gala_conv_plan_rotations")
+        return [(arr[i].swap, arr[i].step) for i in range(n.value)]
+
+    def bind(self, gk):
+        _check(self.ctx.lib.gala_conv_plan_bind(self.h, gk.h), "gala_conv_plan_bind")
+        self._gk = gk
+
+    def pack_input(self, x):
+        x, xp = _host(x); out = np.empty((self.nin, self.ctx.n), np.uint64)
+        _check(self.ctx.lib.gala_conv_pack_input(self.h, xp, out.ctypes.data_as(C.c_void_p)), "gala_conv_pack_input")
+        return out
+
+    def unpack_share(self, O, slots, out):
+        s, sp = _host(slots)
+        assert out.dtype == np.uint64 and out.flags["C_CONTIGUOUS"]
+        _check(self.ctx.lib.gala_conv_unpack_share(self.h, O, sp, out.ctypes.data_as(C.c_void_p)),
+               "gala_conv_unpack_share")
+
+    def workspace_bytes(self, batch):
+        return int(self.ctx.lib.gala_he_conv_workspace(self.h, batch))
+
+    def he_conv(self, ct_in, batch, r, mask_seed, ct_out, workspace, workspace_bytes, stream=None):
+        cnt = OpCount()
+        _check(self.ctx.lib.gala_he_conv(self.ctx.h, _stream(stream), self.h, _dev(ct_in), batch, _dev(r), mask_seed,
+                                         _dev(ct_out), _dev(workspace), workspace_bytes, C.byref(cnt)), "gala_he_conv")
+        return cnt.as_dict()
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            self.ctx.lib.gala_conv_plan_destroy(self.h)
+            self.h = None

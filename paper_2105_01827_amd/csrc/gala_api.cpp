@@ -1,0 +1,191 @@
+// Device-side entry points of the C ABI: argument checks, workspace carving and
+// the kernel sequences of Perm, he_fc and he_conv.  No allocation happens here.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cstdlib>
+
+#include "gala_internal.h"
+
+using namespace gala;
+
+namespace gala {
+int galois_element(int n, int swap, int step);
+}
+
+namespace {
+
+// Workgroups the rotate-and-accumulate launch aims for: a few per compute unit
+// (256 CUs) so that every CU has several transforms in flight.
+int target_workgroups() {
+    static int v = [] {
+        const char *e = std::getenv("GALA_WG_TARGET");
+        int t = e ? std::atoi(e) : 0;
+        return t > 0 ? t : 1024;
+    }();
+    return v;
+}
+// The G rotations of one item are split into this many chunks, each summed by one workgroup.
+int choose_chunks(int items, int G) {
+    int c = (target_workgroups() + items - 1) / std::max(items, 1);
+    return std::max(1, std::min(c, G));
+}
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" int gala_ct_import(const gala_ctx *c, void *stream, const uint64_t *src, int count, uint64_t *dst) {
+    if (!c || !src || !dst || count < 0) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    return launch_ntt(c, stream, src, dst, (size_t)count * 2, 0) ? GALA_EHIP : GALA_OK;
+}
+extern "C" int gala_ct_export(const gala_ctx *c, void *stream, const uint64_t *src, int count, uint64_t *dst) {
+    if (!c || !src || !dst || count < 0) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    return launch_ntt(c, stream, src, dst, (size_t)count * 2, 1) ? GALA_EHIP : GALA_OK;
+}
+
+extern "C" int gala_rotate(const gala_ctx *c, void *stream, const gala_gk *gk, const uint64_t *ct_in, int count,
+                           gala_rot rot, uint64_t *ct_out) {
+    if (!c || !gk || !ct_in || !ct_out || count < 0 || rot.step < 0 || rot.step >= c->n / 2 || (rot.swap & ~1))
+        return GALA_EARG;
+    if (ct_in == ct_out) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    const int g = galois_element(c->n, rot.swap, rot.step);
+    PermJob job{};
+    job.ct_in = ct_in;
+    job.in_item_stride = 2 * (size_t)c->n;
+    job.in_g_stride = 0;
+    job.w = nullptr;
+    job.G = 1; job.items = count; job.nchunks = 1;
+    job.partial = ct_out;
+    job.keys = gk->d_keys;
+    if (g == 1) {
+        job.gal = gk->d_one; job.key_idx = gk->d_one;
+    } else {
+        auto it = gk->index_of.find(g);
+        if (it == gk->index_of.end()) return GALA_ENOKEY;
+        job.gal = gk->d_elements + it->second;
+        job.key_idx = gk->d_iota + it->second;
+    }
+    return launch_perm_accumulate(c, stream, job) ? GALA_EHIP : GALA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// he_fc
+// ---------------------------------------------------------------------------
+extern "C" size_t gala_he_fc_workspace(const gala_fc_plan *pl, int batch) {
+    if (!pl || batch <= 0) return 0;
+    const int chunks = choose_chunks(batch, pl->G);
+    return align_up((size_t)batch * chunks * 2 * pl->ctx->n * sizeof(u64));
+}
+extern "C" int gala_he_fc(const gala_ctx *c, void *stream, const gala_fc_plan *pl, const uint64_t *ct_in, int batch,
+                          const uint64_t *r, uint64_t mask_seed, uint64_t *ct_out, void *workspace,
+                          size_t workspace_bytes, gala_opcount *counts) {
+    if (!c || !pl || pl->ctx != c || !ct_in || !ct_out || !r || batch <= 0) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    if (pl->G > 1 && !pl->bound) return GALA_ENOKEY;
+    if (!workspace || workspace_bytes < gala_he_fc_workspace(pl, batch)) return GALA_ENOMEM;
+    const int n = c->n, chunks = choose_chunks(batch, pl->G);
+    PermJob job{};
+    job.ct_in = ct_in;
+    job.in_item_stride = 2 * (size_t)n;
+    job.in_g_stride = 0;                 // every rotation starts from the same input ciphertext
+    job.w = pl->d_w;
+    job.gal = pl->d_gal; job.key_idx = pl->d_key_idx;
+    job.keys = pl->bound ? pl->bound->d_keys : nullptr;
+    job.G = pl->G; job.items = batch; job.nchunks = chunks;
+    job.partial = (u64 *)workspace;
+    if (launch_perm_accumulate(c, stream, job)) return GALA_EHIP;
+    FinalizeJob fin{};
+    fin.partial = job.partial;
+    fin.items = batch; fin.nchunks = chunks; fin.nout = 1;
+    fin.r = r; fin.r_stride = (size_t)pl->n_o;
+    fin.mask_seed = mask_seed;
+    fin.mask = pl->mask_d;
+    fin.ct_out = ct_out;
+    if (launch_finalize(c, stream, fin)) return GALA_EHIP;
+    if (counts) {
+        counts->perm = (int64_t)batch * (pl->G - 1);
+        counts->scmult = (int64_t)batch * pl->G;
+        counts->add = (int64_t)batch * (pl->G - 1);
+        counts->decperm_in = counts->hstperm_in = 0;
+    }
+    return GALA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// he_conv
+// ---------------------------------------------------------------------------
+namespace {
+struct ConvWorkspace {
+    size_t digits, xrot, acc, partial, total;
+    int chunks;
+};
+ConvWorkspace conv_workspace(const gala_conv_plan *pl, int batch) {
+    const gala_ctx *c = pl->ctx;
+    const size_t n = c->n, w = sizeof(u64);
+    ConvWorkspace ws{};
+    ws.chunks = choose_chunks(batch * pl->nout, pl->cn);
+    ws.digits = 0;
+    ws.xrot = ws.digits + align_up((size_t)batch * pl->nin * c->ndigits * n * w);
+    ws.acc = ws.xrot + align_up((size_t)batch * pl->nin * pl->ntap * 2 * n * w);
+    ws.partial = ws.acc + align_up((size_t)batch * pl->nout * pl->cn * 2 * n * w);
+    ws.total = ws.partial + align_up((size_t)batch * pl->nout * ws.chunks * 2 * n * w);
+    return ws;
+}
+}  // namespace
+
+extern "C" size_t gala_he_conv_workspace(const gala_conv_plan *pl, int batch) {
+    if (!pl || batch <= 0) return 0;
+    return conv_workspace(pl, batch).total;
+}
+extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_plan *pl, const uint64_t *ct_in,
+                            int batch, const uint64_t *r, uint64_t mask_seed, uint64_t *ct_out, void *workspace,
+                            size_t workspace_bytes, gala_opcount *counts) {
+    if (!c || !pl || pl->ctx != c || !ct_in || !ct_out || !r || batch <= 0) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    if ((pl->ntap > 1 || pl->cn > 1) && !pl->bound) return GALA_ENOKEY;
+    const ConvWorkspace ws = conv_workspace(pl, batch);
+    if (!workspace || workspace_bytes < ws.total) return GALA_ENOMEM;
+    char *base = (char *)workspace;
+    u64 *digits = (u64 *)(base + ws.digits), *xrot = (u64 *)(base + ws.xrot), *acc = (u64 *)(base + ws.acc),
+        *partial = (u64 *)(base + ws.partial);
+    const int n = c->n;
+    const size_t nct_in = (size_t)batch * pl->nin;
+    const u64 *keys = pl->bound ? pl->bound->d_keys : nullptr;
+    // 1. input rotations: one DecPerm per input ciphertext, one HstPerm per non-central tap
+    if (pl->ntap > 1 && launch_decperm(c, stream, ct_in, nct_in, digits)) return GALA_EHIP;
+    if (launch_hstperm_taps(c, stream, ct_in, digits, nct_in, pl->ntap, pl->d_tap_gal, pl->d_tap_key, keys, xrot))
+        return GALA_EHIP;
+    // 2. ScMult and Add first: one sum per (output block, kernel order)
+    if (launch_conv_mac(c, stream, pl->d_w, xrot, batch, pl->nout, pl->cn, pl->nin, pl->ntap, acc)) return GALA_EHIP;
+    // 3. Perm second: rotate each kernel order into place and add, then subtract the mask
+    PermJob job{};
+    job.ct_in = acc;
+    job.in_item_stride = (size_t)pl->cn * 2 * n;
+    job.in_g_stride = 2 * (size_t)n;
+    job.w = nullptr;
+    job.gal = pl->d_grp_gal; job.key_idx = pl->d_grp_key;
+    job.keys = keys;
+    job.G = pl->cn; job.items = batch * pl->nout; job.nchunks = ws.chunks;
+    job.partial = partial;
+    if (launch_perm_accumulate(c, stream, job)) return GALA_EHIP;
+    FinalizeJob fin{};
+    fin.partial = partial;
+    fin.items = job.items; fin.nchunks = ws.chunks; fin.nout = pl->nout;
+    fin.r = r; fin.r_stride = (size_t)pl->c_o * pl->u_h * pl->u_w;
+    fin.mask_seed = mask_seed;
+    fin.mask = pl->mask_d;
+    fin.ct_out = ct_out;
+    if (launch_finalize(c, stream, fin)) return GALA_EHIP;
+    if (counts) {
+        const int64_t terms = (int64_t)pl->nin * pl->ntap;
+        counts->decperm_in = pl->ntap > 1 ? (int64_t)batch * pl->nin : 0;
+        counts->hstperm_in = (int64_t)batch * pl->nin * (pl->ntap - 1);
+        counts->scmult = (int64_t)batch * pl->nout * pl->cn * terms;
+        counts->perm = (int64_t)batch * pl->nout * (pl->cn - 1);
+        counts->add = (int64_t)batch * pl->nout * (pl->cn * (terms - 1) + (pl->cn - 1));
+    }
+    return GALA_OK;
+}

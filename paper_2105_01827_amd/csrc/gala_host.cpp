@@ -1,0 +1,762 @@
+// Host half of the library: number theory, transform tables, seeded samplers,
+// slot encoding, key generation, encryption / decryption and the offline
+// encoders of the two layer types.  Device memory is touched only to upload
+// tables, keys and encoded weights.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <thread>
+
+#include "gala_internal.h"
+
+namespace gala {
+
+// ---------------------------------------------------------------------------
+// number theory
+// ---------------------------------------------------------------------------
+static u64 mulmod_slow(u64 a, u64 b, u64 m) { return (u64)(((u128)a * b) % m); }
+u64 pow_mod(u64 b, u64 e, u64 m) {
+    u64 r = 1 % m;
+    b %= m;
+    for (; e; e >>= 1) {
+        if (e & 1) r = mulmod_slow(r, b, m);
+        b = mulmod_slow(b, b, m);
+    }
+    return r;
+}
+u64 inv_mod(u64 a, u64 m) { return pow_mod(a, m - 2, m); }
+u64 shoup_companion(u64 w, u64 q) { return (u64)((((u128)w) << 64) / q); }
+int bit_length(u64 v) {
+    int l = 0;
+    for (; v; v >>= 1) ++l;
+    return l;
+}
+Modulus make_modulus(u64 q) {
+    Modulus m;
+    m.q = q;
+    m.q2 = 2 * q;
+    m.c64 = (u64)((((u128)1) << 64) % q);
+    m.c64s = shoup_companion(m.c64, q);
+    m.one_s = shoup_companion(1, q);
+    return m;
+}
+bool is_prime_u64(u64 v) {
+    if (v < 2) return false;
+    static const u64 bases[] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37};
+    for (u64 b : bases)
+        if (v % b == 0) return v == b;
+    u64 d = v - 1;
+    int r = 0;
+    while (!(d & 1)) { d >>= 1; ++r; }
+    for (u64 a : bases) {                 // deterministic for 64-bit inputs
+        u64 x = pow_mod(a, d, v);
+        if (x == 1 || x == v - 1) continue;
+        bool composite = true;
+        for (int i = 1; i < r && composite; ++i) {
+            x = mulmod_slow(x, x, v);
+            if (x == v - 1) composite = false;
+        }
+        if (composite) return false;
+    }
+    return true;
+}
+// a generator of the 2n-th roots of unity, found from the first x whose
+// ((m-1)/2n)-th power has order exactly 2n
+static u64 primitive_2n_root(u64 m, int n) {
+    for (u64 x = 2; x < m; ++x) {
+        u64 c = pow_mod(x, (m - 1) / (2 * (u64)n), m);
+        if (pow_mod(c, (u64)n, m) == m - 1) return c;
+    }
+    return 0;
+}
+static u64 least_primitive_2n_root(u64 m, int n) {
+    u64 c = primitive_2n_root(m, n), sq = mulmod_slow(c, c, m), cur = c, best = c;
+    for (int e = 3; e < 2 * n; e += 2) {
+        cur = mulmod_slow(cur, sq, m);
+        best = std::min(best, cur);
+    }
+    return best;
+}
+
+// ---------------------------------------------------------------------------
+// transform tables and the host transform
+// ---------------------------------------------------------------------------
+void NttHost::init(int n_, u64 q, u64 psi_) {
+    n = n_;
+    logn = bit_length((u64)n) - 1;
+    mod = make_modulus(q);
+    psi = psi_;
+    u64 ipsi = inv_mod(psi, q);
+    tw.assign(n, 0); tws.assign(n, 0); itw.assign(n, 0); itws.assign(n, 0);
+    std::vector<u64> pw(n), ipw(n);
+    pw[0] = ipw[0] = 1;
+    for (int i = 1; i < n; ++i) {
+        pw[i] = mulmod_slow(pw[i - 1], psi, q);
+        ipw[i] = mulmod_slow(ipw[i - 1], ipsi, q);
+    }
+    for (int k = 0; k < n; ++k) {
+        int r = brev(k, logn);
+        tw[k] = pw[r];   tws[k] = shoup_companion(tw[k], q);
+        itw[k] = ipw[r]; itws[k] = shoup_companion(itw[k], q);
+    }
+    ninv = inv_mod((u64)n, q);           ninvs = shoup_companion(ninv, q);
+    itw1n = mulmod_slow(itw[1], ninv, q); itw1ns = shoup_companion(itw1n, q);
+}
+void NttHost::forward(u64 *a) const {
+    const u64 q = mod.q, q2 = mod.q2;
+    for (int m = 1, t = n >> 1; m < n; m <<= 1, t >>= 1)
+        for (int i = 0; i < m; ++i) {
+            const u64 w = tw[m + i], ws = tws[m + i];
+            u64 *x = a + 2 * i * t, *y = x + t;
+            for (int j = 0; j < t; ++j) butterfly_fwd(x[j], y[j], w, ws, q, q2);
+        }
+    for (int i = 0; i < n; ++i) a[i] = csub(csub(a[i], q2), q);
+}
+void NttHost::inverse(u64 *a) const {
+    const u64 q = mod.q, q2 = mod.q2;
+    int t = 1;
+    for (int m = n >> 1; m > 1; m >>= 1, t <<= 1)
+        for (int i = 0; i < m; ++i) {
+            const u64 w = itw[m + i], ws = itws[m + i];
+            u64 *x = a + 2 * i * t, *y = x + t;
+            for (int j = 0; j < t; ++j) butterfly_inv(x[j], y[j], w, ws, q, q2);
+        }
+    // last stage (one block, t = n/2) with n^-1 folded in
+    for (int j = 0; j < t; ++j) {
+        u64 x = a[j], y = a[j + t];
+        a[j] = mul_shoup(x + y, ninv, ninvs, q);
+        a[j + t] = mul_shoup(x - y + q2, itw1n, itw1ns, q);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// samplers
+// ---------------------------------------------------------------------------
+// floor(2^64 * P[X <= -19+i]) for the discrete Gaussian with sigma = 3.2 on [-19,19]
+static const u64 kGaussCdf[38] = {
+    0x0000000bd798c7acull, 0x00000053f5e234f7ull, 0x000001e24b89625aull, 0x000009adbc7900e1ull,
+    0x00002d17ca1e3a82ull, 0x0000bf05ff772ee2ull, 0x0002e06843bbf95dull, 0x000a19062dceb033ull,
+    0x00204c0ded173b17ull, 0x005e3163ffc656a8ull, 0x00fab6a7e614dfaeull, 0x0261b16e99bc14f8ull,
+    0x054c69348bbc9867ull, 0x0acd276539458231ull, 0x143796b3c337f00bull, 0x22d43df09de40e7aull,
+    0x37651d96aa4fb429ull, 0x51a5da2b40f1bff1ull, 0x700ad4bf5a6e80e2ull, 0x8ff52b40a5917f1dull,
+    0xae5a25d4bf0e400eull, 0xc89ae26955b04bd6ull, 0xdd2bc20f621bf185ull, 0xebc8694c3cc80ff4ull,
+    0xf532d89ac6ba7dceull, 0xfab396cb74436798ull, 0xfd9e4e916643eb07ull, 0xff05495819eb2051ull,
+    0xffa1ce9c0039a957ull, 0xffdfb3f212e8c4e8ull, 0xfff5e6f9d2314fccull, 0xfffd1f97bc4406a2ull,
+    0xffff40fa0088d11dull, 0xffffd2e835e1c57dull, 0xfffff6524386ff1eull, 0xfffffe1db4769da5ull,
+    0xffffffac0a1dcb08ull, 0xfffffff428673853ull};
+const u64 *gauss_cdf_table() { return kGaussCdf; }
+
+static int draw_gauss(u64 seed, u64 stream, u64 idx) {
+    const u64 u = rand64(seed, stream, idx, 0);
+    // the table is increasing: binary search for the number of thresholds <= u
+    int lo = 0, hi = 38;
+    while (lo < hi) {
+        int mid = (lo + hi) / 2;
+        if (u >= kGaussCdf[mid]) lo = mid + 1; else hi = mid;
+    }
+    return lo - kGaussBound;
+}
+static int draw_ternary(u64 seed, u64 stream, u64 idx) {
+    for (u64 t = 0;; ++t) {
+        u64 v = rand64(seed, stream, idx, t) >> 62;
+        if (v < 3) return (int)v - 1;
+    }
+}
+static u64 lift_signed(int v, u64 q) { return v >= 0 ? (u64)v : q - (u64)(-v); }
+
+// a(X) -> a(X^g) on coefficients
+static void substitute_power(const u64 *a, int g, int n, u64 q, u64 *out) {
+    for (int i = 0; i < n; ++i) {
+        int e = (int)(((long)i * g) % (2 * n));
+        if (e < n) out[e] = a[i];
+        else out[e - n] = a[i] ? q - a[i] : 0;
+    }
+}
+int galois_element(int n, int swap, int step) {
+    long g = 1;
+    for (int i = 0; i < step; ++i) g = g * 3 % (2 * n);
+    return (int)(swap ? 2 * n - g : g);
+}
+
+// run f(i) for i in [0,count) on a few host threads
+template <class F>
+static void parallel_for(size_t count, F f) {
+    unsigned nt = std::min<size_t>(std::max(1u, std::thread::hardware_concurrency()), 16);
+    nt = (unsigned)std::min<size_t>(nt, count);
+    if (nt <= 1) {
+        for (size_t i = 0; i < count; ++i) f(i);
+        return;
+    }
+    std::vector<std::thread> th;
+    for (unsigned t = 0; t < nt; ++t)
+        th.emplace_back([=]() { for (size_t i = t; i < count; i += nt) f(i); });
+    for (auto &x : th) x.join();
+}
+
+static int pow2_ceil(int v) {
+    int r = 1;
+    while (r < v) r <<= 1;
+    return r;
+}
+
+// slot vector -> weight plaintext in the evaluation domain mod q (centred lift)
+static void encode_weight_hat(const gala_ctx *c, const u64 *slots, u64 *out) {
+    const int n = c->n;
+    std::vector<u64> a(n);
+    for (int s = 0; s < n; ++s) a[c->slot_to_idx[s]] = slots[s] % c->p;
+    c->ntt_p.inverse(a.data());
+    for (int i = 0; i < n; ++i) out[i] = a[i] > c->p / 2 ? c->q - (c->p - a[i]) : a[i];
+    c->ntt_q.forward(out);
+}
+
+template <class T>
+static int upload(T **dst, const std::vector<T> &src) {
+    if (src.empty()) { *dst = nullptr; return GALA_OK; }
+    if (hipMalloc((void **)dst, src.size() * sizeof(T)) != hipSuccess) return GALA_ENOMEM;
+    if (hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice) != hipSuccess) return GALA_EHIP;
+    return GALA_OK;
+}
+static int upload_mask_layout(const MaskLayoutHost &h, MaskLayoutDev *d) {
+    int rc;
+    if ((rc = upload(&d->row_ptr, h.row_ptr))) return rc;
+    if ((rc = upload(&d->row_slots, h.row_slots))) return rc;
+    if ((rc = upload(&d->row_rindex, h.row_rindex))) return rc;
+    if ((rc = upload(&d->nrows, h.nrows))) return rc;
+    return upload(&d->is_first, h.is_first);
+}
+static void free_mask_layout(MaskLayoutDev *d) {
+    hipFree(d->row_ptr); hipFree(d->row_slots); hipFree(d->row_rindex); hipFree(d->nrows); hipFree(d->is_first);
+}
+
+}  // namespace gala
+
+using namespace gala;
+
+// ===========================================================================
+// context
+// ===========================================================================
+extern "C" int gala_ctx_create(const gala_params *par, gala_ctx **out) {
+    if (!par || !out) return GALA_EARG;
+    const int n = par->n;
+    const u64 q = par->q, p = par->p;
+    if (n < 8 || n > kMaxN || (n & (n - 1))) return GALA_EARG;
+    if (q < (1ull << 40) || q >= (1ull << 61) || p >= (1ull << 31) || p >= q || p < 3) return GALA_EARG;
+    if ((q - 1) % (2 * (u64)n) || (p - 1) % (2 * (u64)n)) return GALA_EARG;
+    if (!is_prime_u64(q) || !is_prime_u64(p)) return GALA_EARG;
+    if (par->gadget_bits < 1 || par->gadget_bits > 62) return GALA_EARG;
+    int ndigits = (bit_length(q - 1) + par->gadget_bits - 1) / par->gadget_bits;
+    if (ndigits > kMaxDigits) return GALA_EARG;
+
+    gala_ctx *c = new (std::nothrow) gala_ctx;
+    if (!c) return GALA_ENOMEM;
+    c->n = n; c->logn = bit_length((u64)n) - 1;
+    c->q = q; c->p = p;
+    c->gadget_bits = par->gadget_bits; c->ndigits = ndigits;
+    c->qbits = bit_length(q); c->pbits = bit_length(p);
+    c->delta = q / p; c->delta_s = shoup_companion(c->delta, q);
+    c->zeta = least_primitive_2n_root(p, n);
+    c->ntt_q.init(n, q, primitive_2n_root(q, n));
+    c->ntt_p.init(n, p, c->zeta);
+    // slot (h,k) is the value at zeta^(+-3^k); the transform puts the value at
+    // zeta^(2 r + 1) at index brev(r)
+    c->slot_to_idx.resize(n);
+    long e = 1;
+    for (int k = 0; k < n / 2; ++k) {
+        c->slot_to_idx[k] = brev((int)((e - 1) / 2), c->logn);
+        c->slot_to_idx[n / 2 + k] = brev((int)((2 * n - e - 1) / 2), c->logn);
+        e = e * 3 % (2 * n);
+    }
+    // device tables; a host without a HIP device still gets a context for the
+    // client-side calls (keygen, encode, encrypt, decrypt), every device entry
+    // point then fails with GALA_EHIP
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) {
+        (void)hipGetLastError();
+        c->has_device = false;
+        *out = c;
+        return GALA_OK;
+    }
+    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return GALA_EHIP; }
+    std::vector<u64> host(8 * (size_t)n);
+    const NttHost *hs[2] = {&c->ntt_q, &c->ntt_p};
+    for (int k = 0; k < 2; ++k) {
+        u64 *base = host.data() + (size_t)k * 4 * n;
+        std::copy(hs[k]->tw.begin(), hs[k]->tw.end(), base);
+        std::copy(hs[k]->tws.begin(), hs[k]->tws.end(), base + n);
+        std::copy(hs[k]->itw.begin(), hs[k]->itw.end(), base + 2 * n);
+        std::copy(hs[k]->itws.begin(), hs[k]->itws.end(), base + 3 * n);
+    }
+    if (upload(&c->d_tables, host) || upload(&c->d_slot_to_idx, c->slot_to_idx)) {
+        gala_ctx_destroy(c);
+        return GALA_EHIP;
+    }
+    NttDev *dv[2] = {&c->dev_q, &c->dev_p};
+    for (int k = 0; k < 2; ++k) {
+        const u64 *base = c->d_tables + (size_t)k * 4 * n;
+        dv[k]->tw = base; dv[k]->tws = base + n; dv[k]->itw = base + 2 * n; dv[k]->itws = base + 3 * n;
+        dv[k]->ninv = hs[k]->ninv; dv[k]->ninvs = hs[k]->ninvs;
+        dv[k]->itw1n = hs[k]->itw1n; dv[k]->itw1ns = hs[k]->itw1ns;
+        dv[k]->mod = hs[k]->mod;
+    }
+    c->has_device = true;
+    *out = c;
+    return GALA_OK;
+}
+extern "C" void gala_ctx_destroy(gala_ctx *c) {
+    if (!c) return;
+    if (c->has_device) {
+        hipFree(c->d_tables);
+        hipFree(c->d_slot_to_idx);
+    }
+    delete c;
+}
+extern "C" int gala_ctx_ndigits(const gala_ctx *c) { return c ? c->ndigits : GALA_EARG; }
+extern "C" uint64_t gala_ctx_delta(const gala_ctx *c) { return c ? c->delta : 0; }
+extern "C" const uint64_t *gala_gauss_cdf(void) { return gauss_cdf_table(); }
+
+// ===========================================================================
+// keys
+// ===========================================================================
+extern "C" int gala_keygen(const gala_ctx *c, uint64_t seed, gala_sk **out) {
+    if (!c || !out) return GALA_EARG;
+    gala_sk *sk = new (std::nothrow) gala_sk;
+    if (!sk) return GALA_ENOMEM;
+    sk->s.resize(c->n);
+    for (int i = 0; i < c->n; ++i) sk->s[i] = lift_signed(draw_ternary(seed, kStreamSk, (u64)i), c->q);
+    sk->s_hat = sk->s;
+    c->ntt_q.forward(sk->s_hat.data());
+    *out = sk;
+    return GALA_OK;
+}
+extern "C" void gala_sk_destroy(gala_sk *sk) { delete sk; }
+extern "C" int gala_sk_export(const gala_ctx *c, const gala_sk *sk, uint64_t *s_host) {
+    if (!c || !sk || !s_host) return GALA_EARG;
+    std::memcpy(s_host, sk->s.data(), sizeof(u64) * c->n);
+    return GALA_OK;
+}
+
+extern "C" int gala_galois_keygen(gala_ctx *c, const gala_sk *sk, const gala_rot *rots, int nrots, uint64_t seed,
+                                  gala_gk **out) {
+    if (!c || !sk || !out || nrots < 0 || (nrots && !rots)) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    const int n = c->n, L = c->ndigits;
+    gala_gk *gk = new (std::nothrow) gala_gk;
+    if (!gk) return GALA_ENOMEM;
+    gk->n = n; gk->ndigits = L;
+    for (int i = 0; i < nrots; ++i) {
+        if (rots[i].step < 0 || rots[i].step >= n / 2 || (rots[i].swap & ~1)) { delete gk; return GALA_EARG; }
+        int g = galois_element(n, rots[i].swap, rots[i].step);
+        if (g == 1 || gk->index_of.count(g)) continue;
+        gk->index_of[g] = (int)gk->elements.size();
+        gk->elements.push_back(g);
+    }
+    const size_t nkeys = gk->elements.size(), kw = gk->key_words();
+    {
+        std::vector<int> iota(nkeys), one(1, 1);
+        for (size_t k = 0; k < nkeys; ++k) iota[k] = (int)k;
+        if (upload(&gk->d_elements, gk->elements) || upload(&gk->d_iota, iota) || upload(&gk->d_one, one)) {
+            gala_gk_destroy(gk);
+            return GALA_EHIP;
+        }
+    }
+    *out = gk;
+    if (!nkeys) return GALA_OK;
+    // coefficient-domain samples: slot [j][1] <- a_j, slot [j][0] <- e_j + B^j s(X^g)
+    std::vector<u64> host;
+    try { host.resize(nkeys * kw); } catch (...) { gala_gk_destroy(gk); *out = nullptr; return GALA_ENOMEM; }
+    const u64 q = c->q;
+    parallel_for(nkeys, [&](size_t k) {
+        const int g = gk->elements[k];
+        std::vector<u64> sg(n);
+        substitute_power(sk->s.data(), g, n, q, sg.data());
+        u64 Bj = 1;
+        const u64 B = (1ull << c->gadget_bits) % q;
+        for (int j = 0; j < L; ++j) {
+            u64 *t = host.data() + k * kw + (size_t)(2 * j) * n, *a = t + n;
+            const u64 base = ((u64)g << 32) + ((u64)j << 16);
+            for (int i = 0; i < n; ++i) {
+                a[i] = draw_uniform(q, c->qbits, seed, kStreamKskA, base + i);
+                u64 e = lift_signed(draw_gauss(seed, kStreamKskE, base + i), q);
+                t[i] = add_mod(e, mulmod_slow(Bj, sg[i], q), q);
+            }
+            Bj = mulmod_slow(Bj, B, q);
+        }
+    });
+    u64 *d_s = nullptr;
+    int rc = GALA_OK;
+    if (hipMalloc((void **)&gk->d_keys, nkeys * kw * sizeof(u64)) != hipSuccess ||
+        hipMalloc((void **)&d_s, n * sizeof(u64)) != hipSuccess)
+        rc = GALA_ENOMEM;
+    if (!rc && (hipMemcpy(gk->d_keys, host.data(), nkeys * kw * sizeof(u64), hipMemcpyHostToDevice) != hipSuccess ||
+                hipMemcpy(d_s, sk->s_hat.data(), n * sizeof(u64), hipMemcpyHostToDevice) != hipSuccess))
+        rc = GALA_EHIP;
+    // to the evaluation domain, then b_hat = t_hat - a_hat * s_hat in place
+    if (!rc && launch_ntt(c, nullptr, gk->d_keys, gk->d_keys, nkeys * L * 2, 0)) rc = GALA_EHIP;
+    if (!rc && launch_key_finish(c, nullptr, gk->d_keys, d_s, nkeys * L)) rc = GALA_EHIP;
+    if (!rc && hipDeviceSynchronize() != hipSuccess) rc = GALA_EHIP;
+    hipFree(d_s);
+    if (rc) { gala_gk_destroy(gk); *out = nullptr; }
+    return rc;
+}
+extern "C" void gala_gk_destroy(gala_gk *gk) {
+    if (!gk) return;
+    hipFree(gk->d_keys); hipFree(gk->d_elements); hipFree(gk->d_iota); hipFree(gk->d_one);
+    delete gk;
+}
+extern "C" int gala_gk_export(gala_ctx *c, const gala_gk *gk, gala_rot rot, uint64_t *ksk_host) {
+    if (!c || !gk || !ksk_host || rot.step < 0 || rot.step >= c->n / 2) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    auto it = gk->index_of.find(galois_element(c->n, rot.swap, rot.step));
+    if (it == gk->index_of.end()) return GALA_ENOKEY;
+    const size_t kw = gk->key_words();
+    u64 *tmp = nullptr;
+    if (hipMalloc((void **)&tmp, kw * sizeof(u64)) != hipSuccess) return GALA_ENOMEM;
+    int rc = GALA_OK;
+    if (launch_ntt(c, nullptr, gk->d_keys + it->second * kw, tmp, (size_t)gk->ndigits * 2, 1)) rc = GALA_EHIP;
+    if (!rc && hipMemcpy(ksk_host, tmp, kw * sizeof(u64), hipMemcpyDeviceToHost) != hipSuccess) rc = GALA_EHIP;
+    hipFree(tmp);
+    return rc;
+}
+
+// ===========================================================================
+// encoding, encryption, decryption (host)
+// ===========================================================================
+extern "C" int gala_encode(const gala_ctx *c, const uint64_t *slots, uint64_t *poly_p) {
+    if (!c || !slots || !poly_p) return GALA_EARG;
+    std::vector<u64> a(c->n);
+    for (int s = 0; s < c->n; ++s) a[c->slot_to_idx[s]] = slots[s] % c->p;
+    c->ntt_p.inverse(a.data());
+    std::memcpy(poly_p, a.data(), sizeof(u64) * c->n);
+    return GALA_OK;
+}
+extern "C" int gala_decode(const gala_ctx *c, const uint64_t *poly_p, uint64_t *slots) {
+    if (!c || !slots || !poly_p) return GALA_EARG;
+    std::vector<u64> a(c->n);
+    for (int i = 0; i < c->n; ++i) a[i] = poly_p[i] % c->p;
+    c->ntt_p.forward(a.data());
+    for (int s = 0; s < c->n; ++s) slots[s] = a[c->slot_to_idx[s]];
+    return GALA_OK;
+}
+extern "C" int gala_encrypt(const gala_ctx *c, const gala_sk *sk, const uint64_t *slots, uint64_t seed,
+                            uint64_t *ct) {
+    if (!c || !sk || !slots || !ct) return GALA_EARG;
+    const int n = c->n;
+    const u64 q = c->q;
+    std::vector<u64> m(n), as(n);
+    gala_encode(c, slots, m.data());
+    u64 *c0 = ct, *c1 = ct + n;
+    for (int i = 0; i < n; ++i) as[i] = c1[i] = draw_uniform(q, c->qbits, seed, kStreamCtA, (u64)i);
+    c->ntt_q.forward(as.data());
+    for (int i = 0; i < n; ++i) as[i] = mul_mod(as[i], sk->s_hat[i], c->ntt_q.mod);
+    c->ntt_q.inverse(as.data());
+    for (int i = 0; i < n; ++i) {
+        u64 e = lift_signed(draw_gauss(seed, kStreamCtE, (u64)i), q);
+        u64 dm = mul_shoup(m[i], c->delta, c->delta_s, q);
+        c0[i] = add_mod(sub_mod(e, as[i], q), dm, q);
+    }
+    return GALA_OK;
+}
+extern "C" int gala_decrypt(const gala_ctx *c, const gala_sk *sk, const uint64_t *ct, uint64_t *slots) {
+    if (!c || !sk || !slots || !ct) return GALA_EARG;
+    const int n = c->n;
+    const u64 q = c->q, p = c->p;
+    std::vector<u64> v(ct + n, ct + 2 * n), m(n);
+    c->ntt_q.forward(v.data());
+    for (int i = 0; i < n; ++i) v[i] = mul_mod(v[i], sk->s_hat[i], c->ntt_q.mod);
+    c->ntt_q.inverse(v.data());
+    for (int i = 0; i < n; ++i) {
+        u64 ph = add_mod(v[i], ct[i] % q, q);
+        m[i] = (u64)((((u128)p * ph) + q / 2) / q) % p;
+    }
+    return gala_decode(c, m.data(), slots);
+}
+
+// ===========================================================================
+// he_fc plan: row-wise weight encoding (Sec. III-A(3))
+// ===========================================================================
+namespace {
+// row of W whose partial sum sits in slot (h,k) after all rotations; -1 if none
+int fc_slot_row(const gala_fc_plan *pl, int h, int k) {
+    const int n = pl->ctx->n, half = n / 2;
+    if (pl->big) return k % pl->nop;
+    const int copy = h * (half / pl->nip) + k / pl->nip, j = k % pl->nip;
+    if ((long)pl->nip * pl->nop < n && copy >= pl->nop) return -1;
+    int r = (j - copy * pl->G) % pl->nop;
+    return r < 0 ? r + pl->nop : r;
+}
+int fc_slot_col(const gala_fc_plan *pl, int h, int k) {
+    return pl->big ? h * (pl->ctx->n / 2) + k : k % pl->nip;
+}
+}  // namespace
+
+extern "C" int gala_fc_plan_create(gala_ctx *c, const uint64_t *W, int n_o, int n_i, gala_fc_plan **out) {
+    if (!c || !W || !out || n_o < 1 || n_i < 1) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    const int n = c->n, half = n / 2;
+    gala_fc_plan *pl = new (std::nothrow) gala_fc_plan;
+    if (!pl) return GALA_ENOMEM;
+    pl->ctx = c; pl->n_o = n_o; pl->n_i = n_i;
+    pl->nop = pow2_ceil(n_o); pl->nip = pow2_ceil(n_i);
+    if (pl->nip > n || pl->nop > n) { delete pl; return GALA_ESHAPE; }
+    pl->big = pl->nip == n;
+    if (pl->big) {
+        if (pl->nop > half) { delete pl; return GALA_ESHAPE; }
+        pl->G = pl->nop;
+    } else {
+        long prod = (long)pl->nip * pl->nop;
+        pl->G = prod >= n ? (int)(prod / n) : 1;
+    }
+    const int G = pl->G;
+    pl->slot_row.resize(n);
+    for (int s = 0; s < n; ++s) {
+        int row = fc_slot_row(pl, s / half, s % half);
+        pl->slot_row[s] = row < n_o ? row : -1;
+    }
+    pl->gal.resize(G);
+    for (int g = 0; g < G; ++g) pl->gal[g] = galois_element(n, 0, g);
+    // encoded weights: before the left rotation by g, slot (h,k) holds W[row(h,k-g)][col(h,k)]
+    std::vector<u64> w((size_t)G * n);
+    parallel_for((size_t)G, [&](size_t g) {
+        std::vector<u64> slots(n);
+        for (int h = 0; h < 2; ++h)
+            for (int k = 0; k < half; ++k) {
+                int row = fc_slot_row(pl, h, ((k - (int)g) % half + half) % half), col = fc_slot_col(pl, h, k);
+                slots[h * half + k] = (row >= 0 && row < n_o && col < n_i) ? W[(size_t)row * n_i + col] % c->p : 0;
+            }
+        encode_weight_hat(c, slots.data(), w.data() + g * n);
+    });
+    // mask layout: one output ciphertext, rows = real outputs
+    MaskLayoutHost &mh = pl->mask_h;
+    mh.nout = 1;
+    mh.nrows = {n_o};
+    mh.row_ptr.assign(n + 1, 0);
+    mh.row_slots.assign(n, 0);
+    mh.row_rindex.assign(n, 0);
+    mh.is_first.assign(n, 0);
+    std::vector<std::vector<int>> members(n_o);
+    for (int s = 0; s < n; ++s)
+        if (pl->slot_row[s] >= 0) members[pl->slot_row[s]].push_back(s);
+    int pos = 0;
+    for (int t = 0; t < n_o; ++t) {
+        mh.row_ptr[t] = pos;
+        mh.row_rindex[t] = t;
+        for (int s : members[t]) mh.row_slots[pos++] = s;
+        if (!members[t].empty()) mh.is_first[members[t][0]] = 1;
+    }
+    for (int t = n_o; t <= n; ++t) mh.row_ptr[t] = pos;
+    std::vector<int> key_idx(G, -1);
+    int rc = upload(&pl->d_w, w);
+    if (!rc) rc = upload(&pl->d_gal, pl->gal);
+    if (!rc) rc = upload(&pl->d_key_idx, key_idx);
+    if (!rc) rc = upload_mask_layout(mh, &pl->mask_d);
+    if (rc) { gala_fc_plan_destroy(pl); return rc; }
+    *out = pl;
+    return GALA_OK;
+}
+extern "C" void gala_fc_plan_destroy(gala_fc_plan *pl) {
+    if (!pl) return;
+    hipFree(pl->d_w); hipFree(pl->d_gal); hipFree(pl->d_key_idx);
+    free_mask_layout(&pl->mask_d);
+    delete pl;
+}
+extern "C" int gala_fc_plan_G(const gala_fc_plan *pl) { return pl ? pl->G : GALA_EARG; }
+extern "C" int gala_fc_plan_rotations(const gala_fc_plan *pl, gala_rot *rots, int *nrots) {
+    if (!pl || !nrots) return GALA_EARG;
+    *nrots = pl->G - 1;
+    if (rots)
+        for (int g = 1; g < pl->G; ++g) rots[g - 1] = gala_rot{0, g};
+    return GALA_OK;
+}
+extern "C" int gala_fc_plan_bind(gala_fc_plan *pl, const gala_gk *gk) {
+    if (!pl || !gk) return GALA_EARG;
+    std::vector<int> idx(pl->G, -1);
+    for (int g = 1; g < pl->G; ++g) {
+        auto it = gk->index_of.find(pl->gal[g]);
+        if (it == gk->index_of.end()) return GALA_ENOKEY;
+        idx[g] = it->second;
+    }
+    if (hipMemcpy(pl->d_key_idx, idx.data(), sizeof(int) * pl->G, hipMemcpyHostToDevice) != hipSuccess) return GALA_EHIP;
+    pl->bound = gk;
+    return GALA_OK;
+}
+extern "C" int gala_fc_pack_input(const gala_fc_plan *pl, const uint64_t *x, uint64_t *slots) {
+    if (!pl || !x || !slots) return GALA_EARG;
+    const int half = pl->ctx->n / 2;
+    for (int h = 0; h < 2; ++h)
+        for (int k = 0; k < half; ++k) {
+            int col = fc_slot_col(pl, h, k);
+            slots[h * half + k] = col < pl->n_i ? x[col] % pl->ctx->p : 0;
+        }
+    return GALA_OK;
+}
+extern "C" int gala_fc_unpack_share(const gala_fc_plan *pl, const uint64_t *slots, uint64_t *out) {
+    if (!pl || !out || !slots) return GALA_EARG;
+    const u64 p = pl->ctx->p;
+    for (int t = 0; t < pl->n_o; ++t) out[t] = 0;
+    for (int s = 0; s < pl->ctx->n; ++s)
+        if (pl->slot_row[s] >= 0) out[pl->slot_row[s]] = add_mod(out[pl->slot_row[s]], slots[s] % p, p);
+    return GALA_OK;
+}
+
+// ===========================================================================
+// he_conv plan: kernel grouping (Sec. III-B(3))
+// ===========================================================================
+extern "C" int gala_conv_plan_create(gala_ctx *c, const uint64_t *K, int c_o, int c_i, int k_h, int k_w, int u_h,
+                                     int u_w, gala_conv_plan **out) {
+    if (!c || !K || !out || c_o < 1 || c_i < 1 || k_h < 1 || k_w < 1 || u_h < 1 || u_w < 1) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    const int n = c->n, half = n / 2;
+    if (!(k_h & 1) || !(k_w & 1)) return GALA_ESHAPE;
+    if ((long)u_h * u_w > half) return GALA_ESHAPE;
+    gala_conv_plan *pl = new (std::nothrow) gala_conv_plan;
+    if (!pl) return GALA_ENOMEM;
+    pl->ctx = c; pl->c_o = c_o; pl->c_i = c_i; pl->k_h = k_h; pl->k_w = k_w; pl->u_h = u_h; pl->u_w = u_w;
+    pl->T = pow2_ceil(u_h * u_w);
+    pl->cn = n / pl->T; pl->hpos = pl->cn / 2;
+    pl->nin = (c_i + pl->cn - 1) / pl->cn; pl->nout = (c_o + pl->cn - 1) / pl->cn;
+    pl->ntap = k_h * k_w; pl->centre = (k_h / 2) * k_w + k_w / 2;
+    const int T = pl->T, cn = pl->cn, hpos = pl->hpos, nin = pl->nin, nout = pl->nout, ntap = pl->ntap;
+    // taps: the input shifted so that pixel (y+dy, x+dx) lands on (y,x): left rotation by dy*u_w+dx
+    pl->tap_gal.resize(ntap);
+    for (int tap = 0; tap < ntap; ++tap) {
+        int off = (tap / k_w - k_h / 2) * u_w + (tap % k_w - k_w / 2);
+        pl->tap_gal[tap] = galois_element(n, 0, ((off % half) + half) % half);
+    }
+    // kernel orders: group element (s,t) moves channel position (h,kappa) <- (h^s, kappa+t)
+    pl->grp_gal.resize(cn);
+    for (int gam = 0; gam < cn; ++gam) pl->grp_gal[gam] = galois_element(n, gam / hpos, (gam % hpos) * T);
+
+    const size_t npoly = (size_t)nout * cn * nin * ntap;
+    std::vector<u64> w;
+    try { w.resize(npoly * n); } catch (...) { delete pl; return GALA_ENOMEM; }
+    parallel_for(npoly, [&](size_t id) {
+        const int tap = (int)(id % ntap), I = (int)(id / ntap % nin), gam = (int)(id / ntap / nin % cn),
+                  O = (int)(id / ntap / nin / cn);
+        const int gs = gam / hpos, gt = gam % hpos, dy = tap / k_w - k_h / 2, dx = tap % k_w - k_w / 2;
+        std::vector<u64> slots(n, 0);
+        for (int h = 0; h < 2; ++h)
+            for (int kap = 0; kap < hpos; ++kap) {
+                const int in_ch = I * cn + h * hpos + kap;
+                const int okap = ((kap - gt) % hpos + hpos) % hpos;
+                const int out_ch = O * cn + (h ^ gs) * hpos + okap;
+                if (in_ch >= c_i || out_ch >= c_o) continue;
+                const u64 *ker = K + ((size_t)out_ch * c_i + in_ch) * k_h * k_w;
+                for (int y = std::max(0, -dy); y < std::min(u_h, u_h - dy); ++y)
+                    for (int x = std::max(0, -dx); x < std::min(u_w, u_w - dx); ++x)
+                        slots[h * half + kap * T + y * u_w + x] = ker[tap] % c->p;
+            }
+        encode_weight_hat(c, slots.data(), w.data() + id * n);
+    });
+    // mask layout: every real output is a row of its own
+    MaskLayoutHost &mh = pl->mask_h;
+    mh.nout = nout;
+    mh.nrows.assign(nout, 0);
+    mh.row_ptr.assign((size_t)nout * (n + 1), 0);
+    mh.row_slots.assign((size_t)nout * n, 0);
+    mh.row_rindex.assign((size_t)nout * n, 0);
+    mh.is_first.assign((size_t)nout * n, 0);
+    for (int O = 0; O < nout; ++O) {
+        int rows = 0;
+        for (int s = 0; s < n; ++s) {
+            const int h = s / half, k = s % half, ch = O * cn + h * hpos + k / T, off = k % T;
+            if (ch >= c_o || off >= u_h * u_w) continue;
+            mh.row_ptr[(size_t)O * (n + 1) + rows] = rows;
+            mh.row_slots[(size_t)O * n + rows] = s;
+            mh.row_rindex[(size_t)O * n + rows] = ch * u_h * u_w + off;
+            mh.is_first[(size_t)O * n + s] = 1;
+            ++rows;
+        }
+        for (int t = rows; t <= n; ++t) mh.row_ptr[(size_t)O * (n + 1) + t] = rows;
+        mh.nrows[O] = rows;
+    }
+    std::vector<int> tap_key(ntap, -1), grp_key(cn, -1);
+    int rc = upload(&pl->d_w, w);
+    if (!rc) rc = upload(&pl->d_tap_gal, pl->tap_gal);
+    if (!rc) rc = upload(&pl->d_grp_gal, pl->grp_gal);
+    if (!rc) rc = upload(&pl->d_tap_key, tap_key);
+    if (!rc) rc = upload(&pl->d_grp_key, grp_key);
+    if (!rc) rc = upload_mask_layout(mh, &pl->mask_d);
+    if (rc) { gala_conv_plan_destroy(pl); return rc; }
+    *out = pl;
+    return GALA_OK;
+}
+extern "C" void gala_conv_plan_destroy(gala_conv_plan *pl) {
+    if (!pl) return;
+    hipFree(pl->d_w); hipFree(pl->d_tap_gal); hipFree(pl->d_grp_gal); hipFree(pl->d_tap_key); hipFree(pl->d_grp_key);
+    free_mask_layout(&pl->mask_d);
+    delete pl;
+}
+extern "C" int gala_conv_plan_geometry(const gala_conv_plan *pl, int32_t *g) {
+    if (!pl || !g) return GALA_EARG;
+    g[0] = pl->T; g[1] = pl->cn; g[2] = pl->nin; g[3] = pl->nout; g[4] = pl->ntap;
+    return GALA_OK;
+}
+namespace {
+// rotation (swap, step) of a Galois element produced by galois_element()
+gala_rot rot_of(const gala_ctx *c, int g) {
+    const int n = c->n;
+    gala_rot r{0, 0};
+    if (g == 1) return r;
+    long e = 1;
+    for (int step = 0; step < n / 2; ++step) {
+        if (e == g) { r.step = step; return r; }
+        if (2 * n - e == g) { r.swap = 1; r.step = step; return r; }
+        e = e * 3 % (2 * n);
+    }
+    return r;
+}
+}  // namespace
+extern "C" int gala_conv_plan_rotations(const gala_conv_plan *pl, gala_rot *rots, int *nrots) {
+    if (!pl || !nrots) return GALA_EARG;
+    std::vector<int> els;
+    for (int g : pl->tap_gal) if (g != 1 && std::find(els.begin(), els.end(), g) == els.end()) els.push_back(g);
+    for (int g : pl->grp_gal) if (g != 1 && std::find(els.begin(), els.end(), g) == els.end()) els.push_back(g);
+    *nrots = (int)els.size();
+    if (rots)
+        for (size_t i = 0; i < els.size(); ++i) rots[i] = rot_of(pl->ctx, els[i]);
+    return GALA_OK;
+}
+extern "C" int gala_conv_plan_bind(gala_conv_plan *pl, const gala_gk *gk) {
+    if (!pl || !gk) return GALA_EARG;
+    std::vector<int> tk(pl->ntap, -1), gkey(pl->cn, -1);
+    for (int t = 0; t < pl->ntap; ++t) {
+        if (pl->tap_gal[t] == 1) continue;
+        auto it = gk->index_of.find(pl->tap_gal[t]);
+        if (it == gk->index_of.end()) return GALA_ENOKEY;
+        tk[t] = it->second;
+    }
+    for (int g = 0; g < pl->cn; ++g) {
+        if (pl->grp_gal[g] == 1) continue;
+        auto it = gk->index_of.find(pl->grp_gal[g]);
+        if (it == gk->index_of.end()) return GALA_ENOKEY;
+        gkey[g] = it->second;
+    }
+    if (hipMemcpy(pl->d_tap_key, tk.data(), sizeof(int) * pl->ntap, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(pl->d_grp_key, gkey.data(), sizeof(int) * pl->cn, hipMemcpyHostToDevice) != hipSuccess)
+        return GALA_EHIP;
+    pl->bound = gk;
+    return GALA_OK;
+}
+extern "C" int gala_conv_pack_input(const gala_conv_plan *pl, const uint64_t *x, uint64_t *slots) {
+    if (!pl || !x || !slots) return GALA_EARG;
+    const int n = pl->ctx->n, half = n / 2, px = pl->u_h * pl->u_w;
+    std::fill(slots, slots + (size_t)pl->nin * n, 0);
+    for (int ch = 0; ch < pl->c_i; ++ch) {
+        const int I = ch / pl->cn, pos = ch % pl->cn, h = pos / pl->hpos, kap = pos % pl->hpos;
+        for (int off = 0; off < px; ++off)
+            slots[(size_t)I * n + h * half + kap * pl->T + off] = x[(size_t)ch * px + off] % pl->ctx->p;
+    }
+    return GALA_OK;
+}
+extern "C" int gala_conv_unpack_share(const gala_conv_plan *pl, int O, const uint64_t *slots, uint64_t *out) {
+    if (!pl || !out || !slots || O < 0 || O >= pl->nout) return GALA_EARG;
+    const int half = pl->ctx->n / 2, px = pl->u_h * pl->u_w;
+    for (int pos = 0; pos < pl->cn; ++pos) {
+        const int ch = O * pl->cn + pos, h = pos / pl->hpos, kap = pos % pl->hpos;
+        if (ch >= pl->c_o) continue;
+        for (int off = 0; off < px; ++off) out[(size_t)ch * px + off] = slots[h * half + kap * pl->T + off] % pl->ctx->p;
+    }
+    return GALA_OK;
+}

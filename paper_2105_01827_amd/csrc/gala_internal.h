@@ -1,0 +1,179 @@
+// Internal data structures of the library (host side) and the launch interface
+// of the HIP kernels.  Nothing here is visible through the C ABI.
+#pragma once
+#include <cstddef>
+#include <map>
+#include <vector>
+
+#include "../../include/gala.h"
+#include "modarith.h"
+
+namespace gala {
+
+constexpr int kMaxDigits = 32;
+constexpr int kMaxN = 2048;
+constexpr int kGaussBound = 19;
+
+// ---------------------------------------------------------------------------
+// Negacyclic number-theoretic transform tables for one modulus.
+// Forward: natural-order coefficients -> values a(psi^(2*brev(i)+1)) at index i.
+// tw[m+i] = psi^brev(m+i) for the stage with m blocks; itw holds the inverses.
+// The inverse folds n^-1 into its last stage (ninv, itw1n = itw[1]*ninv).
+// ---------------------------------------------------------------------------
+struct NttHost {
+    int n = 0, logn = 0;
+    Modulus mod{};
+    u64 psi = 0;
+    std::vector<u64> tw, tws, itw, itws;
+    u64 ninv = 0, ninvs = 0, itw1n = 0, itw1ns = 0;
+
+    void init(int n, u64 q, u64 psi);
+    void forward(u64 *a) const;   // in place, canonical in -> canonical out
+    void inverse(u64 *a) const;
+};
+
+// Device view of the same tables (pointers into one device allocation).
+struct NttDev {
+    const u64 *tw, *tws, *itw, *itws;
+    u64 ninv, ninvs, itw1n, itw1ns;
+    Modulus mod;
+};
+
+u64 pow_mod(u64 b, u64 e, u64 m);
+u64 inv_mod(u64 a, u64 m);
+u64 shoup_companion(u64 w, u64 q);
+Modulus make_modulus(u64 q);
+bool is_prime_u64(u64 v);
+int bit_length(u64 v);
+inline int brev(int v, int bits) {
+    int r = 0;
+    for (int b = 0; b < bits; ++b) r |= ((v >> b) & 1) << (bits - 1 - b);
+    return r;
+}
+
+}  // namespace gala
+
+// ---------------------------------------------------------------------------
+// Handles
+// ---------------------------------------------------------------------------
+struct gala_ctx {
+    int n = 0, logn = 0, gadget_bits = 0, ndigits = 0, pbits = 0, qbits = 0;
+    gala::u64 q = 0, p = 0, delta = 0, delta_s = 0, zeta = 0;
+    gala::NttHost ntt_q, ntt_p;
+    std::vector<int> slot_to_idx;      // slot s -> index of its value in the mod-p transform
+    int device = 0;
+    bool has_device = false;           // tables uploaded; false on a host without a HIP device
+    gala::u64 *d_tables = nullptr;     // 8*n words: tw,tws,itw,itws for q then for p
+    int *d_slot_to_idx = nullptr;
+    gala::NttDev dev_q{}, dev_p{};
+};
+
+struct gala_sk {
+    std::vector<gala::u64> s;          // coefficients mod q (0, 1, q-1)
+    std::vector<gala::u64> s_hat;      // forward transform of s
+};
+
+struct gala_gk {
+    int n = 0, ndigits = 0;
+    std::map<int, int> index_of;       // Galois element -> key index
+    std::vector<int> elements;
+    gala::u64 *d_keys = nullptr;       // nkeys x ndigits x 2 x n, evaluation domain (b then a)
+    int *d_elements = nullptr;         // nkeys Galois elements, device
+    int *d_iota = nullptr;             // 0,1,2,... (key index of element k is k), device
+    int *d_one = nullptr;              // the single value 1 (Galois element of the identity), device
+    size_t key_words() const { return (size_t)ndigits * 2 * n; }
+};
+
+// Device description of how the server's mask is laid out in one output
+// ciphertext: which slots are drawn from the generator and which absorb r.
+struct MaskLayoutHost {
+    int nout = 0;                      // output ciphertexts
+    std::vector<int> row_ptr;          // nout x (n+1): CSR over the "rows" (outputs) of each ciphertext
+    std::vector<int> row_slots;        // nout x n: slots of each row, first slot first
+    std::vector<int> row_rindex;       // nout x n: index into r of each row
+    std::vector<int> nrows;            // nout
+    std::vector<unsigned char> is_first;  // nout x n: slot is the first of a real row (not drawn)
+};
+struct MaskLayoutDev {
+    int *row_ptr = nullptr, *row_slots = nullptr, *row_rindex = nullptr, *nrows = nullptr;
+    unsigned char *is_first = nullptr;
+};
+
+struct gala_fc_plan {
+    gala_ctx *ctx = nullptr;
+    int n_o = 0, n_i = 0, nop = 0, nip = 0, G = 0;
+    bool big = false;
+    std::vector<int> slot_row;         // padded row of each slot, -1 if it carries no weight
+    std::vector<int> gal;              // Galois element of rotation g (gal[0] = 1)
+    gala::u64 *d_w = nullptr;          // G x n encoded weights, evaluation domain
+    int *d_gal = nullptr;              // G Galois elements
+    int *d_key_idx = nullptr;          // G key indices (valid once bound)
+    const gala_gk *bound = nullptr;
+    MaskLayoutHost mask_h;
+    MaskLayoutDev mask_d;
+};
+
+struct gala_conv_plan {
+    gala_ctx *ctx = nullptr;
+    int c_o = 0, c_i = 0, k_h = 0, k_w = 0, u_h = 0, u_w = 0;
+    int T = 0, cn = 0, hpos = 0, nin = 0, nout = 0, ntap = 0, centre = 0;
+    std::vector<int> tap_gal, grp_gal; // Galois elements of taps (ntap) and kernel orders (cn)
+    gala::u64 *d_w = nullptr;          // nout x cn x nin x ntap x n encoded kernels, evaluation domain
+    int *d_tap_gal = nullptr, *d_tap_key = nullptr;   // ntap
+    int *d_grp_gal = nullptr, *d_grp_key = nullptr;   // cn
+    const gala_gk *bound = nullptr;
+    MaskLayoutHost mask_h;
+    MaskLayoutDev mask_d;
+};
+
+// ---------------------------------------------------------------------------
+// Kernel launchers (defined in gala_kernels.hip).  All return a hipError_t cast to int.
+// ---------------------------------------------------------------------------
+namespace gala {
+
+// batched transform of `count` polynomials of n words: inverse=0 forward.
+int launch_ntt(const gala_ctx *ctx, void *stream, const u64 *src, u64 *dst, size_t count, int inverse);
+
+// key generation helper on `npairs` consecutive (t_hat, a_hat) pairs of n-word evaluation-domain
+// polynomials: t_hat <- t_hat - a_hat * s_hat in place (s_hat shared by all pairs).
+int launch_key_finish(const gala_ctx *ctx, void *stream, u64 *pairs, const u64 *s_hat, size_t npairs);
+
+// One job of the rotate-and-accumulate kernel.  For item in [0,items), chunk in [0,nchunks):
+//   partial[item][chunk] = sum over g in the chunk of Perm_{gal[g]}( in[item][g] (.) w[g] )
+// where in[item][g] = ct_in + item*in_item_stride + g*in_g_stride (2n words each) and w[g] = w + g*n
+// (w == nullptr: no ScMult).  gal[g] == 1 means no rotation.  key_idx[g] selects the key.
+struct PermJob {
+    const u64 *ct_in;
+    size_t in_item_stride, in_g_stride;
+    const u64 *w;
+    const int *gal, *key_idx;
+    const u64 *keys;
+    int G, items, nchunks;
+    u64 *partial;            // items x nchunks x 2n
+};
+int launch_perm_accumulate(const gala_ctx *ctx, void *stream, const PermJob &job);
+
+// out[item] = sum_chunk partial[item][chunk] - mask(item) ; mask built from r and the generator.
+struct FinalizeJob {
+    const u64 *partial;
+    int items, nchunks;
+    int nout;                // output ciphertexts per batch element (item = b*nout + O)
+    const u64 *r;            // batch x r_stride values mod p (nullptr: no mask)
+    size_t r_stride;
+    u64 mask_seed;
+    MaskLayoutDev mask;
+    u64 *ct_out;             // items x 2n
+};
+int launch_finalize(const gala_ctx *ctx, void *stream, const FinalizeJob &job);
+
+// DecPerm of `count` ciphertexts: digits[c][j] = forward(digit_j(inverse(c1))), j < ndigits.
+int launch_decperm(const gala_ctx *ctx, void *stream, const u64 *ct_in, size_t count, u64 *digits);
+// HstPerm for the convolution's input rotations:
+//   xrot[c][tap] = HstPerm_{tap_gal[tap]}(ct_in[c], digits[c]) ; the tap with Galois element 1 is a copy.
+int launch_hstperm_taps(const gala_ctx *ctx, void *stream, const u64 *ct_in, const u64 *digits, size_t count,
+                        int ntap, const int *tap_gal, const int *tap_key, const u64 *keys, u64 *xrot);
+// acc[b][O][gam] = sum_{I,tap} w[O][gam][I][tap] (.) xrot[b][I][tap]   (both polynomials)
+int launch_conv_mac(const gala_ctx *ctx, void *stream, const u64 *w, const u64 *xrot, int batch, int nout, int cn,
+                    int nin, int ntap, u64 *acc);
+
+}  // namespace gala

@@ -1,0 +1,442 @@
+// HIP kernels for gfx950: batched negacyclic transforms staged through LDS, the
+// fused rotate-and-accumulate kernel (ScMult -> DecPerm -> HstPerm -> Add over
+// the rotations of a layer), share generation, and the convolution's
+// multiply-accumulate.  All arithmetic is unsigned 64-bit modulo a prime below
+// 2^61; there is no floating point on this path.
+#include <hip/hip_runtime.h>
+
+#include "gala_internal.h"
+
+namespace gala {
+
+namespace {
+
+constexpr int kMaxPer = 8;   // coefficients owned by one thread (n <= kMaxPer * block size)
+
+__device__ __forceinline__ int bitrev(int v, int bits) { return (int)(__brev((unsigned)v) >> (32 - bits)); }
+
+// Index permutation of the Galois map X -> X^gal in the evaluation domain:
+// position i holds the value at psi^(2 brev(i) + 1), and (a o gal)(x) = a(x^gal).
+__device__ __forceinline__ int galois_index(int i, int gal, int logn, int n) {
+    const int e = ((2 * bitrev(i, logn) + 1) * gal) & (2 * n - 1);
+    return bitrev((e - 1) >> 1, logn);
+}
+
+// Forward transform of the n words in LDS; any input below 4q, output below 4q.
+template <int NT>
+__device__ void ntt_forward_lds(u64 *a, int n, int logn, const NttDev &T) {
+    const u64 q = T.mod.q, q2 = T.mod.q2;
+    for (int s = 0; s < logn; ++s) {
+        const int tlog = logn - 1 - s, t = 1 << tlog, m = 1 << s;
+        for (int b = threadIdx.x; b < (n >> 1); b += NT) {
+            const int i = b >> tlog, j = (i << (tlog + 1)) | (b & (t - 1));
+            u64 x = a[j], y = a[j + t];
+            butterfly_fwd(x, y, T.tw[m + i], T.tws[m + i], q, q2);
+            a[j] = x;
+            a[j + t] = y;
+        }
+        __syncthreads();
+    }
+}
+// Inverse transform in LDS; input below 2q, output canonical.
+template <int NT>
+__device__ void ntt_inverse_lds(u64 *a, int n, int logn, const NttDev &T) {
+    const u64 q = T.mod.q, q2 = T.mod.q2;
+    for (int s = 0; s < logn - 1; ++s) {
+        const int t = 1 << s, m = n >> (s + 1);
+        for (int b = threadIdx.x; b < (n >> 1); b += NT) {
+            const int i = b >> s, j = (i << (s + 1)) | (b & (t - 1));
+            u64 x = a[j], y = a[j + t];
+            butterfly_inv(x, y, T.itw[m + i], T.itws[m + i], q, q2);
+            a[j] = x;
+            a[j + t] = y;
+        }
+        __syncthreads();
+    }
+    const int t = n >> 1;
+    for (int b = threadIdx.x; b < t; b += NT) {
+        const u64 x = a[b], y = a[b + t];
+        a[b] = mul_shoup(x + y, T.ninv, T.ninvs, q);
+        a[b + t] = mul_shoup(x - y + q2, T.itw1n, T.itw1ns, q);
+    }
+    __syncthreads();
+}
+
+// ---------------------------------------------------------------------------
+// batched transform (import / export / key upload): one workgroup per polynomial
+// ---------------------------------------------------------------------------
+template <int NT>
+__global__ __launch_bounds__(NT) void ntt_kernel(const u64 *src, u64 *dst, int n, int logn, NttDev T, int inverse) {
+    extern __shared__ u64 buf[];
+    const size_t base = (size_t)blockIdx.x * n;
+    for (int i = threadIdx.x; i < n; i += NT) buf[i] = src[base + i];
+    __syncthreads();
+    if (inverse) ntt_inverse_lds<NT>(buf, n, logn, T);
+    else ntt_forward_lds<NT>(buf, n, logn, T);
+    for (int i = threadIdx.x; i < n; i += NT) dst[base + i] = csub(csub(buf[i], T.mod.q2), T.mod.q);
+}
+
+__global__ void key_finish_kernel(u64 *pairs, const u64 *s_hat, int n, size_t total, Modulus mod) {
+    const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= total) return;
+    const size_t pair = id / n;
+    const int i = (int)(id % n);
+    u64 *t = pairs + pair * 2 * n, *a = t + n;
+    t[i] = sub_mod(t[i], mul_mod(a[i], s_hat[i], mod), mod.q);
+}
+
+// ---------------------------------------------------------------------------
+// rotate-and-accumulate
+// ---------------------------------------------------------------------------
+template <int NT>
+__global__ __launch_bounds__(NT) void perm_accumulate_kernel(PermJob job, NttDev T, int n, int logn, int gadget_bits,
+                                                             int ndigits) {
+    extern __shared__ u64 buf[];
+    const int tid = threadIdx.x;
+    const int item = blockIdx.x / job.nchunks, chunk = blockIdx.x % job.nchunks;
+    const int g0 = (int)((long)chunk * job.G / job.nchunks), g1 = (int)((long)(chunk + 1) * job.G / job.nchunks);
+    const u64 q = T.mod.q, q2 = T.mod.q2;
+    const u64 digit_mask = (1ull << gadget_bits) - 1;
+    const size_t key_words = (size_t)ndigits * 2 * n;
+
+    u128 acc0[kMaxPer], acc1[kMaxPer];
+#pragma unroll
+    for (int k = 0; k < kMaxPer; ++k) acc0[k] = acc1[k] = 0;
+    int terms = 0;   // products (each below q^2 < 2^122) summed into the accumulators so far
+
+    for (int g = g0; g < g1; ++g) {
+        const u64 *c0 = job.ct_in + (size_t)item * job.in_item_stride + (size_t)g * job.in_g_stride;
+        const u64 *c1 = c0 + n;
+        const u64 *w = job.w ? job.w + (size_t)g * n : nullptr;
+        const int gal = job.gal[g];
+        if (terms + ndigits + 1 > 60) {   // keep the 128-bit sums from overflowing
+#pragma unroll
+            for (int k = 0; k < kMaxPer; ++k) {
+                acc0[k] = reduce128(acc0[k], T.mod);
+                acc1[k] = reduce128(acc1[k], T.mod);
+            }
+            terms = 1;
+        }
+        if (gal == 1) {   // the rotation by zero: ScMult and Add only
+#pragma unroll
+            for (int k = 0; k < kMaxPer; ++k) {
+                const int i = tid + k * NT;
+                if (i < n) {
+                    if (w) {
+                        acc0[k] += (u128)c0[i] * w[i];
+                        acc1[k] += (u128)c1[i] * w[i];
+                    } else {
+                        acc0[k] += c0[i];
+                        acc1[k] += c1[i];
+                    }
+                }
+            }
+            terms += 1;
+            continue;
+        }
+        const u64 *key = job.keys + (size_t)job.key_idx[g] * key_words;
+        // ScMult of c1, then DecPerm: back to coefficients, digits, forward again
+        for (int k = 0; k < kMaxPer; ++k) {
+            const int i = tid + k * NT;
+            if (i < n) buf[i] = w ? mul_mod(c1[i], w[i], T.mod) : c1[i];
+        }
+        __syncthreads();
+        ntt_inverse_lds<NT>(buf, n, logn, T);
+        u64 coef[kMaxPer];
+#pragma unroll
+        for (int k = 0; k < kMaxPer; ++k) {
+            const int i = tid + k * NT;
+            coef[k] = i < n ? buf[i] : 0;
+        }
+        __syncthreads();
+        for (int j = 0; j < ndigits; ++j) {
+#pragma unroll
+            for (int k = 0; k < kMaxPer; ++k) {
+                const int i = tid + k * NT;
+                if (i < n) buf[i] = (coef[k] >> (j * gadget_bits)) & digit_mask;
+            }
+            __syncthreads();
+            ntt_forward_lds<NT>(buf, n, logn, T);
+            // HstPerm: automorphism as a gather, inner product with the key
+            const u64 *kb = key + (size_t)(2 * j) * n, *ka = kb + n;
+#pragma unroll
+            for (int k = 0; k < kMaxPer; ++k) {
+                const int i = tid + k * NT;
+                if (i < n) {
+                    const u64 d = csub(csub(buf[galois_index(i, gal, logn, n)], q2), q);
+                    acc0[k] += (u128)d * kb[i];
+                    acc1[k] += (u128)d * ka[i];
+                }
+            }
+            __syncthreads();
+        }
+        // the c0 part of the rotated ciphertext
+#pragma unroll
+        for (int k = 0; k < kMaxPer; ++k) {
+            const int i = tid + k * NT;
+            if (i < n) {
+                const int pi = galois_index(i, gal, logn, n);
+                if (w) acc0[k] += (u128)c0[pi] * w[pi];
+                else acc0[k] += c0[pi];
+            }
+        }
+        terms += ndigits + 1;
+    }
+    u64 *out = job.partial + ((size_t)item * job.nchunks + chunk) * 2 * n;
+#pragma unroll
+    for (int k = 0; k < kMaxPer; ++k) {
+        const int i = tid + k * NT;
+        if (i < n) {
+            out[i] = reduce128(acc0[k], T.mod);
+            out[n + i] = reduce128(acc1[k], T.mod);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// share generation: sum the partial ciphertexts of an item, subtract the mask
+// ---------------------------------------------------------------------------
+template <int NT>
+__global__ __launch_bounds__(NT) void finalize_kernel(FinalizeJob job, NttDev Tq, NttDev Tp, const int *slot_to_idx,
+                                                      int n, int logn, int pbits, u64 delta, u64 delta_s) {
+    extern __shared__ u64 buf[];
+    const int tid = threadIdx.x;
+    const int item = blockIdx.x, b = item / job.nout, O = item % job.nout;
+    const u64 q = Tq.mod.q, p = Tp.mod.q;
+    if (job.r) {
+        const int *row_ptr = job.mask.row_ptr + (size_t)O * (n + 1);
+        const int *row_slots = job.mask.row_slots + (size_t)O * n;
+        const int *row_rindex = job.mask.row_rindex + (size_t)O * n;
+        const unsigned char *is_first = job.mask.is_first + (size_t)O * n;
+        // every slot but the first of each real output is a draw from the mask stream
+        for (int s = tid; s < n; s += NT) {
+            u64 v = 0;
+            if (!is_first[s]) v = draw_uniform(p, pbits, job.mask_seed, kStreamMask, ((u64)b << 32) + ((u64)O << 16) + (u64)s);
+            buf[slot_to_idx[s]] = v;
+        }
+        __syncthreads();
+        // the first slot absorbs r[t] minus the rest of its group
+        const int nrows = job.mask.nrows[O];
+        for (int t = tid; t < nrows; t += NT) {
+            const int e0 = row_ptr[t], e1 = row_ptr[t + 1];
+            if (e1 <= e0) continue;
+            u64 sum = 0;
+            for (int e = e0 + 1; e < e1; ++e) sum = add_mod(sum, buf[slot_to_idx[row_slots[e]]], p);
+            u64 rv = job.r[(size_t)b * job.r_stride + row_rindex[t]];
+            if (rv >= p) rv %= p;
+            buf[slot_to_idx[row_slots[e0]]] = sub_mod(rv, sum, p);
+        }
+        __syncthreads();
+        // encode: slots -> plaintext polynomial mod p -> delta * m mod q -> evaluation domain
+        ntt_inverse_lds<NT>(buf, n, logn, Tp);
+        for (int i = tid; i < n; i += NT) buf[i] = mul_shoup(buf[i], delta, delta_s, q);
+        __syncthreads();
+        ntt_forward_lds<NT>(buf, n, logn, Tq);
+    }
+    const u64 *part = job.partial + (size_t)item * job.nchunks * 2 * n;
+    u64 *out = job.ct_out + (size_t)item * 2 * n;
+    for (int i = tid; i < n; i += NT) {
+        u64 s0 = 0, s1 = 0;
+        for (int c = 0; c < job.nchunks; ++c) {
+            s0 = add_mod(s0, part[(size_t)c * 2 * n + i], q);
+            s1 = add_mod(s1, part[(size_t)c * 2 * n + n + i], q);
+        }
+        if (job.r) s0 = sub_mod(s0, csub(csub(buf[i], Tq.mod.q2), q), q);
+        out[i] = s0;
+        out[n + i] = s1;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// convolution: hoisted input rotations and the multiply-accumulate
+// ---------------------------------------------------------------------------
+template <int NT>
+__global__ __launch_bounds__(NT) void decperm_kernel(const u64 *ct_in, u64 *digits, NttDev T, int n, int logn,
+                                                     int gadget_bits, int ndigits) {
+    extern __shared__ u64 buf[];
+    const int tid = threadIdx.x;
+    const u64 *c1 = ct_in + (size_t)blockIdx.x * 2 * n + n;
+    u64 *out = digits + (size_t)blockIdx.x * ndigits * n;
+    const u64 digit_mask = (1ull << gadget_bits) - 1;
+    for (int i = tid; i < n; i += NT) buf[i] = c1[i];
+    __syncthreads();
+    ntt_inverse_lds<NT>(buf, n, logn, T);
+    u64 coef[kMaxPer];
+#pragma unroll
+    for (int k = 0; k < kMaxPer; ++k) {
+        const int i = tid + k * NT;
+        coef[k] = i < n ? buf[i] : 0;
+    }
+    __syncthreads();
+    for (int j = 0; j < ndigits; ++j) {
+#pragma unroll
+        for (int k = 0; k < kMaxPer; ++k) {
+            const int i = tid + k * NT;
+            if (i < n) buf[i] = (coef[k] >> (j * gadget_bits)) & digit_mask;
+        }
+        __syncthreads();
+        ntt_forward_lds<NT>(buf, n, logn, T);
+        for (int i = tid; i < n; i += NT) out[(size_t)j * n + i] = csub(csub(buf[i], T.mod.q2), T.mod.q);
+        __syncthreads();
+    }
+}
+
+__global__ void hstperm_taps_kernel(const u64 *ct_in, const u64 *digits, int ntap, const int *tap_gal,
+                                    const int *tap_key, const u64 *keys, u64 *xrot, Modulus mod, int n, int logn,
+                                    int ndigits) {
+    const int c = blockIdx.x / ntap, tap = blockIdx.x % ntap;
+    const u64 *c0 = ct_in + (size_t)c * 2 * n, *c1 = c0 + n;
+    const u64 *dig = digits + (size_t)c * ndigits * n;
+    u64 *out = xrot + ((size_t)c * ntap + tap) * 2 * n;
+    const int gal = tap_gal[tap];
+    if (gal == 1) {
+        for (int i = threadIdx.x; i < n; i += blockDim.x) {
+            out[i] = c0[i];
+            out[n + i] = c1[i];
+        }
+        return;
+    }
+    const u64 *key = keys + (size_t)tap_key[tap] * ndigits * 2 * n;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+        const int pi = galois_index(i, gal, logn, n);
+        u128 a0 = c0[pi], a1 = 0;
+        int terms = 0;
+        for (int j = 0; j < ndigits; ++j) {
+            const u64 d = dig[(size_t)j * n + pi];
+            a0 += (u128)d * key[(size_t)(2 * j) * n + i];
+            a1 += (u128)d * key[(size_t)(2 * j + 1) * n + i];
+            if (++terms == 32) {
+                a0 = reduce128(a0, mod);
+                a1 = reduce128(a1, mod);
+                terms = 0;
+            }
+        }
+        out[i] = reduce128(a0, mod);
+        out[n + i] = reduce128(a1, mod);
+    }
+}
+
+// One thread per coefficient; a tile of TB inputs shares each weight word.
+template <int TB>
+__global__ void conv_mac_kernel(const u64 *w, const u64 *xrot, int batch, int nterm, u64 *acc, Modulus mod, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int og = blockIdx.y;          // O*cn + gam
+    const int b0 = blockIdx.z * TB;
+    const int groups = gridDim.y;
+    u128 a[TB][2];
+#pragma unroll
+    for (int t = 0; t < TB; ++t) a[t][0] = a[t][1] = 0;
+    const u64 *wp = w + (size_t)og * nterm * n + i;
+    int terms = 0;
+    for (int e = 0; e < nterm; ++e) {
+        const u64 wv = wp[(size_t)e * n];
+#pragma unroll
+        for (int t = 0; t < TB; ++t) {
+            if (b0 + t < batch) {
+                const u64 *x = xrot + (((size_t)(b0 + t) * nterm + e) * 2) * n + i;
+                a[t][0] += (u128)wv * x[0];
+                a[t][1] += (u128)wv * x[n];
+            }
+        }
+        if (++terms == 60) {
+#pragma unroll
+            for (int t = 0; t < TB; ++t) {
+                a[t][0] = reduce128(a[t][0], mod);
+                a[t][1] = reduce128(a[t][1], mod);
+            }
+            terms = 1;
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < TB; ++t) {
+        if (b0 + t < batch) {
+            u64 *out = acc + (((size_t)(b0 + t) * groups + og) * 2) * n + i;
+            out[0] = reduce128(a[t][0], mod);
+            out[n] = reduce128(a[t][1], mod);
+        }
+    }
+}
+
+inline int block_threads(int n) { return n >= 512 ? 256 : 64; }
+inline int last_error() { return (int)hipGetLastError(); }
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+int launch_ntt(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, size_t count, int inverse) {
+    if (!count) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t lds = sizeof(u64) * c->n;
+    if (block_threads(c->n) == 256)
+        hipLaunchKernelGGL(ntt_kernel<256>, dim3((unsigned)count), dim3(256), lds, st, src, dst, c->n, c->logn, c->dev_q, inverse);
+    else
+        hipLaunchKernelGGL(ntt_kernel<64>, dim3((unsigned)count), dim3(64), lds, st, src, dst, c->n, c->logn, c->dev_q, inverse);
+    return last_error();
+}
+int launch_key_finish(const gala_ctx *c, void *stream, u64 *pairs, const u64 *s_hat, size_t npairs) {
+    if (!npairs) return 0;
+    const size_t total = npairs * c->n;
+    hipLaunchKernelGGL(key_finish_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream, pairs,
+                       s_hat, c->n, total, c->dev_q.mod);
+    return last_error();
+}
+int launch_perm_accumulate(const gala_ctx *c, void *stream, const PermJob &job) {
+    if (job.items <= 0 || job.nchunks <= 0) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t lds = sizeof(u64) * c->n;
+    const dim3 grid((unsigned)(job.items * job.nchunks));
+    if (block_threads(c->n) == 256)
+        hipLaunchKernelGGL(perm_accumulate_kernel<256>, grid, dim3(256), lds, st, job, c->dev_q, c->n, c->logn,
+                           c->gadget_bits, c->ndigits);
+    else
+        hipLaunchKernelGGL(perm_accumulate_kernel<64>, grid, dim3(64), lds, st, job, c->dev_q, c->n, c->logn,
+                           c->gadget_bits, c->ndigits);
+    return last_error();
+}
+int launch_finalize(const gala_ctx *c, void *stream, const FinalizeJob &job) {
+    if (job.items <= 0) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t lds = sizeof(u64) * c->n;
+    if (block_threads(c->n) == 256)
+        hipLaunchKernelGGL(finalize_kernel<256>, dim3(job.items), dim3(256), lds, st, job, c->dev_q, c->dev_p,
+                           c->d_slot_to_idx, c->n, c->logn, c->pbits, c->delta, c->delta_s);
+    else
+        hipLaunchKernelGGL(finalize_kernel<64>, dim3(job.items), dim3(64), lds, st, job, c->dev_q, c->dev_p,
+                           c->d_slot_to_idx, c->n, c->logn, c->pbits, c->delta, c->delta_s);
+    return last_error();
+}
+int launch_decperm(const gala_ctx *c, void *stream, const u64 *ct_in, size_t count, u64 *digits) {
+    if (!count) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t lds = sizeof(u64) * c->n;
+    if (block_threads(c->n) == 256)
+        hipLaunchKernelGGL(decperm_kernel<256>, dim3((unsigned)count), dim3(256), lds, st, ct_in, digits, c->dev_q, c->n,
+                           c->logn, c->gadget_bits, c->ndigits);
+    else
+        hipLaunchKernelGGL(decperm_kernel<64>, dim3((unsigned)count), dim3(64), lds, st, ct_in, digits, c->dev_q, c->n,
+                           c->logn, c->gadget_bits, c->ndigits);
+    return last_error();
+}
+int launch_hstperm_taps(const gala_ctx *c, void *stream, const u64 *ct_in, const u64 *digits, size_t count, int ntap,
+                        const int *tap_gal, const int *tap_key, const u64 *keys, u64 *xrot) {
+    if (!count) return 0;
+    hipLaunchKernelGGL(hstperm_taps_kernel, dim3((unsigned)(count * ntap)), dim3(block_threads(c->n)), 0,
+                       (hipStream_t)stream, ct_in, digits, ntap, tap_gal, tap_key, keys, xrot, c->dev_q.mod, c->n,
+                       c->logn, c->ndigits);
+    return last_error();
+}
+int launch_conv_mac(const gala_ctx *c, void *stream, const u64 *w, const u64 *xrot, int batch, int nout, int cn,
+                    int nin, int ntap, u64 *acc) {
+    if (batch <= 0) return 0;
+    constexpr int TB = 4;
+    const int threads = c->n >= 256 ? 256 : c->n;
+    const dim3 grid((unsigned)((c->n + threads - 1) / threads), (unsigned)(nout * cn), (unsigned)((batch + TB - 1) / TB));
+    hipLaunchKernelGGL(conv_mac_kernel<TB>, grid, dim3(threads), 0, (hipStream_t)stream, w, xrot, batch, nin * ntap, acc,
+                       c->dev_q.mod, c->n);
+    return last_error();
+}
+
+}  // namespace gala

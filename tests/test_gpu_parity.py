@@ -1,0 +1,243 @@
+"""GPU parity: the HIP library against the CPU oracle, bit for bit, through the C ABI.
+
+Same seeded keys, noise and masks on both sides; ciphertexts are compared in
+interchange form (coefficient domain), so every comparison is exact equality.
+"""
+import ctypes
+
+import numpy as np
+import pytest
+
+from oracle.oracle import Oracle
+from paper_2105_01827_amd import binding, workloads as wl
+from tests.helpers import rotate_slots, small_params
+
+pytestmark = pytest.mark.gpu
+
+
+def harness():
+    from tests import gpu_harness
+    return gpu_harness
+
+
+def both(par):
+    return binding.Context(par.n, par.q, par.p, par.gadget_bits), Oracle(par.n, par.q, par.p, par.gadget_bits)
+
+
+def plain_matvec(W, x, p):
+    return np.array([sum(int(a) * int(b) for a, b in zip(row, x)) % p for row in W], dtype=np.uint64)
+
+
+@pytest.mark.parametrize("n", [8, 64, 512, 2048])
+def test_import_export_roundtrip_and_transform_is_a_ring_map(n):
+    H = harness()
+    par = small_params(n) if n != 2048 else wl.DEFAULT
+    ctx, o = both(par)
+    rng = np.random.default_rng(n)
+    cts = rng.integers(0, par.q, size=(5, 2 * n), dtype=np.uint64)
+    dev = H.import_cts(ctx, cts)
+    assert np.array_equal(H.export_cts(ctx, dev, 5), cts)
+    # pointwise product in the internal form is the negacyclic product: check through a one-row FC below;
+    # here: the internal form of the constant polynomial 1 is all ones
+    one = np.zeros((1, 2 * n), np.uint64); one[0, 0] = 1; one[0, n] = 1
+    assert np.all(H.to_host(H.import_cts(ctx, one)) == 1)
+
+
+@pytest.mark.parametrize("n,gb", [(64, 20), (64, 2), (2048, 20)])
+def test_galois_keys_match_the_oracle(n, gb):
+    par = small_params(n, gadget_bits=gb) if n != 2048 else wl.DEFAULT
+    ctx, o = both(par)
+    sk, osk = ctx.keygen(3), o.keygen(3)
+    rots = [(0, 1), (0, 5), (1, 0), (1, n // 2 - 1), (0, 1)]
+    gk = ctx.galois_keygen(sk, rots, seed=42)
+    for swap, step in rots:
+        want = o.galois_key(osk, o.galois_elt(swap, step), 42)
+        assert np.array_equal(gk.export((swap, step)), want), (swap, step)
+    with pytest.raises(binding.GalaError) as e:
+        gk.export((0, 2))
+    assert e.value.code == binding.GALA_ENOKEY
+
+
+@pytest.mark.parametrize("n,gb,rots", [
+    (8, 20, [(0, 1), (0, 3), (1, 0), (1, 2)]),
+    (64, 20, [(0, 1), (0, 31), (1, 0), (1, 17)]),
+    (64, 2, [(0, 3), (1, 5)]),                          # 30 digits
+    (256, 16, [(0, 100)]),
+    (1024, 20, [(0, 511), (1, 1)]),
+    (2048, 20, [(0, 1), (0, 63), (0, 1023), (1, 0), (1, 512)]),
+])
+def test_rotate_matches_oracle_perm(n, gb, rots):
+    H = harness()
+    par = small_params(n, gadget_bits=gb) if (n, gb) != (2048, 20) else wl.DEFAULT
+    ctx, o = both(par)
+    sk, osk = ctx.keygen(3), o.keygen(3)
+    rng = np.random.default_rng(5)
+    count = 3
+    slots = rng.integers(0, par.p, size=(count, n), dtype=np.uint64)
+    cts = np.stack([ctx.encrypt(sk, slots[i], seed=10 + i) for i in range(count)])
+    gk = ctx.galois_keygen(sk, rots, seed=42)
+    d_in = H.import_cts(ctx, cts)
+    for swap, step in rots:
+        d_out = H.dev_empty(count * 2 * n)
+        ctx.rotate(gk, d_in, count, (swap, step), d_out)
+        got = H.export_cts(ctx, d_out, count)
+        g = o.galois_elt(swap, step)
+        ksk = o.galois_key(osk, g, 42)
+        for i in range(count):
+            assert np.array_equal(got[i], o.perm(cts[i], g, ksk)), (swap, step, i)
+            assert np.array_equal(ctx.decrypt(sk, got[i]), rotate_slots(slots[i], step, bool(swap)))
+    # the identity rotation copies, a missing key is an error
+    d_out = H.dev_empty(count * 2 * n)
+    ctx.rotate(gk, d_in, count, (0, 0), d_out)
+    assert np.array_equal(H.export_cts(ctx, d_out, count), cts)
+    missing = (0, 2) if (0, 2) not in rots else (0, 4)
+    with pytest.raises(binding.GalaError) as e:
+        ctx.rotate(gk, d_in, count, missing, d_out)
+    assert e.value.code == binding.GALA_ENOKEY
+
+
+def fc_case(par, n_o, n_i, batch, oracle_items, seed=0):
+    """Run he_fc on the GPU for the whole batch and on the oracle for the chosen items; compare exactly."""
+    H = harness()
+    ctx, o = both(par)
+    W, x, r = wl.fc_inputs(wl.FcShape("t", n_o, n_i, batch), p=par.p, seed=seed)
+    sk, osk = ctx.keygen(0), o.keygen(0)
+    plan = ctx.fc_plan(W)
+    assert plan.G == o.fc_G(n_o, n_i)
+    rots = plan.rotations()
+    assert rots == [(0, g) for g in range(1, plan.G)]
+    gk = ctx.galois_keygen(sk, rots, seed=1)
+    plan.bind(gk)
+    slots = np.stack([plan.pack_input(x[b]) for b in range(batch)])
+    for b in oracle_items[:2]:
+        assert np.array_equal(slots[b], o.fc_pack_input(n_o, n_i, x[b]))
+    cts = np.stack([ctx.encrypt(sk, slots[b], seed=b) for b in range(batch)])
+    got, cnt = H.gpu_he_fc(ctx, plan, cts, r, mask_seed=17)
+    G = plan.G
+    assert cnt == dict(perm=batch * (G - 1), decperm_in=0, hstperm_in=0, scmult=batch * G, add=batch * (G - 1))
+    wpoly = o.fc_encode_rowwise(W)
+    ksk = o.fc_keys(osk, n_o, n_i, seed=1)
+    for b in oracle_items:
+        mask = o.fc_mask_slots(n_o, n_i, r[b], 17, b)
+        want, ocnt = o.he_fc(wpoly, cts[b], ksk, mask)
+        assert np.array_equal(got[b], want), f"ciphertext mismatch at batch item {b}"
+        assert ocnt["perm"] == G - 1 and ocnt["scmult"] == G
+    return ctx, o, plan, sk, W, x, r, got
+
+
+@pytest.mark.parametrize("n,n_o,n_i,batch", [
+    (64, 4, 16, 3), (64, 8, 32, 2), (64, 16, 64, 2), (64, 3, 20, 1), (64, 1, 64, 1), (64, 32, 2, 1),
+    (256, 2, 256, 2), (256, 64, 128, 5), (1024, 8, 512, 3),
+])
+def test_he_fc_small_rings(n, n_o, n_i, batch):
+    par = small_params(n)
+    ctx, o, plan, sk, W, x, r, got = fc_case(par, n_o, n_i, batch, list(range(batch)), seed=n_o + n_i)
+    for b in range(batch):     # the identity of Sec. III-A(3): client share + server share = W x
+        share = plan.unpack_share(ctx.decrypt(sk, got[b]))
+        assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_matvec(W, x[b], par.p))
+
+
+def test_he_fc_config1_16x128():
+    par = wl.DEFAULT
+    ctx, o, plan, sk, W, x, r, got = fc_case(par, 16, 128, 1, [0])
+    share = plan.unpack_share(ctx.decrypt(sk, got[0]))
+    assert np.array_equal((share + r[0]) % np.uint64(par.p), plain_matvec(W, x[0], par.p))
+
+
+def test_he_fc_config2_128x1024_batch64():
+    par = wl.DEFAULT
+    ctx, o, plan, sk, W, x, r, got = fc_case(par, 128, 1024, 64, list(range(64)))
+    for b in (0, 31, 63):
+        share = plan.unpack_share(ctx.decrypt(sk, got[b]))
+        assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_matvec(W, x[b], par.p))
+
+
+def test_he_fc_config3_1000x2048_batch64_sampled():
+    """All 64 inputs run on the GPU; the oracle recomputes two of them in full (1023 Perms each) and
+    the decrypt identity is checked on every one."""
+    par = wl.DEFAULT
+    ctx, o, plan, sk, W, x, r, got = fc_case(par, 1000, 2048, 64, [0, 41])
+    for b in range(64):
+        share = plan.unpack_share(ctx.decrypt(sk, got[b]))
+        want = (W @ x[b]) % np.uint64(par.p)          # exact in uint64: 2048 products below 2^40
+        assert np.array_equal((share + r[b]) % np.uint64(par.p), want), b
+
+
+def conv_case(par, shape, batch, oracle_outputs, seed=0):
+    """oracle_outputs: list of (b, O) ciphertexts the oracle recomputes."""
+    H = harness()
+    ctx, o = both(par)
+    co, ci, kh, kw, uh, uw = shape
+    K, x, r = wl.conv_inputs(wl.ConvShape("t", co, ci, kh, kw, uh, uw, batch), p=par.p, seed=seed)
+    sk, osk = ctx.keygen(0), o.keygen(0)
+    plan = ctx.conv_plan(K, uh, uw)
+    geo = o.conv_geometry(*shape)
+    assert (plan.T, plan.cn, plan.nin, plan.nout, plan.ntap) == (geo["T"], geo["cn"], geo["nin"], geo["nout"], geo["ntap"])
+    gk = ctx.galois_keygen(sk, plan.rotations(), seed=8)
+    plan.bind(gk)
+    slots = np.stack([plan.pack_input(x[b]) for b in range(batch)])           # (batch, nin, n)
+    assert np.array_equal(slots[0], o.conv_pack_input(shape, x[0]))
+    cts = np.stack([[ctx.encrypt(sk, slots[b, I], seed=1000 * b + I) for I in range(plan.nin)] for b in range(batch)])
+    got, cnt = H.gpu_he_conv(ctx, plan, cts, r, mask_seed=3)
+    tk, gkk = o.conv_keys(osk, shape, seed=8)
+    cache = {}
+    for b, O in oracle_outputs:
+        if b not in cache:
+            cache = {b: (np.empty(plan.nin * plan.ntap * 2 * par.n, np.uint64), ctypes.c_int(0))}
+        xrot, ready = cache[b]
+        mask = o.conv_mask_slots(shape, r[b], 3, b, O)
+        want, _ = o.he_conv_block(shape, K, O, cts[b], tk, gkk, mask, xrot, ready)
+        assert np.array_equal(got[b, O], want), f"ciphertext mismatch at input {b}, output block {O}"
+    return ctx, o, plan, sk, K, x, r, got, cnt
+
+
+def plain_conv(K, x, p):
+    co, ci, kh, kw = K.shape
+    _, uh, uw = x.shape
+    out = np.zeros((co, uh, uw), dtype=object)
+    Ko, xo = K.astype(object), x.astype(object)
+    for dy in range(kh):
+        for dx in range(kw):
+            oy, ox = dy - kh // 2, dx - kw // 2
+            ys = slice(max(0, -oy), min(uh, uh - oy)); xs = slice(max(0, -ox), min(uw, uw - ox))
+            src = xo[:, ys.start + oy:ys.stop + oy, xs.start + ox:xs.stop + ox]
+            out[:, ys, xs] += np.einsum("oc,cyx->oyx", Ko[:, :, dy, dx], src)
+    return (out % p).astype(np.uint64)
+
+
+@pytest.mark.parametrize("n,p_limit,gb,shape,batch", [
+    (16, 1 << 7, 4, (4, 4, 3, 3, 2, 2), 2),
+    (64, 1 << 9, 4, (8, 8, 3, 3, 2, 4), 3),
+    (64, 1 << 9, 4, (5, 3, 3, 1, 3, 2), 1),
+    (64, 1 << 9, 4, (4, 12, 1, 1, 4, 4), 2),
+    (128, 1 << 9, 4, (6, 6, 5, 5, 4, 4), 1),
+    (512, 1 << 11, 8, (20, 12, 3, 3, 5, 6), 5),
+])
+def test_he_conv_small_rings(n, p_limit, gb, shape, batch):
+    par = small_params(n, p_limit=p_limit, gadget_bits=gb)
+    co, ci, kh, kw, uh, uw = shape
+    o = Oracle(par.n, par.q, par.p, par.gadget_bits)
+    nout = o.conv_geometry(*shape)["nout"]
+    ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, shape, batch, [(b, O) for b in range(batch) for O in range(nout)],
+                                                    seed=n)
+    cn, cip, cop = plan.cn, plan.nin * plan.cn, plan.nout * plan.cn
+    k2 = kh * kw
+    assert cnt == dict(perm=batch * cop * (cn - 1) // cn, decperm_in=batch * (cip // cn if k2 > 1 else 0),
+                       hstperm_in=batch * cip * (k2 - 1) // cn, scmult=batch * cip * cop * k2 // cn,
+                       add=batch * cop * (cip * k2 - 1) // cn)
+    for b in range(batch):
+        share = np.zeros((co, uh, uw), np.uint64)
+        for O in range(plan.nout):
+            plan.unpack_share(O, ctx.decrypt(sk, got[b, O]), share)
+        assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_conv(K, x[b], par.p))
+
+
+def test_he_conv_config4_sampled():
+    """16x16x128 input, 128 kernels 3x3, batch 16 on the GPU; the oracle recomputes three of the 256 output
+    ciphertexts in full (1152 ScMult + 7 Perm each, plus the 144 input rotations of their inputs)."""
+    par = wl.DEFAULT
+    s = wl.CONV_16x16_128_3x3
+    ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, s.tuple, s.batch, [(0, 0), (0, 15), (11, 6)])
+    # Table "Computation complexity of convolution", 16x16@128 with 3x3@128, per input
+    assert (cnt["decperm_in"] + cnt["perm"], cnt["hstperm_in"] + cnt["perm"], cnt["scmult"], cnt["add"]) == \
+           (16 * 128, 16 * 240, 16 * 18432, 16 * 18416)

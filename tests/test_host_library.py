@@ -1,0 +1,58 @@
+"""CPU-side checks of the HIP library: it loads, exports the whole C ABI, and its
+host-side (client) functions agree bit for bit with the oracle.  No GPU needed."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle.oracle import Oracle
+from paper_2105_01827_amd import binding, workloads as wl
+from tests.helpers import small_params
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+RNG = np.random.default_rng(7)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "gala.h")).read()
+    declared = set(re.findall(r"\b(gala_[A-Za-z0-9_]+)\s*\(", header))
+    lib = binding.load()
+    assert declared == set(binding.SIGNATURES), declared ^ set(binding.SIGNATURES)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_bad_parameters_are_rejected():
+    lib = binding.load()
+    for n, q, p, gb in [(100, wl.Q, wl.P, 20), (4096, wl.Q, wl.P, 20), (2048, wl.Q + 2, wl.P, 20),
+                        (2048, wl.Q, wl.P + 4096, 20), (2048, wl.Q, wl.P, 0), (2048, wl.Q, wl.P, 1),
+                        (2048, 12289, 12289, 4)]:
+        with pytest.raises(binding.GalaError) as e:
+            binding.Context(n, q, p, gb)
+        assert e.value.code == binding.GALA_EARG
+    assert lib.gala_ctx_create(None, None) == binding.GALA_EARG
+
+
+@pytest.mark.parametrize("n", [8, 64, 2048])
+def test_client_side_functions_match_the_oracle_bit_for_bit(n):
+    par = small_params(n) if n != 2048 else wl.DEFAULT
+    ctx = binding.Context(par.n, par.q, par.p, par.gadget_bits)
+    o = Oracle(par.n, par.q, par.p, par.gadget_bits)
+    assert ctx.ndigits == o.ndigits and ctx.delta == o.delta
+    assert ctx.gauss_cdf() == o.gauss_cdf()
+    sk = ctx.keygen(5)
+    osk = o.keygen(5)
+    assert np.array_equal(sk.export(), osk)
+    v = RNG.integers(0, par.p, n, dtype=np.uint64)
+    assert np.array_equal(ctx.encode(v), o.encode(v))
+    assert np.array_equal(ctx.decode(ctx.encode(v)), v)
+    assert np.array_equal(ctx.decode(v), o.decode(v))
+    ct = ctx.encrypt(sk, v, seed=123)
+    assert np.array_equal(ct, o.encrypt(osk, v, seed=123))
+    assert np.array_equal(ctx.decrypt(sk, ct), v)
+    # decrypting an oracle-made ciphertext after homomorphic work
+    w = RNG.integers(0, par.p, n, dtype=np.uint64)
+    prod = o.scmult(ct, o.encode_weight(w))
+    assert np.array_equal(ctx.decrypt(sk, prod), o.decrypt(osk, prod))
+    assert np.array_equal(ctx.decrypt(sk, prod), v * w % np.uint64(par.p))
