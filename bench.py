@@ -1,0 +1,153 @@
+#!/usr/bin/env python3
+"""Benchmark of the GALA linear-layer hot path on one MI355X.
+
+A "step" is one he_fc call over the whole batch of the workload (ScMult, Perm,
+Add and share generation for every input), with ciphertexts, encoded weights
+and Galois keys already resident on the device in internal form.  The reported
+value is homomorphic rotations (Perm) per second inside that layer; layers/s
+and inputs/s are given beside it.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# Integer-ALU roofline: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 32-bit integer lane-operations per second.
+# The multiply instructions the modular arithmetic is made of (v_mul_hi_u32, v_mad_u64_u32) were measured
+# at 0.82-0.94 of this rate with csrc/probe_int_mul.hip, so multiplies and adds are priced alike.
+ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+
+# 32-bit integer operations of the 64-bit modular primitives (multiplies, multiply-adds, adds with
+# carry and the selects of conditional subtractions; no address arithmetic, no moves):
+OPS_CONST_MUL = 16      # a*w mod q with precomputed quotient: 4+3+3 multiplies, 6 adds/subs -> [0,2q)
+OPS_LAZY_ADDSUB = 2     # 64-bit add or sub on lazy residues
+OPS_BUTTERFLY = OPS_CONST_MUL + 2 * OPS_LAZY_ADDSUB          # 20
+OPS_MAC128 = 8          # 64x64 product added into a 128-bit sum: 4 multiply-adds, 4 carry adds
+OPS_REDUCE128 = 2 * OPS_CONST_MUL + 4                        # 128-bit sum -> canonical residue
+
+
+def ops_per_fused_perm(n, logn, ndigits):
+    """Algorithmic integer operations of one ScMult + Perm + Add on one ciphertext (one 'fused unit')."""
+    butterflies = (1 + ndigits) * (n // 2) * logn            # one inverse and ndigits forward transforms
+    scmult_c1 = n * (OPS_MAC128 + OPS_REDUCE128)              # c1 (.) w before the inverse transform
+    digits = ndigits * n * 2                                  # shift and mask
+    key_mac = 2 * ndigits * n * OPS_MAC128                    # inner product with (b_j, a_j)
+    c0_mac = n * OPS_MAC128                                   # permuted c0 (.) w
+    accumulate = 2 * n * (OPS_REDUCE128 + OPS_LAZY_ADDSUB)    # reduce and Add into the running sum
+    return butterflies * OPS_BUTTERFLY + scmult_c1 + digits + key_mac + c0_mac + accumulate
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="fc_128x1024_b64", choices=["fc_128x1024_b64", "fc_1000x2048_b64"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=64, help="inputs the oracle is timed on")
+    ap.add_argument("--cpu-repeat", type=int, default=3, help="passes of the oracle over the sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2105_01827_amd import binding, workloads as wl
+    from tests import gpu_harness as H
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    par = wl.DEFAULT
+    shape = {"fc_128x1024_b64": wl.FC_128x1024, "fc_1000x2048_b64": wl.FC_1000x2048}[args.workload]
+    ctx = binding.Context(par.n, par.q, par.p, par.gadget_bits)
+    W, x, r = wl.fc_inputs(shape)
+    sk = ctx.keygen(0)
+    plan = ctx.fc_plan(W)
+    gk = ctx.galois_keygen(sk, plan.rotations(), seed=1)
+    plan.bind(gk)
+    batch = shape.batch
+    cts = np.stack([ctx.encrypt(sk, plan.pack_input(x[b]), seed=b) for b in range(batch)])
+    d_in = H.import_cts(ctx, cts)
+    d_out = H.dev_empty(batch * 2 * par.n)
+    d_r = H.to_dev(r)
+    ws_bytes = plan.workspace_bytes(batch)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        return plan.he_fc(d_in, batch, d_r, 17, d_out, ws, ws_bytes, stream=stream)
+
+    for _ in range(args.warmup):
+        cnt = step()
+    torch.cuda.synchronize()
+    ctx.profile_enable(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        cnt = step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernel_ms = ctx.profile_collect(args.steps)
+    ctx.profile_enable(0)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    perms_per_step = cnt["perm"]
+    rot_per_s = perms_per_step / (ms_per_step * 1e-3)
+    # roofline of the dominant kernel (rotate-and-accumulate): G fused units per input
+    units = batch * plan.G
+    unit_ops = ops_per_fused_perm(par.n, 11, ctx.ndigits)
+    ops = unit_ops * batch * (plan.G - 1)          # the g = 0 unit has no Perm and is not counted
+    kavg_ms = float(np.mean(kernel_ms)) if kernel_ms else float("nan")
+    achieved = ops / (kavg_ms * 1e-3) / 1e12
+    out = {
+        "metric": "HE rotations/sec and he_fc/he_conv layers/sec at n=2048; % of HBM/int roofline",
+        "value": rot_per_s,
+        "unit": "rotations/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u64",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "layer": "he_fc", "n": par.n, "n_o": shape.n_o, "n_i": shape.n_i,
+                   "batch": batch, "G": plan.G, "gadget_digits": ctx.ndigits},
+        "layers_per_s": 1e3 / ms_per_step,
+        "inputs_per_s": batch * 1e3 / ms_per_step,
+        "ops_per_step": cnt,
+        "roofline": {"bound": "alu", "kernel": "perm_accumulate_kernel", "achieved": achieved, "peak": ALU_PEAK_TOPS,
+                     "unit": "TOP/s (32-bit integer)", "frac": achieved / ALU_PEAK_TOPS, "traffic": None,
+                     "kernel_ms_avg": kavg_ms, "fused_units_per_launch": units, "int_ops_per_unit": unit_ops},
+    }
+    if not args.no_cpu_baseline:
+        from oracle.oracle import Oracle
+        o = Oracle(par.n, par.q, par.p, par.gadget_bits)
+        sample = min(args.cpu_sample, batch)
+        osk = o.keygen(0)
+        wpoly = o.fc_encode_rowwise(W)
+        ksk = o.fc_keys(osk, shape.n_o, shape.n_i, seed=1)
+        c0 = time.perf_counter()
+        for _ in range(args.cpu_repeat):
+            outs, ocnt = o.he_fc_batch(wpoly, shape.n_o, shape.n_i, cts[:sample], ksk, r[:sample], 17)
+        c1 = time.perf_counter()
+        got = H.export_cts(ctx, d_out, batch)
+        assert np.array_equal(got[:sample], outs), "HIP result differs from the oracle"
+        out["cpu_baseline"] = {"value": args.cpu_repeat * ocnt["perm"] / (c1 - c0), "unit": "rotations/s", "cores": o.max_threads(),
+                               "kind": "oracle",
+                               "sample": f"{sample} of the {batch} inputs of {args.workload}, {args.cpu_repeat} passes "
+                                         f"(he_fc_batch: {ocnt['perm']} Perm, {ocnt['scmult']} ScMult per pass), "
+                                         f"{c1 - c0:.1f} s wall"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

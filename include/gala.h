@@ -89,6 +89,16 @@ uint64_t gala_ctx_delta(const gala_ctx *ctx);
 /* The 38 thresholds floor(2^64 * P[X <= -19+i]) of the error sampler (host). */
 const uint64_t *gala_gauss_cdf(void);
 
+/* Measurement aid.  After gala_profile_enable(ctx, capacity) the next `capacity`
+ * launches of the rotate-and-accumulate kernel (the Perm kernel inside
+ * gala_rotate, gala_he_fc and gala_he_conv) are bracketed by HIP events on the
+ * call's stream; gala_profile_collect waits for them, writes the elapsed
+ * milliseconds of each launch (host array) and re-arms the events.
+ * capacity = 0 switches it off.  Creates / destroys HIP events, so call it
+ * outside timed regions. */
+int gala_profile_enable(gala_ctx *ctx, int capacity);
+int gala_profile_collect(gala_ctx *ctx, float *ms, int capacity, int *count);
+
 /* ---- keys (client side, host; Sec. II-C(1)) ------------------------------- */
 /* Ternary secret drawn from the seeded generator. */
 int gala_keygen(const gala_ctx *ctx, uint64_t seed, gala_sk **out);

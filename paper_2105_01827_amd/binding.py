@@ -51,6 +51,8 @@ SIGNATURES = {
     "gala_ctx_ndigits": (_I, [_VP]),
     "gala_ctx_delta": (C.c_uint64, [_VP]),
     "gala_gauss_cdf": (C.POINTER(C.c_uint64), []),
+    "gala_profile_enable": (_I, [_VP, _I]),
+    "gala_profile_collect": (_I, [_VP, C.POINTER(C.c_float), _I, C.POINTER(_I)]),
     "gala_keygen": (_I, [_VP, C.c_uint64, C.POINTER(_VP)]),
     "gala_sk_destroy": (None, [_VP]),
     "gala_sk_export": (_I, [_VP, _VP, _U64P]),
@@ -154,6 +156,14 @@ class Context:
     def gauss_cdf(self):
         ptr = self.lib.gala_gauss_cdf()
         return [int(ptr[i]) for i in range(38)]
+
+    def profile_enable(self, capacity):
+        _check(self.lib.gala_profile_enable(self.h, capacity), "gala_profile_enable")
+
+    def profile_collect(self, capacity):
+        ms = (C.c_float * max(1, capacity))(); n = C.c_int()
+        _check(self.lib.gala_profile_collect(self.h, ms, capacity, C.byref(n)), "gala_profile_collect")
+        return [float(ms[i]) for i in range(n.value)]
 
     # ---- client side (host)
     def keygen(self, seed):

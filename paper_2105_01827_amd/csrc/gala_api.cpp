@@ -34,6 +34,34 @@ size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 }  // namespace
 
+// ---------------------------------------------------------------------------
+// measurement aid: HIP events around every rotate-and-accumulate launch
+// ---------------------------------------------------------------------------
+extern "C" int gala_profile_enable(gala_ctx *c, int capacity) {
+    if (!c || capacity < 0) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    for (void *e : c->prof_events) (void)hipEventDestroy((hipEvent_t)e);
+    c->prof_events.clear();
+    c->prof_used = 0;
+    for (int i = 0; i < 2 * capacity; ++i) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return GALA_EHIP;
+        c->prof_events.push_back((void *)e);
+    }
+    return GALA_OK;
+}
+extern "C" int gala_profile_collect(gala_ctx *c, float *ms, int capacity, int *count) {
+    if (!c || !ms || !count) return GALA_EARG;
+    const int n = std::min(capacity, c->prof_used);
+    for (int i = 0; i < n; ++i) {
+        hipEvent_t a = (hipEvent_t)c->prof_events[2 * i], b = (hipEvent_t)c->prof_events[2 * i + 1];
+        if (hipEventSynchronize(b) != hipSuccess || hipEventElapsedTime(&ms[i], a, b) != hipSuccess) return GALA_EHIP;
+    }
+    *count = n;
+    c->prof_used = 0;
+    return GALA_OK;
+}
+
 extern "C" int gala_ct_import(const gala_ctx *c, void *stream, const uint64_t *src, int count, uint64_t *dst) {
     if (!c || !src || !dst || count < 0) return GALA_EARG;
     if (!c->has_device) return GALA_EHIP;

@@ -307,6 +307,7 @@ extern "C" int gala_ctx_create(const gala_params *par, gala_ctx **out) {
 extern "C" void gala_ctx_destroy(gala_ctx *c) {
     if (!c) return;
     if (c->has_device) {
+        for (void *e : c->prof_events) (void)hipEventDestroy((hipEvent_t)e);
         hipFree(c->d_tables);
         hipFree(c->d_slot_to_idx);
     }

@@ -66,6 +66,9 @@ struct gala_ctx {
     gala::u64 *d_tables = nullptr;     // 8*n words: tw,tws,itw,itws for q then for p
     int *d_slot_to_idx = nullptr;
     gala::NttDev dev_q{}, dev_p{};
+    // measurement aid: event pairs recorded around rotate-and-accumulate launches
+    mutable std::vector<void *> prof_events;   // 2*capacity hipEvent_t
+    mutable int prof_used = 0;
 };
 
 struct gala_sk {

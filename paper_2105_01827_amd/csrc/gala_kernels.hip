@@ -388,12 +388,15 @@ int launch_perm_accumulate(const gala_ctx *c, void *stream, const PermJob &job) 
     hipStream_t st = (hipStream_t)stream;
     const size_t lds = sizeof(u64) * c->n;
     const dim3 grid((unsigned)(job.items * job.nchunks));
+    const bool timed = (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
+    if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used], st);
     if (block_threads(c->n) == 256)
         hipLaunchKernelGGL(perm_accumulate_kernel<256>, grid, dim3(256), lds, st, job, c->dev_q, c->n, c->logn,
                            c->gadget_bits, c->ndigits);
     else
         hipLaunchKernelGGL(perm_accumulate_kernel<64>, grid, dim3(64), lds, st, job, c->dev_q, c->n, c->logn,
                            c->gadget_bits, c->ndigits);
+    if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used++ + 1], st);
     return last_error();
 }
 int launch_finalize(const gala_ctx *c, void *stream, const FinalizeJob &job) {

@@ -9,6 +9,7 @@ def small_params(n, p_limit=None, p=None, gadget_bits=20):
     """A test parameter set for ring degree n: p = 1 mod 2n, 60-bit q = 1 mod 2n*p."""
     if p is None:
         p = wl.find_prime_below(p_limit or (1 << 20), 2 * n)
+    assert p > 2 * n, "no prime p = 1 mod 2n below the limit"
     q = wl.find_prime_below(1 << 60, 2 * n * p)
     return wl.Params(n=n, q=q, p=p, gadget_bits=gadget_bits)
 

@@ -211,7 +211,7 @@ def plain_conv(K, x, p):
     (64, 1 << 9, 4, (5, 3, 3, 1, 3, 2), 1),
     (64, 1 << 9, 4, (4, 12, 1, 1, 4, 4), 2),
     (128, 1 << 9, 4, (6, 6, 5, 5, 4, 4), 1),
-    (512, 1 << 11, 8, (20, 12, 3, 3, 5, 6), 5),
+    (512, 1 << 14, 8, (20, 12, 3, 3, 5, 6), 5),
 ])
 def test_he_conv_small_rings(n, p_limit, gb, shape, batch):
     par = small_params(n, p_limit=p_limit, gadget_bits=gb)
