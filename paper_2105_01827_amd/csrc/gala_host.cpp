@@ -288,7 +288,12 @@ extern "C" int gala_ctx_create(const gala_params *par, gala_ctx **out) {
         std::copy(hs[k]->itw.begin(), hs[k]->itw.end(), base + 2 * n);
         std::copy(hs[k]->itws.begin(), hs[k]->itws.end(), base + 3 * n);
     }
-    if (upload(&c->d_tables, host) || upload(&c->d_slot_to_idx, c->slot_to_idx)) {
+    std::vector<u64> pairs(4 * (size_t)n);
+    for (int k = 0; k < n; ++k) {
+        pairs[2 * k] = c->ntt_q.tw[k];               pairs[2 * k + 1] = c->ntt_q.tws[k];
+        pairs[2 * (n + k)] = c->ntt_q.itw[k];        pairs[2 * (n + k) + 1] = c->ntt_q.itws[k];
+    }
+    if (upload(&c->d_tables, host) || upload(&c->d_slot_to_idx, c->slot_to_idx) || upload(&c->d_tw2, pairs)) {
         gala_ctx_destroy(c);
         return GALA_EHIP;
     }
@@ -310,6 +315,7 @@ extern "C" void gala_ctx_destroy(gala_ctx *c) {
         for (void *e : c->prof_events) (void)hipEventDestroy((hipEvent_t)e);
         hipFree(c->d_tables);
         hipFree(c->d_slot_to_idx);
+        hipFree(c->d_tw2);
     }
     delete c;
 }

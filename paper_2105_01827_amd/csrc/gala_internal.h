@@ -65,6 +65,7 @@ struct gala_ctx {
     bool has_device = false;           // tables uploaded; false on a host without a HIP device
     gala::u64 *d_tables = nullptr;     // 8*n words: tw,tws,itw,itws for q then for p
     int *d_slot_to_idx = nullptr;
+    gala::u64 *d_tw2 = nullptr;        // mod q: n (w, companion) pairs of the forward table, then n of the inverse
     gala::NttDev dev_q{}, dev_p{};
     // measurement aid: event pairs recorded around rotate-and-accumulate launches
     mutable std::vector<void *> prof_events;   // 2*capacity hipEvent_t
@@ -155,6 +156,8 @@ struct PermJob {
     u64 *partial;            // items x nchunks x 2n
 };
 int launch_perm_accumulate(const gala_ctx *ctx, void *stream, const PermJob &job);
+// the n = 2048, q < 2^60 specialisation (gala_perm2048.hip); launch_perm_accumulate dispatches to it
+int launch_perm_accumulate_2048(const gala_ctx *ctx, void *stream, const PermJob &job);
 
 // out[item] = sum_chunk partial[item][chunk] - mask(item) ; mask built from r and the generator.
 struct FinalizeJob {

@@ -5,6 +5,8 @@
 // 2^61; there is no floating point on this path.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "gala_internal.h"
 
 namespace gala {
@@ -390,6 +392,12 @@ int launch_perm_accumulate(const gala_ctx *c, void *stream, const PermJob &job) 
     const dim3 grid((unsigned)(job.items * job.nchunks));
     const bool timed = (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
     if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used], st);
+    static const bool generic_only = std::getenv("GALA_GENERIC_PERM") != nullptr;
+    if (c->n == 2048 && c->q < (1ull << 60) && !generic_only) {
+        const int rc = launch_perm_accumulate_2048(c, stream, job);
+        if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used++ + 1], st);
+        return rc;
+    }
     if (block_threads(c->n) == 256)
         hipLaunchKernelGGL(perm_accumulate_kernel<256>, grid, dim3(256), lds, st, job, c->dev_q, c->n, c->logn,
                            c->gadget_bits, c->ndigits);
