@@ -88,6 +88,7 @@ extern "C" int gala_rotate(const gala_ctx *c, void *stream, const gala_gk *gk, c
     job.G = 1; job.items = count; job.nchunks = 1;
     job.partial = ct_out;
     job.keys = gk->d_keys;
+    job.keys2 = gk->d_keys2;
     if (g == 1) {
         job.gal = gk->d_one; job.key_idx = gk->d_one;
     } else {
@@ -122,6 +123,8 @@ extern "C" int gala_he_fc(const gala_ctx *c, void *stream, const gala_fc_plan *p
     job.w = pl->d_w;
     job.gal = pl->d_gal; job.key_idx = pl->d_key_idx;
     job.keys = pl->bound ? pl->bound->d_keys : nullptr;
+    job.keys2 = pl->bound ? pl->bound->d_keys2 : nullptr;
+    job.w2 = pl->d_w2;
     job.G = pl->G; job.items = batch; job.nchunks = chunks;
     job.partial = (u64 *)workspace;
     if (launch_perm_accumulate(c, stream, job)) return GALA_EHIP;
@@ -196,6 +199,7 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
     job.w = nullptr;
     job.gal = pl->d_grp_gal; job.key_idx = pl->d_grp_key;
     job.keys = keys;
+    job.keys2 = pl->bound ? pl->bound->d_keys2 : nullptr;
     job.G = pl->cn; job.items = batch * pl->nout; job.nchunks = ws.chunks;
     job.partial = partial;
     if (launch_perm_accumulate(c, stream, job)) return GALA_EHIP;

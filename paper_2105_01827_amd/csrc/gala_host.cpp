@@ -288,12 +288,25 @@ extern "C" int gala_ctx_create(const gala_params *par, gala_ctx **out) {
         std::copy(hs[k]->itw.begin(), hs[k]->itw.end(), base + 2 * n);
         std::copy(hs[k]->itws.begin(), hs[k]->itws.end(), base + 3 * n);
     }
-    std::vector<u64> pairs(4 * (size_t)n);
-    for (int k = 0; k < n; ++k) {
-        pairs[2 * k] = c->ntt_q.tw[k];               pairs[2 * k + 1] = c->ntt_q.tws[k];
-        pairs[2 * (n + k)] = c->ntt_q.itw[k];        pairs[2 * (n + k) + 1] = c->ntt_q.itws[k];
+    // pass-major twiddle blocks for the n = 2048 kernel: block T (1 <= T < 512) holds the pairs
+    // tw[T], tw[2T], tw[2T+1], tw[4T..4T+3] and one unused pair; forward table then inverse table
+    std::vector<u64> pairs;
+    if (n == 2048) {
+        pairs.assign(2 * 2 * 8 * (size_t)512, 0);
+        for (int inv = 0; inv < 2; ++inv) {
+            const std::vector<u64> &w = inv ? c->ntt_q.itw : c->ntt_q.tw, &ws = inv ? c->ntt_q.itws : c->ntt_q.tws;
+            u64 *base = pairs.data() + (size_t)inv * 2 * 8 * 512;
+            for (int T = 1; T < 512; ++T) {
+                const int idx[7] = {T, 2 * T, 2 * T + 1, 4 * T, 4 * T + 1, 4 * T + 2, 4 * T + 3};
+                for (int e = 0; e < 7; ++e) {
+                    base[2 * (8 * T + e)] = w[idx[e]];
+                    base[2 * (8 * T + e) + 1] = ws[idx[e]];
+                }
+            }
+        }
     }
-    if (upload(&c->d_tables, host) || upload(&c->d_slot_to_idx, c->slot_to_idx) || upload(&c->d_tw2, pairs)) {
+    if (upload(&c->d_tables, host) || upload(&c->d_slot_to_idx, c->slot_to_idx) ||
+        upload(&c->d_tw2, pairs)) {
         gala_ctx_destroy(c);
         return GALA_EHIP;
     }
@@ -402,6 +415,10 @@ extern "C" int gala_galois_keygen(gala_ctx *c, const gala_sk *sk, const gala_rot
     // to the evaluation domain, then b_hat = t_hat - a_hat * s_hat in place
     if (!rc && launch_ntt(c, nullptr, gk->d_keys, gk->d_keys, nkeys * L * 2, 0)) rc = GALA_EHIP;
     if (!rc && launch_key_finish(c, nullptr, gk->d_keys, d_s, nkeys * L)) rc = GALA_EHIP;
+    if (!rc && uses_fast_perm(c)) {
+        if (hipMalloc((void **)&gk->d_keys2, 2 * nkeys * kw * sizeof(u64)) != hipSuccess) rc = GALA_ENOMEM;
+        if (!rc && launch_pair_pack(c, nullptr, gk->d_keys, gk->d_keys2, nkeys * kw)) rc = GALA_EHIP;
+    }
     if (!rc && hipDeviceSynchronize() != hipSuccess) rc = GALA_EHIP;
     hipFree(d_s);
     if (rc) { gala_gk_destroy(gk); *out = nullptr; }
@@ -409,7 +426,7 @@ extern "C" int gala_galois_keygen(gala_ctx *c, const gala_sk *sk, const gala_rot
 }
 extern "C" void gala_gk_destroy(gala_gk *gk) {
     if (!gk) return;
-    hipFree(gk->d_keys); hipFree(gk->d_elements); hipFree(gk->d_iota); hipFree(gk->d_one);
+    hipFree(gk->d_keys); hipFree(gk->d_keys2); hipFree(gk->d_elements); hipFree(gk->d_iota); hipFree(gk->d_one);
     delete gk;
 }
 extern "C" int gala_gk_export(gala_ctx *c, const gala_gk *gk, gala_rot rot, uint64_t *ksk_host) {
@@ -555,6 +572,11 @@ extern "C" int gala_fc_plan_create(gala_ctx *c, const uint64_t *W, int n_o, int 
     for (int t = n_o; t <= n; ++t) mh.row_ptr[t] = pos;
     std::vector<int> key_idx(G, -1);
     int rc = upload(&pl->d_w, w);
+    if (!rc && uses_fast_perm(c)) {
+        if (hipMalloc((void **)&pl->d_w2, 2 * w.size() * sizeof(u64)) != hipSuccess) rc = GALA_ENOMEM;
+        if (!rc && (launch_pair_pack(c, nullptr, pl->d_w, pl->d_w2, w.size()) || hipDeviceSynchronize() != hipSuccess))
+            rc = GALA_EHIP;
+    }
     if (!rc) rc = upload(&pl->d_gal, pl->gal);
     if (!rc) rc = upload(&pl->d_key_idx, key_idx);
     if (!rc) rc = upload_mask_layout(mh, &pl->mask_d);
@@ -564,7 +586,7 @@ extern "C" int gala_fc_plan_create(gala_ctx *c, const uint64_t *W, int n_o, int 
 }
 extern "C" void gala_fc_plan_destroy(gala_fc_plan *pl) {
     if (!pl) return;
-    hipFree(pl->d_w); hipFree(pl->d_gal); hipFree(pl->d_key_idx);
+    hipFree(pl->d_w); hipFree(pl->d_w2); hipFree(pl->d_gal); hipFree(pl->d_key_idx);
     free_mask_layout(&pl->mask_d);
     delete pl;
 }

@@ -65,7 +65,7 @@ struct gala_ctx {
     bool has_device = false;           // tables uploaded; false on a host without a HIP device
     gala::u64 *d_tables = nullptr;     // 8*n words: tw,tws,itw,itws for q then for p
     int *d_slot_to_idx = nullptr;
-    gala::u64 *d_tw2 = nullptr;        // mod q: n (w, companion) pairs of the forward table, then n of the inverse
+    gala::u64 *d_tw2 = nullptr;        // n = 2048 only: pass-major (w, companion) twiddle blocks, forward then inverse
     gala::NttDev dev_q{}, dev_p{};
     // measurement aid: event pairs recorded around rotate-and-accumulate launches
     mutable std::vector<void *> prof_events;   // 2*capacity hipEvent_t
@@ -82,6 +82,7 @@ struct gala_gk {
     std::map<int, int> index_of;       // Galois element -> key index
     std::vector<int> elements;
     gala::u64 *d_keys = nullptr;       // nkeys x ndigits x 2 x n, evaluation domain (b then a)
+    gala::u64 *d_keys2 = nullptr;      // same keys as (value, companion) pairs for the n = 2048 kernel, or null
     int *d_elements = nullptr;         // nkeys Galois elements, device
     int *d_iota = nullptr;             // 0,1,2,... (key index of element k is k), device
     int *d_one = nullptr;              // the single value 1 (Galois element of the identity), device
@@ -110,6 +111,7 @@ struct gala_fc_plan {
     std::vector<int> slot_row;         // padded row of each slot, -1 if it carries no weight
     std::vector<int> gal;              // Galois element of rotation g (gal[0] = 1)
     gala::u64 *d_w = nullptr;          // G x n encoded weights, evaluation domain
+    gala::u64 *d_w2 = nullptr;         // the same as (value, companion) pairs for the n = 2048 kernel, or null
     int *d_gal = nullptr;              // G Galois elements
     int *d_key_idx = nullptr;          // G key indices (valid once bound)
     const gala_gk *bound = nullptr;
@@ -141,6 +143,11 @@ int launch_ntt(const gala_ctx *ctx, void *stream, const u64 *src, u64 *dst, size
 // key generation helper on `npairs` consecutive (t_hat, a_hat) pairs of n-word evaluation-domain
 // polynomials: t_hat <- t_hat - a_hat * s_hat in place (s_hat shared by all pairs).
 int launch_key_finish(const gala_ctx *ctx, void *stream, u64 *pairs, const u64 *s_hat, size_t npairs);
+// dst[i] = (src[i], floor(src[i] * 2^64 / q)) for i < count: constants with the precomputed quotient
+// that the n = 2048 kernel multiplies by.
+int launch_pair_pack(const gala_ctx *ctx, void *stream, const u64 *src, u64 *dst, size_t count);
+// whether launch_perm_accumulate will use the n = 2048 kernel for this context
+bool uses_fast_perm(const gala_ctx *ctx);
 
 // One job of the rotate-and-accumulate kernel.  For item in [0,items), chunk in [0,nchunks):
 //   partial[item][chunk] = sum over g in the chunk of Perm_{gal[g]}( in[item][g] (.) w[g] )
@@ -152,6 +159,7 @@ struct PermJob {
     const u64 *w;
     const int *gal, *key_idx;
     const u64 *keys;
+    const u64 *w2, *keys2;   // (value, companion) pair images of w and keys (n = 2048 kernel only)
     int G, items, nchunks;
     u64 *partial;            // items x nchunks x 2n
 };

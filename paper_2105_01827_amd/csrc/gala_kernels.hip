@@ -87,6 +87,22 @@ __global__ void key_finish_kernel(u64 *pairs, const u64 *s_hat, int n, size_t to
     t[i] = sub_mod(t[i], mul_mod(a[i], s_hat[i], mod), mod.q);
 }
 
+// companion of a constant w < q: floor(w * 2^64 / q), by 64 steps of binary long division
+__global__ void pair_pack_kernel(const u64 *src, u64 *dst, size_t count, u64 q) {
+    const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= count) return;
+    const u64 w = src[id];
+    u64 rem = w, quot = 0;
+    for (int b = 0; b < 64; ++b) {
+        rem <<= 1;                       // rem < q < 2^61, no overflow
+        const bool ge = rem >= q;
+        rem -= ge ? q : 0;
+        quot = (quot << 1) | (ge ? 1 : 0);
+    }
+    dst[2 * id] = w;
+    dst[2 * id + 1] = quot;
+}
+
 // ---------------------------------------------------------------------------
 // rotate-and-accumulate
 // ---------------------------------------------------------------------------
@@ -385,6 +401,16 @@ int launch_key_finish(const gala_ctx *c, void *stream, u64 *pairs, const u64 *s_
                        s_hat, c->n, total, c->dev_q.mod);
     return last_error();
 }
+int launch_pair_pack(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, size_t count) {
+    if (!count) return 0;
+    hipLaunchKernelGGL(pair_pack_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, (hipStream_t)stream, src,
+                       dst, count, c->q);
+    return last_error();
+}
+bool uses_fast_perm(const gala_ctx *c) {
+    static const bool generic_only = std::getenv("GALA_GENERIC_PERM") != nullptr;
+    return c->n == 2048 && c->q < (1ull << 60) && !generic_only;
+}
 int launch_perm_accumulate(const gala_ctx *c, void *stream, const PermJob &job) {
     if (job.items <= 0 || job.nchunks <= 0) return 0;
     hipStream_t st = (hipStream_t)stream;
@@ -392,8 +418,7 @@ int launch_perm_accumulate(const gala_ctx *c, void *stream, const PermJob &job) 
     const dim3 grid((unsigned)(job.items * job.nchunks));
     const bool timed = (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
     if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used], st);
-    static const bool generic_only = std::getenv("GALA_GENERIC_PERM") != nullptr;
-    if (c->n == 2048 && c->q < (1ull << 60) && !generic_only) {
+    if (uses_fast_perm(c)) {
         const int rc = launch_perm_accumulate_2048(c, stream, job);
         if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used++ + 1], st);
         return rc;

@@ -33,107 +33,182 @@ __device__ __forceinline__ int galois_index11(int i, int gal) {
     return bitrev11((e - 1) >> 1);
 }
 
+// ---- 64-bit modular primitives shaped for the gfx950 VALU ---------------------------------------
+// v_mad_u64_u32 (32x32 + 64 -> 64 with carry-out) issues at the full VALU rate, so everything is built
+// from it.  The compiler's own lowering of 64x64 products spends a quarter of its instructions on
+// register moves; the sequences below are written out so that it cannot re-associate them.
+__device__ __forceinline__ u64 mad_u64(u32 a, u32 b, u64 c) {
+    u64 r, carry;
+    asm("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(r), "=s"(carry) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ __forceinline__ u64 mul_u64(u32 a, u32 b) {
+    u64 r, carry;
+    asm("v_mad_u64_u32 %0, %1, %2, %3, 0" : "=v"(r), "=s"(carry) : "v"(a), "v"(b));
+    return r;
+}
+// high 64 bits of y*s in 6 instructions: with A1 = hi32(y0 s0), B = y0 s1 + A1 and
+// S = y1 s0 + B (65 bits: C plus the carry-out), the result is y1 s1 + floor(S / 2^32).
+__device__ __forceinline__ u64 mulhi64_dev(u64 y, u64 s) {
+    const u32 y0 = (u32)y, y1 = (u32)(y >> 32), s0 = (u32)s, s1 = (u32)(s >> 32);
+    const u64 B = mad_u64(y0, s1, (u64)__umulhi(y0, s0));
+    u64 C, carry;
+    asm("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(C), "=s"(carry) : "v"(y1), "v"(s0), "v"(B));
+    u32 top;
+    asm("v_cndmask_b32_e64 %0, 0, 1, %1" : "=v"(top) : "s"(carry));
+    return mad_u64(y1, s1, ((u64)top << 32) | (u32)(C >> 32));
+}
+// negated modulus split in two VGPR words, set up once per kernel
+struct NegQ { u32 lo, hi; };
+// y*w mod q up to one extra q (a value in [0,2q)) for any 64-bit y, w a constant with companion ws:
+// y*w - h*q = y*w + h*(-q) mod 2^64 as one chain for the low word and one for the high word.
+__device__ __forceinline__ u64 mul_const(u64 y, u64 w, u64 ws, NegQ nq) {
+    const u64 h = mulhi64_dev(y, ws);
+    const u32 y0 = (u32)y, y1 = (u32)(y >> 32), w0 = (u32)w, w1 = (u32)(w >> 32);
+    const u32 h0 = (u32)h, h1 = (u32)(h >> 32);
+    u64 u = mul_u64(y0, w1);          // only the low word of this chain is used
+    u = mad_u64(y1, w0, u);
+    u = mad_u64(h0, nq.hi, u);
+    u = mad_u64(h1, nq.lo, u);
+    u64 t = mul_u64(y0, w0);
+    t = mad_u64(h0, nq.lo, t);
+    u32 hi;
+    asm("v_add_u32 %0, %1, %2" : "=v"(hi) : "v"((u32)(t >> 32)), "v"((u32)u));
+    return ((u64)hi << 32) | (u32)t;
+}
+// x - c if x >= c else x, in 4 instructions (the borrow of the subtraction selects);
+// needs x - c < 2^63 when x >= c, which holds for every use here (x < 2c, c <= 8q < 2^63).
+__device__ __forceinline__ u64 csub_dev(u64 x, u64 c) {
+    u32 r0, r1;
+    asm("v_sub_co_u32 %0, vcc, %2, %4\n\tv_subb_co_u32 %1, vcc, %3, %5, vcc\n\t"
+        "v_cndmask_b32 %0, %0, %2, vcc\n\tv_cndmask_b32 %1, %1, %3, vcc"
+        : "=&v"(r0), "=&v"(r1)
+        : "v"((u32)x), "v"((u32)(x >> 32)), "v"((u32)c), "v"((u32)(c >> 32))
+        : "vcc");
+    return ((u64)r1 << 32) | r0;
+}
+
 // x,y -> x + w*y, x - w*y + 2q  without any correction (bound grows by 2q per stage)
-__device__ __forceinline__ void bf_fwd(u64 &x, u64 &y, const ulonglong2 t, u64 q, u64 q2) {
-    const u64 v = mul_shoup_lazy(y, t.x, t.y, q);
+__device__ __forceinline__ void bf_fwd(u64 &x, u64 &y, const ulonglong2 t, NegQ nq, u64 q2) {
+    const u64 v = mul_const(y, t.x, t.y, nq);
     y = x - v + q2;
     x = x + v;
 }
 // x,y in [0,2q) -> x + y (below 2q), (x - y)*w (below 2q)
-__device__ __forceinline__ void bf_inv(u64 &x, u64 &y, const ulonglong2 t, u64 q, u64 q2) {
+__device__ __forceinline__ void bf_inv(u64 &x, u64 &y, const ulonglong2 t, NegQ nq, u64 q2) {
     const u64 s = x + y, d = x - y + q2;
-    x = csub(s, q2);
-    y = mul_shoup_lazy(d, t.x, t.y, q);
+    x = csub_dev(s, q2);
+    y = mul_const(d, t.x, t.y, nq);
 }
 
-// Radix-8 forward pass on the three index bits held in the register number
-// (bit 2 of k first).  T = (n >> (B+3)) + (index >> (B+3)) selects the twiddles:
-// tw[T], tw[2T..2T+1], tw[4T..4T+3].  FIRST = false skips the first stage (the
-// last pass of the transform has only two stages).
+// Twiddles are stored pass-major: the seven constants one thread needs for a radix-8 pass sit in
+// one 128-byte block {t1, t2a, t2b, t4[0..3], unused}; block T of the natural table order
+// tw[T], tw[2T], tw[2T+1], tw[4T..4T+3]  (T = (n >> (B+3)) + (index >> (B+3)) for a pass on bits B..B+2).
+// Block numbering: T itself (1 <= T < 512), so the table has 512 blocks of 8 pairs.
+//
+// Radix-8 forward pass on the three index bits held in the register number (bit 2 of k first).
+// FIRST = false skips the first stage (the last pass of the transform has only two stages).
 template <bool FIRST, bool CORRECT>
-__device__ __forceinline__ void fwd_pass(u64 (&a)[8], const ulonglong2 *__restrict__ tw, int T, u64 q, u64 q2) {
+__device__ __forceinline__ void fwd_pass(u64 (&a)[8], const ulonglong2 *__restrict__ blk, NegQ q, u64 q2) {
     if (FIRST) {
-        const ulonglong2 t1 = tw[T];
+        const ulonglong2 t1 = blk[0];
 #pragma unroll
         for (int k = 0; k < 4; ++k) bf_fwd(a[k], a[k + 4], t1, q, q2);
     }
     if (CORRECT) {   // seven stages done: everything is below 15q, bring it below 8q
         const u64 q8 = 4 * q2;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) a[k] = csub(a[k], q8);
+        for (int k = 0; k < 8; ++k) a[k] = csub_dev(a[k], q8);
     }
-    const ulonglong2 t2a = tw[2 * T], t2b = tw[2 * T + 1];
+    const ulonglong2 t2a = blk[1], t2b = blk[2];
     bf_fwd(a[0], a[2], t2a, q, q2);
     bf_fwd(a[1], a[3], t2a, q, q2);
     bf_fwd(a[4], a[6], t2b, q, q2);
     bf_fwd(a[5], a[7], t2b, q, q2);
-    const ulonglong2 *t4 = tw + 4 * T;
-    bf_fwd(a[0], a[1], t4[0], q, q2);
-    bf_fwd(a[2], a[3], t4[1], q, q2);
-    bf_fwd(a[4], a[5], t4[2], q, q2);
-    bf_fwd(a[6], a[7], t4[3], q, q2);
+    bf_fwd(a[0], a[1], blk[3], q, q2);
+    bf_fwd(a[2], a[3], blk[4], q, q2);
+    bf_fwd(a[4], a[5], blk[5], q, q2);
+    bf_fwd(a[6], a[7], blk[6], q, q2);
 }
-// Radix-8 inverse pass (bit 0 of k first), same twiddle addressing on the inverse table.
-__device__ __forceinline__ void inv_pass(u64 (&a)[8], const ulonglong2 *__restrict__ tw, int T, u64 q, u64 q2) {
-    const ulonglong2 *t4 = tw + 4 * T;
-    bf_inv(a[0], a[1], t4[0], q, q2);
-    bf_inv(a[2], a[3], t4[1], q, q2);
-    bf_inv(a[4], a[5], t4[2], q, q2);
-    bf_inv(a[6], a[7], t4[3], q, q2);
-    const ulonglong2 t2a = tw[2 * T], t2b = tw[2 * T + 1];
+// Radix-8 inverse pass (bit 0 of k first), same block layout on the inverse table.
+__device__ __forceinline__ void inv_pass(u64 (&a)[8], const ulonglong2 *__restrict__ blk, NegQ q, u64 q2) {
+    bf_inv(a[0], a[1], blk[3], q, q2);
+    bf_inv(a[2], a[3], blk[4], q, q2);
+    bf_inv(a[4], a[5], blk[5], q, q2);
+    bf_inv(a[6], a[7], blk[6], q, q2);
+    const ulonglong2 t2a = blk[1], t2b = blk[2];
     bf_inv(a[0], a[2], t2a, q, q2);
     bf_inv(a[1], a[3], t2a, q, q2);
     bf_inv(a[4], a[6], t2b, q, q2);
     bf_inv(a[5], a[7], t2b, q, q2);
-    const ulonglong2 t1 = tw[T];
+    const ulonglong2 t1 = blk[0];
 #pragma unroll
     for (int k = 0; k < 4; ++k) bf_inv(a[k], a[k + 4], t1, q, q2);
 }
 
-// store the 8 registers at index(k) = base | (k << shift), barrier, load index'(k) = base2 | (k << shift2)
+// Store the 8 registers at index(k) = base_out | (k << SH_OUT), barrier, load index(k) = base_in | (k << SH_IN).
+// The bases have zeros in the three bits the register number fills, so the padded address of
+// register k is pad(base) plus a compile-time offset.
+template <int SH>
+__device__ __forceinline__ constexpr int reg_offset(int k) { return (k << SH) + ((k << SH) >> 5); }
 template <int SH_OUT, int SH_IN>
 __device__ __forceinline__ void exchange(u64 (&a)[8], u64 *buf, int base_out, int base_in) {
+    u64 *po = buf + pad(base_out);
 #pragma unroll
-    for (int k = 0; k < 8; ++k) buf[pad(base_out | (k << SH_OUT))] = a[k];
+    for (int k = 0; k < 8; ++k) po[reg_offset<SH_OUT>(k)] = a[k];
     __syncthreads();
+    const u64 *pi = buf + pad(base_in);
 #pragma unroll
-    for (int k = 0; k < 8; ++k) a[k] = buf[pad(base_in | (k << SH_IN))];
+    for (int k = 0; k < 8; ++k) a[k] = pi[reg_offset<SH_IN>(k)];
 }
 
 struct Tables2048 {
-    const ulonglong2 *tw, *itw;   // (w, companion) pairs, forward and inverse
+    const ulonglong2 *tw, *itw;   // pass-major blocks of (w, companion) pairs, forward and inverse
     ulonglong2 ninv, itw1n;       // n^-1 and itw[1]*n^-1 with companions
     Modulus mod;
+    NegQ nq;                      // 2^64 - q
 };
+
+// The thread id goes through an empty asm so that the address arithmetic of a transform is redone
+// where it is used instead of being hoisted out of the rotation loop into long-lived registers.
+__device__ __forceinline__ int fresh(int tid) {
+    asm volatile("" : "+v"(tid));
+    return tid;
+}
 
 // Forward transform of the 8 registers (ownership t + 256k, values below q); the result is left in
 // LDS buffer `res` (natural index, padded), values below 16q.  LDS phases: other, res, other, res.
-__device__ __forceinline__ void forward_to_lds(u64 (&a)[8], u64 *res, u64 *other, const Tables2048 &T, int tid) {
-    const u64 q = T.mod.q, q2 = T.mod.q2;
-    fwd_pass<true, false>(a, T.tw, 1, q, q2);                                        // bits 8-10
+__device__ __forceinline__ void forward_to_lds(u64 (&a)[8], u64 *res, u64 *other, const Tables2048 &T, int tid_) {
+    const int tid = fresh(tid_);
+    const NegQ q = T.nq;
+    const u64 q2 = T.mod.q2;
+    fwd_pass<true, false>(a, T.tw + 8 * 1, q, q2);                                   // bits 8-10
     exchange<8, 5>(a, other, tid, ((tid >> 5) << 8) | (tid & 31));
-    fwd_pass<true, false>(a, T.tw, 8 + (tid >> 5), q, q2);                           // bits 5-7
+    fwd_pass<true, false>(a, T.tw + 8 * (8 + (tid >> 5)), q, q2);                    // bits 5-7
     exchange<5, 2>(a, res, ((tid >> 5) << 8) | (tid & 31), ((tid >> 2) << 5) | (tid & 3));
-    fwd_pass<true, true>(a, T.tw, 64 + (tid >> 2), q, q2);                           // bits 2-4
+    fwd_pass<true, true>(a, T.tw + 8 * (64 + (tid >> 2)), q, q2);                    // bits 2-4
     exchange<2, 0>(a, other, ((tid >> 2) << 5) | (tid & 3), tid << 3);
-    fwd_pass<false, false>(a, T.tw, 256 + tid, q, q2);                               // bits 0-1
+    fwd_pass<false, false>(a, T.tw + 8 * (256 + tid), q, q2);                        // bits 0-1
+    u64 *po = res + pad(tid << 3);
 #pragma unroll
-    for (int k = 0; k < 8; ++k) res[pad((tid << 3) | k)] = a[k];
+    for (int k = 0; k < 8; ++k) po[k] = a[k];
     __syncthreads();
 }
 
 // Inverse transform: registers hold index 8t + k (values below 2q) on entry and index t + 256k,
 // canonical, on return.
-__device__ __forceinline__ void inverse_in_regs(u64 (&a)[8], u64 *bufA, u64 *bufB, const Tables2048 &T, int tid) {
-    const u64 q = T.mod.q, q2 = T.mod.q2;
-    inv_pass(a, T.itw, 256 + tid, q, q2);                                            // bits 0-2
+__device__ __forceinline__ void inverse_in_regs(u64 (&a)[8], u64 *bufA, u64 *bufB, const Tables2048 &T, int tid_) {
+    const int tid = fresh(tid_);
+    const NegQ q = T.nq;
+    const u64 q2 = T.mod.q2;
+    inv_pass(a, T.itw + 8 * (256 + tid), q, q2);                                     // bits 0-2
     exchange<0, 3>(a, bufA, tid << 3, ((tid >> 3) << 6) | (tid & 7));
-    inv_pass(a, T.itw, 32 + (tid >> 3), q, q2);                                      // bits 3-5
+    inv_pass(a, T.itw + 8 * (32 + (tid >> 3)), q, q2);                               // bits 3-5
     exchange<3, 6>(a, bufB, ((tid >> 3) << 6) | (tid & 7), ((tid >> 6) << 9) | (tid & 63));
-    inv_pass(a, T.itw, 4 + (tid >> 6), q, q2);                                       // bits 6-8
+    inv_pass(a, T.itw + 8 * (4 + (tid >> 6)), q, q2);                                // bits 6-8
     exchange<6, 8>(a, bufA, ((tid >> 6) << 9) | (tid & 63), tid);
     // bits 9-10 (register bits 1,2; register bit 0 is index bit 8), n^-1 folded into the last stage
-    const ulonglong2 t2a = T.itw[2], t2b = T.itw[3];
+    const ulonglong2 t2a = T.itw[8 * 1 + 1], t2b = T.itw[8 * 1 + 2];
     bf_inv(a[0], a[2], t2a, q, q2);
     bf_inv(a[1], a[3], t2a, q, q2);
     bf_inv(a[4], a[6], t2b, q, q2);
@@ -141,8 +216,8 @@ __device__ __forceinline__ void inverse_in_regs(u64 (&a)[8], u64 *bufA, u64 *buf
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const u64 x = a[k], y = a[k + 4];
-        a[k] = mul_shoup(x + y, T.ninv.x, T.ninv.y, q);
-        a[k + 4] = mul_shoup(x - y + q2, T.itw1n.x, T.itw1n.y, q);
+        a[k] = csub_dev(mul_const(x + y, T.ninv.x, T.ninv.y, q), T.mod.q);
+        a[k + 4] = csub_dev(mul_const(x - y + q2, T.itw1n.x, T.itw1n.y, q), T.mod.q);
     }
 }
 
@@ -151,44 +226,42 @@ __device__ __forceinline__ u64 reduce64(u64 x, const Modulus &m) {
     return csub(x - mulhi64(x, m.one_s) * m.q, m.q);
 }
 
+// Every product on this path is a multiplication by a constant that carries its precomputed
+// quotient (twiddles, encoded weights, key polynomials), so sums of products stay in 64-bit
+// registers: each product is below 2q, a running sum is kept below 8q and may take four more
+// products before one conditional subtraction of 8q.
 template <bool HAS_W>
 __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables2048 T, int gadget_bits, int ndigits) {
     __shared__ u64 bufA[LDS_WORDS], bufB[LDS_WORDS];
+    __shared__ u64 stash[N];   // each thread parks its 8 coefficients here between digits (private slots, no barrier)
     const int tid = threadIdx.x;
     const int item = blockIdx.x / job.nchunks, chunk = blockIdx.x % job.nchunks;
     const int g0 = (int)((long)chunk * job.G / job.nchunks), g1 = (int)((long)(chunk + 1) * job.G / job.nchunks);
+    const NegQ q = T.nq;
+    const u64 q8 = 8 * T.mod.q;
     const u64 digit_mask = (1ull << gadget_bits) - 1;
-    const size_t key_words = (size_t)ndigits * 2 * N;
+    const size_t key_pairs = (size_t)ndigits * 2 * N;
 
-    u64 sum0[PER], sum1[PER];   // running sums over the rotations of this chunk, lazy (below 16q)
+    u64 sum0[PER], sum1[PER];   // running sums over the rotations of this chunk, below 8q between products
 #pragma unroll
     for (int k = 0; k < PER; ++k) sum0[k] = sum1[k] = 0;
-    int lazy = 0;
 
     for (int g = g0; g < g1; ++g) {
         const u64 *c0 = job.ct_in + (size_t)item * job.in_item_stride + (size_t)g * job.in_g_stride;
         const u64 *c1 = c0 + N;
-        const u64 *w = HAS_W ? job.w + (size_t)g * N : nullptr;
+        const ulonglong2 *w = HAS_W ? reinterpret_cast<const ulonglong2 *>(job.w2) + (size_t)g * N : nullptr;
         const int gal = job.gal[g];
-        if (lazy == 14) {
-#pragma unroll
-            for (int k = 0; k < PER; ++k) {
-                sum0[k] = reduce64(sum0[k], T.mod);
-                sum1[k] = reduce64(sum1[k], T.mod);
-            }
-            lazy = 1;
-        }
-        ++lazy;
         if (gal == 1) {   // rotation by zero: ScMult and Add only
 #pragma unroll
             for (int k = 0; k < PER; ++k) {
                 const int i = tid + k * NT;
                 if (HAS_W) {
-                    sum0[k] += mul_mod(c0[i], w[i], T.mod);
-                    sum1[k] += mul_mod(c1[i], w[i], T.mod);
+                    const ulonglong2 ww = w[i];
+                    sum0[k] = csub_dev(sum0[k] + mul_const(c0[i], ww.x, ww.y, q), q8);
+                    sum1[k] = csub_dev(sum1[k] + mul_const(c1[i], ww.x, ww.y, q), q8);
                 } else {
-                    sum0[k] += c0[i];
-                    sum1[k] += c1[i];
+                    sum0[k] = csub_dev(sum0[k] + c0[i], q8);
+                    sum1[k] = csub_dev(sum1[k] + c1[i], q8);
                 }
             }
             continue;
@@ -197,7 +270,7 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
         // different buffers, which is what lets each exchange do with one barrier; a rotation ends on
         // A and the next one starts on A, so that one boundary needs a barrier of its own.
         __syncthreads();
-        const u64 *key = job.keys + (size_t)job.key_idx[g] * key_words;
+        const ulonglong2 *key = reinterpret_cast<const ulonglong2 *>(job.keys2) + (size_t)job.key_idx[g] * key_pairs;
         int src[PER];   // where the automorphism takes output index tid + 256k from
 #pragma unroll
         for (int k = 0; k < PER; ++k) src[k] = galois_index11(tid + k * NT, gal);
@@ -206,14 +279,13 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
         u64 a[PER];
         {
             const ulonglong2 *c1v = reinterpret_cast<const ulonglong2 *>(c1 + 8 * tid);
-            const ulonglong2 *wv = reinterpret_cast<const ulonglong2 *>(w + 8 * tid);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const ulonglong2 cv = c1v[k];
                 if (HAS_W) {
-                    const ulonglong2 ww = wv[k];
-                    a[2 * k] = mul_mod(cv.x, ww.x, T.mod);
-                    a[2 * k + 1] = mul_mod(cv.y, ww.y, T.mod);
+                    const ulonglong2 wa = w[8 * tid + 2 * k], wb = w[8 * tid + 2 * k + 1];
+                    a[2 * k] = mul_const(cv.x, wa.x, wa.y, q);
+                    a[2 * k + 1] = mul_const(cv.y, wb.x, wb.y, q);
                 } else {
                     a[2 * k] = cv.x;
                     a[2 * k + 1] = cv.y;
@@ -221,45 +293,47 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
             }
         }
         inverse_in_regs(a, bufA, bufB, T, tid);
-        u64 coef[PER];
 #pragma unroll
-        for (int k = 0; k < PER; ++k) coef[k] = a[k];
+        for (int k = 0; k < PER; ++k) stash[tid + k * NT] = a[k];
 
-        u128 acc0[PER], acc1[PER];
         // the c0 part: permuted c0 (.) w
 #pragma unroll
         for (int k = 0; k < PER; ++k) {
-            if (HAS_W) acc0[k] = (u128)c0[src[k]] * w[src[k]];
-            else acc0[k] = c0[src[k]];
-            acc1[k] = 0;
+            if (HAS_W) {
+                const ulonglong2 ww = w[src[k]];
+                sum0[k] += mul_const(c0[src[k]], ww.x, ww.y, q);
+            } else {
+                sum0[k] += c0[src[k]];
+            }
         }
-        int terms = 1;
+        int pending = 1;   // products added to sum0 since it was last brought below 8q
         for (int j = 0; j < ndigits; ++j) {
 #pragma unroll
-            for (int k = 0; k < PER; ++k) a[k] = (coef[k] >> (j * gadget_bits)) & digit_mask;
-            forward_to_lds(a, bufA, bufB, T, tid);   // result in bufA
-            const u64 *kb = key + (size_t)(2 * j) * N, *ka = kb + N;
-            if (terms + 1 > 15) {   // products are below 2^124 here (digit transforms are below 16q)
+            for (int k = 0; k < PER; ++k) a[k] = (stash[tid + k * NT] >> (j * gadget_bits)) & digit_mask;
+            forward_to_lds(a, bufA, bufB, T, tid);   // result in bufA, any 64-bit value below 16q
+            const ulonglong2 *kb = key + (size_t)(2 * j) * N, *ka = kb + N;
+            if (pending == 4) {
 #pragma unroll
                 for (int k = 0; k < PER; ++k) {
-                    acc0[k] = reduce128(acc0[k], T.mod);
-                    acc1[k] = reduce128(acc1[k], T.mod);
+                    sum0[k] = csub_dev(sum0[k], q8);
+                    sum1[k] = csub_dev(sum1[k], q8);
                 }
-                terms = 1;
+                pending = 0;
             }
 #pragma unroll
             for (int k = 0; k < PER; ++k) {
                 const int i = tid + k * NT;
                 const u64 d = bufA[pad(src[k])];
-                acc0[k] += (u128)d * kb[i];
-                acc1[k] += (u128)d * ka[i];
+                const ulonglong2 b = kb[i], aa = ka[i];
+                sum0[k] += mul_const(d, b.x, b.y, q);
+                sum1[k] += mul_const(d, aa.x, aa.y, q);
             }
-            ++terms;
+            ++pending;
         }
 #pragma unroll
         for (int k = 0; k < PER; ++k) {
-            sum0[k] += reduce128(acc0[k], T.mod);
-            sum1[k] += reduce128(acc1[k], T.mod);
+            sum0[k] = csub_dev(sum0[k], q8);
+            sum1[k] = csub_dev(sum1[k], q8);
         }
     }
     u64 *out = job.partial + ((size_t)item * job.nchunks + chunk) * 2 * N;
@@ -277,10 +351,13 @@ int launch_perm_accumulate_2048(const gala_ctx *c, void *stream, const PermJob &
     hipStream_t st = (hipStream_t)stream;
     Tables2048 T;
     T.tw = reinterpret_cast<const ulonglong2 *>(c->d_tw2);
-    T.itw = reinterpret_cast<const ulonglong2 *>(c->d_tw2 + 2 * (size_t)N);
+    T.itw = reinterpret_cast<const ulonglong2 *>(c->d_tw2 + 2 * 8 * (size_t)512);
     T.ninv = make_ulonglong2(c->dev_q.ninv, c->dev_q.ninvs);
     T.itw1n = make_ulonglong2(c->dev_q.itw1n, c->dev_q.itw1ns);
     T.mod = c->dev_q.mod;
+    const u64 negq = 0 - c->q;
+    T.nq.lo = (u32)negq;
+    T.nq.hi = (u32)(negq >> 32);
     const dim3 grid((unsigned)(job.items * job.nchunks));
     if (job.w)
         hipLaunchKernelGGL(perm_accumulate_2048<true>, grid, dim3(NT), 0, st, job, T, c->gadget_bits, c->ndigits);
