@@ -85,7 +85,7 @@ extern "C" int gala_rotate(const gala_ctx *c, void *stream, const gala_gk *gk, c
     job.in_item_stride = 2 * (size_t)c->n;
     job.in_g_stride = 0;
     job.w = nullptr;
-    job.G = 1; job.items = count; job.nchunks = 1;
+    job.G = 1; job.items = count; job.nchunks = 1; job.slots = 1;
     job.partial = ct_out;
     job.keys = gk->d_keys;
     job.keys2 = gk->d_keys2;
@@ -106,7 +106,7 @@ extern "C" int gala_rotate(const gala_ctx *c, void *stream, const gala_gk *gk, c
 extern "C" size_t gala_he_fc_workspace(const gala_fc_plan *pl, int batch) {
     if (!pl || batch <= 0) return 0;
     const int chunks = choose_chunks(batch, pl->G);
-    return align_up((size_t)batch * chunks * 2 * pl->ctx->n * sizeof(u64));
+    return align_up((size_t)batch * (chunks + 1) * 2 * pl->ctx->n * sizeof(u64));
 }
 extern "C" int gala_he_fc(const gala_ctx *c, void *stream, const gala_fc_plan *pl, const uint64_t *ct_in, int batch,
                           const uint64_t *r, uint64_t mask_seed, uint64_t *ct_out, void *workspace,
@@ -125,17 +125,16 @@ extern "C" int gala_he_fc(const gala_ctx *c, void *stream, const gala_fc_plan *p
     job.keys = pl->bound ? pl->bound->d_keys : nullptr;
     job.keys2 = pl->bound ? pl->bound->d_keys2 : nullptr;
     job.w2 = pl->d_w2;
-    job.G = pl->G; job.items = batch; job.nchunks = chunks;
+    job.G = pl->G; job.items = batch; job.nchunks = chunks; job.slots = chunks + 1;
     job.partial = (u64 *)workspace;
-    if (launch_perm_accumulate(c, stream, job)) return GALA_EHIP;
     FinalizeJob fin{};
     fin.partial = job.partial;
-    fin.items = batch; fin.nchunks = chunks; fin.nout = 1;
+    fin.items = batch; fin.nchunks = chunks; fin.slots = chunks + 1; fin.nout = 1;
     fin.r = r; fin.r_stride = (size_t)pl->n_o;
     fin.mask_seed = mask_seed;
     fin.mask = pl->mask_d;
     fin.ct_out = ct_out;
-    if (launch_finalize(c, stream, fin)) return GALA_EHIP;
+    if (launch_perm_finalize(c, stream, job, fin)) return GALA_EHIP;
     if (counts) {
         counts->perm = (int64_t)batch * (pl->G - 1);
         counts->scmult = (int64_t)batch * pl->G;
@@ -162,7 +161,7 @@ ConvWorkspace conv_workspace(const gala_conv_plan *pl, int batch) {
     ws.xrot = ws.digits + align_up((size_t)batch * pl->nin * c->ndigits * n * w);
     ws.acc = ws.xrot + align_up((size_t)batch * pl->nin * pl->ntap * 2 * n * w);
     ws.partial = ws.acc + align_up((size_t)batch * pl->nout * pl->cn * 2 * n * w);
-    ws.total = ws.partial + align_up((size_t)batch * pl->nout * ws.chunks * 2 * n * w);
+    ws.total = ws.partial + align_up((size_t)batch * pl->nout * (ws.chunks + 1) * 2 * n * w);
     return ws;
 }
 }  // namespace
@@ -200,17 +199,16 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
     job.gal = pl->d_grp_gal; job.key_idx = pl->d_grp_key;
     job.keys = keys;
     job.keys2 = pl->bound ? pl->bound->d_keys2 : nullptr;
-    job.G = pl->cn; job.items = batch * pl->nout; job.nchunks = ws.chunks;
+    job.G = pl->cn; job.items = batch * pl->nout; job.nchunks = ws.chunks; job.slots = ws.chunks + 1;
     job.partial = partial;
-    if (launch_perm_accumulate(c, stream, job)) return GALA_EHIP;
     FinalizeJob fin{};
     fin.partial = partial;
-    fin.items = job.items; fin.nchunks = ws.chunks; fin.nout = pl->nout;
+    fin.items = job.items; fin.nchunks = ws.chunks; fin.slots = ws.chunks + 1; fin.nout = pl->nout;
     fin.r = r; fin.r_stride = (size_t)pl->c_o * pl->u_h * pl->u_w;
     fin.mask_seed = mask_seed;
     fin.mask = pl->mask_d;
     fin.ct_out = ct_out;
-    if (launch_finalize(c, stream, fin)) return GALA_EHIP;
+    if (launch_perm_finalize(c, stream, job, fin)) return GALA_EHIP;
     if (counts) {
         const int64_t terms = (int64_t)pl->nin * pl->ntap;
         counts->decperm_in = pl->ntap > 1 ? (int64_t)batch * pl->nin : 0;

@@ -290,23 +290,27 @@ extern "C" int gala_ctx_create(const gala_params *par, gala_ctx **out) {
     }
     // pass-major twiddle blocks for the n = 2048 kernel: block T (1 <= T < 512) holds the pairs
     // tw[T], tw[2T], tw[2T+1], tw[4T..4T+3] and one unused pair; forward table then inverse table
-    std::vector<u64> pairs;
+    std::vector<u64> pairs, pairs_p;
     if (n == 2048) {
-        pairs.assign(2 * 2 * 8 * (size_t)512, 0);
-        for (int inv = 0; inv < 2; ++inv) {
-            const std::vector<u64> &w = inv ? c->ntt_q.itw : c->ntt_q.tw, &ws = inv ? c->ntt_q.itws : c->ntt_q.tws;
-            u64 *base = pairs.data() + (size_t)inv * 2 * 8 * 512;
-            for (int T = 1; T < 512; ++T) {
-                const int idx[7] = {T, 2 * T, 2 * T + 1, 4 * T, 4 * T + 1, 4 * T + 2, 4 * T + 3};
-                for (int e = 0; e < 7; ++e) {
-                    base[2 * (8 * T + e)] = w[idx[e]];
-                    base[2 * (8 * T + e) + 1] = ws[idx[e]];
+        auto build = [&](const NttHost &h, std::vector<u64> &out) {
+            out.assign(2 * 2 * 8 * (size_t)512, 0);
+            for (int inv = 0; inv < 2; ++inv) {
+                const std::vector<u64> &w = inv ? h.itw : h.tw, &ws = inv ? h.itws : h.tws;
+                u64 *base = out.data() + (size_t)inv * 2 * 8 * 512;
+                for (int T = 1; T < 512; ++T) {
+                    const int idx[7] = {T, 2 * T, 2 * T + 1, 4 * T, 4 * T + 1, 4 * T + 2, 4 * T + 3};
+                    for (int e = 0; e < 7; ++e) {
+                        base[2 * (8 * T + e)] = w[idx[e]];
+                        base[2 * (8 * T + e) + 1] = ws[idx[e]];
+                    }
                 }
             }
-        }
+        };
+        build(c->ntt_q, pairs);
+        build(c->ntt_p, pairs_p);
     }
     if (upload(&c->d_tables, host) || upload(&c->d_slot_to_idx, c->slot_to_idx) ||
-        upload(&c->d_tw2, pairs)) {
+        upload(&c->d_tw2, pairs) || upload(&c->d_tw2p, pairs_p)) {
         gala_ctx_destroy(c);
         return GALA_EHIP;
     }
@@ -329,6 +333,7 @@ extern "C" void gala_ctx_destroy(gala_ctx *c) {
         hipFree(c->d_tables);
         hipFree(c->d_slot_to_idx);
         hipFree(c->d_tw2);
+        hipFree(c->d_tw2p);
     }
     delete c;
 }

@@ -66,6 +66,7 @@ struct gala_ctx {
     gala::u64 *d_tables = nullptr;     // 8*n words: tw,tws,itw,itws for q then for p
     int *d_slot_to_idx = nullptr;
     gala::u64 *d_tw2 = nullptr;        // n = 2048 only: pass-major (w, companion) twiddle blocks, forward then inverse
+    gala::u64 *d_tw2p = nullptr;       // the same for the plaintext modulus
     gala::NttDev dev_q{}, dev_p{};
     // measurement aid: event pairs recorded around rotate-and-accumulate launches
     mutable std::vector<void *> prof_events;   // 2*capacity hipEvent_t
@@ -161,7 +162,8 @@ struct PermJob {
     const u64 *keys;
     const u64 *w2, *keys2;   // (value, companion) pair images of w and keys (n = 2048 kernel only)
     int G, items, nchunks;
-    u64 *partial;            // items x nchunks x 2n
+    int slots;               // partial ciphertexts reserved per item (>= nchunks)
+    u64 *partial;            // items x slots x 2n
 };
 int launch_perm_accumulate(const gala_ctx *ctx, void *stream, const PermJob &job);
 // the n = 2048, q < 2^60 specialisation (gala_perm2048.hip); launch_perm_accumulate dispatches to it
@@ -171,6 +173,7 @@ int launch_perm_accumulate_2048(const gala_ctx *ctx, void *stream, const PermJob
 struct FinalizeJob {
     const u64 *partial;
     int items, nchunks;
+    int slots;               // partial ciphertexts reserved per item (>= nchunks)
     int nout;                // output ciphertexts per batch element (item = b*nout + O)
     const u64 *r;            // batch x r_stride values mod p (nullptr: no mask)
     size_t r_stride;
@@ -179,6 +182,12 @@ struct FinalizeJob {
     u64 *ct_out;             // items x 2n
 };
 int launch_finalize(const gala_ctx *ctx, void *stream, const FinalizeJob &job);
+// Rotate-and-accumulate followed by share generation.  With the n = 2048 kernel the mask of every
+// item is built by extra workgroups of the same launch (as one more partial ciphertext, slot
+// `nchunks`, so job.slots must be >= nchunks + 1) and a light kernel adds the partials up;
+// otherwise this is launch_perm_accumulate + launch_finalize.
+int launch_perm_finalize(const gala_ctx *ctx, void *stream, const PermJob &job, const FinalizeJob &fin);
+int launch_perm_accumulate_2048_masked(const gala_ctx *ctx, void *stream, const PermJob &job, const FinalizeJob &fin);
 
 // DecPerm of `count` ciphertexts: digits[c][j] = forward(digit_j(inverse(c1))), j < ndigits.
 int launch_decperm(const gala_ctx *ctx, void *stream, const u64 *ct_in, size_t count, u64 *digits);

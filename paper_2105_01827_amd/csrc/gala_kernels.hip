@@ -200,7 +200,7 @@ __global__ __launch_bounds__(NT) void perm_accumulate_kernel(PermJob job, NttDev
         }
         terms += ndigits + 1;
     }
-    u64 *out = job.partial + ((size_t)item * job.nchunks + chunk) * 2 * n;
+    u64 *out = job.partial + ((size_t)item * job.slots + chunk) * 2 * n;
 #pragma unroll
     for (int k = 0; k < kMaxPer; ++k) {
         const int i = tid + k * NT;
@@ -251,7 +251,7 @@ __global__ __launch_bounds__(NT) void finalize_kernel(FinalizeJob job, NttDev Tq
         __syncthreads();
         ntt_forward_lds<NT>(buf, n, logn, Tq);
     }
-    const u64 *part = job.partial + (size_t)item * job.nchunks * 2 * n;
+    const u64 *part = job.partial + (size_t)item * job.slots * 2 * n;
     u64 *out = job.ct_out + (size_t)item * 2 * n;
     for (int i = tid; i < n; i += NT) {
         u64 s0 = 0, s1 = 0;
@@ -443,6 +443,11 @@ int launch_finalize(const gala_ctx *c, void *stream, const FinalizeJob &job) {
         hipLaunchKernelGGL(finalize_kernel<64>, dim3(job.items), dim3(64), lds, st, job, c->dev_q, c->dev_p,
                            c->d_slot_to_idx, c->n, c->logn, c->pbits, c->delta, c->delta_s);
     return last_error();
+}
+int launch_perm_finalize(const gala_ctx *c, void *stream, const PermJob &job, const FinalizeJob &fin) {
+    if (uses_fast_perm(c) && fin.r && job.slots > job.nchunks) return launch_perm_accumulate_2048_masked(c, stream, job, fin);
+    const int rc = launch_perm_accumulate(c, stream, job);
+    return rc ? rc : launch_finalize(c, stream, fin);
 }
 int launch_decperm(const gala_ctx *c, void *stream, const u64 *ct_in, size_t count, u64 *digits) {
     if (!count) return 0;

@@ -226,15 +226,81 @@ __device__ __forceinline__ u64 reduce64(u64 x, const Modulus &m) {
     return csub(x - mulhi64(x, m.one_s) * m.q, m.q);
 }
 
+// Share generation inside the same launch: the workgroups after the last (item, chunk) pair build the
+// negated mask of one output ciphertext each and store it as one more partial ciphertext.
+struct MaskJob {
+    int enabled;
+    int nout;                   // output ciphertexts per batch element
+    const u64 *r;               // batch x r_stride server shares mod p
+    size_t r_stride;
+    u64 mask_seed;
+    MaskLayoutDev layout;
+    const int *slot_to_idx;
+    int pbits;
+    ulonglong2 delta;           // delta = floor(q/p) and its companion mod q
+    Tables2048 Tp;              // inverse-transform tables of the plaintext modulus
+};
+
+__device__ __forceinline__ void mask_role(const PermJob &job, const Tables2048 &T, const MaskJob &mj, int item,
+                                          u64 *bufA, u64 *bufB) {
+    const int tid = threadIdx.x;
+    const int b = item / mj.nout, O = item % mj.nout;
+    const u64 p = mj.Tp.mod.q, q = T.mod.q;
+    const int *row_ptr = mj.layout.row_ptr + (size_t)O * (N + 1);
+    const int *row_slots = mj.layout.row_slots + (size_t)O * N;
+    const int *row_rindex = mj.layout.row_rindex + (size_t)O * N;
+    const unsigned char *is_first = mj.layout.is_first + (size_t)O * N;
+    // every slot but the first of each real output is a draw from the mask stream; values go to the
+    // position the mod-p transform expects them at
+    for (int s = tid; s < N; s += NT) {
+        u64 v = 0;
+        if (!is_first[s]) v = draw_uniform(p, mj.pbits, mj.mask_seed, kStreamMask, ((u64)b << 32) + ((u64)O << 16) + (u64)s);
+        bufB[mj.slot_to_idx[s]] = v;
+    }
+    __syncthreads();
+    const int nrows = mj.layout.nrows[O];
+    for (int t = tid; t < nrows; t += NT) {
+        const int e0 = row_ptr[t], e1 = row_ptr[t + 1];
+        if (e1 <= e0) continue;
+        u64 sum = 0;
+        for (int e = e0 + 1; e < e1; ++e) sum = add_mod(sum, bufB[mj.slot_to_idx[row_slots[e]]], p);
+        u64 rv = mj.r[(size_t)b * mj.r_stride + row_rindex[t]];
+        if (rv >= p) rv %= p;
+        bufB[mj.slot_to_idx[row_slots[e0]]] = sub_mod(rv, sum, p);
+    }
+    __syncthreads();
+    // slots -> plaintext polynomial (inverse transform mod p) -> delta * m mod q -> evaluation domain mod q
+    u64 a[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) a[k] = bufB[8 * tid + k];
+    inverse_in_regs(a, bufA, bufB, mj.Tp, tid);        // LDS phases A B A; the reads of bufB above precede the first barrier
+#pragma unroll
+    for (int k = 0; k < PER; ++k) a[k] = csub_dev(mul_const(a[k], mj.delta.x, mj.delta.y, T.nq), q);
+    forward_to_lds(a, bufA, bufB, T, tid);             // LDS phases B A B A, result in bufA (below 16q)
+    u64 *out = job.partial + ((size_t)item * job.slots + job.nchunks) * 2 * N;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int i = tid + k * NT;
+        const u64 m = reduce64(bufA[pad(i)], T.mod);
+        out[i] = m ? q - m : 0;       // minus the mask on c0
+        out[N + i] = 0;
+    }
+}
+
 // Every product on this path is a multiplication by a constant that carries its precomputed
 // quotient (twiddles, encoded weights, key polynomials), so sums of products stay in 64-bit
 // registers: each product is below 2q, a running sum is kept below 8q and may take four more
 // products before one conditional subtraction of 8q.
 template <bool HAS_W>
-__global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables2048 T, int gadget_bits, int ndigits) {
+__global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables2048 T, MaskJob mj, int gadget_bits,
+                                                           int ndigits) {
     __shared__ u64 bufA[LDS_WORDS], bufB[LDS_WORDS];
     __shared__ u64 stash[N];   // each thread parks its 8 coefficients here between digits (private slots, no barrier)
     const int tid = threadIdx.x;
+    if ((int)blockIdx.x >= job.items * job.nchunks) {   // only launched when mj.enabled
+        mask_role(job, T, mj, (int)blockIdx.x - job.items * job.nchunks, bufA, bufB);
+        return;
+    }
     const int item = blockIdx.x / job.nchunks, chunk = blockIdx.x % job.nchunks;
     const int g0 = (int)((long)chunk * job.G / job.nchunks), g1 = (int)((long)(chunk + 1) * job.G / job.nchunks);
     const NegQ q = T.nq;
@@ -336,7 +402,7 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
             sum1[k] = csub_dev(sum1[k], q8);
         }
     }
-    u64 *out = job.partial + ((size_t)item * job.nchunks + chunk) * 2 * N;
+    u64 *out = job.partial + ((size_t)item * job.slots + chunk) * 2 * N;
 #pragma unroll
     for (int k = 0; k < PER; ++k) {
         const int i = tid + k * NT;
@@ -345,24 +411,71 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
     }
 }
 
+// out[item] = sum over the first `used` partial ciphertexts of the item (mod q); one thread per word pair
+__global__ void sum_partials_kernel(const u64 *partial, int slots, int used, u64 *out, size_t words, u64 q) {
+    const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= words) return;
+    const size_t item = id / (2 * N), e = id % (2 * N);
+    const u64 *src = partial + item * slots * 2 * N + e;
+    u64 acc = 0;
+    for (int s = 0; s < used; ++s) acc = add_mod(acc, src[(size_t)s * 2 * N], q);
+    out[id] = acc;
+}
+
 }  // namespace
 
-int launch_perm_accumulate_2048(const gala_ctx *c, void *stream, const PermJob &job) {
-    hipStream_t st = (hipStream_t)stream;
+static Tables2048 make_tables(const gala_ctx *c, const u64 *blocks, const NttDev &dev) {
     Tables2048 T;
-    T.tw = reinterpret_cast<const ulonglong2 *>(c->d_tw2);
-    T.itw = reinterpret_cast<const ulonglong2 *>(c->d_tw2 + 2 * 8 * (size_t)512);
-    T.ninv = make_ulonglong2(c->dev_q.ninv, c->dev_q.ninvs);
-    T.itw1n = make_ulonglong2(c->dev_q.itw1n, c->dev_q.itw1ns);
-    T.mod = c->dev_q.mod;
-    const u64 negq = 0 - c->q;
-    T.nq.lo = (u32)negq;
-    T.nq.hi = (u32)(negq >> 32);
-    const dim3 grid((unsigned)(job.items * job.nchunks));
+    T.tw = reinterpret_cast<const ulonglong2 *>(blocks);
+    T.itw = reinterpret_cast<const ulonglong2 *>(blocks + 2 * 8 * (size_t)512);
+    T.ninv = make_ulonglong2(dev.ninv, dev.ninvs);
+    T.itw1n = make_ulonglong2(dev.itw1n, dev.itw1ns);
+    T.mod = dev.mod;
+    const u64 neg = 0 - dev.mod.q;
+    T.nq.lo = (u32)neg;
+    T.nq.hi = (u32)(neg >> 32);
+    (void)c;
+    return T;
+}
+
+static int launch_2048(const gala_ctx *c, void *stream, const PermJob &job, const MaskJob &mj) {
+    hipStream_t st = (hipStream_t)stream;
+    const Tables2048 T = make_tables(c, c->d_tw2, c->dev_q);
+    const dim3 grid((unsigned)(job.items * job.nchunks + (mj.enabled ? job.items : 0)));
     if (job.w)
-        hipLaunchKernelGGL(perm_accumulate_2048<true>, grid, dim3(NT), 0, st, job, T, c->gadget_bits, c->ndigits);
+        hipLaunchKernelGGL(perm_accumulate_2048<true>, grid, dim3(NT), 0, st, job, T, mj, c->gadget_bits, c->ndigits);
     else
-        hipLaunchKernelGGL(perm_accumulate_2048<false>, grid, dim3(NT), 0, st, job, T, c->gadget_bits, c->ndigits);
+        hipLaunchKernelGGL(perm_accumulate_2048<false>, grid, dim3(NT), 0, st, job, T, mj, c->gadget_bits, c->ndigits);
+    return (int)hipGetLastError();
+}
+
+int launch_perm_accumulate_2048(const gala_ctx *c, void *stream, const PermJob &job) {
+    MaskJob mj{};
+    mj.enabled = 0;
+    return launch_2048(c, stream, job, mj);
+}
+
+int launch_perm_accumulate_2048_masked(const gala_ctx *c, void *stream, const PermJob &job, const FinalizeJob &fin) {
+    MaskJob mj{};
+    mj.enabled = 1;
+    mj.nout = fin.nout;
+    mj.r = fin.r;
+    mj.r_stride = fin.r_stride;
+    mj.mask_seed = fin.mask_seed;
+    mj.layout = fin.mask;
+    mj.slot_to_idx = c->d_slot_to_idx;
+    mj.pbits = c->pbits;
+    mj.delta = make_ulonglong2(c->delta, c->delta_s);
+    mj.Tp = make_tables(c, c->d_tw2p, c->dev_p);
+    hipStream_t st = (hipStream_t)stream;
+    const bool timed = (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
+    if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used], st);
+    int rc = launch_2048(c, stream, job, mj);
+    if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used++ + 1], st);
+    if (rc) return rc;
+    const size_t words = (size_t)job.items * 2 * N;
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, job.partial, job.slots,
+                       job.nchunks + 1, fin.ct_out, words, c->q);
     return (int)hipGetLastError();
 }
 
