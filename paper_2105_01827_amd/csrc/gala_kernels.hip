@@ -334,46 +334,89 @@ __global__ void hstperm_taps_kernel(const u64 *ct_in, const u64 *digits, int nta
     }
 }
 
-// One thread per coefficient; a tile of TB inputs shares each weight word.
-template <int TB>
-__global__ void conv_mac_kernel(const u64 *w, const u64 *xrot, int batch, int nterm, u64 *acc, Modulus mod, int n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+// acc (128 bits in lo, hi) += x * w with ten instructions: four 32x32+64 multiply-adds (low, high and
+// the two cross products) and six carry additions; written out because the compiler's own 128-bit
+// multiply-accumulate spends a third of its instructions on register moves.
+__device__ __forceinline__ void mac128(u64 &lo, u64 &hi, u64 x, u64 w) {
+    const u32 x0 = (u32)x, x1 = (u32)(x >> 32), w0 = (u32)w, w1 = (u32)(w >> 32);
+    u64 carry_lo, carry_mid, unused, mid;
+    asm("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(lo), "=s"(carry_lo) : "v"(x0), "v"(w0), "v"(lo));
+    asm("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(hi), "=s"(unused) : "v"(x1), "v"(w1), "v"(hi));
+    asm("v_mad_u64_u32 %0, %1, %2, %3, 0" : "=v"(mid), "=s"(unused) : "v"(x0), "v"(w1));
+    asm("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(mid), "=s"(carry_mid) : "v"(x1), "v"(w0), "v"(mid));
+    // words 1..3 += mid, then the carry of the low product into word 2 and of the cross sum into word 3
+    u32 a1 = (u32)(lo >> 32), a2 = (u32)hi, a3 = (u32)(hi >> 32);
+    asm("v_add_co_u32 %0, vcc, %0, %3\n\t"
+        "v_addc_co_u32 %1, vcc, %1, %4, vcc\n\t"
+        "v_addc_co_u32 %2, vcc, 0, %2, vcc\n\t"
+        "v_addc_co_u32_e64 %1, vcc, 0, %1, %5\n\t"
+        "v_addc_co_u32 %2, vcc, 0, %2, vcc\n\t"
+        "v_addc_co_u32_e64 %2, vcc, 0, %2, %6"
+        : "+v"(a1), "+v"(a2), "+v"(a3)
+        : "v"((u32)mid), "v"((u32)(mid >> 32)), "s"(carry_lo), "s"(carry_mid)
+        : "vcc");
+    lo = ((u64)a1 << 32) | (u32)lo;
+    hi = ((u64)a3 << 32) | a2;
+}
+
+// Per coefficient the convolution's ScMult/Add step is a small dense product: (O,gam) x (I,tap) weights
+// times (I,tap) x (input, polynomial) rotated ciphertext words.  One thread owns one coefficient and a
+// TM x TN register tile of 128-bit sums, so each loaded word feeds TN (weights) or TM (inputs) products.
+// nterm = nin*ntap; groups = nout*cn; cols = 2*batch (input-major, c0 then c1).
+// A workgroup is WM x WN wavefronts on the same 64 coefficients: the wavefronts of a row read the same
+// weight words and those of a column the same input words, so those reads hit in the CU's vector cache.
+template <int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(64 * WM * WN) void conv_mac_kernel(const u64 *w, const u64 *xrot, int cols, int groups,
+                                                                int nterm, u64 *acc, Modulus mod, int n,
+                                                                int flush_every) {
+    const int i = blockIdx.x * 64 + (threadIdx.x & 63);
     if (i >= n) return;
-    const int og = blockIdx.y;          // O*cn + gam
-    const int b0 = blockIdx.z * TB;
-    const int groups = gridDim.y;
-    u128 a[TB][2];
+    const int wave = threadIdx.x >> 6;
+    const int m0 = (blockIdx.y * WM + wave % WM) * TM, c0 = (blockIdx.z * WN + wave / WM) * TN;
+    // rows / columns past the end repeat the last valid one; their sums are computed but not stored
+    const u64 *wp[TM], *xp[TN];
 #pragma unroll
-    for (int t = 0; t < TB; ++t) a[t][0] = a[t][1] = 0;
-    const u64 *wp = w + (size_t)og * nterm * n + i;
-    int terms = 0;
+    for (int a = 0; a < TM; ++a) wp[a] = w + (size_t)min(m0 + a, groups - 1) * nterm * n + i;
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+        const int col = min(c0 + b, cols - 1);          // col = 2*input + polynomial
+        xp[b] = xrot + ((size_t)(col >> 1) * nterm * 2 + (col & 1)) * n + i;
+    }
+    u64 lo[TM][TN], hi[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b) lo[a][b] = hi[a][b] = 0;
+    int pending = 0;
     for (int e = 0; e < nterm; ++e) {
-        const u64 wv = wp[(size_t)e * n];
+        u64 wv[TM], xv[TN];
 #pragma unroll
-        for (int t = 0; t < TB; ++t) {
-            if (b0 + t < batch) {
-                const u64 *x = xrot + (((size_t)(b0 + t) * nterm + e) * 2) * n + i;
-                a[t][0] += (u128)wv * x[0];
-                a[t][1] += (u128)wv * x[n];
-            }
-        }
-        if (++terms == 60) {
+        for (int a = 0; a < TM; ++a) wv[a] = wp[a][(size_t)e * n];
 #pragma unroll
-            for (int t = 0; t < TB; ++t) {
-                a[t][0] = reduce128(a[t][0], mod);
-                a[t][1] = reduce128(a[t][1], mod);
-            }
-            terms = 1;
-        }
-    }
+        for (int b = 0; b < TN; ++b) xv[b] = xp[b][(size_t)e * 2 * n];
 #pragma unroll
-    for (int t = 0; t < TB; ++t) {
-        if (b0 + t < batch) {
-            u64 *out = acc + (((size_t)(b0 + t) * groups + og) * 2) * n + i;
-            out[0] = reduce128(a[t][0], mod);
-            out[n] = reduce128(a[t][1], mod);
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) mac128(lo[a][b], hi[a][b], xv[b], wv[a]);
+        if (++pending == flush_every) {   // keep the 128-bit sums of products below q^2 from overflowing
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b) {
+                    lo[a][b] = reduce128(hi[a][b], lo[a][b], mod);
+                    hi[a][b] = 0;
+                }
+            pending = 1;
         }
     }
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            const int m = m0 + a, col = c0 + b;
+            if (m < groups && col < cols)
+                acc[(((size_t)(col >> 1) * groups + m) * 2 + (col & 1)) * n + i] = reduce128(hi[a][b], lo[a][b], mod);
+        }
 }
 
 inline int block_threads(int n) { return n >= 512 ? 256 : 64; }
@@ -472,11 +515,14 @@ int launch_hstperm_taps(const gala_ctx *c, void *stream, const u64 *ct_in, const
 int launch_conv_mac(const gala_ctx *c, void *stream, const u64 *w, const u64 *xrot, int batch, int nout, int cn,
                     int nin, int ntap, u64 *acc) {
     if (batch <= 0) return 0;
-    constexpr int TB = 4;
-    const int threads = c->n >= 256 ? 256 : c->n;
-    const dim3 grid((unsigned)((c->n + threads - 1) / threads), (unsigned)(nout * cn), (unsigned)((batch + TB - 1) / TB));
-    hipLaunchKernelGGL(conv_mac_kernel<TB>, grid, dim3(threads), 0, (hipStream_t)stream, w, xrot, batch, nin * ntap, acc,
-                       c->dev_q.mod, c->n);
+    constexpr int TM = 4, TN = 8, WM = 4, WN = 2;
+    const int groups = nout * cn, cols = 2 * batch;
+    // products are below q^2: 255 of them fit 128 bits when q < 2^60, 63 when q < 2^61
+    const int flush_every = c->q < (1ull << 60) ? 255 : 63;
+    const dim3 grid((unsigned)((c->n + 63) / 64), (unsigned)((groups + TM * WM - 1) / (TM * WM)),
+                    (unsigned)((cols + TN * WN - 1) / (TN * WN)));
+    hipLaunchKernelGGL((conv_mac_kernel<TM, TN, WM, WN>), grid, dim3(64 * WM * WN), 0, (hipStream_t)stream, w, xrot, cols,
+                       groups, nin * ntap, acc, c->dev_q.mod, c->n, flush_every);
     return last_error();
 }
 
