@@ -194,6 +194,31 @@ int gala_he_conv(const gala_ctx *ctx, void *stream, const gala_conv_plan *plan, 
                  const uint64_t *r, uint64_t mask_seed, uint64_t *ct_out, void *workspace, size_t workspace_bytes,
                  gala_opcount *counts);
 
+/* ---- spatial tiling and stride for images larger than half a ciphertext (host) ---- */
+/* The paper assumes u_w*u_h fits a ciphertext (Sec. III-B(1), footnote) and never mentions stride.
+ * Here an in_h x in_w image is cut into overlapping tile_h x tile_w tiles (tile_h*tile_w <= n/2) whose
+ * halo of k-1 rows/columns supplies the neighbours; every tile is an independent input of the same
+ * convolution plan (u_h = tile_h, u_w = tile_w), i.e. the tiles form the batch of gala_he_conv.  Only
+ * the interior of a tile is a valid output.  A stride-s convolution is evaluated at stride 1 and the
+ * outputs at multiples of s are kept (out_h = ceil(in_h/s)), the rest is masked and dropped. */
+typedef struct {
+    int32_t in_h, in_w, k_h, k_w, stride;
+    int32_t tile_h, tile_w;      /* u_h, u_w of the plan to create                          */
+    int32_t tiles_y, tiles_x;    /* number of tiles; the batch is tiles_y*tiles_x per image */
+    int32_t step_y, step_x;      /* interior size = distance between tile origins           */
+    int32_t halo_y, halo_x;      /* rows / columns of halo on each side (0 if not tiled)    */
+    int32_t out_h, out_w;
+} gala_conv_tiling;
+int gala_conv_tiling_plan(const gala_ctx *ctx, int in_h, int in_w, int k_h, int k_w, int stride,
+                          gala_conv_tiling *out);
+/* tile_out (ch x tile_h x tile_w) = the tile's window of image (ch x in_h x in_w), zeros outside it. */
+int gala_conv_tile_extract(const gala_conv_tiling *t, int ch, const uint64_t *image, int tile, uint64_t *tile_out);
+/* r_tile (ch x tile_h x tile_w) = the layer-level mask r (ch x out_h x out_w) at the outputs this tile
+ * keeps, 0 at the positions that are dropped. */
+int gala_conv_tile_mask(const gala_conv_tiling *t, int ch, const uint64_t *r, int tile, uint64_t *r_tile);
+/* Writes the outputs this tile keeps from tile_vals (ch x tile_h x tile_w) into out (ch x out_h x out_w). */
+int gala_conv_tile_scatter(const gala_conv_tiling *t, int ch, const uint64_t *tile_vals, int tile, uint64_t *out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -35,6 +35,15 @@ class Rot(C.Structure):
     _fields_ = [("swap", C.c_int32), ("step", C.c_int32)]
 
 
+class ConvTiling(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in ("in_h", "in_w", "k_h", "k_w", "stride", "tile_h", "tile_w", "tiles_y",
+                                         "tiles_x", "step_y", "step_x", "halo_y", "halo_x", "out_h", "out_w")]
+
+    @property
+    def tiles(self):
+        return self.tiles_y * self.tiles_x
+
+
 class OpCount(C.Structure):
     _fields_ = [("perm", C.c_int64), ("decperm_in", C.c_int64), ("hstperm_in", C.c_int64),
                 ("scmult", C.c_int64), ("add", C.c_int64)]
@@ -84,6 +93,10 @@ SIGNATURES = {
     "gala_conv_unpack_share": (_I, [_VP, _I, _U64P, _U64P]),
     "gala_he_conv_workspace": (C.c_size_t, [_VP, _I]),
     "gala_he_conv": (_I, [_VP, _VP, _VP, _U64P, _I, _U64P, C.c_uint64, _U64P, _VP, C.c_size_t, C.POINTER(OpCount)]),
+    "gala_conv_tiling_plan": (_I, [_VP, _I, _I, _I, _I, _I, C.POINTER(ConvTiling)]),
+    "gala_conv_tile_extract": (_I, [C.POINTER(ConvTiling), _I, _U64P, _I, _U64P]),
+    "gala_conv_tile_mask": (_I, [C.POINTER(ConvTiling), _I, _U64P, _I, _U64P]),
+    "gala_conv_tile_scatter": (_I, [C.POINTER(ConvTiling), _I, _U64P, _I, _U64P]),
 }
 
 _lib = None
@@ -201,6 +214,30 @@ class Context:
 
     def fc_plan(self, W):
         return FcPlan(self, W)
+
+    # ---- spatial tiling / stride helpers (host)
+    def conv_tiling(self, in_h, in_w, k_h, k_w, stride):
+        t = ConvTiling()
+        _check(self.lib.gala_conv_tiling_plan(self.h, in_h, in_w, k_h, k_w, stride, C.byref(t)), "gala_conv_tiling_plan")
+        return t
+
+    def tile_extract(self, t, image, tile):
+        a, ap = _host(image); ch = a.shape[0]; out = np.empty((ch, t.tile_h, t.tile_w), np.uint64)
+        _check(self.lib.gala_conv_tile_extract(C.byref(t), ch, ap, tile, out.ctypes.data_as(C.c_void_p)),
+               "gala_conv_tile_extract")
+        return out
+
+    def tile_mask(self, t, r, tile):
+        a, ap = _host(r); ch = a.shape[0]; out = np.empty((ch, t.tile_h, t.tile_w), np.uint64)
+        _check(self.lib.gala_conv_tile_mask(C.byref(t), ch, ap, tile, out.ctypes.data_as(C.c_void_p)),
+               "gala_conv_tile_mask")
+        return out
+
+    def tile_scatter(self, t, vals, tile, out):
+        a, ap = _host(vals); ch = a.shape[0]
+        assert out.dtype == np.uint64 and out.flags["C_CONTIGUOUS"] and out.shape == (ch, t.out_h, t.out_w)
+        _check(self.lib.gala_conv_tile_scatter(C.byref(t), ch, ap, tile, out.ctypes.data_as(C.c_void_p)),
+               "gala_conv_tile_scatter")
 
     def conv_plan(self, K, u_h, u_w):
         return ConvPlan(self, K, u_h, u_w)

@@ -794,3 +794,84 @@ extern "C" int gala_conv_unpack_share(const gala_conv_plan *pl, int O, const uin
     }
     return GALA_OK;
 }
+
+// ===========================================================================
+// spatial tiling and stride (host)
+// ===========================================================================
+extern "C" int gala_conv_tiling_plan(const gala_ctx *c, int in_h, int in_w, int k_h, int k_w, int stride,
+                                     gala_conv_tiling *t) {
+    if (!c || !t || in_h < 1 || in_w < 1 || k_h < 1 || k_w < 1 || stride < 1) return GALA_EARG;
+    if (!(k_h & 1) || !(k_w & 1)) return GALA_ESHAPE;
+    const int half = c->n / 2;
+    int side = 1;
+    while ((long)(2 * side) * (2 * side) <= half) side *= 2;       // largest power of two with side^2 <= n/2
+    t->in_h = in_h; t->in_w = in_w; t->k_h = k_h; t->k_w = k_w; t->stride = stride;
+    if ((long)in_h * in_w <= half) {                                // the whole image is one tile
+        t->tile_h = in_h; t->tile_w = in_w;
+    } else {
+        t->tile_w = in_w <= side ? in_w : side;
+        t->tile_h = std::min(in_h, half / t->tile_w);
+    }
+    t->halo_x = t->tile_w == in_w ? 0 : k_w / 2;
+    t->halo_y = t->tile_h == in_h ? 0 : k_h / 2;
+    t->step_x = t->tile_w - 2 * t->halo_x;
+    t->step_y = t->tile_h - 2 * t->halo_y;
+    if (t->step_x < 1 || t->step_y < 1) return GALA_ESHAPE;
+    t->tiles_x = (in_w + t->step_x - 1) / t->step_x;
+    t->tiles_y = (in_h + t->step_y - 1) / t->step_y;
+    t->out_h = (in_h + stride - 1) / stride;
+    t->out_w = (in_w + stride - 1) / stride;
+    return GALA_OK;
+}
+namespace {
+// image coordinates of the tile's local (0,0)
+inline void tile_origin(const gala_conv_tiling *t, int tile, int *oy, int *ox) {
+    *oy = (tile / t->tiles_x) * t->step_y - t->halo_y;
+    *ox = (tile % t->tiles_x) * t->step_x - t->halo_x;
+}
+// whether local (ty,tx) is an output this tile keeps, and where it goes
+inline bool tile_keeps(const gala_conv_tiling *t, int oy, int ox, int ty, int tx, int *yo, int *xo) {
+    if (ty < t->halo_y || ty >= t->halo_y + t->step_y || tx < t->halo_x || tx >= t->halo_x + t->step_x) return false;
+    const int y = oy + ty, x = ox + tx;
+    if (y < 0 || y >= t->in_h || x < 0 || x >= t->in_w || y % t->stride || x % t->stride) return false;
+    *yo = y / t->stride; *xo = x / t->stride;
+    return true;
+}
+}  // namespace
+extern "C" int gala_conv_tile_extract(const gala_conv_tiling *t, int ch, const uint64_t *image, int tile,
+                                      uint64_t *out) {
+    if (!t || !image || !out || ch < 1 || tile < 0 || tile >= t->tiles_x * t->tiles_y) return GALA_EARG;
+    int oy, ox;
+    tile_origin(t, tile, &oy, &ox);
+    for (int c = 0; c < ch; ++c)
+        for (int ty = 0; ty < t->tile_h; ++ty)
+            for (int tx = 0; tx < t->tile_w; ++tx) {
+                const int y = oy + ty, x = ox + tx;
+                const bool in = y >= 0 && y < t->in_h && x >= 0 && x < t->in_w;
+                out[((size_t)c * t->tile_h + ty) * t->tile_w + tx] = in ? image[((size_t)c * t->in_h + y) * t->in_w + x] : 0;
+            }
+    return GALA_OK;
+}
+extern "C" int gala_conv_tile_mask(const gala_conv_tiling *t, int ch, const uint64_t *r, int tile, uint64_t *out) {
+    if (!t || !r || !out || ch < 1 || tile < 0 || tile >= t->tiles_x * t->tiles_y) return GALA_EARG;
+    int oy, ox, yo, xo;
+    tile_origin(t, tile, &oy, &ox);
+    for (int c = 0; c < ch; ++c)
+        for (int ty = 0; ty < t->tile_h; ++ty)
+            for (int tx = 0; tx < t->tile_w; ++tx)
+                out[((size_t)c * t->tile_h + ty) * t->tile_w + tx] =
+                    tile_keeps(t, oy, ox, ty, tx, &yo, &xo) ? r[((size_t)c * t->out_h + yo) * t->out_w + xo] : 0;
+    return GALA_OK;
+}
+extern "C" int gala_conv_tile_scatter(const gala_conv_tiling *t, int ch, const uint64_t *vals, int tile,
+                                      uint64_t *out) {
+    if (!t || !vals || !out || ch < 1 || tile < 0 || tile >= t->tiles_x * t->tiles_y) return GALA_EARG;
+    int oy, ox, yo, xo;
+    tile_origin(t, tile, &oy, &ox);
+    for (int c = 0; c < ch; ++c)
+        for (int ty = 0; ty < t->tile_h; ++ty)
+            for (int tx = 0; tx < t->tile_w; ++tx)
+                if (tile_keeps(t, oy, ox, ty, tx, &yo, &xo))
+                    out[((size_t)c * t->out_h + yo) * t->out_w + xo] = vals[((size_t)c * t->tile_h + ty) * t->tile_w + tx];
+    return GALA_OK;
+}

@@ -515,14 +515,25 @@ int launch_hstperm_taps(const gala_ctx *c, void *stream, const u64 *ct_in, const
 int launch_conv_mac(const gala_ctx *c, void *stream, const u64 *w, const u64 *xrot, int batch, int nout, int cn,
                     int nin, int ntap, u64 *acc) {
     if (batch <= 0) return 0;
-    constexpr int TM = 4, TN = 8, WM = 4, WN = 2;
     const int groups = nout * cn, cols = 2 * batch;
     // products are below q^2: 255 of them fit 128 bits when q < 2^60, 63 when q < 2^61
     const int flush_every = c->q < (1ull << 60) ? 255 : 63;
-    const dim3 grid((unsigned)((c->n + 63) / 64), (unsigned)((groups + TM * WM - 1) / (TM * WM)),
-                    (unsigned)((cols + TN * WN - 1) / (TN * WN)));
-    hipLaunchKernelGGL((conv_mac_kernel<TM, TN, WM, WN>), grid, dim3(64 * WM * WN), 0, (hipStream_t)stream, w, xrot, cols,
-                       groups, nin * ntap, acc, c->dev_q.mod, c->n, flush_every);
+    const int nterm = nin * ntap;
+    hipStream_t st = (hipStream_t)stream;
+    auto grid = [&](int tm, int tn, int wm, int wn) {
+        return dim3((unsigned)((c->n + 63) / 64), (unsigned)((groups + tm * wm - 1) / (tm * wm)),
+                    (unsigned)((cols + tn * wn - 1) / (tn * wn)));
+    };
+    // the tile's width follows the number of (input, polynomial) columns: a single input is 2 columns
+    if (cols <= 2)
+        hipLaunchKernelGGL((conv_mac_kernel<8, 2, 4, 1>), grid(8, 2, 4, 1), dim3(256), 0, st, w, xrot, cols, groups, nterm, acc,
+                           c->dev_q.mod, c->n, flush_every);
+    else if (cols <= 4)
+        hipLaunchKernelGGL((conv_mac_kernel<4, 4, 4, 1>), grid(4, 4, 4, 1), dim3(256), 0, st, w, xrot, cols, groups, nterm, acc,
+                           c->dev_q.mod, c->n, flush_every);
+    else
+        hipLaunchKernelGGL((conv_mac_kernel<4, 8, 4, 2>), grid(4, 8, 4, 2), dim3(512), 0, st, w, xrot, cols, groups, nterm, acc,
+                           c->dev_q.mod, c->n, flush_every);
     return last_error();
 }
 

@@ -115,3 +115,32 @@ def _is_prime(v):
         else:
             return False
     return True
+
+
+@dataclass(frozen=True)
+class ConvLayer:
+    """One convolution of a network: c_o kernels of k x k over c_i channels of an in_hw x in_hw image."""
+    name: str
+    c_o: int
+    c_i: int
+    k: int
+    stride: int
+    in_hw: int
+
+
+def resnet18_layers():
+    """The 20 convolutions and the final FC of an ImageNet-shaped ResNet-18 (random weights stand in for a
+    trained network): conv1 7x7/2 on 224x224, four stages of two basic blocks at 64/128/256/512 channels on
+    56/28/14/7 pixels, 1x1/2 downsample convolutions at the stage transitions, FC 512 -> 1000."""
+    layers = [ConvLayer("conv1", 64, 3, 7, 2, 224)]
+    layers += [ConvLayer(f"layer1.{b}.conv{c}", 64, 64, 3, 1, 56) for b in (0, 1) for c in (1, 2)]
+    ch_in, hw = 64, 56
+    for stage, ch in ((2, 128), (3, 256), (4, 512)):
+        layers.append(ConvLayer(f"layer{stage}.0.conv1", ch, ch_in, 3, 2, hw))
+        layers.append(ConvLayer(f"layer{stage}.0.downsample", ch, ch_in, 1, 2, hw))
+        hw //= 2
+        layers += [ConvLayer(f"layer{stage}.0.conv2", ch, ch, 3, 1, hw),
+                   ConvLayer(f"layer{stage}.1.conv1", ch, ch, 3, 1, hw),
+                   ConvLayer(f"layer{stage}.1.conv2", ch, ch, 3, 1, hw)]
+        ch_in = ch
+    return layers, FcShape("fc_1000x512_b1", 1000, 512, 1)

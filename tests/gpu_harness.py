@@ -56,3 +56,33 @@ def gpu_he_conv(ctx, plan, cts_coeff, r, mask_seed):
     ws = torch.empty(max(ws_bytes, 8), dtype=torch.uint8, device="cuda")
     cnt = plan.he_conv(d_in, batch, d_r, mask_seed, d_out, ws, ws_bytes)
     return export_cts(ctx, d_out, batch * plan.nout).reshape(batch, plan.nout, 2 * ctx.n), cnt
+
+
+def gpu_conv_layer(ctx, sk, K, image, r_layer, stride, mask_seed, key_seed=8, enc_seed=0):
+    """A whole convolution layer on one image (c_i x H x W) through the library: spatial tiling, stride,
+    he_conv over the tiles.  Returns (tiling, plan, tile inputs, tile masks, input cts, output cts, counts)."""
+    c_o, c_i, k_h, k_w = K.shape
+    _, H, W = image.shape
+    t = ctx.conv_tiling(H, W, k_h, k_w, stride)
+    plan = ctx.conv_plan(K, t.tile_h, t.tile_w)
+    gk = ctx.galois_keygen(sk, plan.rotations(), seed=key_seed)
+    plan.bind(gk)
+    tiles = t.tiles
+    x_tiles = np.stack([ctx.tile_extract(t, image, b) for b in range(tiles)])
+    r_tiles = np.stack([ctx.tile_mask(t, r_layer, b) for b in range(tiles)])
+    slots = np.stack([plan.pack_input(x_tiles[b]) for b in range(tiles)])          # (tiles, nin, n)
+    cts = np.stack([[ctx.encrypt(sk, slots[b, I], seed=enc_seed + 1000 * b + I) for I in range(plan.nin)]
+                    for b in range(tiles)])
+    got, cnt = gpu_he_conv(ctx, plan, cts, r_tiles, mask_seed)
+    return t, plan, x_tiles, r_tiles, cts, got, cnt
+
+
+def stitch_layer_share(ctx, sk, t, plan, got, c_o):
+    """Client side: decrypt every tile's outputs, unpack, keep the outputs each tile is responsible for."""
+    share = np.zeros((c_o, t.out_h, t.out_w), np.uint64)
+    for b in range(t.tiles):
+        tile_vals = np.zeros((c_o, t.tile_h, t.tile_w), np.uint64)
+        for O in range(plan.nout):
+            plan.unpack_share(O, ctx.decrypt(sk, got[b, O]), tile_vals)
+        ctx.tile_scatter(t, tile_vals, b, share)
+    return share
