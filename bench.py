@@ -20,37 +20,40 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 # Integer-ALU roofline: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 32-bit integer lane-operations per second.
-# The multiply instructions the modular arithmetic is made of (v_mul_hi_u32, v_mad_u64_u32) were measured
-# at 0.82-0.94 of this rate with csrc/probe_int_mul.hip, so multiplies and adds are priced alike.
+# The instructions the modular arithmetic is made of (v_mad_u64_u32, v_mul_lo_u32, 32-bit adds) were all
+# measured at 0.93-0.96 of this rate with csrc/probe_int_mul.hip, so multiplies and adds are priced alike.
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
-# 32-bit integer operations of the 64-bit modular primitives (multiplies, multiply-adds, adds with
-# carry and the selects of conditional subtractions; no address arithmetic, no moves):
-OPS_CONST_MUL = 16      # a*w mod q with precomputed quotient: 4+3+3 multiplies, 6 adds/subs -> [0,2q)
-OPS_LAZY_ADDSUB = 2     # 64-bit add or sub on lazy residues
-OPS_BUTTERFLY = OPS_CONST_MUL + 2 * OPS_LAZY_ADDSUB          # 20
-OPS_MAC128 = 8          # 64x64 product added into a 128-bit sum: 4 multiply-adds, 4 carry adds
-OPS_REDUCE128 = 2 * OPS_CONST_MUL + 4                        # 128-bit sum -> canonical residue
+# 32-bit integer operations of the leanest formulation known here of each 64-bit modular primitive
+# (multiply-adds, adds with carry, selects; no address arithmetic, no register moves):
+OPS_CONST_MUL = 13      # y*w mod q, w with precomputed quotient: 6 for the high product, 6 + 1 for y*w - h*q
+OPS_CSUB = 4            # conditional subtraction: sub, subb, two selects on the borrow
+OPS_BF_FWD = OPS_CONST_MUL + 1 + 3             # lazy forward butterfly: x + v, x + 2q - v
+OPS_BF_INV = OPS_CONST_MUL + 1 + 3 + OPS_CSUB  # inverse butterfly: x + y reduced, (x - y + 2q) * w
 
 
 def ops_per_fused_perm(n, logn, ndigits):
     """Algorithmic integer operations of one ScMult + Perm + Add on one ciphertext (one 'fused unit')."""
-    butterflies = (1 + ndigits) * (n // 2) * logn            # one inverse and ndigits forward transforms
-    scmult_c1 = n * (OPS_MAC128 + OPS_REDUCE128)              # c1 (.) w before the inverse transform
-    digits = ndigits * n * 2                                  # shift and mask
-    key_mac = 2 * ndigits * n * OPS_MAC128                    # inner product with (b_j, a_j)
-    c0_mac = n * OPS_MAC128                                   # permuted c0 (.) w
-    accumulate = 2 * n * (OPS_REDUCE128 + OPS_LAZY_ADDSUB)    # reduce and Add into the running sum
-    return butterflies * OPS_BUTTERFLY + scmult_c1 + digits + key_mac + c0_mac + accumulate
+    half = n // 2
+    inverse = half * (logn - 1) * OPS_BF_INV + half * (2 * OPS_CONST_MUL + 2 * OPS_CSUB + 4)   # n^-1 folded in
+    forward = half * logn * OPS_BF_FWD + n * OPS_CSUB           # one conditional subtraction per coefficient
+    scmult_c1 = n * OPS_CONST_MUL                               # c1 (.) w before the inverse transform
+    c0_term = n * (OPS_CONST_MUL + 1)                           # permuted c0 (.) w added to the sum
+    digits = ndigits * n * 2                                    # shift and mask
+    key_mac = 2 * ndigits * n * (OPS_CONST_MUL + 1)             # inner product with (b_j, a_j)
+    accumulate = 2 * n * OPS_CSUB                               # keep the running sums below 8q
+    return inverse + ndigits * forward + scmult_c1 + c0_term + digits + key_mac + accumulate
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="fc_128x1024_b64", choices=["fc_128x1024_b64", "fc_1000x2048_b64"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run one plain device copy of this size (calibrates rocprofv3 HBM byte counters)")
     ap.add_argument("--cpu-sample", type=int, default=64, help="inputs the oracle is timed on")
     ap.add_argument("--cpu-repeat", type=int, default=3, help="passes of the oracle over the sample")
     args = ap.parse_args()
@@ -84,6 +87,12 @@ def main():
     def step():
         return plan.he_fc(d_in, batch, d_r, 17, d_out, ws, ws_bytes, stream=stream)
 
+    if args.copy_probe_mib:
+        src = torch.ones(args.copy_probe_mib << 17, dtype=torch.int64, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         cnt = step()
     torch.cuda.synchronize()
@@ -106,6 +115,9 @@ def main():
     ops = unit_ops * batch * (plan.G - 1)          # the g = 0 unit has no Perm and is not counted
     kavg_ms = float(np.mean(kernel_ms)) if kernel_ms else float("nan")
     achieved = ops / (kavg_ms * 1e-3) / 1e12
+    # HBM bytes per launch of the Perm kernel measured with rocprofv3 counters for the default workload
+    # (profiles/perm_accumulate_fc_128x1024_b64_hbm_traffic.txt); not measured for the others
+    traffic = (47438 + 34816) * 1024.0 if args.workload == "fc_128x1024_b64" else None
     out = {
         "metric": "HE rotations/sec and he_fc/he_conv layers/sec at n=2048; % of HBM/int roofline",
         "value": rot_per_s,
@@ -124,8 +136,8 @@ def main():
         "layers_per_s": 1e3 / ms_per_step,
         "inputs_per_s": batch * 1e3 / ms_per_step,
         "ops_per_step": cnt,
-        "roofline": {"bound": "alu", "kernel": "perm_accumulate_kernel", "achieved": achieved, "peak": ALU_PEAK_TOPS,
-                     "unit": "TOP/s (32-bit integer)", "frac": achieved / ALU_PEAK_TOPS, "traffic": None,
+        "roofline": {"bound": "alu", "kernel": "perm_accumulate_2048", "achieved": achieved, "peak": ALU_PEAK_TOPS,
+                     "unit": "TOP/s (32-bit integer)", "frac": achieved / ALU_PEAK_TOPS, "traffic": traffic,
                      "kernel_ms_avg": kavg_ms, "fused_units_per_launch": units, "int_ops_per_unit": unit_ops},
     }
     if not args.no_cpu_baseline:
