@@ -45,16 +45,84 @@ def ops_per_fused_perm(n, logn, ndigits):
     return inverse + ndigits * forward + scmult_c1 + c0_term + digits + key_mac + accumulate
 
 
+def timed(fn, torch, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def secondary_workloads(ctx, sk, H, torch):
+    """Short runs of the other entry points at n = 2048 (same context and keys' secret): plain Perm on a batch of
+    ciphertexts, the 16x16x128 / 3x3x128 convolution of batch 16, and the 1000x2048 FC of batch 64."""
+    from paper_2105_01827_amd import workloads as wl
+    par, res = wl.DEFAULT, {}
+    rng = np.random.default_rng(0)
+    # gala_rotate: 4096 ciphertexts, one rotation
+    count = 4096
+    gk = ctx.galois_keygen(sk, [(0, 1)], seed=3)
+    d_in = H.to_dev(rng.integers(0, par.q, size=(count, 2 * par.n), dtype=np.uint64))
+    d_out = H.dev_empty(count * 2 * par.n)
+    t = timed(lambda: ctx.rotate(gk, d_in, count, (0, 1), d_out), torch, 100, 20)
+    res["rotate_4096_cts"] = {"ms": t * 1e3, "rotations_per_s": count / t}
+    del d_in, d_out
+    # he_conv, 16x16x128 input, 128 kernels of 3x3, batch 16
+    s = wl.CONV_16x16_128_3x3
+    K, x, r = wl.conv_inputs(s)
+    plan = ctx.conv_plan(K, s.u_h, s.u_w)
+    gkc = ctx.galois_keygen(sk, plan.rotations(), seed=8)
+    plan.bind(gkc)
+    d_in = H.to_dev(rng.integers(0, par.q, size=(s.batch * plan.nin, 2 * par.n), dtype=np.uint64))
+    d_out = H.dev_empty(s.batch * plan.nout * 2 * par.n)
+    d_r = H.to_dev(r)
+    wsb = plan.workspace_bytes(s.batch)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    cnt = {}
+    def conv():
+        cnt.update(plan.he_conv(d_in, s.batch, d_r, 3, d_out, ws, wsb))
+    t = timed(conv, torch, 100, 20)
+    res[s.name] = {"ms_per_layer": t * 1e3, "layers_per_s": 1 / t, "inputs_per_s": s.batch / t,
+                   "rotations_per_s": (cnt["perm"] + cnt["hstperm_in"]) / t, "ops_per_layer": dict(cnt)}
+    del plan, d_in, d_out, ws
+    # he_fc 1000x2048, batch 64 (1023 rotations per input)
+    f = wl.FC_1000x2048
+    W, x, r = wl.fc_inputs(f)
+    plan = ctx.fc_plan(W)
+    gkf = ctx.galois_keygen(sk, plan.rotations(), seed=1)
+    plan.bind(gkf)
+    d_in = H.to_dev(rng.integers(0, par.q, size=(f.batch, 2 * par.n), dtype=np.uint64))
+    d_out = H.dev_empty(f.batch * 2 * par.n)
+    d_r = H.to_dev(r)
+    wsb = plan.workspace_bytes(f.batch)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    def fc():
+        cnt.update(plan.he_fc(d_in, f.batch, d_r, 5, d_out, ws, wsb))
+    t = timed(fc, torch, 30, 5)
+    res[f.name] = {"ms_per_layer": t * 1e3, "layers_per_s": 1 / t, "inputs_per_s": f.batch / t,
+                   "rotations_per_s": cnt["perm"] / t}
+    return res
+
+
+OPS_MAC128 = 10         # 64x64 product added into a 128-bit sum: 4 multiply-adds and 6 carry additions
+OPS_REDUCE128 = 2 * OPS_CONST_MUL + 2 * OPS_CSUB + 1
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="fc_128x1024_b64", choices=["fc_128x1024_b64", "fc_1000x2048_b64"])
+    ap.add_argument("--workload", default="fc_128x1024_b64",
+                    choices=["fc_128x1024_b64", "fc_1000x2048_b64", "conv_16x16x128_3x3x128_b16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device copy of this size (calibrates rocprofv3 HBM byte counters)")
-    ap.add_argument("--cpu-sample", type=int, default=64, help="inputs the oracle is timed on")
+    ap.add_argument("--cpu-sample", type=int, default=64, help="inputs the oracle is timed on (FC workloads)")
     ap.add_argument("--cpu-repeat", type=int, default=3, help="passes of the oracle over the sample")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -68,24 +136,44 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     par = wl.DEFAULT
-    shape = {"fc_128x1024_b64": wl.FC_128x1024, "fc_1000x2048_b64": wl.FC_1000x2048}[args.workload]
     ctx = binding.Context(par.n, par.q, par.p, par.gadget_bits)
-    W, x, r = wl.fc_inputs(shape)
     sk = ctx.keygen(0)
-    plan = ctx.fc_plan(W)
-    gk = ctx.galois_keygen(sk, plan.rotations(), seed=1)
-    plan.bind(gk)
-    batch = shape.batch
-    cts = np.stack([ctx.encrypt(sk, plan.pack_input(x[b]), seed=b) for b in range(batch)])
-    d_in = H.import_cts(ctx, cts)
-    d_out = H.dev_empty(batch * 2 * par.n)
-    d_r = H.to_dev(r)
-    ws_bytes = plan.workspace_bytes(batch)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream()
+    is_conv = args.workload.startswith("conv")
+    if is_conv:
+        shape = wl.CONV_16x16_128_3x3
+        K, x, r = wl.conv_inputs(shape)
+        plan = ctx.conv_plan(K, shape.u_h, shape.u_w)
+        gk = ctx.galois_keygen(sk, plan.rotations(), seed=8)
+        plan.bind(gk)
+        batch = shape.batch
+        slots = np.stack([plan.pack_input(x[b]) for b in range(batch)])
+        cts = np.stack([[ctx.encrypt(sk, slots[b, I], seed=1000 * b + I) for I in range(plan.nin)] for b in range(batch)])
+        d_in = H.import_cts(ctx, cts.reshape(-1, 2 * par.n))
+        d_out = H.dev_empty(batch * plan.nout * 2 * par.n)
+        d_r = H.to_dev(r)
+        ws_bytes = plan.workspace_bytes(batch)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        ctx.profile_select(1)
 
-    def step():
-        return plan.he_fc(d_in, batch, d_r, 17, d_out, ws, ws_bytes, stream=stream)
+        def step():
+            return plan.he_conv(d_in, batch, d_r, 3, d_out, ws, ws_bytes, stream=stream)
+    else:
+        shape = {"fc_128x1024_b64": wl.FC_128x1024, "fc_1000x2048_b64": wl.FC_1000x2048}[args.workload]
+        W, x, r = wl.fc_inputs(shape)
+        plan = ctx.fc_plan(W)
+        gk = ctx.galois_keygen(sk, plan.rotations(), seed=1)
+        plan.bind(gk)
+        batch = shape.batch
+        cts = np.stack([ctx.encrypt(sk, plan.pack_input(x[b]), seed=b) for b in range(batch)])
+        d_in = H.import_cts(ctx, cts)
+        d_out = H.dev_empty(batch * 2 * par.n)
+        d_r = H.to_dev(r)
+        ws_bytes = plan.workspace_bytes(batch)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+
+        def step():
+            return plan.he_fc(d_in, batch, d_r, 17, d_out, ws, ws_bytes, stream=stream)
 
     if args.copy_probe_mib:
         src = torch.ones(args.copy_probe_mib << 17, dtype=torch.int64, device="cuda")
@@ -105,19 +193,32 @@ def main():
     t1 = time.perf_counter()
     kernel_ms = ctx.profile_collect(args.steps)
     ctx.profile_enable(0)
+    ctx.profile_select(0)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    perms_per_step = cnt["perm"]
-    rot_per_s = perms_per_step / (ms_per_step * 1e-3)
-    # roofline of the dominant kernel (rotate-and-accumulate): G fused units per input
-    units = batch * plan.G
-    unit_ops = ops_per_fused_perm(par.n, 11, ctx.ndigits)
-    ops = unit_ops * batch * (plan.G - 1)          # the g = 0 unit has no Perm and is not counted
+    rotations = cnt["perm"] + cnt["hstperm_in"]
+    rot_per_s = rotations / (ms_per_step * 1e-3)
     kavg_ms = float(np.mean(kernel_ms)) if kernel_ms else float("nan")
+    if is_conv:
+        # dominant kernel: the per-coefficient multiply-accumulate (ScMult + Add of Sec. III-B)
+        macs = cnt["scmult"] * 2 * par.n                       # two polynomials per ciphertext
+        unit_ops = OPS_MAC128
+        ops = macs * OPS_MAC128 + batch * plan.nout * plan.cn * 2 * par.n * OPS_REDUCE128
+        kernel, units, traffic = "conv_mac_kernel", macs, None
+        config = {"workload": args.workload, "layer": "he_conv", "n": par.n, "c_o": shape.c_o, "c_i": shape.c_i,
+                  "k": shape.k_h, "image": [shape.u_h, shape.u_w], "batch": batch, "c_n": plan.cn,
+                  "gadget_digits": ctx.ndigits}
+    else:
+        # dominant kernel: rotate-and-accumulate, G fused ScMult+Perm+Add units per input
+        unit_ops = ops_per_fused_perm(par.n, 11, ctx.ndigits)
+        ops = unit_ops * batch * (plan.G - 1)      # the g = 0 unit has no Perm and is not counted
+        kernel, units = "perm_accumulate_2048", batch * plan.G
+        # HBM bytes per launch measured with rocprofv3 counters for the default workload
+        # (profiles/perm_accumulate_fc_128x1024_b64_hbm_traffic.txt); not measured for the others
+        traffic = (47438 + 34816) * 1024.0 if args.workload == "fc_128x1024_b64" else None
+        config = {"workload": args.workload, "layer": "he_fc", "n": par.n, "n_o": shape.n_o, "n_i": shape.n_i,
+                  "batch": batch, "G": plan.G, "gadget_digits": ctx.ndigits}
     achieved = ops / (kavg_ms * 1e-3) / 1e12
-    # HBM bytes per launch of the Perm kernel measured with rocprofv3 counters for the default workload
-    # (profiles/perm_accumulate_fc_128x1024_b64_hbm_traffic.txt); not measured for the others
-    traffic = (47438 + 34816) * 1024.0 if args.workload == "fc_128x1024_b64" else None
     out = {
         "metric": "HE rotations/sec and he_fc/he_conv layers/sec at n=2048; % of HBM/int roofline",
         "value": rot_per_s,
@@ -131,33 +232,48 @@ def main():
         "vs_baseline": None,
         "dtype": "u64",
         "data": "synthetic",
-        "config": {"workload": args.workload, "layer": "he_fc", "n": par.n, "n_o": shape.n_o, "n_i": shape.n_i,
-                   "batch": batch, "G": plan.G, "gadget_digits": ctx.ndigits},
+        "config": config,
         "layers_per_s": 1e3 / ms_per_step,
         "inputs_per_s": batch * 1e3 / ms_per_step,
         "ops_per_step": cnt,
-        "roofline": {"bound": "alu", "kernel": "perm_accumulate_2048", "achieved": achieved, "peak": ALU_PEAK_TOPS,
+        "roofline": {"bound": "alu", "kernel": kernel, "achieved": achieved, "peak": ALU_PEAK_TOPS,
                      "unit": "TOP/s (32-bit integer)", "frac": achieved / ALU_PEAK_TOPS, "traffic": traffic,
-                     "kernel_ms_avg": kavg_ms, "fused_units_per_launch": units, "int_ops_per_unit": unit_ops},
+                     "kernel_ms_avg": kavg_ms, "units_per_launch": units, "int_ops_per_unit": unit_ops},
     }
+    if not args.no_secondary:
+        out["also"] = secondary_workloads(ctx, sk, H, torch)
     if not args.no_cpu_baseline:
         from oracle.oracle import Oracle
         o = Oracle(par.n, par.q, par.p, par.gadget_bits)
-        sample = min(args.cpu_sample, batch)
         osk = o.keygen(0)
-        wpoly = o.fc_encode_rowwise(W)
-        ksk = o.fc_keys(osk, shape.n_o, shape.n_i, seed=1)
-        c0 = time.perf_counter()
-        for _ in range(args.cpu_repeat):
-            outs, ocnt = o.he_fc_batch(wpoly, shape.n_o, shape.n_i, cts[:sample], ksk, r[:sample], 17)
-        c1 = time.perf_counter()
-        got = H.export_cts(ctx, d_out, batch)
-        assert np.array_equal(got[:sample], outs), "HIP result differs from the oracle"
-        out["cpu_baseline"] = {"value": args.cpu_repeat * ocnt["perm"] / (c1 - c0), "unit": "rotations/s", "cores": o.max_threads(),
-                               "kind": "oracle",
-                               "sample": f"{sample} of the {batch} inputs of {args.workload}, {args.cpu_repeat} passes "
-                                         f"(he_fc_batch: {ocnt['perm']} Perm, {ocnt['scmult']} ScMult per pass), "
-                                         f"{c1 - c0:.1f} s wall"}
+        got = H.export_cts(ctx, d_out, batch * (plan.nout if is_conv else 1))
+        if is_conv:
+            # one output ciphertext of one input: 1152 ScMult, 7 Perm plus the 128 hoisted input rotations
+            tk, gkk = o.conv_keys(osk, shape.tuple, seed=8)
+            mask = o.conv_mask_slots(shape.tuple, r[0], 3, 0, 0)
+            c0 = time.perf_counter()
+            want, ocnt = o.he_conv_block(shape.tuple, K, 0, cts[0], tk, gkk, mask)
+            c1 = time.perf_counter()
+            assert np.array_equal(got[0], want), "HIP result differs from the oracle"
+            out["cpu_baseline"] = {"value": (ocnt["perm"] + ocnt["hstperm_in"]) / (c1 - c0), "unit": "rotations/s",
+                                   "cores": 1, "kind": "oracle",
+                                   "sample": f"output ciphertext 0 of input 0 of {args.workload} (he_conv_block: "
+                                             f"{ocnt['scmult']} ScMult, {ocnt['perm']} Perm, {ocnt['hstperm_in']} HstPerm), "
+                                             f"{c1 - c0:.1f} s wall"}
+        else:
+            sample = min(args.cpu_sample, batch)
+            wpoly = o.fc_encode_rowwise(W)
+            ksk = o.fc_keys(osk, shape.n_o, shape.n_i, seed=1)
+            c0 = time.perf_counter()
+            for _ in range(args.cpu_repeat):
+                outs, ocnt = o.he_fc_batch(wpoly, shape.n_o, shape.n_i, cts[:sample], ksk, r[:sample], 17)
+            c1 = time.perf_counter()
+            assert np.array_equal(got[:sample], outs), "HIP result differs from the oracle"
+            out["cpu_baseline"] = {"value": args.cpu_repeat * ocnt["perm"] / (c1 - c0), "unit": "rotations/s",
+                                   "cores": o.max_threads(), "kind": "oracle",
+                                   "sample": f"{sample} of the {batch} inputs of {args.workload}, {args.cpu_repeat} passes "
+                                             f"(he_fc_batch: {ocnt['perm']} Perm, {ocnt['scmult']} ScMult per pass), "
+                                             f"{c1 - c0:.1f} s wall"}
     print(json.dumps(out))
 
 

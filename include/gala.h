@@ -97,6 +97,9 @@ const uint64_t *gala_gauss_cdf(void);
  * capacity = 0 switches it off.  Creates / destroys HIP events, so call it
  * outside timed regions. */
 int gala_profile_enable(gala_ctx *ctx, int capacity);
+/* Which kernel the events bracket: 0 = rotate-and-accumulate (default), 1 = the convolution's
+ * multiply-accumulate kernel inside gala_he_conv. */
+int gala_profile_select(gala_ctx *ctx, int which);
 int gala_profile_collect(gala_ctx *ctx, float *ms, int capacity, int *count);
 
 /* ---- keys (client side, host; Sec. II-C(1)) ------------------------------- */

@@ -61,6 +61,7 @@ SIGNATURES = {
     "gala_ctx_delta": (C.c_uint64, [_VP]),
     "gala_gauss_cdf": (C.POINTER(C.c_uint64), []),
     "gala_profile_enable": (_I, [_VP, _I]),
+    "gala_profile_select": (_I, [_VP, _I]),
     "gala_profile_collect": (_I, [_VP, C.POINTER(C.c_float), _I, C.POINTER(_I)]),
     "gala_keygen": (_I, [_VP, C.c_uint64, C.POINTER(_VP)]),
     "gala_sk_destroy": (None, [_VP]),
@@ -172,6 +173,9 @@ class Context:
 
     def profile_enable(self, capacity):
         _check(self.lib.gala_profile_enable(self.h, capacity), "gala_profile_enable")
+
+    def profile_select(self, which):
+        _check(self.lib.gala_profile_select(self.h, which), "gala_profile_select")
 
     def profile_collect(self, capacity):
         ms = (C.c_float * max(1, capacity))(); n = C.c_int()

@@ -50,6 +50,11 @@ extern "C" int gala_profile_enable(gala_ctx *c, int capacity) {
     }
     return GALA_OK;
 }
+extern "C" int gala_profile_select(gala_ctx *c, int which) {
+    if (!c || (which != 0 && which != 1)) return GALA_EARG;
+    c->prof_which = which;
+    return GALA_OK;
+}
 extern "C" int gala_profile_collect(gala_ctx *c, float *ms, int capacity, int *count) {
     if (!c || !ms || !count) return GALA_EARG;
     const int n = std::min(capacity, c->prof_used);

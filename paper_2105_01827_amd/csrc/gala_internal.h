@@ -71,6 +71,7 @@ struct gala_ctx {
     // measurement aid: event pairs recorded around rotate-and-accumulate launches
     mutable std::vector<void *> prof_events;   // 2*capacity hipEvent_t
     mutable int prof_used = 0;
+    int prof_which = 0;                        // 0: rotate-and-accumulate launches, 1: convolution multiply-accumulate
 };
 
 struct gala_sk {

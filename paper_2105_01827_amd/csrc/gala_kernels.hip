@@ -459,7 +459,7 @@ int launch_perm_accumulate(const gala_ctx *c, void *stream, const PermJob &job) 
     hipStream_t st = (hipStream_t)stream;
     const size_t lds = sizeof(u64) * c->n;
     const dim3 grid((unsigned)(job.items * job.nchunks));
-    const bool timed = (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
+    const bool timed = c->prof_which == 0 && (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
     if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used], st);
     if (uses_fast_perm(c)) {
         const int rc = launch_perm_accumulate_2048(c, stream, job);
@@ -520,6 +520,8 @@ int launch_conv_mac(const gala_ctx *c, void *stream, const u64 *w, const u64 *xr
     const int flush_every = c->q < (1ull << 60) ? 255 : 63;
     const int nterm = nin * ntap;
     hipStream_t st = (hipStream_t)stream;
+    const bool timed = c->prof_which == 1 && (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
+    if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used], st);
     auto grid = [&](int tm, int tn, int wm, int wn) {
         return dim3((unsigned)((c->n + 63) / 64), (unsigned)((groups + tm * wm - 1) / (tm * wm)),
                     (unsigned)((cols + tn * wn - 1) / (tn * wn)));
@@ -534,6 +536,7 @@ int launch_conv_mac(const gala_ctx *c, void *stream, const u64 *w, const u64 *xr
     else
         hipLaunchKernelGGL((conv_mac_kernel<4, 8, 4, 2>), grid(4, 8, 4, 2), dim3(512), 0, st, w, xrot, cols, groups, nterm, acc,
                            c->dev_q.mod, c->n, flush_every);
+    if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used++ + 1], st);
     return last_error();
 }
 

@@ -468,7 +468,7 @@ int launch_perm_accumulate_2048_masked(const gala_ctx *c, void *stream, const Pe
     mj.delta = make_ulonglong2(c->delta, c->delta_s);
     mj.Tp = make_tables(c, c->d_tw2p, c->dev_p);
     hipStream_t st = (hipStream_t)stream;
-    const bool timed = (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
+    const bool timed = c->prof_which == 0 && (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
     if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used], st);
     int rc = launch_2048(c, stream, job, mj);
     if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used++ + 1], st);
