@@ -76,6 +76,7 @@ def secondary_workloads(ctx, sk, H, torch):
     plan = ctx.conv_plan(K, s.u_h, s.u_w)
     gkc = ctx.galois_keygen(sk, plan.rotations(), seed=8)
     plan.bind(gkc)
+    plan.prepare_batched()
     d_in = H.to_dev(rng.integers(0, par.q, size=(s.batch * plan.nin, 2 * par.n), dtype=np.uint64))
     d_out = H.dev_empty(s.batch * plan.nout * 2 * par.n)
     d_r = H.to_dev(r)
@@ -119,6 +120,8 @@ def main():
     ap.add_argument("--workload", default="fc_128x1024_b64",
                     choices=["fc_128x1024_b64", "fc_1000x2048_b64", "conv_16x16x128_3x3x128_b16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--vector-mac", action="store_true",
+                    help="convolution: keep the multiply-accumulate on the vector ALU instead of the matrix cores")
     ap.add_argument("--no-secondary", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device copy of this size (calibrates rocprofv3 HBM byte counters)")
@@ -146,6 +149,8 @@ def main():
         plan = ctx.conv_plan(K, shape.u_h, shape.u_w)
         gk = ctx.galois_keygen(sk, plan.rotations(), seed=8)
         plan.bind(gk)
+        if not args.vector_mac:
+            plan.prepare_batched()      # multiply-accumulate on the matrix cores
         batch = shape.batch
         slots = np.stack([plan.pack_input(x[b]) for b in range(batch)])
         cts = np.stack([[ctx.encrypt(sk, slots[b, I], seed=1000 * b + I) for I in range(plan.nin)] for b in range(batch)])

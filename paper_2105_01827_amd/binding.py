@@ -87,6 +87,7 @@ SIGNATURES = {
     "gala_he_fc": (_I, [_VP, _VP, _VP, _U64P, _I, _U64P, C.c_uint64, _U64P, _VP, C.c_size_t, C.POINTER(OpCount)]),
     "gala_conv_plan_create": (_I, [_VP, _U64P, _I, _I, _I, _I, _I, _I, C.POINTER(_VP)]),
     "gala_conv_plan_destroy": (None, [_VP]),
+    "gala_conv_plan_prepare_batched": (_I, [_VP]),
     "gala_conv_plan_geometry": (_I, [_VP, C.POINTER(C.c_int32)]),
     "gala_conv_plan_rotations": (_I, [_VP, C.POINTER(Rot), C.POINTER(_I)]),
     "gala_conv_plan_bind": (_I, [_VP, _VP]),
@@ -358,6 +359,9 @@ class ConvPlan:
     def bind(self, gk):
         _check(self.ctx.lib.gala_conv_plan_bind(self.h, gk.h), "gala_conv_plan_bind")
         self._gk = gk
+
+    def prepare_batched(self):
+        _check(self.ctx.lib.gala_conv_plan_prepare_batched(self.h), "gala_conv_plan_prepare_batched")
 
     def pack_input(self, x):
         x, xp = _host(x); out = np.empty((self.nin, self.ctx.n), np.uint64)

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgala_hip.so")
-SOURCES = ["gala_host.cpp", "gala_api.cpp", "gala_kernels.hip", "gala_perm2048.hip"]
+SOURCES = ["gala_host.cpp", "gala_api.cpp", "gala_kernels.hip", "gala_perm2048.hip", "gala_conv_mfma.hip"]
 HEADERS = ["gala_internal.h", "modarith.h", os.path.join("..", "..", "include", "gala.h")]
 # packed-FP32 instructions are switched off for every device compile on the test machines
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread", "-Wno-unused-value", "-Wno-unused-command-line-argument",

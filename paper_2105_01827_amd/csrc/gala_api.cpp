@@ -154,8 +154,9 @@ extern "C" int gala_he_fc(const gala_ctx *c, void *stream, const gala_fc_plan *p
 // ---------------------------------------------------------------------------
 namespace {
 struct ConvWorkspace {
-    size_t digits, xrot, acc, partial, total;
+    size_t digits, xrot, acc, partial, xl, tmp, total;
     int chunks;
+    bool mfma;      // the multiply-accumulate of this call runs on the matrix cores
 };
 ConvWorkspace conv_workspace(const gala_conv_plan *pl, int batch) {
     const gala_ctx *c = pl->ctx;
@@ -166,7 +167,17 @@ ConvWorkspace conv_workspace(const gala_conv_plan *pl, int batch) {
     ws.xrot = ws.digits + align_up((size_t)batch * pl->nin * c->ndigits * n * w);
     ws.acc = ws.xrot + align_up((size_t)batch * pl->nin * pl->ntap * 2 * n * w);
     ws.partial = ws.acc + align_up((size_t)batch * pl->nout * pl->cn * 2 * n * w);
-    ws.total = ws.partial + align_up((size_t)batch * pl->nout * (ws.chunks + 1) * 2 * n * w);
+    ws.xl = ws.partial + align_up((size_t)batch * pl->nout * (ws.chunks + 1) * 2 * n * w);
+    ws.mfma = pl->d_wl && 2 * batch >= 16;
+    size_t xl_bytes = 0, tmp_bytes = 0;
+    if (ws.mfma) {
+        int mt, nt, kb;
+        conv_mfma_geometry(pl->nout * pl->cn, 2 * batch, pl->nin * pl->ntap, &mt, &nt, &kb);
+        xl_bytes = conv_mfma_image_bytes(c->n, nt, kb);
+        tmp_bytes = conv_mfma_tmp_bytes(c->n, mt, nt);
+    }
+    ws.tmp = ws.xl + align_up(xl_bytes);
+    ws.total = ws.tmp + align_up(tmp_bytes);
     return ws;
 }
 }  // namespace
@@ -194,7 +205,18 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
     if (launch_hstperm_taps(c, stream, ct_in, digits, nct_in, pl->ntap, pl->d_tap_gal, pl->d_tap_key, keys, xrot))
         return GALA_EHIP;
     // 2. ScMult and Add first: one sum per (output block, kernel order)
-    if (launch_conv_mac(c, stream, pl->d_w, xrot, batch, pl->nout, pl->cn, pl->nin, pl->ntap, acc)) return GALA_EHIP;
+    const bool timed = c->prof_which == 1 && (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
+    if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used], (hipStream_t)stream);
+    if (ws.mfma) {
+        u64 *xl = (u64 *)(base + ws.xl);
+        const int nterm = pl->nin * pl->ntap;
+        if (launch_limb_pack(c, stream, xrot, 1, 2 * batch, nterm, xl)) return GALA_EHIP;
+        if (launch_conv_mfma(c, stream, pl->d_wl, xl, batch, pl->nout * pl->cn, nterm, (u64 *)(base + ws.tmp), acc))
+            return GALA_EHIP;
+    } else if (launch_conv_mac(c, stream, pl->d_w, xrot, batch, pl->nout, pl->cn, pl->nin, pl->ntap, acc)) {
+        return GALA_EHIP;
+    }
+    if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used++ + 1], (hipStream_t)stream);
     // 3. Perm second: rotate each kernel order into place and add, then subtract the mask
     PermJob job{};
     job.ct_in = acc;

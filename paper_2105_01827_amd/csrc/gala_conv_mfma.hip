@@ -1,0 +1,224 @@
+// The convolution's ScMult/Add step on the matrix cores.
+//
+// For one coefficient index i the step is a dense product  S_i[m][c] = sum_k W_i[m][k] * X_i[k][c]  of 60-bit
+// residues (m: output block x kernel order, k: input ciphertext x tap, c: input x polynomial), accumulated
+// exactly and reduced mod q once at the end.  It is mapped on the int8 MFMA units by writing every residue in
+// eight balanced base-256 digits d_0..d_7 in [-128,127] (x = sum d_u 256^u): then
+//     S = sum_{s=0..14} 256^s * D_s,   D_s[m][c] = sum_{u+v=s} sum_k W_u[m][k] * X_v[k][c]
+// and every D_s is an int8 x int8 -> int32 matrix product (|D_s| <= 8 * 144 * 2^14 < 2^31, exact).
+// One v_mfma_i32_16x16x64_i8 multiplies a 16x64 by a 64x16 digit tile; the 64 (u,v) digit pairs of a tile feed
+// 15 accumulators of four registers each.  The recombination of the 15 diagonals, the reduction mod q and the
+// transposition back to coefficient-major order run on the vector ALU in the same kernel.
+//
+// Operand images ("digit planes"): 16-byte chunks  [i][tile][kblock][digit][lane]  where lane l of the MFMA
+// holds row/column l%16 of the tile and the 16 terms k = 64*kblock + 16*(l/16) + j; one digit plane of a
+// tile is 1 KiB contiguous.
+#include <hip/hip_runtime.h>
+
+#include "gala_internal.h"
+
+namespace gala {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// balanced base-256 digits of x < 2^61, one per byte: the bytes of x + 0x80..80 are the digits plus 128
+__device__ __forceinline__ u64 balanced_digits(u64 x) {
+    const u64 k = 0x8080808080808080ull;
+    return (x + k) ^ k;
+}
+
+// Builds the digit-plane image of 16 rows x 16 terms x 16 coefficients per workgroup.  Phase 1 reads the
+// source with the coefficient index fastest (128-byte segments), phase 2 writes with the row fastest, so that
+// the 16 chunks of a (coefficient, digit) land in 256 contiguous bytes.  mode 0: source is the encoded
+// kernels [row][e][i]; mode 1: the tap-rotated inputs [input][e][polynomial][i] with row = 2*input + polynomial.
+__global__ __launch_bounds__(256) void limb_pack_kernel(const u64 *src, int mode, int rows, int nterm, int n, int tiles,
+                                                        int kblocks, v4i *dst) {
+    __shared__ u64 stage[16 * 16 * 17];   // [row][term][coefficient], coefficient dimension padded
+    const int i0 = blockIdx.x * 16, tile = blockIdx.y, kb = blockIdx.z >> 2, g = blockIdx.z & 3;
+    {
+        const int il = threadIdx.x & 15, rl = threadIdx.x >> 4, row = tile * 16 + rl;
+        const size_t row_off = mode == 0 ? (size_t)row * nterm * n : ((size_t)(row >> 1) * nterm * 2 + (row & 1)) * n;
+        const size_t e_stride = mode == 0 ? (size_t)n : 2 * (size_t)n;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int e = kb * 64 + g * 16 + j;
+            const u64 x = (row < rows && e < nterm && i0 + il < n) ? src[row_off + (size_t)e * e_stride + i0 + il] : 0;
+            stage[(rl * 16 + j) * 17 + il] = balanced_digits(x);
+        }
+    }
+    __syncthreads();
+    const int rl = threadIdx.x & 15, il = threadIdx.x >> 4;
+    if (i0 + il >= n) return;
+    u64 d[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) d[j] = stage[(rl * 16 + j) * 17 + il];
+    const size_t base = ((((size_t)(i0 + il) * tiles + tile) * kblocks + kb) * 8) * 64 + (size_t)(g * 16 + rl);
+#pragma unroll
+    for (int limb = 0; limb < 8; ++limb) {
+        v4i c;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            u32 wd = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) wd |= (u32)((d[4 * t + b] >> (8 * limb)) & 0xff) << (8 * b);
+            c[t] = (int)wd;
+        }
+        dst[base + (size_t)limb * 64] = c;
+    }
+}
+
+// sum_s 256^s * c[s] for 15 signed 32-bit diagonals, as an unsigned 128-bit value (the true sum is non-negative)
+__device__ __forceinline__ u128 recombine(const int (&c)[15]) {
+    i64 d[8];
+#pragma unroll
+    for (int t = 0; t < 7; ++t) d[t] = (i64)c[2 * t] + ((i64)c[2 * t + 1] << 8);
+    d[7] = (i64)c[14];
+    i64 e[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) e[u] = d[2 * u] + (d[2 * u + 1] << 16);
+    typedef __int128 i128;
+    const i128 v = (i128)e[0] + ((i128)e[1] << 32) + ((i128)e[2] << 64) + ((i128)e[3] << 96);
+    return (u128)v;
+}
+
+// One workgroup = one coefficient, WAVES row tiles (one per wavefront) and 2 column tiles.  The column
+// operand (rotated inputs) of a term block is staged once in LDS and read by all wavefronts; every wavefront
+// streams its own row operand (encoded kernels) from memory, so each operand byte is fetched once per
+// workgroup.  Loads of the next term block are issued before the MFMAs of the current one.
+// Output: tmp[i][row][column] (rows and columns padded to tiles), transposed afterwards.
+template <int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void conv_mfma_kernel(const v4i *wl, const v4i *xl, u64 *tmp, int mtiles,
+                                                               int ntiles, int kblocks, Modulus mod) {
+    constexpr int NT = 64 * WAVES, BLOADS = 1024 / NT;
+    __shared__ v4i bsm[2][2][8][64];     // [buffer][column tile][digit][lane], 32 KiB
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t i = blockIdx.x;
+    const int mt = blockIdx.y * WAVES + wave, nt0 = blockIdx.z * 2;
+    const bool live = mt < mtiles;
+    const int mtc = live ? mt : mtiles - 1;
+    // cooperative load of the column operand: 2 tiles x 8 digits x 64 lanes chunks, BLOADS per thread
+    auto b_src = [&](int kb, int r) -> const v4i * {
+        const int c = threadIdx.x + NT * r, nl = c >> 9, nt = min(nt0 + nl, ntiles - 1);
+        return xl + (((i * ntiles + nt) * kblocks + kb) * 8) * 64 + (c & 511);
+    };
+    auto a_src = [&](int kb) { return wl + (((i * mtiles + mtc) * kblocks + kb) * 8) * 64 + lane; };
+    v4i s[2][15];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int k = 0; k < 15; ++k) s[t][k] = v4i{0, 0, 0, 0};
+    v4i av[8], an[8], bstage[BLOADS];
+#pragma unroll
+    for (int r = 0; r < BLOADS; ++r) bstage[r] = *b_src(0, r);
+    {
+        const v4i *a = a_src(0);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) av[u] = a[(size_t)u * 64];
+    }
+    for (int kb = 0; kb < kblocks; ++kb) {
+        v4i *flat = &bsm[kb & 1][0][0][0];
+#pragma unroll
+        for (int r = 0; r < BLOADS; ++r) flat[threadIdx.x + NT * r] = bstage[r];
+        __syncthreads();     // the other buffer was last read two barriers ago
+        const int nxt = min(kb + 1, kblocks - 1);
+#pragma unroll
+        for (int r = 0; r < BLOADS; ++r) bstage[r] = *b_src(nxt, r);
+        {
+            const v4i *a = a_src(nxt);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) an[u] = a[(size_t)u * 64];
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            v4i bv[8];
+#pragma unroll
+            for (int v = 0; v < 8; ++v) bv[v] = bsm[kb & 1][t][v][lane];
+            // column-major over the digit pairs: the same accumulator comes back only every seventh instruction
+#pragma unroll
+            for (int v = 0; v < 8; ++v)
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    s[t][u + v] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[u], bv[v], s[t][u + v], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) av[u] = an[u];
+    }
+    if (!live) return;
+    // lane holds rows 4*(lane/16) + r, column lane%16 of each 16x16 output tile
+    const size_t rowsP = (size_t)mtiles * 16, colsP = (size_t)ntiles * 16;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        if (nt0 + t >= ntiles) break;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            int c[15];
+#pragma unroll
+            for (int k = 0; k < 15; ++k) c[k] = s[t][k][r];
+            const u64 val = reduce128(recombine(c), mod);
+            const int m = mt * 16 + 4 * (lane >> 4) + r, col = (nt0 + t) * 16 + (lane & 15);
+            tmp[(i * rowsP + m) * colsP + col] = val;
+        }
+    }
+}
+
+// acc[input][row][polynomial][i] = tmp[i][row][2*input + polynomial]: a tiled transpose through LDS
+__global__ __launch_bounds__(256) void conv_untranspose_kernel(const u64 *tmp, u64 *acc, int rowsP, int colsP, int groups,
+                                                               int cols, int n) {
+    __shared__ u64 tile[32][33];
+    const int i0 = blockIdx.x * 32, r0 = blockIdx.y * 32;       // r = row * colsP + column, flattened
+    const size_t flat = (size_t)rowsP * colsP;
+    for (int k = threadIdx.x; k < 32 * 32; k += 256) {
+        const int di = k >> 5, dr = k & 31;
+        if (i0 + di < n && (size_t)(r0 + dr) < flat) tile[di][dr] = tmp[(size_t)(i0 + di) * flat + r0 + dr];
+    }
+    __syncthreads();
+    for (int k = threadIdx.x; k < 32 * 32; k += 256) {
+        const int dr = k >> 5, di = k & 31;
+        const int r = r0 + dr, row = r / colsP, col = r % colsP;
+        if (i0 + di < n && row < groups && col < cols)
+            acc[(((size_t)(col >> 1) * groups + row) * 2 + (col & 1)) * n + i0 + di] = tile[di][dr];
+    }
+}
+
+}  // namespace
+
+void conv_mfma_geometry(int groups, int cols, int nterm, int *mtiles, int *ntiles, int *kblocks) {
+    *mtiles = (groups + 15) / 16;
+    *ntiles = (cols + 15) / 16;
+    *kblocks = (nterm + 63) / 64;
+}
+size_t conv_mfma_image_bytes(int n, int tiles, int kblocks) {
+    return (size_t)n * tiles * kblocks * 8 * 64 * 16;
+}
+size_t conv_mfma_tmp_bytes(int n, int mtiles, int ntiles) { return (size_t)n * mtiles * 16 * ntiles * 16 * sizeof(u64); }
+// mode 0: encoded kernels (rows = groups), mode 1: rotated inputs (rows = 2*batch columns)
+int launch_limb_pack(const gala_ctx *c, void *stream, const u64 *src, int mode, int rows, int nterm, u64 *dst) {
+    int tiles, unused, kblocks;
+    conv_mfma_geometry(rows, rows, nterm, &tiles, &unused, &kblocks);
+    const dim3 grid((unsigned)((c->n + 15) / 16), (unsigned)tiles, (unsigned)(kblocks * 4));
+    hipLaunchKernelGGL(limb_pack_kernel, grid, dim3(256), 0, (hipStream_t)stream, src, mode, rows, nterm, c->n, tiles,
+                       kblocks, reinterpret_cast<v4i *>(dst));
+    return (int)hipGetLastError();
+}
+int launch_conv_mfma(const gala_ctx *c, void *stream, const u64 *wl, const u64 *xl, int batch, int groups, int nterm,
+                     u64 *tmp, u64 *acc) {
+    int mtiles, ntiles, kblocks;
+    const int cols = 2 * batch;
+    conv_mfma_geometry(groups, cols, nterm, &mtiles, &ntiles, &kblocks);
+    hipStream_t st = (hipStream_t)stream;
+    constexpr int WAVES = 4;
+    const dim3 grid((unsigned)c->n, (unsigned)((mtiles + WAVES - 1) / WAVES), (unsigned)((ntiles + 1) / 2));
+    hipLaunchKernelGGL(conv_mfma_kernel<WAVES>, grid, dim3(64 * WAVES), 0, st, reinterpret_cast<const v4i *>(wl),
+                       reinterpret_cast<const v4i *>(xl), tmp, mtiles, ntiles, kblocks, c->dev_q.mod);
+    int rc = (int)hipGetLastError();
+    if (rc) return rc;
+    const int rowsP = mtiles * 16, colsP = ntiles * 16;
+    const dim3 tgrid((unsigned)((c->n + 31) / 32), (unsigned)((rowsP * colsP + 31) / 32));
+    hipLaunchKernelGGL(conv_untranspose_kernel, tgrid, dim3(256), 0, st, tmp, acc, rowsP, colsP, groups, cols, c->n);
+    return (int)hipGetLastError();
+}
+
+}  // namespace gala

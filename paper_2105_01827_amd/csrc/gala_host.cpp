@@ -716,9 +716,25 @@ extern "C" int gala_conv_plan_create(gala_ctx *c, const uint64_t *K, int c_o, in
     *out = pl;
     return GALA_OK;
 }
+extern "C" int gala_conv_plan_prepare_batched(gala_conv_plan *pl) {
+    if (!pl) return GALA_EARG;
+    if (pl->d_wl) return GALA_OK;
+    const gala_ctx *c = pl->ctx;
+    if (c->n < 16) return GALA_ESHAPE;
+    const int groups = pl->nout * pl->cn, nterm = pl->nin * pl->ntap;
+    int mt, nt, kb;
+    conv_mfma_geometry(groups, groups, nterm, &mt, &nt, &kb);
+    if (hipMalloc((void **)&pl->d_wl, conv_mfma_image_bytes(c->n, mt, kb)) != hipSuccess) return GALA_ENOMEM;
+    if (launch_limb_pack(c, nullptr, pl->d_w, 0, groups, nterm, pl->d_wl) || hipDeviceSynchronize() != hipSuccess) {
+        hipFree(pl->d_wl);
+        pl->d_wl = nullptr;
+        return GALA_EHIP;
+    }
+    return GALA_OK;
+}
 extern "C" void gala_conv_plan_destroy(gala_conv_plan *pl) {
     if (!pl) return;
-    hipFree(pl->d_w); hipFree(pl->d_tap_gal); hipFree(pl->d_grp_gal); hipFree(pl->d_tap_key); hipFree(pl->d_grp_key);
+    hipFree(pl->d_w); hipFree(pl->d_wl); hipFree(pl->d_tap_gal); hipFree(pl->d_grp_gal); hipFree(pl->d_tap_key); hipFree(pl->d_grp_key);
     free_mask_layout(&pl->mask_d);
     delete pl;
 }

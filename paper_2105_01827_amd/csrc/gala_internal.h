@@ -127,6 +127,7 @@ struct gala_conv_plan {
     int T = 0, cn = 0, hpos = 0, nin = 0, nout = 0, ntap = 0, centre = 0;
     std::vector<int> tap_gal, grp_gal; // Galois elements of taps (ntap) and kernel orders (cn)
     gala::u64 *d_w = nullptr;          // nout x cn x nin x ntap x n encoded kernels, evaluation domain
+    gala::u64 *d_wl = nullptr;         // the same as balanced base-256 digit planes for the matrix-core path, or null
     int *d_tap_gal = nullptr, *d_tap_key = nullptr;   // ntap
     int *d_grp_gal = nullptr, *d_grp_key = nullptr;   // cn
     const gala_gk *bound = nullptr;
@@ -199,5 +200,14 @@ int launch_hstperm_taps(const gala_ctx *ctx, void *stream, const u64 *ct_in, con
 // acc[b][O][gam] = sum_{I,tap} w[O][gam][I][tap] (.) xrot[b][I][tap]   (both polynomials)
 int launch_conv_mac(const gala_ctx *ctx, void *stream, const u64 *w, const u64 *xrot, int batch, int nout, int cn,
                     int nin, int ntap, u64 *acc);
+
+// Matrix-core path of the convolution's multiply-accumulate (gala_conv_mfma.hip): digit-plane images of the
+// encoded kernels (built once per plan) and of the rotated inputs (built per call), then one MFMA kernel.
+void conv_mfma_geometry(int groups, int cols, int nterm, int *mtiles, int *ntiles, int *kblocks);
+size_t conv_mfma_image_bytes(int n, int tiles, int kblocks);
+int launch_limb_pack(const gala_ctx *ctx, void *stream, const u64 *src, int mode, int rows, int nterm, u64 *dst);
+size_t conv_mfma_tmp_bytes(int n, int mtiles, int ntiles);
+int launch_conv_mfma(const gala_ctx *ctx, void *stream, const u64 *wl, const u64 *xl, int batch, int groups,
+                     int nterm, u64 *tmp, u64 *acc);
 
 }  // namespace gala

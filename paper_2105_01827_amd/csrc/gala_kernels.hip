@@ -520,8 +520,6 @@ int launch_conv_mac(const gala_ctx *c, void *stream, const u64 *w, const u64 *xr
     const int flush_every = c->q < (1ull << 60) ? 255 : 63;
     const int nterm = nin * ntap;
     hipStream_t st = (hipStream_t)stream;
-    const bool timed = c->prof_which == 1 && (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
-    if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used], st);
     auto grid = [&](int tm, int tn, int wm, int wn) {
         return dim3((unsigned)((c->n + 63) / 64), (unsigned)((groups + tm * wm - 1) / (tm * wm)),
                     (unsigned)((cols + tn * wn - 1) / (tn * wn)));
@@ -536,7 +534,6 @@ int launch_conv_mac(const gala_ctx *c, void *stream, const u64 *w, const u64 *xr
     else
         hipLaunchKernelGGL((conv_mac_kernel<4, 8, 4, 2>), grid(4, 8, 4, 2), dim3(512), 0, st, w, xrot, cols, groups, nterm, acc,
                            c->dev_q.mod, c->n, flush_every);
-    if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used++ + 1], st);
     return last_error();
 }
 

@@ -163,8 +163,9 @@ def test_he_fc_config3_1000x2048_batch64_sampled():
         assert np.array_equal((share + r[b]) % np.uint64(par.p), want), b
 
 
-def conv_case(par, shape, batch, oracle_outputs, seed=0):
-    """oracle_outputs: list of (b, O) ciphertexts the oracle recomputes."""
+def conv_case(par, shape, batch, oracle_outputs, seed=0, matrix_cores=False):
+    """oracle_outputs: list of (b, O) ciphertexts the oracle recomputes.  matrix_cores: keep the digit-plane
+    image of the kernels so that the multiply-accumulate runs on the MFMA units (needs batch >= 8)."""
     H = harness()
     ctx, o = both(par)
     co, ci, kh, kw, uh, uw = shape
@@ -175,6 +176,8 @@ def conv_case(par, shape, batch, oracle_outputs, seed=0):
     assert (plan.T, plan.cn, plan.nin, plan.nout, plan.ntap) == (geo["T"], geo["cn"], geo["nin"], geo["nout"], geo["ntap"])
     gk = ctx.galois_keygen(sk, plan.rotations(), seed=8)
     plan.bind(gk)
+    if matrix_cores:
+        plan.prepare_batched()
     slots = np.stack([plan.pack_input(x[b]) for b in range(batch)])           # (batch, nin, n)
     assert np.array_equal(slots[0], o.conv_pack_input(shape, x[0]))
     cts = np.stack([[ctx.encrypt(sk, slots[b, I], seed=1000 * b + I) for I in range(plan.nin)] for b in range(batch)])
@@ -230,6 +233,35 @@ def test_he_conv_small_rings(n, p_limit, gb, shape, batch):
         for O in range(plan.nout):
             plan.unpack_share(O, ctx.decrypt(sk, got[b, O]), share)
         assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_conv(K, x[b], par.p))
+
+
+@pytest.mark.parametrize("n,p_limit,gb,shape,batch", [
+    (16, 1 << 7, 4, (4, 4, 3, 3, 2, 2), 8),            # one 16-coefficient group, one tile each way
+    (64, 1 << 9, 4, (8, 8, 3, 3, 2, 4), 9),            # ragged column tile (18 of 32 columns)
+    (64, 1 << 9, 4, (20, 40, 3, 3, 2, 2), 8),          # 360 terms: six blocks of 64, ragged rows
+    (512, 1 << 14, 8, (20, 12, 3, 3, 5, 6), 12),
+])
+def test_he_conv_on_matrix_cores_small_rings(n, p_limit, gb, shape, batch):
+    par = small_params(n, p_limit=p_limit, gadget_bits=gb)
+    co, ci, kh, kw, uh, uw = shape
+    o = Oracle(par.n, par.q, par.p, par.gadget_bits)
+    nout = o.conv_geometry(*shape)["nout"]
+    picks = [(b, O) for b in (0, batch // 2, batch - 1) for O in range(nout)]
+    ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, shape, batch, picks, seed=n + 1, matrix_cores=True)
+    for b in range(batch):
+        share = np.zeros((co, uh, uw), np.uint64)
+        for O in range(plan.nout):
+            plan.unpack_share(O, ctx.decrypt(sk, got[b, O]), share)
+        assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_conv(K, x[b], par.p))
+
+
+def test_he_conv_config4_matrix_cores_equals_vector_path():
+    """Both implementations of the multiply-accumulate give the same ciphertexts on the whole config-4 batch."""
+    par = wl.DEFAULT
+    s = wl.CONV_16x16_128_3x3
+    a = conv_case(par, s.tuple, s.batch, [(3, 9)], matrix_cores=True)
+    b = conv_case(par, s.tuple, s.batch, [], matrix_cores=False)
+    assert np.array_equal(a[7], b[7])
 
 
 def test_he_conv_config4_sampled():
