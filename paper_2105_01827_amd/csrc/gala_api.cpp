@@ -201,9 +201,15 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
     const size_t nct_in = (size_t)batch * pl->nin;
     const u64 *keys = pl->bound ? pl->bound->d_keys : nullptr;
     // 1. input rotations: one DecPerm per input ciphertext, one HstPerm per non-central tap
-    if (pl->ntap > 1 && launch_decperm(c, stream, ct_in, nct_in, digits)) return GALA_EHIP;
-    if (launch_hstperm_taps(c, stream, ct_in, digits, nct_in, pl->ntap, pl->d_tap_gal, pl->d_tap_key, keys, xrot))
-        return GALA_EHIP;
+    if (uses_fast_hoist(c) && (pl->ntap == 1 || (pl->bound && pl->bound->d_keys2))) {
+        if (launch_hoist_taps_2048(c, stream, ct_in, nct_in, pl->ntap, pl->d_tap_gal, pl->d_tap_key,
+                                   pl->bound ? pl->bound->d_keys2 : nullptr, digits, xrot))
+            return GALA_EHIP;
+    } else {
+        if (pl->ntap > 1 && launch_decperm(c, stream, ct_in, nct_in, digits)) return GALA_EHIP;
+        if (launch_hstperm_taps(c, stream, ct_in, digits, nct_in, pl->ntap, pl->d_tap_gal, pl->d_tap_key, keys, xrot))
+            return GALA_EHIP;
+    }
     // 2. ScMult and Add first: one sum per (output block, kernel order)
     const bool timed = c->prof_which == 1 && (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
     if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used], (hipStream_t)stream);

@@ -206,6 +206,9 @@ int launch_conv_mac(const gala_ctx *ctx, void *stream, const u64 *w, const u64 *
 void conv_mfma_geometry(int groups, int cols, int nterm, int *mtiles, int *ntiles, int *kblocks);
 size_t conv_mfma_image_bytes(int n, int tiles, int kblocks);
 int launch_limb_pack(const gala_ctx *ctx, void *stream, const u64 *src, int mode, int rows, int nterm, u64 *dst);
+bool uses_fast_hoist(const gala_ctx *ctx);
+int launch_hoist_taps_2048(const gala_ctx *ctx, void *stream, const u64 *ct_in, size_t count, int ntap,
+                           const int *tap_gal, const int *tap_key, const u64 *keys2, u64 *digits, u64 *xrot);
 size_t conv_mfma_tmp_bytes(int n, int mtiles, int ntiles);
 int launch_conv_mfma(const gala_ctx *ctx, void *stream, const u64 *wl, const u64 *xl, int batch, int groups,
                      int nterm, u64 *tmp, u64 *acc);

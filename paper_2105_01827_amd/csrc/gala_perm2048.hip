@@ -411,6 +411,97 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
     }
 }
 
+// Hoisted rotations of the input ciphertexts (Sec. III-B: one DecPerm shared by all the taps of a kernel,
+// then one HstPerm per tap), as two launches so that both fill the chip at small batches.
+//
+// DecPerm: one workgroup per (ciphertext, digit); each repeats the inverse transform of c1 and runs the
+// forward transform of its digit.  digits[ct][j][i] holds lazy values (any 64-bit word below 16q), which is
+// what the constant multiplications of the inner product accept.
+constexpr int HOIST_DIGITS = 3;
+__global__ __launch_bounds__(NT) void decperm_2048(const u64 *ct_in, u64 *digits, Tables2048 T, int gadget_bits,
+                                                   int ndigits) {
+    __shared__ u64 bufA[LDS_WORDS], bufB[LDS_WORDS];
+    const int tid = threadIdx.x;
+    const int ct = blockIdx.x / ndigits, j = blockIdx.x % ndigits;
+    const u64 *c1 = ct_in + (size_t)ct * 2 * N + N;
+    u64 a[PER];
+    const ulonglong2 *c1v = reinterpret_cast<const ulonglong2 *>(c1 + 8 * tid);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const ulonglong2 cv = c1v[k];
+        a[2 * k] = cv.x;
+        a[2 * k + 1] = cv.y;
+    }
+    inverse_in_regs(a, bufA, bufB, T, tid);      // LDS phases A B A
+    const u64 digit_mask = (1ull << gadget_bits) - 1;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) a[k] = (a[k] >> (j * gadget_bits)) & digit_mask;
+    forward_to_lds(a, bufA, bufB, T, tid);       // LDS phases B A B A, ends on a barrier
+    u64 *out = digits + ((size_t)ct * ndigits + j) * N;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) out[tid + k * NT] = bufA[pad(tid + k * NT)];
+}
+
+// HstPerm: one workgroup per (ciphertext, tap).  c0 and the digits are read through the automorphism's index
+// map straight from memory: the map sends every aligned block of 64 indices onto another such block, so a
+// wavefront's gather still touches whole cache lines.  Output: xrot[ct][tap][c0|c1][i], canonical.
+__global__ __launch_bounds__(NT) void hstperm_taps_2048(const u64 *ct_in, const u64 *digits, int ntap, const int *tap_gal,
+                                                        const int *tap_key, const u64 *keys2, u64 *xrot, Tables2048 T,
+                                                        int ndigits) {
+    const int tid = threadIdx.x;
+    const int ct = blockIdx.x / ntap, tap = blockIdx.x % ntap;
+    const u64 *c0 = ct_in + (size_t)ct * 2 * N, *c1 = c0 + N;
+    u64 *out = xrot + ((size_t)ct * ntap + tap) * 2 * N;
+    const int gal = tap_gal[tap];
+    if (gal == 1) {
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int i = tid + k * NT;
+            out[i] = c0[i];
+            out[N + i] = c1[i];
+        }
+        return;
+    }
+    const NegQ q = T.nq;
+    const u64 *dsrc = digits + (size_t)ct * ndigits * N;
+    const ulonglong2 *key = reinterpret_cast<const ulonglong2 *>(keys2) + (size_t)tap_key[tap] * ndigits * 2 * N;
+    // two batches of four coefficients keep the loads of a batch in flight together at a modest register count
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        constexpr int H = PER / 2;
+        int idx[H], src[H];
+        u64 s0[H], s1[H];
+#pragma unroll
+        for (int k = 0; k < H; ++k) {
+            idx[k] = tid + (half * H + k) * NT;
+            src[k] = galois_index11(idx[k], gal);
+            s0[k] = c0[src[k]];
+            s1[k] = 0;
+        }
+        for (int j = 0; j < ndigits; ++j) {
+            const ulonglong2 *kb = key + (size_t)(2 * j) * N, *ka = kb + N;
+            ulonglong2 b[H], aa[H];
+            u64 d[H];
+#pragma unroll
+            for (int k = 0; k < H; ++k) {
+                d[k] = dsrc[(size_t)j * N + src[k]];
+                b[k] = kb[idx[k]];
+                aa[k] = ka[idx[k]];
+            }
+#pragma unroll
+            for (int k = 0; k < H; ++k) {
+                s0[k] += mul_const(d[k], b[k].x, b[k].y, q);    // each product is below 2q: at most 7q in all
+                s1[k] += mul_const(d[k], aa[k].x, aa[k].y, q);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < H; ++k) {
+            out[idx[k]] = reduce64(s0[k], T.mod);
+            out[N + idx[k]] = reduce64(s1[k], T.mod);
+        }
+    }
+}
+
 // out[item] = sum over the first `used` partial ciphertexts of the item (mod q); one thread per word pair
 __global__ void sum_partials_kernel(const u64 *partial, int slots, int used, u64 *out, size_t words, u64 q) {
     const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -476,6 +567,23 @@ int launch_perm_accumulate_2048_masked(const gala_ctx *c, void *stream, const Pe
     const size_t words = (size_t)job.items * 2 * N;
     hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, job.partial, job.slots,
                        job.nchunks + 1, fin.ct_out, words, c->q);
+    return (int)hipGetLastError();
+}
+
+bool uses_fast_hoist(const gala_ctx *c) { return uses_fast_perm(c) && c->ndigits <= HOIST_DIGITS; }
+int launch_hoist_taps_2048(const gala_ctx *c, void *stream, const u64 *ct_in, size_t count, int ntap, const int *tap_gal,
+                           const int *tap_key, const u64 *keys2, u64 *digits, u64 *xrot) {
+    if (!count) return 0;
+    const Tables2048 T = make_tables(c, c->d_tw2, c->dev_q);
+    hipStream_t st = (hipStream_t)stream;
+    if (ntap > 1) {
+        hipLaunchKernelGGL(decperm_2048, dim3((unsigned)(count * c->ndigits)), dim3(NT), 0, st, ct_in, digits, T,
+                           c->gadget_bits, c->ndigits);
+        const int rc = (int)hipGetLastError();
+        if (rc) return rc;
+    }
+    hipLaunchKernelGGL(hstperm_taps_2048, dim3((unsigned)(count * ntap)), dim3(NT), 0, st, ct_in, digits, ntap, tap_gal,
+                       tap_key, keys2, xrot, T, c->ndigits);
     return (int)hipGetLastError();
 }
 
