@@ -15,13 +15,13 @@ int galois_element(int n, int swap, int step);
 
 namespace {
 
-// Workgroups the rotate-and-accumulate launch aims for: a few per compute unit
-// (256 CUs) so that every CU has several transforms in flight.
+// Workgroups the rotate-and-accumulate launch aims for: what the chip holds at once (256 CUs, three
+// workgroups each at this kernel's register count), so that the launch has no partly filled last round.
 int target_workgroups() {
     static int v = [] {
         const char *e = std::getenv("GALA_WG_TARGET");
         int t = e ? std::atoi(e) : 0;
-        return t > 0 ? t : 1024;
+        return t > 0 ? t : 768;
     }();
     return v;
 }
@@ -201,28 +201,46 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
     const size_t nct_in = (size_t)batch * pl->nin;
     const u64 *keys = pl->bound ? pl->bound->d_keys : nullptr;
     // 1. input rotations: one DecPerm per input ciphertext, one HstPerm per non-central tap
-    if (uses_fast_hoist(c) && (pl->ntap == 1 || (pl->bound && pl->bound->d_keys2))) {
-        if (launch_hoist_taps_2048(c, stream, ct_in, nct_in, pl->ntap, pl->d_tap_gal, pl->d_tap_key,
-                                   pl->bound ? pl->bound->d_keys2 : nullptr, digits, xrot))
-            return GALA_EHIP;
-    } else {
-        if (pl->ntap > 1 && launch_decperm(c, stream, ct_in, nct_in, digits)) return GALA_EHIP;
-        if (launch_hstperm_taps(c, stream, ct_in, digits, nct_in, pl->ntap, pl->d_tap_gal, pl->d_tap_key, keys, xrot))
-            return GALA_EHIP;
-    }
     // 2. ScMult and Add first: one sum per (output block, kernel order)
+    const bool fast_hoist = uses_fast_hoist(c) && (pl->ntap == 1 || (pl->bound && pl->bound->d_keys2));
+    const u64 *keys2 = pl->bound ? pl->bound->d_keys2 : nullptr;
+    const int nterm = pl->nin * pl->ntap, groups = pl->nout * pl->cn;
     const bool timed = c->prof_which == 1 && (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
-    if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used], (hipStream_t)stream);
-    if (ws.mfma) {
-        u64 *xl = (u64 *)(base + ws.xl);
-        const int nterm = pl->nin * pl->ntap;
-        if (launch_limb_pack(c, stream, xrot, 1, 2 * batch, nterm, xl)) return GALA_EHIP;
-        if (launch_conv_mfma(c, stream, pl->d_wl, xl, batch, pl->nout * pl->cn, nterm, (u64 *)(base + ws.tmp), acc))
+    auto mark = [&](int end) {
+        if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used + end], (hipStream_t)stream);
+        if (timed && end) ++c->prof_used;
+    };
+    if (ws.mfma && fast_hoist) {
+        // the rotated inputs go straight into the column image of the matrix-core product
+        u64 *xl = (u64 *)(base + ws.xl), *tmp = (u64 *)(base + ws.tmp);
+        if (launch_hstperm_pack_2048(c, stream, ct_in, digits, batch, pl->nin, pl->ntap, pl->d_tap_gal, pl->d_tap_key, keys2, xl))
             return GALA_EHIP;
-    } else if (launch_conv_mac(c, stream, pl->d_w, xrot, batch, pl->nout, pl->cn, pl->nin, pl->ntap, acc)) {
-        return GALA_EHIP;
+        mark(0);
+        if (launch_conv_mfma(c, stream, pl->d_wl, xl, batch, groups, nterm, tmp)) return GALA_EHIP;
+        mark(1);
+        if (launch_conv_untranspose(c, stream, tmp, batch, groups, acc)) return GALA_EHIP;
+    } else {
+        if (fast_hoist) {
+            if (launch_hoist_taps_2048(c, stream, ct_in, nct_in, pl->ntap, pl->d_tap_gal, pl->d_tap_key, keys2, digits, xrot))
+                return GALA_EHIP;
+        } else {
+            if (pl->ntap > 1 && launch_decperm(c, stream, ct_in, nct_in, digits)) return GALA_EHIP;
+            if (launch_hstperm_taps(c, stream, ct_in, digits, nct_in, pl->ntap, pl->d_tap_gal, pl->d_tap_key, keys, xrot))
+                return GALA_EHIP;
+        }
+        if (ws.mfma) {
+            u64 *xl = (u64 *)(base + ws.xl), *tmp = (u64 *)(base + ws.tmp);
+            if (launch_limb_pack(c, stream, xrot, 1, 2 * batch, nterm, xl)) return GALA_EHIP;
+            mark(0);
+            if (launch_conv_mfma(c, stream, pl->d_wl, xl, batch, groups, nterm, tmp)) return GALA_EHIP;
+            mark(1);
+            if (launch_conv_untranspose(c, stream, tmp, batch, groups, acc)) return GALA_EHIP;
+        } else {
+            mark(0);
+            if (launch_conv_mac(c, stream, pl->d_w, xrot, batch, pl->nout, pl->cn, pl->nin, pl->ntap, acc)) return GALA_EHIP;
+            mark(1);
+        }
     }
-    if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used++ + 1], (hipStream_t)stream);
     // 3. Perm second: rotate each kernel order into place and add, then subtract the mask
     PermJob job{};
     job.ct_in = acc;

@@ -10,9 +10,12 @@
 // 15 accumulators of four registers each.  The recombination of the 15 diagonals, the reduction mod q and the
 // transposition back to coefficient-major order run on the vector ALU in the same kernel.
 //
-// Operand images ("digit planes"): 16-byte chunks  [i][tile][kblock][digit][lane]  where lane l of the MFMA
-// holds row/column l%16 of the tile and the 16 terms k = 64*kblock + 16*(l/16) + j; one digit plane of a
-// tile is 1 KiB contiguous.
+// Operand images ("digit planes") are made of 16-byte chunks: lane l of the MFMA holds row/column l%16 of a
+// tile and the 16 terms k = 64*kblock + 16*(l/16) + j of one digit.
+//   row operand (encoded kernels):     [i][tile][kblock][digit][lane]   one digit plane of a tile is 1 KiB
+//   column operand (rotated inputs):   [tile][kblock][lane][i][digit]   the 8 digits of a coefficient are 128 B
+// The column layout lets the kernel that produces the rotated inputs write it with the coefficient index
+// running across the lanes.  Chunks whose 16 terms all lie beyond the last term are never read.
 #include <hip/hip_runtime.h>
 
 #include "gala_internal.h"
@@ -28,9 +31,22 @@ __device__ __forceinline__ u64 balanced_digits(u64 x) {
     return (x + k) ^ k;
 }
 
+// the 16 bytes of digit `limb` of 16 balanced-digit words
+__device__ __forceinline__ v4i digit_chunk(const u64 (&d)[16], int limb) {
+    v4i c;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        u32 wd = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) wd |= (u32)((d[4 * t + b] >> (8 * limb)) & 0xff) << (8 * b);
+        c[t] = (int)wd;
+    }
+    return c;
+}
+
 // Builds the digit-plane image of 16 rows x 16 terms x 16 coefficients per workgroup.  Phase 1 reads the
-// source with the coefficient index fastest (128-byte segments), phase 2 writes with the row fastest, so that
-// the 16 chunks of a (coefficient, digit) land in 256 contiguous bytes.  mode 0: source is the encoded
+// source with the coefficient index fastest (128-byte segments); phase 2 writes with the index fastest that
+// is contiguous in the destination layout.  mode 0: source is the encoded
 // kernels [row][e][i]; mode 1: the tap-rotated inputs [input][e][polynomial][i] with row = 2*input + polynomial.
 __global__ __launch_bounds__(256) void limb_pack_kernel(const u64 *src, int mode, int rows, int nterm, int n, int tiles,
                                                         int kblocks, v4i *dst) {
@@ -48,24 +64,18 @@ __global__ __launch_bounds__(256) void limb_pack_kernel(const u64 *src, int mode
         }
     }
     __syncthreads();
-    const int rl = threadIdx.x & 15, il = threadIdx.x >> 4;
+    // phase 2: mode 0 runs the row across the threads, mode 1 the coefficient
+    const int rl = mode == 0 ? threadIdx.x & 15 : threadIdx.x >> 4, il = mode == 0 ? threadIdx.x >> 4 : threadIdx.x & 15;
     if (i0 + il >= n) return;
     u64 d[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) d[j] = stage[(rl * 16 + j) * 17 + il];
-    const size_t base = ((((size_t)(i0 + il) * tiles + tile) * kblocks + kb) * 8) * 64 + (size_t)(g * 16 + rl);
+    const size_t lane = (size_t)(g * 16 + rl);
+    const size_t base = mode == 0 ? ((((size_t)(i0 + il) * tiles + tile) * kblocks + kb) * 8) * 64 + lane
+                                  : ((((size_t)tile * kblocks + kb) * 64 + lane) * n + i0 + il) * 8;
+    const size_t step = mode == 0 ? 64 : 1;
 #pragma unroll
-    for (int limb = 0; limb < 8; ++limb) {
-        v4i c;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            u32 wd = 0;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) wd |= (u32)((d[4 * t + b] >> (8 * limb)) & 0xff) << (8 * b);
-            c[t] = (int)wd;
-        }
-        dst[base + (size_t)limb * 64] = c;
-    }
+    for (int limb = 0; limb < 8; ++limb) dst[base + (size_t)limb * step] = digit_chunk(d, limb);
 }
 
 // sum_s 256^s * c[s] for 15 signed 32-bit diagonals, as an unsigned 128-bit value (the true sum is non-negative)
@@ -89,7 +99,7 @@ __device__ __forceinline__ u128 recombine(const int (&c)[15]) {
 // Output: tmp[i][row][column] (rows and columns padded to tiles), transposed afterwards.
 template <int WAVES>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void conv_mfma_kernel(const v4i *wl, const v4i *xl, u64 *tmp, int mtiles,
-                                                               int ntiles, int kblocks, Modulus mod) {
+                                                               int ntiles, int kblocks, int nblk16, int n, Modulus mod) {
     constexpr int NT = 64 * WAVES, BLOADS = 1024 / NT;
     __shared__ v4i bsm[2][2][8][64];     // [buffer][column tile][digit][lane], 32 KiB
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -97,12 +107,22 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void conv_mfma_kernel(const 
     const int mt = blockIdx.y * WAVES + wave, nt0 = blockIdx.z * 2;
     const bool live = mt < mtiles;
     const int mtc = live ? mt : mtiles - 1;
-    // cooperative load of the column operand: 2 tiles x 8 digits x 64 lanes chunks, BLOADS per thread
-    auto b_src = [&](int kb, int r) -> const v4i * {
-        const int c = threadIdx.x + NT * r, nl = c >> 9, nt = min(nt0 + nl, ntiles - 1);
-        return xl + (((i * ntiles + nt) * kblocks + kb) * 8) * 64 + (c & 511);
+    const v4i zero = v4i{0, 0, 0, 0};
+    // cooperative load of the column operand: 2 tiles x 64 lanes x 8 digits chunks, BLOADS per thread, with the
+    // digit fastest (128 contiguous bytes per lane); chunks beyond the last term block are zero without a load
+    auto b_load = [&](int kb, int r) -> v4i {
+        const int c = threadIdx.x + NT * r, nl = c >> 9, ln = (c >> 3) & 63, dg = c & 7;
+        const int nt = min(nt0 + nl, ntiles - 1);
+        if (kb * 4 + (ln >> 4) >= nblk16) return zero;
+        return xl[((((size_t)nt * kblocks + kb) * 64 + ln) * n + i) * 8 + dg];
     };
-    auto a_src = [&](int kb) { return wl + (((i * mtiles + mtc) * kblocks + kb) * 8) * 64 + lane; };
+    auto b_slot = [&](int r) { const int c = threadIdx.x + NT * r; return (c >> 9) * 512 + (c & 7) * 64 + ((c >> 3) & 63); };
+    auto a_load = [&](int kb, v4i (&dst)[8]) {
+        const v4i *a = wl + (((i * mtiles + mtc) * kblocks + kb) * 8) * 64 + lane;
+        const bool on = kb * 4 + (lane >> 4) < nblk16;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) dst[u] = on ? a[(size_t)u * 64] : zero;
+    };
     v4i s[2][15];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
@@ -110,25 +130,17 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void conv_mfma_kernel(const 
         for (int k = 0; k < 15; ++k) s[t][k] = v4i{0, 0, 0, 0};
     v4i av[8], an[8], bstage[BLOADS];
 #pragma unroll
-    for (int r = 0; r < BLOADS; ++r) bstage[r] = *b_src(0, r);
-    {
-        const v4i *a = a_src(0);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) av[u] = a[(size_t)u * 64];
-    }
+    for (int r = 0; r < BLOADS; ++r) bstage[r] = b_load(0, r);
+    a_load(0, av);
     for (int kb = 0; kb < kblocks; ++kb) {
         v4i *flat = &bsm[kb & 1][0][0][0];
 #pragma unroll
-        for (int r = 0; r < BLOADS; ++r) flat[threadIdx.x + NT * r] = bstage[r];
+        for (int r = 0; r < BLOADS; ++r) flat[b_slot(r)] = bstage[r];
         __syncthreads();     // the other buffer was last read two barriers ago
         const int nxt = min(kb + 1, kblocks - 1);
 #pragma unroll
-        for (int r = 0; r < BLOADS; ++r) bstage[r] = *b_src(nxt, r);
-        {
-            const v4i *a = a_src(nxt);
-#pragma unroll
-            for (int u = 0; u < 8; ++u) an[u] = a[(size_t)u * 64];
-        }
+        for (int r = 0; r < BLOADS; ++r) bstage[r] = b_load(nxt, r);
+        a_load(nxt, an);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             v4i bv[8];
@@ -204,20 +216,24 @@ int launch_limb_pack(const gala_ctx *c, void *stream, const u64 *src, int mode, 
     return (int)hipGetLastError();
 }
 int launch_conv_mfma(const gala_ctx *c, void *stream, const u64 *wl, const u64 *xl, int batch, int groups, int nterm,
-                     u64 *tmp, u64 *acc) {
+                     u64 *tmp) {
     int mtiles, ntiles, kblocks;
-    const int cols = 2 * batch;
-    conv_mfma_geometry(groups, cols, nterm, &mtiles, &ntiles, &kblocks);
-    hipStream_t st = (hipStream_t)stream;
+    conv_mfma_geometry(groups, 2 * batch, nterm, &mtiles, &ntiles, &kblocks);
     constexpr int WAVES = 4;
     const dim3 grid((unsigned)c->n, (unsigned)((mtiles + WAVES - 1) / WAVES), (unsigned)((ntiles + 1) / 2));
-    hipLaunchKernelGGL(conv_mfma_kernel<WAVES>, grid, dim3(64 * WAVES), 0, st, reinterpret_cast<const v4i *>(wl),
-                       reinterpret_cast<const v4i *>(xl), tmp, mtiles, ntiles, kblocks, c->dev_q.mod);
-    int rc = (int)hipGetLastError();
-    if (rc) return rc;
+    hipLaunchKernelGGL(conv_mfma_kernel<WAVES>, grid, dim3(64 * WAVES), 0, (hipStream_t)stream,
+                       reinterpret_cast<const v4i *>(wl), reinterpret_cast<const v4i *>(xl), tmp, mtiles, ntiles, kblocks,
+                       (nterm + 15) / 16, c->n, c->dev_q.mod);
+    return (int)hipGetLastError();
+}
+int launch_conv_untranspose(const gala_ctx *c, void *stream, const u64 *tmp, int batch, int groups, u64 *acc) {
+    int mtiles, ntiles, kblocks;
+    const int cols = 2 * batch;
+    conv_mfma_geometry(groups, cols, 1, &mtiles, &ntiles, &kblocks);
     const int rowsP = mtiles * 16, colsP = ntiles * 16;
     const dim3 tgrid((unsigned)((c->n + 31) / 32), (unsigned)((rowsP * colsP + 31) / 32));
-    hipLaunchKernelGGL(conv_untranspose_kernel, tgrid, dim3(256), 0, st, tmp, acc, rowsP, colsP, groups, cols, c->n);
+    hipLaunchKernelGGL(conv_untranspose_kernel, tgrid, dim3(256), 0, (hipStream_t)stream, tmp, acc, rowsP, colsP, groups,
+                       cols, c->n);
     return (int)hipGetLastError();
 }
 

@@ -211,6 +211,9 @@ int launch_hoist_taps_2048(const gala_ctx *ctx, void *stream, const u64 *ct_in, 
                            const int *tap_gal, const int *tap_key, const u64 *keys2, u64 *digits, u64 *xrot);
 size_t conv_mfma_tmp_bytes(int n, int mtiles, int ntiles);
 int launch_conv_mfma(const gala_ctx *ctx, void *stream, const u64 *wl, const u64 *xl, int batch, int groups,
-                     int nterm, u64 *tmp, u64 *acc);
+                     int nterm, u64 *tmp);
+int launch_conv_untranspose(const gala_ctx *ctx, void *stream, const u64 *tmp, int batch, int groups, u64 *acc);
+int launch_hstperm_pack_2048(const gala_ctx *ctx, void *stream, const u64 *ct_in, u64 *digits, int batch, int nin,
+                             int ntap, const int *tap_gal, const int *tap_key, const u64 *keys2, u64 *xl);
 
 }  // namespace gala

@@ -502,6 +502,71 @@ __global__ __launch_bounds__(NT) void hstperm_taps_2048(const u64 *ct_in, const 
     }
 }
 
+// HstPerm of all taps written straight into the column-operand image of the matrix-core multiply-accumulate
+// (16-byte chunks [tile][kblock][lane][i][digit], lane = 16*(term block % 4) + column % 16, one balanced
+// base-256 digit of 16 consecutive terms per chunk).  One thread owns one coefficient of one input and 16
+// consecutive terms (input ciphertext, tap), so a chunk is assembled in registers and the eight digit
+// chunks of a coefficient leave as 128 contiguous bytes.
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(NT) void hstperm_pack_2048(const u64 *ct_in, const u64 *digits, int nin, int ntap, int kblocks,
+                                                        const int *tap_gal, const int *tap_key, const u64 *keys2,
+                                                        v4i_t *xl, Tables2048 T, int ndigits) {
+    const int i = blockIdx.x * NT + threadIdx.x, eb = blockIdx.y, b = blockIdx.z;
+    const int nterm = nin * ntap;
+    const NegQ q = T.nq;
+    const size_t key_pairs = (size_t)ndigits * 2 * N;
+    u64 D0[16], D1[16];     // balanced digits of the 16 terms' c0 and c1 values
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        const int e = eb * 16 + t;
+        u64 v0 = 0, v1 = 0;
+        if (e < nterm) {
+            const int I = e / ntap, tap = e - I * ntap, gal = tap_gal[tap];
+            const size_t ct = (size_t)b * nin + I;
+            const u64 *c0 = ct_in + ct * 2 * N;
+            if (gal == 1) {
+                v0 = c0[i];
+                v1 = c0[N + i];
+            } else {
+                const ulonglong2 *key = reinterpret_cast<const ulonglong2 *>(keys2) + (size_t)tap_key[tap] * key_pairs;
+                const u64 *dsrc = digits + ct * ndigits * N;
+                const int src = galois_index11(i, gal);
+                u64 s0 = c0[src], s1 = 0;
+                for (int j = 0; j < ndigits; ++j) {
+                    const u64 d = dsrc[(size_t)j * N + src];
+                    const ulonglong2 kb = key[(size_t)(2 * j) * N + i], ka = key[(size_t)(2 * j + 1) * N + i];
+                    s0 += mul_const(d, kb.x, kb.y, q);      // each product is below 2q: at most 7q in all
+                    s1 += mul_const(d, ka.x, ka.y, q);
+                }
+                v0 = reduce64(s0, T.mod);
+                v1 = reduce64(s1, T.mod);
+            }
+        }
+        const u64 k80 = 0x8080808080808080ull;   // bytes of x + 0x80..80 are the balanced digits plus 128
+        D0[t] = (v0 + k80) ^ k80;
+        D1[t] = (v1 + k80) ^ k80;
+    }
+    const int kb = eb >> 2, g = eb & 3;
+#pragma unroll
+    for (int poly = 0; poly < 2; ++poly) {
+        const int col = 2 * b + poly, lane = g * 16 + (col & 15);
+        v4i_t *dst = xl + ((((size_t)(col >> 4) * kblocks + kb) * 64 + lane) * N + i) * 8;
+#pragma unroll
+        for (int limb = 0; limb < 8; ++limb) {
+            v4i_t c;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                u32 wd = 0;
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    wd |= (u32)(((poly ? D1[4 * w + t] : D0[4 * w + t]) >> (8 * limb)) & 0xff) << (8 * t);
+                c[w] = (int)wd;
+            }
+            dst[limb] = c;
+        }
+    }
+}
+
 // out[item] = sum over the first `used` partial ciphertexts of the item (mod q); one thread per word pair
 __global__ void sum_partials_kernel(const u64 *partial, int slots, int used, u64 *out, size_t words, u64 q) {
     const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -584,6 +649,24 @@ int launch_hoist_taps_2048(const gala_ctx *c, void *stream, const u64 *ct_in, si
     }
     hipLaunchKernelGGL(hstperm_taps_2048, dim3((unsigned)(count * ntap)), dim3(NT), 0, st, ct_in, digits, ntap, tap_gal,
                        tap_key, keys2, xrot, T, c->ndigits);
+    return (int)hipGetLastError();
+}
+
+// DecPerm (when there is more than one tap) followed by the HstPerm of every tap, written as the column image
+int launch_hstperm_pack_2048(const gala_ctx *c, void *stream, const u64 *ct_in, u64 *digits, int batch, int nin, int ntap,
+                             const int *tap_gal, const int *tap_key, const u64 *keys2, u64 *xl) {
+    if (batch <= 0) return 0;
+    const Tables2048 T = make_tables(c, c->d_tw2, c->dev_q);
+    hipStream_t st = (hipStream_t)stream;
+    if (ntap > 1) {
+        hipLaunchKernelGGL(decperm_2048, dim3((unsigned)((size_t)batch * nin * c->ndigits)), dim3(NT), 0, st, ct_in, digits, T,
+                           c->gadget_bits, c->ndigits);
+        const int rc = (int)hipGetLastError();
+        if (rc) return rc;
+    }
+    const int nterm = nin * ntap, eblocks = (nterm + 15) / 16, kblocks = (nterm + 63) / 64;
+    hipLaunchKernelGGL(hstperm_pack_2048, dim3(N / NT, (unsigned)eblocks, (unsigned)batch), dim3(NT), 0, st, ct_in, digits, nin,
+                       ntap, kblocks, tap_gal, tap_key, keys2, reinterpret_cast<v4i_t *>(xl), T, c->ndigits);
     return (int)hipGetLastError();
 }
 
