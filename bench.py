@@ -108,6 +108,7 @@ def secondary_workloads(ctx, sk, H, torch):
     return res
 
 
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 OPS_MAC128 = 10         # 64x64 product added into a 128-bit sum: 4 multiply-adds and 6 carry additions
 OPS_REDUCE128 = 2 * OPS_CONST_MUL + 2 * OPS_CSUB + 1
 
@@ -204,15 +205,28 @@ def main():
     rotations = cnt["perm"] + cnt["hstperm_in"]
     rot_per_s = rotations / (ms_per_step * 1e-3)
     kavg_ms = float(np.mean(kernel_ms)) if kernel_ms else float("nan")
+    roof = None
     if is_conv:
         # dominant kernel: the per-coefficient multiply-accumulate (ScMult + Add of Sec. III-B)
         macs = cnt["scmult"] * 2 * par.n                       # two polynomials per ciphertext
-        unit_ops = OPS_MAC128
-        ops = macs * OPS_MAC128 + batch * plan.nout * plan.cn * 2 * par.n * OPS_REDUCE128
-        kernel, units, traffic = "conv_mac_kernel", macs, None
+        groups, nterm = plan.nout * plan.cn, plan.nin * plan.ntap
+        if args.vector_mac:
+            unit_ops = OPS_MAC128
+            ops = macs * OPS_MAC128 + batch * groups * 2 * par.n * OPS_REDUCE128
+            kernel, units, traffic = "conv_mac_kernel", macs, None
+        else:
+            # on the matrix cores the product streams the digit-plane images once: it is bound by HBM.
+            # algorithmic bytes: every encoded kernel polynomial, every rotated input, every sum, 8 B a residue
+            alg_bytes = 8.0 * par.n * (groups * nterm + 2 * batch * nterm + 2 * batch * groups)
+            achieved_gbs = alg_bytes / (kavg_ms * 1e-3) / 1e9
+            roof = {"bound": "hbm", "kernel": "conv_mfma_kernel", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": None, "kernel_ms_avg": kavg_ms,
+                    "units_per_launch": macs, "bytes_per_unit": alg_bytes / macs,
+                    "int8_mfma_top_s": macs * 64 * 2 / (kavg_ms * 1e-3) / 1e12}
+            ops, unit_ops, kernel, units, traffic = 0, 0, "conv_mfma_kernel", macs, None
         config = {"workload": args.workload, "layer": "he_conv", "n": par.n, "c_o": shape.c_o, "c_i": shape.c_i,
                   "k": shape.k_h, "image": [shape.u_h, shape.u_w], "batch": batch, "c_n": plan.cn,
-                  "gadget_digits": ctx.ndigits}
+                  "gadget_digits": ctx.ndigits, "multiply_accumulate": "vector" if args.vector_mac else "matrix cores"}
     else:
         # dominant kernel: rotate-and-accumulate, G fused ScMult+Perm+Add units per input
         unit_ops = ops_per_fused_perm(par.n, 11, ctx.ndigits)
@@ -241,9 +255,9 @@ def main():
         "layers_per_s": 1e3 / ms_per_step,
         "inputs_per_s": batch * 1e3 / ms_per_step,
         "ops_per_step": cnt,
-        "roofline": {"bound": "alu", "kernel": kernel, "achieved": achieved, "peak": ALU_PEAK_TOPS,
-                     "unit": "TOP/s (32-bit integer)", "frac": achieved / ALU_PEAK_TOPS, "traffic": traffic,
-                     "kernel_ms_avg": kavg_ms, "units_per_launch": units, "int_ops_per_unit": unit_ops},
+        "roofline": roof or {"bound": "alu", "kernel": kernel, "achieved": achieved, "peak": ALU_PEAK_TOPS,
+                             "unit": "TOP/s (32-bit integer)", "frac": achieved / ALU_PEAK_TOPS, "traffic": traffic,
+                             "kernel_ms_avg": kavg_ms, "units_per_launch": units, "int_ops_per_unit": unit_ops},
     }
     if not args.no_secondary:
         out["also"] = secondary_workloads(ctx, sk, H, torch)
