@@ -56,6 +56,10 @@ typedef struct {
     u64 *zeta_pow;  /* zeta^i, i in [0,2n)                                        */
     u64 ninv_q, ninv_p;
     int *slot_exp;  /* slot s=(h,k) -> odd exponent e with value = m(zeta^e)      */
+    /* optional special prime P for key switching (0 = keys live mod q only)       */
+    u64 P;          /* prime, P = 1 mod 2n, P != q                                */
+    u64 *psiP_pow;  /* powers of a primitive 2n-th root mod P                     */
+    u64 ninv_P, Pinv_q, P_mod_q;
 } orc_ctx;
 
 static int ilog2(u64 v) { int l = 0; while ((1ull << l) < v) l++; return l; }
@@ -107,8 +111,25 @@ orc_ctx *orc_ctx_new(int n, u64 q, u64 p, int gadget_bits) {
 }
 void orc_ctx_free(orc_ctx *c) {
     if (!c) return;
-    free(c->psi_pow); free(c->zeta_pow); free(c->slot_exp); free(c);
+    free(c->psi_pow); free(c->zeta_pow); free(c->slot_exp); free(c->psiP_pow); free(c);
 }
+/* Switch key switching to the special-prime form: keys are generated modulo q*P with the
+ * secret scaled by P, and every key switch ends with an exact division by P (see below). */
+int orc_ctx_set_special(orc_ctx *c, u64 P) {
+    if (!P || P == c->q || P >> 62 || (P - 1) % (2 * (u64)c->n)) return -1;
+    c->P = P;
+    u64 r = some_primitive_root(P, c->n);
+    free(c->psiP_pow);
+    c->psiP_pow = malloc(sizeof(u64) * 2 * c->n);
+    c->psiP_pow[0] = 1;
+    for (int i = 1; i < 2 * c->n; i++) c->psiP_pow[i] = mulm(c->psiP_pow[i - 1], r, P);
+    c->ninv_P = invm(c->n, P);
+    c->P_mod_q = P % c->q;
+    c->Pinv_q = invm(c->P_mod_q, c->q);
+    return 0;
+}
+/* polynomials per key digit: (b, a) mod q, and with a special prime also (b, a) mod P */
+int orc_key_polys(const orc_ctx *c) { return c->P ? 4 : 2; }
 int orc_ndigits(const orc_ctx *c) { return c->ndigits; }
 u64 orc_delta(const orc_ctx *c) { return c->delta; }
 u64 orc_zeta(const orc_ctx *c) { return c->zeta; }
@@ -197,14 +218,21 @@ void orc_polymul_schoolbook(const orc_ctx *c, const u64 *a, const u64 *b, u64 *o
         }
     memcpy(out, r, sizeof(u64) * n); free(r);
 }
-void orc_polymul(const orc_ctx *c, const u64 *a, const u64 *b, u64 *out) {
-    int n = c->n; u64 q = c->q;
+/* product in Z_m[X]/(X^n+1) through evaluation at the odd powers of a 2n-th root mod m */
+static void polymul_mod(int n, u64 m, const u64 *rpow, u64 ninv, const u64 *a, const u64 *b, u64 *out) {
     u64 *ea = malloc(sizeof(u64) * n), *eb = malloc(sizeof(u64) * n);
-    eval_odd(a, ea, n, q, c->psi_pow);
-    eval_odd(b, eb, n, q, c->psi_pow);
-    for (int i = 0; i < n; i++) ea[i] = mulm(ea[i], eb[i], q);
-    interp_odd(ea, out, n, q, c->psi_pow, c->ninv_q);
+    eval_odd(a, ea, n, m, rpow);
+    eval_odd(b, eb, n, m, rpow);
+    for (int i = 0; i < n; i++) ea[i] = mulm(ea[i], eb[i], m);
+    interp_odd(ea, out, n, m, rpow, ninv);
     free(ea); free(eb);
+}
+void orc_polymul(const orc_ctx *c, const u64 *a, const u64 *b, u64 *out) {
+    polymul_mod(c->n, c->q, c->psi_pow, c->ninv_q, a, b, out);
+}
+/* the same product modulo the special prime (exported for the pins) */
+void orc_polymul_special(const orc_ctx *c, const u64 *a, const u64 *b, u64 *out) {
+    polymul_mod(c->n, c->P, c->psiP_pow, c->ninv_P, a, b, out);
 }
 
 /* ------------------------------------------------------------------ */
@@ -243,7 +271,8 @@ void orc_encode_weight(const orc_ctx *c, const u64 *slots, u64 *poly_q) {
 /* ------------------------------------------------------------------ */
 /* seeded samplers (this build's own recipe; both sides implement it)   */
 /* ------------------------------------------------------------------ */
-enum { STREAM_SK = 1, STREAM_KSK_A = 2, STREAM_KSK_E = 3, STREAM_CT_A = 4, STREAM_CT_E = 5, STREAM_MASK = 6 };
+enum { STREAM_SK = 1, STREAM_KSK_A = 2, STREAM_KSK_E = 3, STREAM_CT_A = 4, STREAM_CT_E = 5, STREAM_MASK = 6,
+       STREAM_KSK_AP = 7 };
 
 static u64 mix64(u64 z) {   /* SplitMix64 output function */
     z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
@@ -362,24 +391,30 @@ int orc_galois_elt(const orc_ctx *c, int swap, int step) {
 }
 /* a(X) -> a(X^g) in Z_q[X]/(X^n+1): coefficient i moves to i*g mod 2n, and
  * exponents >= n fold back with a sign change */
-void orc_apply_galois(const orc_ctx *c, const u64 *a, int g, u64 *out) {
-    int n = c->n;
+static void apply_galois_mod(int n, u64 m, const u64 *a, int g, u64 *out) {
     u64 *r = malloc(sizeof(u64) * n);
     for (int i = 0; i < n; i++) {
         int e = (int)(((long)i * g) % (2 * n));
-        if (e < n) r[e] = a[i]; else r[e - n] = a[i] ? c->q - a[i] : 0;
+        if (e < n) r[e] = a[i]; else r[e - n] = a[i] ? m - a[i] : 0;
     }
     memcpy(out, r, sizeof(u64) * n); free(r);
 }
+void orc_apply_galois(const orc_ctx *c, const u64 *a, int g, u64 *out) { apply_galois_mod(c->n, c->q, a, g, out); }
 /* key-switching key for Galois element g: ndigits pairs (b_j, a_j),
- * b_j = -a_j s + e_j + B^j * s(X^g), B = 2^gadget_bits.  Layout ksk[j][0]=b_j, ksk[j][1]=a_j. */
+ * b_j = -a_j s + e_j + B^j * s(X^g), B = 2^gadget_bits.  Layout ksk[j][0]=b_j, ksk[j][1]=a_j.
+ *
+ * With a special prime P the key lives modulo q*P and hides P * B^j * s(X^g): the two residues of a_j are
+ * drawn independently (uniform mod q and mod P), the error is the same small integer on both sides, and
+ *   b_j mod q = -a_{j,q} s + e_j + (P mod q) B^j s(X^g),     b_j mod P = -a_{j,P} s + e_j.
+ * Layout ksk[j][0..3] = b_j mod q, a_j mod q, b_j mod P, a_j mod P. */
 void orc_galois_key(const orc_ctx *c, const u64 *s, int g, u64 seed, u64 *ksk) {
-    int n = c->n; u64 q = c->q;
-    u64 *sg = malloc(sizeof(u64) * n), *as = malloc(sizeof(u64) * n);
+    int n = c->n, kp = orc_key_polys(c); u64 q = c->q, P = c->P;
+    u64 *sg = malloc(sizeof(u64) * n), *as = malloc(sizeof(u64) * n), *sP = malloc(sizeof(u64) * n);
     orc_apply_galois(c, s, g, sg);
-    u64 Bj = 1;
+    for (int i = 0; i < n; i++) sP[i] = s[i] == 0 ? 0 : (s[i] == 1 ? 1 : P - 1);   /* the ternary secret mod P */
+    u64 Bj = P ? c->P_mod_q : 1;
     for (int j = 0; j < c->ndigits; j++) {
-        u64 *b = ksk + (size_t)(2 * j) * n, *a = b + n;
+        u64 *b = ksk + (size_t)(kp * j) * n, *a = b + n;
         u64 base = ((u64)g << 32) + ((u64)j << 16);
         for (int i = 0; i < n; i++) a[i] = orc_uniform(q, seed, STREAM_KSK_A, base + i);
         orc_polymul(c, a, s, as);
@@ -387,9 +422,16 @@ void orc_galois_key(const orc_ctx *c, const u64 *s, int g, u64 seed, u64 *ksk) {
             u64 e = signed_to_mod(orc_gauss(seed, STREAM_KSK_E, base + i), q);
             b[i] = addm(subm(e, as[i], q), mulm(Bj, sg[i], q), q);
         }
+        if (P) {
+            u64 *bP = a + n, *aP = bP + n;
+            for (int i = 0; i < n; i++) aP[i] = orc_uniform(P, seed, STREAM_KSK_AP, base + i);
+            orc_polymul_special(c, aP, sP, as);
+            for (int i = 0; i < n; i++)
+                bP[i] = subm(signed_to_mod(orc_gauss(seed, STREAM_KSK_E, base + i), P), as[i], P);
+        }
         Bj = mulm(Bj, (1ull << c->gadget_bits) % q, q);
     }
-    free(sg); free(as);
+    free(sg); free(as); free(sP);
 }
 /* DecPerm: unsigned base-B digits of the canonical coefficients of c1,
  * digits[j][i] = (c1[i] >> (j*w)) & (B-1).  Done once per ciphertext. */
@@ -401,21 +443,44 @@ void orc_decperm(const orc_ctx *c, const u64 *c1, u64 *digits) {
 }
 /* HstPerm: out = ( c0(X^g) + sum_j d_j(X^g) b_j ,  sum_j d_j(X^g) a_j ).
  * The automorphism is applied to each digit polynomial AFTER decomposition
- * (a negated digit becomes q - d). */
+ * (a negated digit becomes q - d).
+ *
+ * With a special prime the two sums t are formed modulo q and modulo P (a negated digit is -d on both
+ * sides), and each is divided by P exactly: with r = t mod P taken in [0,P),
+ *   (t - r) / P  mod q  =  (t_q - (r mod q)) * P^-1  mod q,
+ * i.e. the floor of t / P.  out = ( c0(X^g) + floor(t_b / P), floor(t_a / P) ). */
 void orc_hstperm(const orc_ctx *c, const u64 *c0, const u64 *digits, int g, const u64 *ksk, u64 *out) {
-    int n = c->n; u64 q = c->q;
+    int n = c->n, kp = orc_key_polys(c); u64 q = c->q, P = c->P;
     u64 *o0 = malloc(sizeof(u64) * n), *o1 = calloc(n, sizeof(u64));
     u64 *dg = malloc(sizeof(u64) * n), *t = malloc(sizeof(u64) * n);
+    u64 *tq = calloc(2 * (size_t)n, sizeof(u64)), *tP = calloc(2 * (size_t)n, sizeof(u64));
     orc_apply_galois(c, c0, g, o0);
     for (int j = 0; j < c->ndigits; j++) {
+        const u64 *key = ksk + (size_t)(kp * j) * n;
         orc_apply_galois(c, digits + (size_t)j * n, g, dg);
-        orc_polymul(c, dg, ksk + (size_t)(2 * j) * n, t);
-        for (int i = 0; i < n; i++) o0[i] = addm(o0[i], t[i], q);
-        orc_polymul(c, dg, ksk + (size_t)(2 * j + 1) * n, t);
-        for (int i = 0; i < n; i++) o1[i] = addm(o1[i], t[i], q);
+        for (int h = 0; h < 2; h++) {
+            orc_polymul(c, dg, key + (size_t)h * n, t);
+            for (int i = 0; i < n; i++) tq[h * n + i] = addm(tq[h * n + i], t[i], q);
+        }
+        if (P) {
+            apply_galois_mod(n, P, digits + (size_t)j * n, g, dg);
+            for (int h = 0; h < 2; h++) {
+                orc_polymul_special(c, dg, key + (size_t)(2 + h) * n, t);
+                for (int i = 0; i < n; i++) tP[h * n + i] = addm(tP[h * n + i], t[i], P);
+            }
+        }
+    }
+    for (int i = 0; i < n; i++) {
+        if (P) {
+            o0[i] = addm(o0[i], mulm(subm(tq[i], tP[i] % q, q), c->Pinv_q, q), q);
+            o1[i] = mulm(subm(tq[n + i], tP[n + i] % q, q), c->Pinv_q, q);
+        } else {
+            o0[i] = addm(o0[i], tq[i], q);
+            o1[i] = tq[n + i];
+        }
     }
     memcpy(out, o0, sizeof(u64) * n); memcpy(out + n, o1, sizeof(u64) * n);
-    free(o0); free(o1); free(dg); free(t);
+    free(o0); free(o1); free(dg); free(t); free(tq); free(tP);
 }
 void orc_perm(const orc_ctx *c, const u64 *ct, int g, const u64 *ksk, u64 *out) {
     u64 *digits = malloc(sizeof(u64) * (size_t)c->ndigits * c->n);
@@ -530,11 +595,11 @@ void orc_fc_mask_slots(const orc_ctx *c, int n_o, int n_i, const u64 *r, u64 see
 }
 /* he_fc for one input ciphertext:
  *   out = sum_g Perm_g( ScMult(ct, w_g) ) - r'      (Perm_0 = identity)
- * ksk holds the keys of rotations g = 1..G-1 in order (each ndigits*2*n words). */
+ * ksk holds the keys of rotations g = 1..G-1 in order (each ndigits * orc_key_polys * n words). */
 void orc_he_fc(const orc_ctx *c, const u64 *wpoly, int G, const u64 *ct, const u64 *ksk,
                const u64 *mask_slots, u64 *out, orc_counts *cnt) {
     int n = c->n;
-    size_t ksz = (size_t)c->ndigits * 2 * n;
+    size_t ksz = (size_t)c->ndigits * orc_key_polys(c) * n;
     u64 *u = malloc(sizeof(u64) * 2 * n), *v = malloc(sizeof(u64) * 2 * n), *acc = malloc(sizeof(u64) * 2 * n);
     for (int g = 0; g < G; g++) {
         orc_scmult(c, ct, wpoly + (size_t)g * n, u); if (cnt) cnt->scmult++;
@@ -646,7 +711,7 @@ void orc_he_conv_block(const orc_ctx *c, const u64 *K, int co, int ci, int kh, i
                        const u64 *mask_slots, u64 *xrot, int *xrot_ready, u64 *out, orc_counts *cnt) {
     cv_geom g; cv_geometry(c, co, ci, kh, kw, uh, uw, &g);
     int n = g.n, centre = (kh / 2) * kw + kw / 2;
-    size_t ksz = (size_t)c->ndigits * 2 * n, ctsz = 2 * (size_t)n;
+    size_t ksz = (size_t)c->ndigits * orc_key_polys(c) * n, ctsz = 2 * (size_t)n;
     u64 *own = NULL;
     if (!xrot) { own = malloc(sizeof(u64) * ctsz * g.nin * g.ntap); xrot = own; }
     if (own || !*xrot_ready) {

@@ -55,19 +55,22 @@ def _u64(a):
 
 
 class Oracle:
-    """One parameter set (n, q, p, gadget_bits)."""
+    """One parameter set (n, q, p, gadget_bits); `special` > 0 turns on special-prime key switching."""
 
-    def __init__(self, n, q, p, gadget_bits):
+    def __init__(self, n, q, p, gadget_bits, special=0):
         self.L = lib()
         self.n, self.q, self.p, self.gadget_bits = n, q, p, gadget_bits
         self.h = C.c_void_p(self.L.orc_ctx_new(n, C.c_uint64(q), C.c_uint64(p), gadget_bits))
         if not self.h:
             raise ValueError("oracle: unsupported parameters")
+        self.special = int(special)
+        if special and self.L.orc_ctx_set_special(self.h, C.c_uint64(special)) != 0:
+            raise ValueError("oracle: unsupported special prime")
         self.ndigits = self.L.orc_ndigits(self.h)
         self.delta = int(self.L.orc_delta(self.h))
         self.zeta = int(self.L.orc_zeta(self.h))
         self.psi = int(self.L.orc_psi(self.h))
-        self.ksk_words = self.ndigits * 2 * n
+        self.ksk_words = self.ndigits * self.L.orc_key_polys(self.h) * n
 
     def __del__(self):
         try:
@@ -88,6 +91,10 @@ class Oracle:
         a, b = _u64(a), _u64(b); out = np.empty(self.n, np.uint64)
         f = self.L.orc_polymul_schoolbook if schoolbook else self.L.orc_polymul
         f(self.h, _p(a), _p(b), _p(out)); return out
+
+    def polymul_special(self, a, b):
+        a, b = _u64(a), _u64(b); out = np.empty(self.n, np.uint64)
+        self.L.orc_polymul_special(self.h, _p(a), _p(b), _p(out)); return out
 
     # ---- slot encoding
     def encode(self, slots, slow=False):

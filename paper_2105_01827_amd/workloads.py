@@ -20,6 +20,10 @@ P = 1032193
 Q = 1152921500113727489
 GADGET_BITS = 20           # key-switching digits of 20 bits -> 3 digits
 SIGMA = 3.2
+# Optional second prime used only inside key switching (keys modulo q * SPECIAL, exact division by SPECIAL
+# at the end): the largest prime below 2^60 that is 1 (mod 2n); it differs from q.  With it a rotation adds
+# almost no noise, which is what lets 3x3 convolutions decrypt at the 20-bit p of Sec. IV.
+SPECIAL = 1152921504606830593
 
 
 @dataclass(frozen=True)
@@ -28,9 +32,11 @@ class Params:
     q: int = Q
     p: int = P
     gadget_bits: int = GADGET_BITS
+    special: int = 0           # 0: one-prime key switching
 
 
 DEFAULT = Params()
+DEFAULT_SPECIAL = Params(special=SPECIAL)
 
 
 @dataclass(frozen=True)
