@@ -55,6 +55,12 @@ typedef struct {
     int32_t gadget_bits;
     uint64_t q;
     uint64_t p;
+    /* 0, or a second prime P (P = 1 mod 2n, P != q, 2^40 <= P < 2^61) used only inside key switching:
+     * Galois keys then live modulo q*P and hide P * B^j * s(X^g), and every key switch ends with the exact
+     * division  floor(t / P)  of its two sums.  A rotation then adds a few units of noise instead of about
+     * sqrt(digits * n) * B * sigma, which is what the input rotations of Sec. III-B need to precede ScMult at
+     * a 20-bit p.  Costs about twice the transforms per Perm; ciphertexts stay modulo q. */
+    uint64_t special_prime;
 } gala_params;
 
 /* One slot rotation: both rows rotate left by step (0 <= step < n/2); the two
@@ -114,8 +120,9 @@ int gala_galois_keygen(gala_ctx *ctx, const gala_sk *sk, const gala_rot *rots, i
                        gala_gk **out);
 void gala_gk_destroy(gala_gk *gk);
 /* Interchange form of one key: ndigits x (b_j, a_j) polynomials, coefficient
- * domain, to host memory (ndigits*2*n words).  Returns GALA_ENOKEY if absent.
- * Synchronises the device. */
+ * domain, to host memory (ndigits*2*n words); with a special prime ndigits x
+ * (b_j mod q, a_j mod q, b_j mod P, a_j mod P), ndigits*4*n words.  Returns
+ * GALA_ENOKEY if absent.  Synchronises the device. */
 int gala_gk_export(gala_ctx *ctx, const gala_gk *gk, gala_rot rot, uint64_t *ksk_host);
 
 /* ---- plaintext encoding, encryption, decryption (host) -------------------- */

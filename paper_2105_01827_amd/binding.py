@@ -28,7 +28,8 @@ class GalaError(RuntimeError):
 
 
 class Params(C.Structure):
-    _fields_ = [("n", C.c_int32), ("gadget_bits", C.c_int32), ("q", C.c_uint64), ("p", C.c_uint64)]
+    _fields_ = [("n", C.c_int32), ("gadget_bits", C.c_int32), ("q", C.c_uint64), ("p", C.c_uint64),
+                ("special_prime", C.c_uint64)]
 
 
 class Rot(C.Structure):
@@ -111,6 +112,12 @@ def load():
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2105_01827_amd.build` "
                               "(there is no CPU fallback for the HIP path)")
+        # PyTorch ships a HIP runtime of its own; when a process uses both, that copy has to be the one that
+        # is loaded first, or torch finds no device afterwards.  Callers pass torch tensors, so import it here.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         lib = C.CDLL(LIB_PATH)
         for name, (res, args) in SIGNATURES.items():
             f = getattr(lib, name)
@@ -150,16 +157,16 @@ def _rots(rots):
 class Context:
     """gala_ctx: one BFV parameter set; device tables live on the current HIP device."""
 
-    def __init__(self, n, q, p, gadget_bits):
+    def __init__(self, n, q, p, gadget_bits, special=0):
         self.lib = load()
-        self.n, self.q, self.p, self.gadget_bits = n, q, p, gadget_bits
-        par = Params(n, gadget_bits, q, p)
+        self.n, self.q, self.p, self.gadget_bits, self.special = n, q, p, gadget_bits, special
+        par = Params(n, gadget_bits, q, p, special)
         h = C.c_void_p()
         _check(self.lib.gala_ctx_create(C.byref(par), C.byref(h)), "gala_ctx_create")
         self.h = h
         self.ndigits = self.lib.gala_ctx_ndigits(h)
         self.delta = int(self.lib.gala_ctx_delta(h))
-        self.ksk_words = self.ndigits * 2 * n
+        self.ksk_words = self.ndigits * (4 if special else 2) * n
 
     def close(self):
         if getattr(self, "h", None):

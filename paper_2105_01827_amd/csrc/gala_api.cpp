@@ -210,7 +210,7 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
         if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used + end], (hipStream_t)stream);
         if (timed && end) ++c->prof_used;
     };
-    if (ws.mfma && fast_hoist) {
+    if (ws.mfma && fast_hoist && !c->special) {
         // the rotated inputs go straight into the column image of the matrix-core product
         u64 *xl = (u64 *)(base + ws.xl), *tmp = (u64 *)(base + ws.tmp);
         if (launch_hstperm_pack_2048(c, stream, ct_in, digits, batch, pl->nin, pl->ntap, pl->d_tap_gal, pl->d_tap_key, keys2, xl))
@@ -220,7 +220,23 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
         mark(1);
         if (launch_conv_untranspose(c, stream, tmp, batch, groups, acc)) return GALA_EHIP;
     } else {
-        if (fast_hoist) {
+        if (c->special) {
+            // every tap as a Perm of its own: xrot[ct][tap] = Perm_{tap}(ct), one workgroup per (ct, tap)
+            PermJob taps{};
+            taps.ct_in = ct_in;
+            taps.in_item_stride = 2 * (size_t)n;
+            taps.in_g_stride = 0;
+            taps.w = nullptr;
+            taps.gal = pl->d_tap_gal; taps.key_idx = pl->d_tap_key;
+            taps.keys = keys; taps.keys2 = keys2;
+            taps.G = pl->ntap; taps.items = (int)nct_in; taps.nchunks = pl->ntap; taps.slots = pl->ntap;
+            taps.partial = xrot;
+            const int which = c->prof_which;     // these launches are not the ones the events are for
+            c->prof_which = -1;
+            const int rc = launch_perm_accumulate(c, stream, taps);
+            c->prof_which = which;
+            if (rc) return GALA_EHIP;
+        } else if (fast_hoist) {
             if (launch_hoist_taps_2048(c, stream, ct_in, nct_in, pl->ntap, pl->d_tap_gal, pl->d_tap_key, keys2, digits, xrot))
                 return GALA_EHIP;
         } else {

@@ -248,6 +248,8 @@ extern "C" int gala_ctx_create(const gala_params *par, gala_ctx **out) {
     if (par->gadget_bits < 1 || par->gadget_bits > 62) return GALA_EARG;
     int ndigits = (bit_length(q - 1) + par->gadget_bits - 1) / par->gadget_bits;
     if (ndigits > kMaxDigits) return GALA_EARG;
+    const u64 P = par->special_prime;
+    if (P && (P < (1ull << 40) || P >= (1ull << 61) || P == q || (P - 1) % (2 * (u64)n) || !is_prime_u64(P))) return GALA_EARG;
 
     gala_ctx *c = new (std::nothrow) gala_ctx;
     if (!c) return GALA_ENOMEM;
@@ -259,6 +261,12 @@ extern "C" int gala_ctx_create(const gala_params *par, gala_ctx **out) {
     c->zeta = least_primitive_2n_root(p, n);
     c->ntt_q.init(n, q, primitive_2n_root(q, n));
     c->ntt_p.init(n, p, c->zeta);
+    if (P) {
+        c->special = P;
+        c->ntt_P.init(n, P, primitive_2n_root(P, n));
+        c->Pq = P % q; c->Pq_s = shoup_companion(c->Pq, q);
+        c->Pinv = inv_mod(c->Pq, q); c->Pinv_s = shoup_companion(c->Pinv, q);
+    }
     // slot (h,k) is the value at zeta^(+-3^k); the transform puts the value at
     // zeta^(2 r + 1) at index brev(r)
     c->slot_to_idx.resize(n);
@@ -290,7 +298,7 @@ extern "C" int gala_ctx_create(const gala_params *par, gala_ctx **out) {
     }
     // pass-major twiddle blocks for the n = 2048 kernel: block T (1 <= T < 512) holds the pairs
     // tw[T], tw[2T], tw[2T+1], tw[4T..4T+3] and one unused pair; forward table then inverse table
-    std::vector<u64> pairs, pairs_p;
+    std::vector<u64> pairs, pairs_p, pairs_P, hostP;
     if (n == 2048) {
         auto build = [&](const NttHost &h, std::vector<u64> &out) {
             out.assign(2 * 2 * 8 * (size_t)512, 0);
@@ -308,11 +316,27 @@ extern "C" int gala_ctx_create(const gala_params *par, gala_ctx **out) {
         };
         build(c->ntt_q, pairs);
         build(c->ntt_p, pairs_p);
+        if (P) build(c->ntt_P, pairs_P);
+    }
+    if (P) {
+        hostP.resize(4 * (size_t)n);
+        std::copy(c->ntt_P.tw.begin(), c->ntt_P.tw.end(), hostP.begin());
+        std::copy(c->ntt_P.tws.begin(), c->ntt_P.tws.end(), hostP.begin() + n);
+        std::copy(c->ntt_P.itw.begin(), c->ntt_P.itw.end(), hostP.begin() + 2 * n);
+        std::copy(c->ntt_P.itws.begin(), c->ntt_P.itws.end(), hostP.begin() + 3 * n);
     }
     if (upload(&c->d_tables, host) || upload(&c->d_slot_to_idx, c->slot_to_idx) ||
-        upload(&c->d_tw2, pairs) || upload(&c->d_tw2p, pairs_p)) {
+        upload(&c->d_tw2, pairs) || upload(&c->d_tw2p, pairs_p) || upload(&c->d_tablesP, hostP) ||
+        upload(&c->d_tw2P, pairs_P)) {
         gala_ctx_destroy(c);
         return GALA_EHIP;
+    }
+    if (P) {
+        const u64 *base = c->d_tablesP;
+        c->dev_P.tw = base; c->dev_P.tws = base + n; c->dev_P.itw = base + 2 * n; c->dev_P.itws = base + 3 * n;
+        c->dev_P.ninv = c->ntt_P.ninv; c->dev_P.ninvs = c->ntt_P.ninvs;
+        c->dev_P.itw1n = c->ntt_P.itw1n; c->dev_P.itw1ns = c->ntt_P.itw1ns;
+        c->dev_P.mod = c->ntt_P.mod;
     }
     NttDev *dv[2] = {&c->dev_q, &c->dev_p};
     for (int k = 0; k < 2; ++k) {
@@ -334,6 +358,8 @@ extern "C" void gala_ctx_destroy(gala_ctx *c) {
         hipFree(c->d_slot_to_idx);
         hipFree(c->d_tw2);
         hipFree(c->d_tw2p);
+        hipFree(c->d_tablesP);
+        hipFree(c->d_tw2P);
     }
     delete c;
 }
@@ -369,7 +395,7 @@ extern "C" int gala_galois_keygen(gala_ctx *c, const gala_sk *sk, const gala_rot
     const int n = c->n, L = c->ndigits;
     gala_gk *gk = new (std::nothrow) gala_gk;
     if (!gk) return GALA_ENOMEM;
-    gk->n = n; gk->ndigits = L;
+    gk->n = n; gk->ndigits = L; gk->polys = c->key_polys();
     for (int i = 0; i < nrots; ++i) {
         if (rots[i].step < 0 || rots[i].step >= n / 2 || (rots[i].swap & ~1)) { delete gk; return GALA_EARG; }
         int g = galois_element(n, rots[i].swap, rots[i].step);
@@ -388,44 +414,67 @@ extern "C" int gala_galois_keygen(gala_ctx *c, const gala_sk *sk, const gala_rot
     }
     *out = gk;
     if (!nkeys) return GALA_OK;
-    // coefficient-domain samples: slot [j][1] <- a_j, slot [j][0] <- e_j + B^j s(X^g)
-    std::vector<u64> host;
+    // Coefficient-domain samples per digit: [1] <- a_j, [0] <- e_j + B^j s(X^g) modulo q.  With a special prime P
+    // the hidden value is P B^j s(X^g) (zero modulo P) and two more polynomials follow: [2] <- e_j, [3] <- a_j
+    // modulo P, the residues of a_j drawn independently.
+    const u64 q = c->q, P = c->special;
+    const int polys = gk->polys;
+    std::vector<u64> host, sP_hat;
     try { host.resize(nkeys * kw); } catch (...) { gala_gk_destroy(gk); *out = nullptr; return GALA_ENOMEM; }
-    const u64 q = c->q;
     parallel_for(nkeys, [&](size_t k) {
         const int g = gk->elements[k];
         std::vector<u64> sg(n);
         substitute_power(sk->s.data(), g, n, q, sg.data());
-        u64 Bj = 1;
+        u64 Bj = P ? c->Pq : 1;
         const u64 B = (1ull << c->gadget_bits) % q;
         for (int j = 0; j < L; ++j) {
-            u64 *t = host.data() + k * kw + (size_t)(2 * j) * n, *a = t + n;
+            u64 *t = host.data() + k * kw + (size_t)(polys * j) * n, *a = t + n;
             const u64 base = ((u64)g << 32) + ((u64)j << 16);
             for (int i = 0; i < n; ++i) {
                 a[i] = draw_uniform(q, c->qbits, seed, kStreamKskA, base + i);
-                u64 e = lift_signed(draw_gauss(seed, kStreamKskE, base + i), q);
-                t[i] = add_mod(e, mulmod_slow(Bj, sg[i], q), q);
+                const int e = draw_gauss(seed, kStreamKskE, base + i);
+                t[i] = add_mod(lift_signed(e, q), mulmod_slow(Bj, sg[i], q), q);
+                if (P) {
+                    t[2 * n + i] = lift_signed(e, P);
+                    t[3 * n + i] = draw_uniform(P, bit_length(P), seed, kStreamKskAP, base + i);
+                }
             }
             Bj = mulmod_slow(Bj, B, q);
         }
     });
-    u64 *d_s = nullptr;
+    if (P) {   // the ternary secret modulo P, evaluation domain
+        sP_hat.resize(n);
+        for (int i = 0; i < n; ++i) sP_hat[i] = sk->s[i] == 0 ? 0 : (sk->s[i] == 1 ? 1 : P - 1);
+        c->ntt_P.forward(sP_hat.data());
+    }
+    u64 *d_s = nullptr, *d_sP = nullptr;
     int rc = GALA_OK;
     if (hipMalloc((void **)&gk->d_keys, nkeys * kw * sizeof(u64)) != hipSuccess ||
-        hipMalloc((void **)&d_s, n * sizeof(u64)) != hipSuccess)
+        hipMalloc((void **)&d_s, n * sizeof(u64)) != hipSuccess || (P && hipMalloc((void **)&d_sP, n * sizeof(u64)) != hipSuccess))
         rc = GALA_ENOMEM;
     if (!rc && (hipMemcpy(gk->d_keys, host.data(), nkeys * kw * sizeof(u64), hipMemcpyHostToDevice) != hipSuccess ||
-                hipMemcpy(d_s, sk->s_hat.data(), n * sizeof(u64), hipMemcpyHostToDevice) != hipSuccess))
+                hipMemcpy(d_s, sk->s_hat.data(), n * sizeof(u64), hipMemcpyHostToDevice) != hipSuccess ||
+                (P && hipMemcpy(d_sP, sP_hat.data(), n * sizeof(u64), hipMemcpyHostToDevice) != hipSuccess)))
         rc = GALA_EHIP;
     // to the evaluation domain, then b_hat = t_hat - a_hat * s_hat in place
-    if (!rc && launch_ntt(c, nullptr, gk->d_keys, gk->d_keys, nkeys * L * 2, 0)) rc = GALA_EHIP;
-    if (!rc && launch_key_finish(c, nullptr, gk->d_keys, d_s, nkeys * L)) rc = GALA_EHIP;
+    if (!P) {
+        if (!rc && launch_ntt(c, nullptr, gk->d_keys, gk->d_keys, nkeys * L * 2, 0)) rc = GALA_EHIP;
+        if (!rc && launch_key_finish(c, nullptr, gk->d_keys, d_s, nkeys * L, c->dev_q.mod)) rc = GALA_EHIP;
+    } else {
+        for (size_t d = 0; d < nkeys * L && !rc; ++d) {   // per digit: one pair modulo q, one modulo P
+            u64 *pq = gk->d_keys + d * 4 * n, *pP = pq + 2 * n;
+            if (launch_ntt_mod(c, nullptr, pq, pq, 2, 0, c->dev_q) || launch_key_finish(c, nullptr, pq, d_s, 1, c->dev_q.mod) ||
+                launch_ntt_mod(c, nullptr, pP, pP, 2, 0, c->dev_P) || launch_key_finish(c, nullptr, pP, d_sP, 1, c->dev_P.mod))
+                rc = GALA_EHIP;
+        }
+    }
     if (!rc && uses_fast_perm(c)) {
         if (hipMalloc((void **)&gk->d_keys2, 2 * nkeys * kw * sizeof(u64)) != hipSuccess) rc = GALA_ENOMEM;
-        if (!rc && launch_pair_pack(c, nullptr, gk->d_keys, gk->d_keys2, nkeys * kw)) rc = GALA_EHIP;
+        if (!rc && launch_pair_pack(c, nullptr, gk->d_keys, gk->d_keys2, nkeys * kw, polys)) rc = GALA_EHIP;
     }
     if (!rc && hipDeviceSynchronize() != hipSuccess) rc = GALA_EHIP;
     hipFree(d_s);
+    hipFree(d_sP);
     if (rc) { gala_gk_destroy(gk); *out = nullptr; }
     return rc;
 }
@@ -443,7 +492,17 @@ extern "C" int gala_gk_export(gala_ctx *c, const gala_gk *gk, gala_rot rot, uint
     u64 *tmp = nullptr;
     if (hipMalloc((void **)&tmp, kw * sizeof(u64)) != hipSuccess) return GALA_ENOMEM;
     int rc = GALA_OK;
-    if (launch_ntt(c, nullptr, gk->d_keys + it->second * kw, tmp, (size_t)gk->ndigits * 2, 1)) rc = GALA_EHIP;
+    if (gk->polys == 2) {
+        if (launch_ntt(c, nullptr, gk->d_keys + it->second * kw, tmp, (size_t)gk->ndigits * 2, 1)) rc = GALA_EHIP;
+    } else {
+        for (int j = 0; j < gk->ndigits && !rc; ++j) {
+            const u64 *src = gk->d_keys + it->second * kw + (size_t)j * 4 * c->n;
+            u64 *dst = tmp + (size_t)j * 4 * c->n;
+            if (launch_ntt_mod(c, nullptr, src, dst, 2, 1, c->dev_q) ||
+                launch_ntt_mod(c, nullptr, src + 2 * c->n, dst + 2 * c->n, 2, 1, c->dev_P))
+                rc = GALA_EHIP;
+        }
+    }
     if (!rc && hipMemcpy(ksk_host, tmp, kw * sizeof(u64), hipMemcpyDeviceToHost) != hipSuccess) rc = GALA_EHIP;
     hipFree(tmp);
     return rc;
@@ -579,7 +638,7 @@ extern "C" int gala_fc_plan_create(gala_ctx *c, const uint64_t *W, int n_o, int 
     int rc = upload(&pl->d_w, w);
     if (!rc && uses_fast_perm(c)) {
         if (hipMalloc((void **)&pl->d_w2, 2 * w.size() * sizeof(u64)) != hipSuccess) rc = GALA_ENOMEM;
-        if (!rc && (launch_pair_pack(c, nullptr, pl->d_w, pl->d_w2, w.size()) || hipDeviceSynchronize() != hipSuccess))
+        if (!rc && (launch_pair_pack(c, nullptr, pl->d_w, pl->d_w2, w.size(), 2) || hipDeviceSynchronize() != hipSuccess))
             rc = GALA_EHIP;
     }
     if (!rc) rc = upload(&pl->d_gal, pl->gal);

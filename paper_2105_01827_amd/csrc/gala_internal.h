@@ -60,6 +60,9 @@ struct gala_ctx {
     int n = 0, logn = 0, gadget_bits = 0, ndigits = 0, pbits = 0, qbits = 0;
     gala::u64 q = 0, p = 0, delta = 0, delta_s = 0, zeta = 0;
     gala::NttHost ntt_q, ntt_p;
+    // special prime of key switching (0: keys modulo q only)
+    gala::u64 special = 0, Pq = 0, Pq_s = 0, Pinv = 0, Pinv_s = 0;   // P mod q and P^-1 mod q with companions
+    gala::NttHost ntt_P;
     std::vector<int> slot_to_idx;      // slot s -> index of its value in the mod-p transform
     int device = 0;
     bool has_device = false;           // tables uploaded; false on a host without a HIP device
@@ -67,11 +70,14 @@ struct gala_ctx {
     int *d_slot_to_idx = nullptr;
     gala::u64 *d_tw2 = nullptr;        // n = 2048 only: pass-major (w, companion) twiddle blocks, forward then inverse
     gala::u64 *d_tw2p = nullptr;       // the same for the plaintext modulus
-    gala::NttDev dev_q{}, dev_p{};
+    gala::u64 *d_tablesP = nullptr;    // 4*n words: tw,tws,itw,itws for the special prime
+    gala::u64 *d_tw2P = nullptr;       // pass-major blocks for the special prime (n = 2048)
+    gala::NttDev dev_q{}, dev_p{}, dev_P{};
+    int key_polys() const { return special ? 4 : 2; }
     // measurement aid: event pairs recorded around rotate-and-accumulate launches
     mutable std::vector<void *> prof_events;   // 2*capacity hipEvent_t
     mutable int prof_used = 0;
-    int prof_which = 0;                        // 0: rotate-and-accumulate launches, 1: convolution multiply-accumulate
+    mutable int prof_which = 0;                // 0: rotate-and-accumulate launches, 1: convolution multiply-accumulate
 };
 
 struct gala_sk {
@@ -80,15 +86,15 @@ struct gala_sk {
 };
 
 struct gala_gk {
-    int n = 0, ndigits = 0;
+    int n = 0, ndigits = 0, polys = 2; // polynomials per digit: (b, a) mod q, then (b, a) mod P with a special prime
     std::map<int, int> index_of;       // Galois element -> key index
     std::vector<int> elements;
-    gala::u64 *d_keys = nullptr;       // nkeys x ndigits x 2 x n, evaluation domain (b then a)
+    gala::u64 *d_keys = nullptr;       // nkeys x ndigits x polys x n, evaluation domain (b then a)
     gala::u64 *d_keys2 = nullptr;      // same keys as (value, companion) pairs for the n = 2048 kernel, or null
     int *d_elements = nullptr;         // nkeys Galois elements, device
     int *d_iota = nullptr;             // 0,1,2,... (key index of element k is k), device
     int *d_one = nullptr;              // the single value 1 (Galois element of the identity), device
-    size_t key_words() const { return (size_t)ndigits * 2 * n; }
+    size_t key_words() const { return (size_t)ndigits * polys * n; }
 };
 
 // Device description of how the server's mask is laid out in one output
@@ -142,13 +148,17 @@ namespace gala {
 
 // batched transform of `count` polynomials of n words: inverse=0 forward.
 int launch_ntt(const gala_ctx *ctx, void *stream, const u64 *src, u64 *dst, size_t count, int inverse);
+// the same with the tables of another modulus of the context (dev_q, dev_p or dev_P)
+int launch_ntt_mod(const gala_ctx *ctx, void *stream, const u64 *src, u64 *dst, size_t count, int inverse, const NttDev &T);
 
 // key generation helper on `npairs` consecutive (t_hat, a_hat) pairs of n-word evaluation-domain
 // polynomials: t_hat <- t_hat - a_hat * s_hat in place (s_hat shared by all pairs).
-int launch_key_finish(const gala_ctx *ctx, void *stream, u64 *pairs, const u64 *s_hat, size_t npairs);
+int launch_key_finish(const gala_ctx *ctx, void *stream, u64 *pairs, const u64 *s_hat, size_t npairs, const Modulus &mod);
 // dst[i] = (src[i], floor(src[i] * 2^64 / q)) for i < count: constants with the precomputed quotient
 // that the n = 2048 kernel multiplies by.
-int launch_pair_pack(const gala_ctx *ctx, void *stream, const u64 *src, u64 *dst, size_t count);
+// With a special prime the polynomials alternate (b, a) mod q, (b, a) mod P: `polys` = 4 selects the modulus
+// by polynomial index, `polys` = 2 uses q throughout.
+int launch_pair_pack(const gala_ctx *ctx, void *stream, const u64 *src, u64 *dst, size_t count, int polys);
 // whether launch_perm_accumulate will use the n = 2048 kernel for this context
 bool uses_fast_perm(const gala_ctx *ctx);
 

@@ -88,9 +88,11 @@ __global__ void key_finish_kernel(u64 *pairs, const u64 *s_hat, int n, size_t to
 }
 
 // companion of a constant w < q: floor(w * 2^64 / q), by 64 steps of binary long division
-__global__ void pair_pack_kernel(const u64 *src, u64 *dst, size_t count, u64 q) {
+// (polys = 4: polynomials 2 and 3 of every group of four are constants modulo the second modulus)
+__global__ void pair_pack_kernel(const u64 *src, u64 *dst, size_t count, u64 q_first, u64 q_second, int n, int polys) {
     const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (id >= count) return;
+    const u64 q = (polys == 4 && ((id / n) & 2)) ? q_second : q_first;
     const u64 w = src[id];
     u64 rem = w, quot = 0;
     for (int b = 0; b < 64; ++b) {
@@ -106,20 +108,33 @@ __global__ void pair_pack_kernel(const u64 *src, u64 *dst, size_t count, u64 q) 
 // ---------------------------------------------------------------------------
 // rotate-and-accumulate
 // ---------------------------------------------------------------------------
-template <int NT>
-__global__ __launch_bounds__(NT) void perm_accumulate_kernel(PermJob job, NttDev T, int n, int logn, int gadget_bits,
-                                                             int ndigits) {
+// SPECIAL: key switching with a special prime P.  Keys hold four polynomials per digit ((b, a) modulo q, then
+// modulo P); the inner products run in both moduli; each sum modulo P goes back to coefficients r in [0,P) and
+// the key switch contributes (t_q - r) / P.  Everything after the lift r -> r mod q is linear modulo q, so a
+// workgroup adds the r of its rotations in the coefficient domain and transforms that sum once at the end;
+// whatever is not divided by P (the c0 part, rotations by zero) enters the sums multiplied by P.
+struct SpecialConst {
+    u64 Pq, Pinv;   // P mod q and its inverse
+};
+template <int NT, bool SPECIAL>
+__global__ __launch_bounds__(NT) void perm_accumulate_kernel(PermJob job, NttDev T, NttDev TP, SpecialConst sc, int n,
+                                                             int logn, int gadget_bits, int ndigits) {
     extern __shared__ u64 buf[];
     const int tid = threadIdx.x;
     const int item = blockIdx.x / job.nchunks, chunk = blockIdx.x % job.nchunks;
     const int g0 = (int)((long)chunk * job.G / job.nchunks), g1 = (int)((long)(chunk + 1) * job.G / job.nchunks);
     const u64 q = T.mod.q, q2 = T.mod.q2;
     const u64 digit_mask = (1ull << gadget_bits) - 1;
-    const size_t key_words = (size_t)ndigits * 2 * n;
+    constexpr int POLYS = SPECIAL ? 4 : 2;
+    const size_t key_words = (size_t)ndigits * POLYS * n;
 
     u128 acc0[kMaxPer], acc1[kMaxPer];
+    u64 R0[kMaxPer], R1[kMaxPer];   // SPECIAL: coefficient-domain sums (mod q) of the lifted remainders
 #pragma unroll
-    for (int k = 0; k < kMaxPer; ++k) acc0[k] = acc1[k] = 0;
+    for (int k = 0; k < kMaxPer; ++k) {
+        acc0[k] = acc1[k] = 0;
+        R0[k] = R1[k] = 0;
+    }
     int terms = 0;   // products (each below q^2 < 2^122) summed into the accumulators so far
 
     for (int g = g0; g < g1; ++g) {
@@ -140,7 +155,10 @@ __global__ __launch_bounds__(NT) void perm_accumulate_kernel(PermJob job, NttDev
             for (int k = 0; k < kMaxPer; ++k) {
                 const int i = tid + k * NT;
                 if (i < n) {
-                    if (w) {
+                    if (SPECIAL) {
+                        acc0[k] += (u128)(w ? mul_mod(c0[i], w[i], T.mod) : c0[i]) * sc.Pq;
+                        acc1[k] += (u128)(w ? mul_mod(c1[i], w[i], T.mod) : c1[i]) * sc.Pq;
+                    } else if (w) {
                         acc0[k] += (u128)c0[i] * w[i];
                         acc1[k] += (u128)c1[i] * w[i];
                     } else {
@@ -167,6 +185,9 @@ __global__ __launch_bounds__(NT) void perm_accumulate_kernel(PermJob job, NttDev
             coef[k] = i < n ? buf[i] : 0;
         }
         __syncthreads();
+        u128 accP0[kMaxPer], accP1[kMaxPer];   // SPECIAL: this rotation's sums modulo P
+#pragma unroll
+        for (int k = 0; k < kMaxPer; ++k) accP0[k] = accP1[k] = 0;
         for (int j = 0; j < ndigits; ++j) {
 #pragma unroll
             for (int k = 0; k < kMaxPer; ++k) {
@@ -176,7 +197,7 @@ __global__ __launch_bounds__(NT) void perm_accumulate_kernel(PermJob job, NttDev
             __syncthreads();
             ntt_forward_lds<NT>(buf, n, logn, T);
             // HstPerm: automorphism as a gather, inner product with the key
-            const u64 *kb = key + (size_t)(2 * j) * n, *ka = kb + n;
+            const u64 *kb = key + (size_t)(POLYS * j) * n, *ka = kb + n;
 #pragma unroll
             for (int k = 0; k < kMaxPer; ++k) {
                 const int i = tid + k * NT;
@@ -187,6 +208,47 @@ __global__ __launch_bounds__(NT) void perm_accumulate_kernel(PermJob job, NttDev
                 }
             }
             __syncthreads();
+            if (SPECIAL) {   // the same digit and gather modulo P
+#pragma unroll
+                for (int k = 0; k < kMaxPer; ++k) {
+                    const int i = tid + k * NT;
+                    if (i < n) buf[i] = (coef[k] >> (j * gadget_bits)) & digit_mask;
+                }
+                __syncthreads();
+                ntt_forward_lds<NT>(buf, n, logn, TP);
+                const u64 *kbP = kb + 2 * (size_t)n, *kaP = kbP + n;
+#pragma unroll
+                for (int k = 0; k < kMaxPer; ++k) {
+                    const int i = tid + k * NT;
+                    if (i < n) {
+                        const u64 d = csub(csub(buf[galois_index(i, gal, logn, n)], TP.mod.q2), TP.mod.q);
+                        accP0[k] += (u128)d * kbP[i];
+                        accP1[k] += (u128)d * kaP[i];
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        if (SPECIAL) {   // remainders modulo P back to coefficients, lifted to [0,P), reduced modulo q, summed
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int k = 0; k < kMaxPer; ++k) {
+                    const int i = tid + k * NT;
+                    if (i < n) buf[i] = reduce128(h ? accP1[k] : accP0[k], TP.mod);
+                }
+                __syncthreads();
+                ntt_inverse_lds<NT>(buf, n, logn, TP);
+#pragma unroll
+                for (int k = 0; k < kMaxPer; ++k) {
+                    const int i = tid + k * NT;
+                    if (i < n) {
+                        const u64 r = buf[i] % q;
+                        if (h) R1[k] = add_mod(R1[k], r, q); else R0[k] = add_mod(R0[k], r, q);
+                    }
+                }
+                __syncthreads();
+            }
         }
         // the c0 part of the rotated ciphertext
 #pragma unroll
@@ -194,13 +256,37 @@ __global__ __launch_bounds__(NT) void perm_accumulate_kernel(PermJob job, NttDev
             const int i = tid + k * NT;
             if (i < n) {
                 const int pi = galois_index(i, gal, logn, n);
-                if (w) acc0[k] += (u128)c0[pi] * w[pi];
+                if (SPECIAL) acc0[k] += (u128)(w ? mul_mod(c0[pi], w[pi], T.mod) : c0[pi]) * sc.Pq;
+                else if (w) acc0[k] += (u128)c0[pi] * w[pi];
                 else acc0[k] += c0[pi];
             }
         }
         terms += ndigits + 1;
     }
     u64 *out = job.partial + ((size_t)item * job.slots + chunk) * 2 * n;
+    if (SPECIAL) {   // out = (sum - transform(R)) / P
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < kMaxPer; ++k) {
+                const int i = tid + k * NT;
+                if (i < n) buf[i] = h ? R1[k] : R0[k];
+            }
+            __syncthreads();
+            ntt_forward_lds<NT>(buf, n, logn, T);
+#pragma unroll
+            for (int k = 0; k < kMaxPer; ++k) {
+                const int i = tid + k * NT;
+                if (i < n) {
+                    const u64 x = csub(csub(buf[i], q2), q);
+                    const u64 t = reduce128(h ? acc1[k] : acc0[k], T.mod);
+                    out[h * n + i] = mul_mod(sub_mod(t, x, q), sc.Pinv, T.mod);
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int k = 0; k < kMaxPer; ++k) {
         const int i = tid + k * NT;
@@ -427,32 +513,35 @@ inline int last_error() { return (int)hipGetLastError(); }
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
-int launch_ntt(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, size_t count, int inverse) {
+int launch_ntt_mod(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, size_t count, int inverse, const NttDev &T) {
     if (!count) return 0;
     hipStream_t st = (hipStream_t)stream;
     const size_t lds = sizeof(u64) * c->n;
     if (block_threads(c->n) == 256)
-        hipLaunchKernelGGL(ntt_kernel<256>, dim3((unsigned)count), dim3(256), lds, st, src, dst, c->n, c->logn, c->dev_q, inverse);
+        hipLaunchKernelGGL(ntt_kernel<256>, dim3((unsigned)count), dim3(256), lds, st, src, dst, c->n, c->logn, T, inverse);
     else
-        hipLaunchKernelGGL(ntt_kernel<64>, dim3((unsigned)count), dim3(64), lds, st, src, dst, c->n, c->logn, c->dev_q, inverse);
+        hipLaunchKernelGGL(ntt_kernel<64>, dim3((unsigned)count), dim3(64), lds, st, src, dst, c->n, c->logn, T, inverse);
     return last_error();
 }
-int launch_key_finish(const gala_ctx *c, void *stream, u64 *pairs, const u64 *s_hat, size_t npairs) {
+int launch_ntt(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, size_t count, int inverse) {
+    return launch_ntt_mod(c, stream, src, dst, count, inverse, c->dev_q);
+}
+int launch_key_finish(const gala_ctx *c, void *stream, u64 *pairs, const u64 *s_hat, size_t npairs, const Modulus &mod) {
     if (!npairs) return 0;
     const size_t total = npairs * c->n;
     hipLaunchKernelGGL(key_finish_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream, pairs,
-                       s_hat, c->n, total, c->dev_q.mod);
+                       s_hat, c->n, total, mod);
     return last_error();
 }
-int launch_pair_pack(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, size_t count) {
+int launch_pair_pack(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, size_t count, int polys) {
     if (!count) return 0;
     hipLaunchKernelGGL(pair_pack_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, (hipStream_t)stream, src,
-                       dst, count, c->q);
+                       dst, count, c->q, c->special, c->n, polys);
     return last_error();
 }
 bool uses_fast_perm(const gala_ctx *c) {
     static const bool generic_only = std::getenv("GALA_GENERIC_PERM") != nullptr;
-    return c->n == 2048 && c->q < (1ull << 60) && !generic_only;
+    return c->n == 2048 && c->q < (1ull << 60) && !generic_only && !c->special;
 }
 int launch_perm_accumulate(const gala_ctx *c, void *stream, const PermJob &job) {
     if (job.items <= 0 || job.nchunks <= 0) return 0;
@@ -466,12 +555,22 @@ int launch_perm_accumulate(const gala_ctx *c, void *stream, const PermJob &job) 
         if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used++ + 1], st);
         return rc;
     }
-    if (block_threads(c->n) == 256)
-        hipLaunchKernelGGL(perm_accumulate_kernel<256>, grid, dim3(256), lds, st, job, c->dev_q, c->n, c->logn,
-                           c->gadget_bits, c->ndigits);
-    else
-        hipLaunchKernelGGL(perm_accumulate_kernel<64>, grid, dim3(64), lds, st, job, c->dev_q, c->n, c->logn,
-                           c->gadget_bits, c->ndigits);
+    const SpecialConst sc{c->Pq, c->Pinv};
+    const bool big = block_threads(c->n) == 256;
+    if (c->special) {
+        if (big)
+            hipLaunchKernelGGL((perm_accumulate_kernel<256, true>), grid, dim3(256), lds, st, job, c->dev_q, c->dev_P, sc, c->n,
+                               c->logn, c->gadget_bits, c->ndigits);
+        else
+            hipLaunchKernelGGL((perm_accumulate_kernel<64, true>), grid, dim3(64), lds, st, job, c->dev_q, c->dev_P, sc, c->n,
+                               c->logn, c->gadget_bits, c->ndigits);
+    } else if (big) {
+        hipLaunchKernelGGL((perm_accumulate_kernel<256, false>), grid, dim3(256), lds, st, job, c->dev_q, c->dev_q, sc, c->n,
+                           c->logn, c->gadget_bits, c->ndigits);
+    } else {
+        hipLaunchKernelGGL((perm_accumulate_kernel<64, false>), grid, dim3(64), lds, st, job, c->dev_q, c->dev_q, sc, c->n,
+                           c->logn, c->gadget_bits, c->ndigits);
+    }
     if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used++ + 1], st);
     return last_error();
 }

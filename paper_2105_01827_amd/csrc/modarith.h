@@ -85,7 +85,8 @@ GALA_HD u64 rand64(u64 seed, u64 stream, u64 idx, u64 attempt) {
     h = mix64(h + idx);
     return mix64(h + attempt);
 }
-enum : u64 { kStreamSk = 1, kStreamKskA = 2, kStreamKskE = 3, kStreamCtA = 4, kStreamCtE = 5, kStreamMask = 6 };
+enum : u64 { kStreamSk = 1, kStreamKskA = 2, kStreamKskE = 3, kStreamCtA = 4, kStreamCtE = 5, kStreamMask = 6,
+             kStreamKskAP = 7 };
 
 // uniform in [0,m): the top `bits` = bitlen(m) bits of a draw, redrawn while >= m
 GALA_HD u64 draw_uniform(u64 m, int bits, u64 seed, u64 stream, u64 idx) {

@@ -21,7 +21,8 @@ def harness():
 
 
 def both(par):
-    return binding.Context(par.n, par.q, par.p, par.gadget_bits), Oracle(par.n, par.q, par.p, par.gadget_bits)
+    return (binding.Context(par.n, par.q, par.p, par.gadget_bits, par.special),
+            Oracle(par.n, par.q, par.p, par.gadget_bits, special=par.special))
 
 
 def plain_matvec(W, x, p):
