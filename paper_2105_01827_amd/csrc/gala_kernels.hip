@@ -88,11 +88,14 @@ __global__ void key_finish_kernel(u64 *pairs, const u64 *s_hat, int n, size_t to
 }
 
 // companion of a constant w < q: floor(w * 2^64 / q), by 64 steps of binary long division
-// (polys = 4: polynomials 2 and 3 of every group of four are constants modulo the second modulus)
-__global__ void pair_pack_kernel(const u64 *src, u64 *dst, size_t count, u64 q_first, u64 q_second, int n, int polys) {
+// (polys = 4: polynomials 2 and 3 of every group of four are constants modulo the second modulus).  The
+// modulus differs from lane to lane; it is picked with a lane mask rather than a branch on purpose: hipcc 7.2
+// kept a branchy `cond ? q_second : q_first` in scalar registers and gave every lane q_second.
+__global__ void pair_pack_kernel(const u64 *src, u64 *dst, size_t count, u64 q_first, u64 q_second, int logn, int polys) {
     const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (id >= count) return;
-    const u64 q = (polys == 4 && ((id / n) & 2)) ? q_second : q_first;
+    const u64 second = polys == 4 ? 0 - (u64)((id >> (logn + 1)) & 1) : 0;   // all ones on polynomials 2, 3 of 4
+    const u64 q = (q_first & ~second) | (q_second & second);
     const u64 w = src[id];
     u64 rem = w, quot = 0;
     for (int b = 0; b < 64; ++b) {
@@ -536,12 +539,13 @@ int launch_key_finish(const gala_ctx *c, void *stream, u64 *pairs, const u64 *s_
 int launch_pair_pack(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, size_t count, int polys) {
     if (!count) return 0;
     hipLaunchKernelGGL(pair_pack_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, (hipStream_t)stream, src,
-                       dst, count, c->q, c->special, c->n, polys);
+                       dst, count, c->q, c->special, c->logn, polys);
     return last_error();
 }
 bool uses_fast_perm(const gala_ctx *c) {
     static const bool generic_only = std::getenv("GALA_GENERIC_PERM") != nullptr;
-    return c->n == 2048 && c->q < (1ull << 60) && !generic_only && !c->special;
+    return c->n == 2048 && c->q < (1ull << 60) && !generic_only &&
+           (!c->special || (c->special < (1ull << 60) && c->special < 2 * c->q));
 }
 int launch_perm_accumulate(const gala_ctx *c, void *stream, const PermJob &job) {
     if (job.items <= 0 || job.nchunks <= 0) return 0;

@@ -567,6 +567,187 @@ __global__ __launch_bounds__(NT) void hstperm_pack_2048(const u64 *ct_in, const 
     }
 }
 
+// ---- key switching with a special prime P -------------------------------------------------------------
+// Keys hold four polynomials per digit ((b, a) modulo q, then modulo P).  Per rotation the digits are
+// transformed in both moduli and multiplied into sums modulo q and modulo P; the sums modulo P go back to
+// coefficients r in [0,P), and the rotation contributes (t_q - r) / P.  After the lift r -> r mod q everything is
+// linear modulo q, so the lifted remainders of a workgroup's rotations are added in the coefficient domain
+// (R0, R1) and transformed once at the end; terms that are not divided by P (the c0 part, rotations by zero)
+// enter the sums multiplied by P.  Needs P < 2^60 and P < 2q.
+struct SpecialJob {
+    Tables2048 TP;          // transform tables of P
+    ulonglong2 Pq, Pinv;    // P mod q and P^-1 mod q with companions
+};
+
+template <bool HAS_W>
+__global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob job, Tables2048 T, SpecialJob S, MaskJob mj,
+                                                                      int gadget_bits, int ndigits) {
+    __shared__ u64 bufA[LDS_WORDS], bufB[LDS_WORDS];
+    __shared__ u64 stash[N];
+    const int tid = threadIdx.x;
+    if ((int)blockIdx.x >= job.items * job.nchunks) {   // only launched when mj.enabled
+        mask_role(job, T, mj, (int)blockIdx.x - job.items * job.nchunks, bufA, bufB);
+        return;
+    }
+    const int item = blockIdx.x / job.nchunks, chunk = blockIdx.x % job.nchunks;
+    const int g0 = (int)((long)chunk * job.G / job.nchunks), g1 = (int)((long)(chunk + 1) * job.G / job.nchunks);
+    const NegQ q = T.nq, qP = S.TP.nq;
+    const u64 q8 = 8 * T.mod.q, P8 = 8 * S.TP.mod.q;
+    const u64 digit_mask = (1ull << gadget_bits) - 1;
+    const size_t key_pairs = (size_t)ndigits * 4 * N;
+
+    u64 sum0[PER], sum1[PER];   // evaluation domain modulo q, below 8q between products
+    u64 R0[PER], R1[PER];       // coefficient domain modulo q, canonical, index tid + 256k
+#pragma unroll
+    for (int k = 0; k < PER; ++k) sum0[k] = sum1[k] = R0[k] = R1[k] = 0;
+
+    for (int g = g0; g < g1; ++g) {
+        const u64 *c0 = job.ct_in + (size_t)item * job.in_item_stride + (size_t)g * job.in_g_stride;
+        const u64 *c1 = c0 + N;
+        const ulonglong2 *w = HAS_W ? reinterpret_cast<const ulonglong2 *>(job.w2) + (size_t)g * N : nullptr;
+        const int gal = job.gal[g];
+        if (gal == 1) {   // rotation by zero: ScMult and Add only, times P
+#pragma unroll
+            for (int k = 0; k < PER; ++k) {
+                const int i = tid + k * NT;
+                u64 x0 = c0[i], x1 = c1[i];
+                if (HAS_W) {
+                    const ulonglong2 ww = w[i];
+                    x0 = mul_const(x0, ww.x, ww.y, q);
+                    x1 = mul_const(x1, ww.x, ww.y, q);
+                }
+                sum0[k] = csub_dev(sum0[k] + mul_const(x0, S.Pq.x, S.Pq.y, q), q8);
+                sum1[k] = csub_dev(sum1[k] + mul_const(x1, S.Pq.x, S.Pq.y, q), q8);
+            }
+            continue;
+        }
+        __syncthreads();   // the previous rotation ended reading bufA, this one starts by writing it
+        const ulonglong2 *key = reinterpret_cast<const ulonglong2 *>(job.keys2) + (size_t)job.key_idx[g] * key_pairs;
+        int src[PER];
+#pragma unroll
+        for (int k = 0; k < PER; ++k) src[k] = galois_index11(tid + k * NT, gal);
+        u64 a[PER];
+        {
+            const ulonglong2 *c1v = reinterpret_cast<const ulonglong2 *>(c1 + 8 * tid);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const ulonglong2 cv = c1v[k];
+                if (HAS_W) {
+                    const ulonglong2 wa = w[8 * tid + 2 * k], wb = w[8 * tid + 2 * k + 1];
+                    a[2 * k] = mul_const(cv.x, wa.x, wa.y, q);
+                    a[2 * k + 1] = mul_const(cv.y, wb.x, wb.y, q);
+                } else {
+                    a[2 * k] = cv.x;
+                    a[2 * k + 1] = cv.y;
+                }
+            }
+        }
+        inverse_in_regs(a, bufA, bufB, T, tid);
+#pragma unroll
+        for (int k = 0; k < PER; ++k) stash[tid + k * NT] = a[k];
+        // the c0 part, times P
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            u64 x = c0[src[k]];
+            if (HAS_W) {
+                const ulonglong2 ww = w[src[k]];
+                x = mul_const(x, ww.x, ww.y, q);
+            }
+            sum0[k] += mul_const(x, S.Pq.x, S.Pq.y, q);
+        }
+        int pending = 1, pendingP = 0;
+        u64 tp0[PER], tp1[PER];   // this rotation's sums modulo P, below 8P between products
+#pragma unroll
+        for (int k = 0; k < PER; ++k) tp0[k] = tp1[k] = 0;
+        for (int j = 0; j < ndigits; ++j) {
+#pragma unroll
+            for (int k = 0; k < PER; ++k) a[k] = (stash[tid + k * NT] >> (j * gadget_bits)) & digit_mask;
+            forward_to_lds(a, bufA, bufB, T, tid);
+            const ulonglong2 *kb = key + (size_t)(4 * j) * N, *ka = kb + N;
+            if (pending == 4) {
+#pragma unroll
+                for (int k = 0; k < PER; ++k) {
+                    sum0[k] = csub_dev(sum0[k], q8);
+                    sum1[k] = csub_dev(sum1[k], q8);
+                }
+                pending = 0;
+            }
+#pragma unroll
+            for (int k = 0; k < PER; ++k) {
+                const int i = tid + k * NT;
+                const u64 d = bufA[pad(src[k])];
+                const ulonglong2 b = kb[i], aa = ka[i];
+                sum0[k] += mul_const(d, b.x, b.y, q);
+                sum1[k] += mul_const(d, aa.x, aa.y, q);
+            }
+            ++pending;
+            // the same digit modulo P
+#pragma unroll
+            for (int k = 0; k < PER; ++k) a[k] = (stash[tid + k * NT] >> (j * gadget_bits)) & digit_mask;
+            forward_to_lds(a, bufA, bufB, S.TP, tid);
+            const ulonglong2 *kbP = kb + 2 * (size_t)N, *kaP = kbP + N;
+            if (pendingP == 4) {
+#pragma unroll
+                for (int k = 0; k < PER; ++k) {
+                    tp0[k] = csub_dev(tp0[k], P8);
+                    tp1[k] = csub_dev(tp1[k], P8);
+                }
+                pendingP = 0;
+            }
+#pragma unroll
+            for (int k = 0; k < PER; ++k) {
+                const int i = tid + k * NT;
+                const u64 d = bufA[pad(src[k])];
+                const ulonglong2 b = kbP[i], aa = kaP[i];
+                tp0[k] += mul_const(d, b.x, b.y, qP);
+                tp1[k] += mul_const(d, aa.x, aa.y, qP);
+            }
+            ++pendingP;
+        }
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            sum0[k] = csub_dev(sum0[k], q8);
+            sum1[k] = csub_dev(sum1[k], q8);
+        }
+        // remainders modulo P: canonical, to the ownership the inverse transform starts from (through bufB, which
+        // nobody reads any more), back to coefficients in [0,P), reduced modulo q and added up
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+            for (int k = 0; k < PER; ++k) bufB[pad(tid + k * NT)] = reduce64(h ? tp1[k] : tp0[k], S.TP.mod);
+            __syncthreads();
+            {
+                const u64 *pi = bufB + pad(tid << 3);
+#pragma unroll
+                for (int k = 0; k < PER; ++k) a[k] = pi[k];
+            }
+            inverse_in_regs(a, bufA, bufB, S.TP, tid);
+#pragma unroll
+            for (int k = 0; k < PER; ++k) {
+                const u64 r = csub_dev(a[k], T.mod.q);
+                if (h) R1[k] = csub_dev(R1[k] + r, T.mod.q); else R0[k] = csub_dev(R0[k] + r, T.mod.q);
+            }
+        }
+    }
+    // partial = (sum - transform(R)) / P
+    u64 *out = job.partial + ((size_t)item * job.slots + chunk) * 2 * N;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        u64 a[PER];
+#pragma unroll
+        for (int k = 0; k < PER; ++k) a[k] = h ? R1[k] : R0[k];
+        forward_to_lds(a, bufA, bufB, T, tid);
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int i = tid + k * NT;
+            const u64 x = reduce64(bufA[pad(i)], T.mod);
+            const u64 t = reduce64(h ? sum1[k] : sum0[k], T.mod);
+            const u64 dlt = t >= x ? t - x : t + T.mod.q - x;
+            out[h * N + i] = csub_dev(mul_const(dlt, S.Pinv.x, S.Pinv.y, q), T.mod.q);
+        }
+    }
+}
+
 // out[item] = sum over the first `used` partial ciphertexts of the item (mod q); one thread per word pair
 __global__ void sum_partials_kernel(const u64 *partial, int slots, int used, u64 *out, size_t words, u64 q) {
     const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -598,6 +779,17 @@ static int launch_2048(const gala_ctx *c, void *stream, const PermJob &job, cons
     hipStream_t st = (hipStream_t)stream;
     const Tables2048 T = make_tables(c, c->d_tw2, c->dev_q);
     const dim3 grid((unsigned)(job.items * job.nchunks + (mj.enabled ? job.items : 0)));
+    if (c->special) {
+        SpecialJob S;
+        S.TP = make_tables(c, c->d_tw2P, c->dev_P);
+        S.Pq = make_ulonglong2(c->Pq, c->Pq_s);
+        S.Pinv = make_ulonglong2(c->Pinv, c->Pinv_s);
+        if (job.w)
+            hipLaunchKernelGGL(perm_accumulate_special_2048<true>, grid, dim3(NT), 0, st, job, T, S, mj, c->gadget_bits, c->ndigits);
+        else
+            hipLaunchKernelGGL(perm_accumulate_special_2048<false>, grid, dim3(NT), 0, st, job, T, S, mj, c->gadget_bits, c->ndigits);
+        return (int)hipGetLastError();
+    }
     if (job.w)
         hipLaunchKernelGGL(perm_accumulate_2048<true>, grid, dim3(NT), 0, st, job, T, mj, c->gadget_bits, c->ndigits);
     else
