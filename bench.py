@@ -45,6 +45,22 @@ def ops_per_fused_perm(n, logn, ndigits):
     return inverse + ndigits * forward + scmult_c1 + c0_term + digits + key_mac + accumulate
 
 
+def ops_per_fused_perm_special(n, logn, ndigits):
+    """The same unit with special-prime key switching: every digit is transformed and multiplied in both moduli,
+    the two sums modulo P go back to coefficients (two inverse transforms); the two forward transforms of the
+    summed remainders happen once per workgroup and are not counted."""
+    half = n // 2
+    inverse = half * (logn - 1) * OPS_BF_INV + half * (2 * OPS_CONST_MUL + 2 * OPS_CSUB + 4)
+    forward = half * logn * OPS_BF_FWD + n * OPS_CSUB
+    scmult_c1 = n * OPS_CONST_MUL
+    c0_term = n * (2 * OPS_CONST_MUL + 1)                       # permuted c0 (.) w, times P
+    digits = 2 * ndigits * n * 2
+    key_mac = 4 * ndigits * n * (OPS_CONST_MUL + 1)             # (b_j, a_j) modulo q and modulo P
+    accumulate = 2 * n * OPS_CSUB
+    remainders = 2 * n * (OPS_CONST_MUL + OPS_CSUB + 2 * OPS_CSUB + 1)   # canonical mod P, lift, reduce mod q, add
+    return 3 * inverse + 2 * ndigits * forward + scmult_c1 + c0_term + digits + key_mac + accumulate + remainders
+
+
 def timed(fn, torch, steps, warmup):
     for _ in range(warmup):
         fn()
@@ -123,6 +139,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--vector-mac", action="store_true",
                     help="convolution: keep the multiply-accumulate on the vector ALU instead of the matrix cores")
+    ap.add_argument("--special-prime", action="store_true",
+                    help="key switching with the special prime (keys modulo q*P, exact division by P): the mode in "
+                         "which 3x3 convolutions decrypt at the 20-bit plaintext modulus")
     ap.add_argument("--no-secondary", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device copy of this size (calibrates rocprofv3 HBM byte counters)")
@@ -139,8 +158,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    par = wl.DEFAULT
-    ctx = binding.Context(par.n, par.q, par.p, par.gadget_bits)
+    par = wl.DEFAULT_SPECIAL if args.special_prime else wl.DEFAULT
+    ctx = binding.Context(par.n, par.q, par.p, par.gadget_bits, par.special)
     sk = ctx.keygen(0)
     stream = torch.cuda.current_stream()
     is_conv = args.workload.startswith("conv")
@@ -229,14 +248,15 @@ def main():
                   "gadget_digits": ctx.ndigits, "multiply_accumulate": "vector" if args.vector_mac else "matrix cores"}
     else:
         # dominant kernel: rotate-and-accumulate, G fused ScMult+Perm+Add units per input
-        unit_ops = ops_per_fused_perm(par.n, 11, ctx.ndigits)
+        unit_ops = (ops_per_fused_perm_special if args.special_prime else ops_per_fused_perm)(par.n, 11, ctx.ndigits)
         ops = unit_ops * batch * (plan.G - 1)      # the g = 0 unit has no Perm and is not counted
-        kernel, units = "perm_accumulate_2048", batch * plan.G
+        kernel, units = "perm_accumulate_special_2048" if args.special_prime else "perm_accumulate_2048", batch * plan.G
         # HBM bytes per launch measured with rocprofv3 counters for the default workload
         # (profiles/perm_accumulate_fc_128x1024_b64_hbm_traffic.txt); not measured for the others
-        traffic = (47438 + 34816) * 1024.0 if args.workload == "fc_128x1024_b64" else None
+        traffic = (47438 + 34816) * 1024.0 if args.workload == "fc_128x1024_b64" and not args.special_prime else None
         config = {"workload": args.workload, "layer": "he_fc", "n": par.n, "n_o": shape.n_o, "n_i": shape.n_i,
                   "batch": batch, "G": plan.G, "gadget_digits": ctx.ndigits}
+    config["key_switching"] = "special prime" if args.special_prime else "one prime"
     achieved = ops / (kavg_ms * 1e-3) / 1e12
     out = {
         "metric": "HE rotations/sec and he_fc/he_conv layers/sec at n=2048; % of HBM/int roofline",
@@ -259,11 +279,11 @@ def main():
                              "unit": "TOP/s (32-bit integer)", "frac": achieved / ALU_PEAK_TOPS, "traffic": traffic,
                              "kernel_ms_avg": kavg_ms, "units_per_launch": units, "int_ops_per_unit": unit_ops},
     }
-    if not args.no_secondary:
+    if not args.no_secondary and not args.special_prime:
         out["also"] = secondary_workloads(ctx, sk, H, torch)
     if not args.no_cpu_baseline:
         from oracle.oracle import Oracle
-        o = Oracle(par.n, par.q, par.p, par.gadget_bits)
+        o = Oracle(par.n, par.q, par.p, par.gadget_bits, special=par.special)
         osk = o.keygen(0)
         got = H.export_cts(ctx, d_out, batch * (plan.nout if is_conv else 1))
         if is_conv:

@@ -120,3 +120,18 @@ def test_he_conv_3x3_decrypts_at_the_papers_parameters():
         for O in range(plan.nout):
             plan.unpack_share(O, ctx.decrypt(sk, got[b, O]), share)
         assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_conv(K, x[b], par.p))
+
+
+def test_he_conv_config4_decrypts_at_full_size():
+    """16x16x128 input, 128 kernels of 3x3, batch 16, n = 2048, p ~ 2^20: the convolution of BASELINE's fourth
+    configuration.  One output ciphertext is recomputed by the oracle; the plain convolution is recovered for two
+    of the inputs from all their output ciphertexts."""
+    par = params(2048)
+    s = wl.CONV_16x16_128_3x3
+    ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, s.tuple, s.batch, [(3, 7)], seed=0, matrix_cores=True)
+    assert cnt == dict(perm=1792, decperm_in=256, hstperm_in=2048, scmult=294912, add=294656)
+    for b in (0, 15):
+        share = np.zeros(r[b].shape, np.uint64)
+        for O in range(plan.nout):
+            plan.unpack_share(O, ctx.decrypt(sk, got[b, O]), share)
+        assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_conv(K, x[b], par.p))
