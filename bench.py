@@ -86,6 +86,18 @@ def secondary_workloads(ctx, sk, H, torch):
     t = timed(lambda: ctx.rotate(gk, d_in, count, (0, 1), d_out), torch, 100, 20)
     res["rotate_4096_cts"] = {"ms": t * 1e3, "rotations_per_s": count / t}
     del d_in, d_out
+    # he_fc 16x128, one input (a single ScMult and the mask, no rotation): launch latency
+    f = wl.FC_16x128
+    W, x, r = wl.fc_inputs(f)
+    plan = ctx.fc_plan(W)
+    d_in = H.to_dev(rng.integers(0, par.q, size=(f.batch, 2 * par.n), dtype=np.uint64))
+    d_out = H.dev_empty(f.batch * 2 * par.n)
+    d_r = H.to_dev(r)
+    wsb = plan.workspace_bytes(f.batch)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    t = timed(lambda: plan.he_fc(d_in, f.batch, d_r, 5, d_out, ws, wsb), torch, 200, 20)
+    res[f.name] = {"ms_per_layer": t * 1e3, "layers_per_s": 1 / t, "inputs_per_s": f.batch / t, "rotations_per_s": 0.0}
+    del plan, d_in, d_out, ws
     # he_conv, 16x16x128 input, 128 kernels of 3x3, batch 16
     s = wl.CONV_16x16_128_3x3
     K, x, r = wl.conv_inputs(s)
@@ -129,13 +141,78 @@ OPS_MAC128 = 10         # 64x64 product added into a 128-bit sum: 4 multiply-add
 OPS_REDUCE128 = 2 * OPS_CONST_MUL + 2 * OPS_CSUB + 1
 
 
+def resnet18_workload(ctx, sk, H, torch, args):
+    """Config 5: every linear layer of an ImageNet-shaped ResNet-18 on one input (random weights and ciphertexts):
+    20 convolutions over their spatial tiles (the tiles are the batch of he_conv) and the final FC.  Each layer
+    is timed on its own with its plan, keys and inputs resident; a 'step' is one pass over all 21 layers."""
+    from paper_2105_01827_amd import workloads as wl
+    par = wl.DEFAULT
+    rng = np.random.default_rng(0)
+    layers, fc = wl.resnet18_layers()
+    per_layer, total_ms, total = [], 0.0, dict(perm=0, decperm_in=0, hstperm_in=0, scmult=0, add=0)
+    weight_bytes, mac_ms = 0.0, 0.0
+    steps, warm = max(3, args.steps // 50), max(1, args.warmup // 50)
+    ctx.profile_select(1)
+    for L in layers:
+        K = rng.integers(0, par.p, size=(L.c_o, L.c_i, L.k, L.k), dtype=np.uint64)
+        t = ctx.conv_tiling(L.in_hw, L.in_hw, L.k, L.k, L.stride)
+        plan = ctx.conv_plan(K, t.tile_h, t.tile_w)
+        gk = ctx.galois_keygen(sk, plan.rotations(), seed=8)
+        plan.bind(gk)
+        if 2 * t.tiles >= 8:
+            plan.prepare_batched()
+        d_in = H.to_dev(rng.integers(0, par.q, size=(t.tiles * plan.nin, 2 * par.n), dtype=np.uint64))
+        d_out = H.dev_empty(t.tiles * plan.nout * 2 * par.n)
+        d_r = H.to_dev(rng.integers(0, par.p, size=(t.tiles, L.c_o, t.tile_h, t.tile_w), dtype=np.uint64))
+        wsb = plan.workspace_bytes(t.tiles)
+        ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+        cnt = {}
+        def conv():
+            cnt.update(plan.he_conv(d_in, t.tiles, d_r, 3, d_out, ws, wsb))
+        for _ in range(warm):
+            conv()
+        torch.cuda.synchronize()
+        ctx.profile_enable(steps)
+        dt = timed(conv, torch, steps, 0)
+        kms = ctx.profile_collect(steps)
+        ctx.profile_enable(0)
+        groups, nterm = plan.nout * plan.cn, plan.nin * plan.ntap
+        weight_bytes += 8.0 * par.n * groups * nterm
+        mac_ms += float(np.mean(kms)) if kms else 0.0
+        per_layer.append({"layer": L.name, "tiles": t.tiles, "c_n": plan.cn, "ms": dt * 1e3,
+                          "multiply_accumulate_ms": float(np.mean(kms)) if kms else None})
+        total_ms += dt * 1e3
+        for k in total:
+            total[k] += cnt[k]
+        del plan, gk, d_in, d_out, ws
+    ctx.profile_select(0)
+    W, x, r = wl.fc_inputs(fc, seed=77)
+    plan = ctx.fc_plan(W)
+    gk = ctx.galois_keygen(sk, plan.rotations(), seed=1)
+    plan.bind(gk)
+    d_in = H.to_dev(rng.integers(0, par.q, size=(1, 2 * par.n), dtype=np.uint64))
+    d_out = H.dev_empty(2 * par.n)
+    d_r = H.to_dev(r)
+    wsb = plan.workspace_bytes(1)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    cnt = {}
+    def fcl():
+        cnt.update(plan.he_fc(d_in, 1, d_r, 5, d_out, ws, wsb))
+    dt = timed(fcl, torch, steps, warm)
+    per_layer.append({"layer": fc.name, "G": plan.G, "ms": dt * 1e3})
+    total_ms += dt * 1e3
+    for k in total:
+        total[k] += cnt[k]
+    return per_layer, total_ms, total, weight_bytes, mac_ms, steps, warm
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="fc_128x1024_b64",
-                    choices=["fc_128x1024_b64", "fc_1000x2048_b64", "conv_16x16x128_3x3x128_b16"])
+                    choices=["fc_128x1024_b64", "fc_1000x2048_b64", "conv_16x16x128_3x3x128_b16", "resnet18_b1"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--vector-mac", action="store_true",
                     help="convolution: keep the multiply-accumulate on the vector ALU instead of the matrix cores")
@@ -162,6 +239,25 @@ def main():
     ctx = binding.Context(par.n, par.q, par.p, par.gadget_bits, par.special)
     sk = ctx.keygen(0)
     stream = torch.cuda.current_stream()
+    if args.workload == "resnet18_b1":
+        per_layer, total_ms, total, weight_bytes, mac_ms, steps, warm = resnet18_workload(ctx, sk, H, torch, args)
+        rot = total["perm"] + total["hstperm_in"]
+        gbs = weight_bytes / (mac_ms * 1e-3) / 1e9
+        print(json.dumps({
+            "metric": "HE rotations/sec and he_fc/he_conv layers/sec at n=2048; % of HBM/int roofline",
+            "value": rot / (total_ms * 1e-3), "unit": "rotations/s", "n_gpus": 1, "steps": steps, "warmup": warm,
+            "ms_per_step": total_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64",
+            "data": "synthetic",
+            "config": {"workload": "resnet18_b1", "layers": len(per_layer), "n": par.n, "batch": 1,
+                       "note": "each layer timed on its own; a step is one pass over the 21 linear layers"},
+            "layers_per_s": len(per_layer) * 1e3 / total_ms, "networks_per_s": 1e3 / total_ms, "ops_per_step": total,
+            "per_layer": per_layer,
+            # at one input the multiply-accumulate streams every encoded kernel polynomial once: HBM-bound
+            "roofline": {"bound": "hbm", "kernel": "conv_mac_kernel / conv_mfma_kernel (all 20 convolutions)",
+                         "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                         "traffic": None, "kernel_ms_total": mac_ms, "bytes_per_step": weight_bytes},
+            "cpu_baseline": None}))
+        return
     is_conv = args.workload.startswith("conv")
     if is_conv:
         shape = wl.CONV_16x16_128_3x3

@@ -623,20 +623,34 @@ int launch_conv_mac(const gala_ctx *c, void *stream, const u64 *w, const u64 *xr
     const int flush_every = c->q < (1ull << 60) ? 255 : 63;
     const int nterm = nin * ntap;
     hipStream_t st = (hipStream_t)stream;
-    auto grid = [&](int tm, int tn, int wm, int wn) {
-        return dim3((unsigned)((c->n + 63) / 64), (unsigned)((groups + tm * wm - 1) / (tm * wm)),
-                    (unsigned)((cols + tn * wn - 1) / (tn * wn)));
+    // The tile's width follows the number of (input, polynomial) columns (a single input is 2 columns); its
+    // height is halved until the launch has a few workgroups per compute unit: with few columns the kernel is
+    // bound by streaming the encoded kernels and needs the whole chip's loads in flight more than it needs reuse.
+    const unsigned iblocks = (unsigned)((c->n + 63) / 64);
+    auto wgs = [&](int tm, int tn, int wm, int wn) {
+        return (size_t)iblocks * ((groups + tm * wm - 1) / (tm * wm)) * ((cols + tn * wn - 1) / (tn * wn));
     };
-    // the tile's width follows the number of (input, polynomial) columns: a single input is 2 columns
-    if (cols <= 2)
-        hipLaunchKernelGGL((conv_mac_kernel<8, 2, 4, 1>), grid(8, 2, 4, 1), dim3(256), 0, st, w, xrot, cols, groups, nterm, acc,
-                           c->dev_q.mod, c->n, flush_every);
-    else if (cols <= 4)
-        hipLaunchKernelGGL((conv_mac_kernel<4, 4, 4, 1>), grid(4, 4, 4, 1), dim3(256), 0, st, w, xrot, cols, groups, nterm, acc,
-                           c->dev_q.mod, c->n, flush_every);
-    else
-        hipLaunchKernelGGL((conv_mac_kernel<4, 8, 4, 2>), grid(4, 8, 4, 2), dim3(512), 0, st, w, xrot, cols, groups, nterm, acc,
-                           c->dev_q.mod, c->n, flush_every);
+    const size_t enough = 1024;
+#define GALA_MAC(TM, TN, WM, WN)                                                                                      \
+    hipLaunchKernelGGL((conv_mac_kernel<TM, TN, WM, WN>),                                                            \
+                       dim3(iblocks, (unsigned)((groups + TM * WM - 1) / (TM * WM)), (unsigned)((cols + TN * WN - 1) / (TN * WN))), \
+                       dim3(64 * WM * WN), 0, st, w, xrot, cols, groups, nterm, acc, c->dev_q.mod, c->n, flush_every)
+    if (cols <= 2) {
+        if (wgs(8, 2, 4, 1) >= enough) GALA_MAC(8, 2, 4, 1);
+        else if (wgs(4, 2, 4, 1) >= enough) GALA_MAC(4, 2, 4, 1);
+        else if (wgs(2, 2, 4, 1) >= enough) GALA_MAC(2, 2, 4, 1);
+        else GALA_MAC(1, 2, 4, 1);
+    } else if (cols <= 4) {
+        if (wgs(4, 4, 4, 1) >= enough) GALA_MAC(4, 4, 4, 1);
+        else if (wgs(2, 4, 4, 1) >= enough) GALA_MAC(2, 4, 4, 1);
+        else GALA_MAC(1, 4, 4, 1);
+    } else {
+        // wide tiles re-read the inputs once per row tile, so they give up height more reluctantly
+        if (wgs(4, 8, 4, 2) >= enough / 2) GALA_MAC(4, 8, 4, 2);
+        else if (wgs(2, 8, 4, 2) >= enough / 2) GALA_MAC(2, 8, 4, 2);
+        else GALA_MAC(1, 8, 4, 2);
+    }
+#undef GALA_MAC
     return last_error();
 }
 

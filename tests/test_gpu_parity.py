@@ -166,7 +166,7 @@ def test_he_fc_config3_1000x2048_batch64_sampled():
 
 def conv_case(par, shape, batch, oracle_outputs, seed=0, matrix_cores=False):
     """oracle_outputs: list of (b, O) ciphertexts the oracle recomputes.  matrix_cores: keep the digit-plane
-    image of the kernels so that the multiply-accumulate runs on the MFMA units (needs batch >= 8)."""
+    image of the kernels so that the multiply-accumulate runs on the MFMA units (needs batch >= 4)."""
     H = harness()
     ctx, o = both(par)
     co, ci, kh, kw, uh, uw = shape
