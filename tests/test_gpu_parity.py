@@ -274,3 +274,36 @@ def test_he_conv_config4_sampled():
     # Table "Computation complexity of convolution", 16x16@128 with 3x3@128, per input
     assert (cnt["decperm_in"] + cnt["perm"], cnt["hstperm_in"] + cnt["perm"], cnt["scmult"], cnt["add"]) == \
            (16 * 128, 16 * 240, 16 * 18432, 16 * 18416)
+
+
+def test_61_bit_modulus_runs_on_the_generic_kernels():
+    """q between 2^60 and 2^61 is outside what the n = 2048 kernels' lazy arithmetic allows (16q must fit 64 bits);
+    the library then uses the generic kernels: Perm, he_fc and a small he_conv against the oracle at n = 2048."""
+    H = harness()
+    q = wl.find_prime_below(1 << 61, 2 * wl.N * wl.P)
+    assert q > (1 << 60)
+    par = wl.Params(q=q)
+    ctx, o = both(par)
+    assert ctx.ndigits == 4
+    sk, osk = ctx.keygen(3), o.keygen(3)
+    rng = np.random.default_rng(61)
+    slots = rng.integers(0, par.p, size=(2, par.n), dtype=np.uint64)
+    cts = np.stack([ctx.encrypt(sk, slots[i], seed=10 + i) for i in range(2)])
+    rots = [(0, 7), (1, 300)]
+    gk = ctx.galois_keygen(sk, rots, seed=42)
+    d_in = H.import_cts(ctx, cts)
+    for swap, step in rots:
+        d_out = H.dev_empty(2 * 2 * par.n)
+        ctx.rotate(gk, d_in, 2, (swap, step), d_out)
+        got = H.export_cts(ctx, d_out, 2)
+        g = o.galois_elt(swap, step)
+        ksk = o.galois_key(osk, g, 42)
+        for i in range(2):
+            assert np.array_equal(got[i], o.perm(cts[i], g, ksk))
+            assert np.array_equal(ctx.decrypt(sk, got[i]), rotate_slots(slots[i], step, bool(swap)))
+    ctx2, o2, plan, sk2, W, x, r, got = fc_case(par, 16, 512, 3, [0, 2], seed=5)
+    assert plan.G == 4
+    for b in range(3):
+        share = plan.unpack_share(ctx2.decrypt(sk2, got[b]))
+        assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_matvec(W, x[b], par.p))
+    conv_case(par, (16, 8, 1, 1, 16, 16), 2, [(0, 0), (1, 1)], seed=9)
