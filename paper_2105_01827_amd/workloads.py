@@ -36,7 +36,9 @@ class Params:
 
 
 DEFAULT = Params()
-DEFAULT_SPECIAL = Params(special=SPECIAL)
+# With the special prime the digit width no longer drives the rotation noise (digits * error / P is far below 1
+# even for 30-bit digits), so two digits are enough; fewer digits mean fewer transforms per rotation.
+DEFAULT_SPECIAL = Params(special=SPECIAL, gadget_bits=30)
 
 
 @dataclass(frozen=True)
