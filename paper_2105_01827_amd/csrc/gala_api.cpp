@@ -164,7 +164,7 @@ ConvWorkspace conv_workspace(const gala_conv_plan *pl, int batch) {
     ConvWorkspace ws{};
     ws.chunks = choose_chunks(batch * pl->nout, pl->cn);
     ws.digits = 0;
-    ws.xrot = ws.digits + align_up((size_t)batch * pl->nin * c->ndigits * n * w);
+    ws.xrot = ws.digits + align_up((size_t)batch * pl->nin * c->ndigits * n * w * (c->special ? 2 : 1));
     ws.acc = ws.xrot + align_up((size_t)batch * pl->nin * pl->ntap * 2 * n * w);
     ws.partial = ws.acc + align_up((size_t)batch * pl->nout * pl->cn * 2 * n * w);
     ws.xl = ws.partial + align_up((size_t)batch * pl->nout * (ws.chunks + 1) * 2 * n * w);
@@ -220,7 +220,10 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
         mark(1);
         if (launch_conv_untranspose(c, stream, tmp, batch, groups, acc)) return GALA_EHIP;
     } else {
-        if (c->special) {
+        if (c->special && fast_hoist) {
+            if (launch_hoist_taps_2048(c, stream, ct_in, nct_in, pl->ntap, pl->d_tap_gal, pl->d_tap_key, keys2, digits, xrot))
+                return GALA_EHIP;
+        } else if (c->special) {
             // every tap as a Perm of its own: xrot[ct][tap] = Perm_{tap}(ct), one workgroup per (ct, tap)
             PermJob taps{};
             taps.ct_in = ct_in;

@@ -748,6 +748,105 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
     }
 }
 
+// ---- hoisted input rotations with a special prime ----------------------------------------------------------
+// DecPerm: one workgroup per (ciphertext, digit, modulus); digits[ct][j][modulus][i], lazy values of that modulus.
+__global__ __launch_bounds__(NT) void decperm_special_2048(const u64 *ct_in, u64 *digits, Tables2048 T, Tables2048 TP,
+                                                           int gadget_bits, int ndigits) {
+    __shared__ u64 bufA[LDS_WORDS], bufB[LDS_WORDS];
+    const int tid = threadIdx.x;
+    const int m = blockIdx.x & 1, j = (blockIdx.x >> 1) % ndigits, ct = (blockIdx.x >> 1) / ndigits;
+    const u64 *c1 = ct_in + (size_t)ct * 2 * N + N;
+    u64 a[PER];
+    const ulonglong2 *c1v = reinterpret_cast<const ulonglong2 *>(c1 + 8 * tid);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const ulonglong2 cv = c1v[k];
+        a[2 * k] = cv.x;
+        a[2 * k + 1] = cv.y;
+    }
+    inverse_in_regs(a, bufA, bufB, T, tid);
+    const u64 digit_mask = (1ull << gadget_bits) - 1;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) a[k] = (a[k] >> (j * gadget_bits)) & digit_mask;
+    if (m) forward_to_lds(a, bufA, bufB, TP, tid);
+    else forward_to_lds(a, bufA, bufB, T, tid);
+    u64 *out = digits + (((size_t)ct * ndigits + j) * 2 + m) * N;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) out[tid + k * NT] = bufA[pad(tid + k * NT)];
+}
+
+// HstPerm: one workgroup per (ciphertext, tap): inner products in both moduli from the stored digits, the sums
+// modulo P back to coefficients, lifted, reduced modulo q and transformed forward again, then
+// out = (P c0(X^g) + t_b - NTT(r_b)) / P, (t_a - NTT(r_a)) / P.  Output: xrot[ct][tap][c0|c1][i], canonical.
+__global__ __launch_bounds__(NT) void hstperm_special_2048(const u64 *ct_in, const u64 *digits, int ntap, const int *tap_gal,
+                                                           const int *tap_key, const u64 *keys2, u64 *xrot, Tables2048 T,
+                                                           SpecialJob S, int ndigits) {
+    __shared__ u64 bufA[LDS_WORDS], bufB[LDS_WORDS];
+    const int tid = threadIdx.x;
+    const int ct = blockIdx.x / ntap, tap = blockIdx.x % ntap;
+    const u64 *c0 = ct_in + (size_t)ct * 2 * N, *c1 = c0 + N;
+    u64 *out = xrot + ((size_t)ct * ntap + tap) * 2 * N;
+    const int gal = tap_gal[tap];
+    if (gal == 1) {
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int i = tid + k * NT;
+            out[i] = c0[i];
+            out[N + i] = c1[i];
+        }
+        return;
+    }
+    const NegQ q = T.nq, qP = S.TP.nq;
+    const u64 *dsrc = digits + (size_t)ct * ndigits * 2 * N;
+    const ulonglong2 *key = reinterpret_cast<const ulonglong2 *>(keys2) + (size_t)tap_key[tap] * ndigits * 4 * N;
+    int src[PER];
+    u64 sum0[PER], sum1[PER], tp0[PER], tp1[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        src[k] = galois_index11(tid + k * NT, gal);
+        sum0[k] = mul_const(c0[src[k]], S.Pq.x, S.Pq.y, q);
+        sum1[k] = tp0[k] = tp1[k] = 0;
+    }
+    for (int j = 0; j < ndigits; ++j) {     // at most three digits: every sum stays below 8 moduli
+        const ulonglong2 *kb = key + (size_t)(4 * j) * N;
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int i = tid + k * NT;
+            const u64 dq = dsrc[(size_t)(2 * j) * N + src[k]], dP = dsrc[(size_t)(2 * j + 1) * N + src[k]];
+            const ulonglong2 b = kb[i], aa = kb[N + i], bP = kb[2 * N + i], aP = kb[3 * N + i];
+            sum0[k] += mul_const(dq, b.x, b.y, q);
+            sum1[k] += mul_const(dq, aa.x, aa.y, q);
+            tp0[k] += mul_const(dP, bP.x, bP.y, qP);
+            tp1[k] += mul_const(dP, aP.x, aP.y, qP);
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        u64 a[PER];
+        // LDS phases: B (ownership change), A B A (inverse), B A B A (forward), then reads of A
+#pragma unroll
+        for (int k = 0; k < PER; ++k) bufB[pad(tid + k * NT)] = reduce64(h ? tp1[k] : tp0[k], S.TP.mod);
+        __syncthreads();
+        {
+            const u64 *pi = bufB + pad(tid << 3);
+#pragma unroll
+            for (int k = 0; k < PER; ++k) a[k] = pi[k];
+        }
+        inverse_in_regs(a, bufA, bufB, S.TP, tid);
+#pragma unroll
+        for (int k = 0; k < PER; ++k) a[k] = csub_dev(a[k], T.mod.q);
+        forward_to_lds(a, bufA, bufB, T, tid);
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int i = tid + k * NT;
+            const u64 x = reduce64(bufA[pad(i)], T.mod);
+            const u64 t = reduce64(h ? sum1[k] : sum0[k], T.mod);
+            const u64 dlt = t >= x ? t - x : t + T.mod.q - x;
+            out[h * N + i] = csub_dev(mul_const(dlt, S.Pinv.x, S.Pinv.y, q), T.mod.q);
+        }
+    }
+}
+
 // out[item] = sum over the first `used` partial ciphertexts of the item (mod q); one thread per word pair
 __global__ void sum_partials_kernel(const u64 *partial, int slots, int used, u64 *out, size_t words, u64 q) {
     const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -833,6 +932,21 @@ int launch_hoist_taps_2048(const gala_ctx *c, void *stream, const u64 *ct_in, si
     if (!count) return 0;
     const Tables2048 T = make_tables(c, c->d_tw2, c->dev_q);
     hipStream_t st = (hipStream_t)stream;
+    if (c->special) {     // digits[ct][j][modulus][N]: twice the digit storage of the one-prime form
+        SpecialJob S;
+        S.TP = make_tables(c, c->d_tw2P, c->dev_P);
+        S.Pq = make_ulonglong2(c->Pq, c->Pq_s);
+        S.Pinv = make_ulonglong2(c->Pinv, c->Pinv_s);
+        if (ntap > 1) {
+            hipLaunchKernelGGL(decperm_special_2048, dim3((unsigned)(count * c->ndigits * 2)), dim3(NT), 0, st, ct_in, digits,
+                               T, S.TP, c->gadget_bits, c->ndigits);
+            const int rc = (int)hipGetLastError();
+            if (rc) return rc;
+        }
+        hipLaunchKernelGGL(hstperm_special_2048, dim3((unsigned)(count * ntap)), dim3(NT), 0, st, ct_in, digits, ntap,
+                           tap_gal, tap_key, keys2, xrot, T, S, c->ndigits);
+        return (int)hipGetLastError();
+    }
     if (ntap > 1) {
         hipLaunchKernelGGL(decperm_2048, dim3((unsigned)(count * c->ndigits)), dim3(NT), 0, st, ct_in, digits, T,
                            c->gadget_bits, c->ndigits);
