@@ -86,6 +86,15 @@ def secondary_workloads(ctx, sk, H, torch):
     t = timed(lambda: ctx.rotate(gk, d_in, count, (0, 1), d_out), torch, 100, 20)
     res["rotate_4096_cts"] = {"ms": t * 1e3, "rotations_per_s": count / t}
     del d_in, d_out
+    # the client's steps on the device: 4096 encryptions and decryptions (internal ciphertext form)
+    d_slots = H.to_dev(rng.integers(0, par.p, size=(count, par.n), dtype=np.uint64))
+    d_seeds = H.to_dev(np.arange(count, dtype=np.uint64))
+    d_ct = H.dev_empty(count * 2 * par.n)
+    t = timed(lambda: ctx.encrypt_batch(sk, d_slots, d_seeds, count, d_ct), torch, 30, 5)
+    res["encrypt_4096_cts"] = {"ms": t * 1e3, "ciphertexts_per_s": count / t}
+    t = timed(lambda: ctx.decrypt_batch(sk, d_ct, count, d_slots), torch, 30, 5)
+    res["decrypt_4096_cts"] = {"ms": t * 1e3, "ciphertexts_per_s": count / t}
+    del d_slots, d_ct
     # he_fc 16x128, one input (a single ScMult and the mask, no rotation): launch latency
     f = wl.FC_16x128
     W, x, r = wl.fc_inputs(f)

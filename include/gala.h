@@ -140,6 +140,18 @@ int gala_decrypt(const gala_ctx *ctx, const gala_sk *sk, const uint64_t *ct_host
 int gala_ct_import(const gala_ctx *ctx, void *stream, const uint64_t *ct_coeff_dev, int count, uint64_t *ct_dev);
 int gala_ct_export(const gala_ctx *ctx, void *stream, const uint64_t *ct_dev, int count, uint64_t *ct_coeff_dev);
 
+/* ---- the client's steps on the device (batched, asynchronous) --------------- */
+/* The same functions as gala_encrypt / gala_decrypt (Sec. II-C(1)) for `count` slot vectors at once, with the
+ * ciphertexts in the INTERNAL device form, so that no import / export is needed around he_fc / he_conv.
+ * slots_dev: count x n values (reduced mod p on the way in); seeds_dev: count generator seeds, one per
+ * ciphertext; ct_dev: count x 2n words.  Bit for bit what gala_encrypt followed by gala_ct_import gives, and
+ * what gala_ct_export followed by gala_decrypt gives.  All pointers are device pointers owned by the caller;
+ * the secret key's device copy belongs to the key handle.  GALA_EHIP without a device. */
+int gala_encrypt_batch(const gala_ctx *ctx, void *stream, const gala_sk *sk, const uint64_t *slots_dev,
+                       const uint64_t *seeds_dev, int count, uint64_t *ct_dev);
+int gala_decrypt_batch(const gala_ctx *ctx, void *stream, const gala_sk *sk, const uint64_t *ct_dev, int count,
+                       uint64_t *slots_dev);
+
 /* ---- Perm: one slot rotation per ciphertext (Sec. II-C(1)) ----------------- */
 /* ct_out[i] = Perm_rot(ct_in[i]) for i < count, internal form, device.  A Perm
  * is a DecPerm (inverse transform of c1, base-2^gadget_bits digits, forward

@@ -76,6 +76,8 @@ SIGNATURES = {
     "gala_decrypt": (_I, [_VP, _VP, _U64P, _U64P]),
     "gala_ct_import": (_I, [_VP, _VP, _U64P, _I, _U64P]),
     "gala_ct_export": (_I, [_VP, _VP, _U64P, _I, _U64P]),
+    "gala_encrypt_batch": (_I, [_VP, _VP, _VP, _U64P, _U64P, _I, _U64P]),
+    "gala_decrypt_batch": (_I, [_VP, _VP, _VP, _U64P, _I, _U64P]),
     "gala_rotate": (_I, [_VP, _VP, _VP, _U64P, _I, Rot, _U64P]),
     "gala_fc_plan_create": (_I, [_VP, _U64P, _I, _I, C.POINTER(_VP)]),
     "gala_fc_plan_destroy": (None, [_VP]),
@@ -219,6 +221,14 @@ class Context:
 
     def ct_export(self, src_dev, count, dst_dev, stream=None):
         _check(self.lib.gala_ct_export(self.h, _stream(stream), _dev(src_dev), count, _dev(dst_dev)), "gala_ct_export")
+
+    def encrypt_batch(self, sk, slots_dev, seeds_dev, count, ct_dev, stream=None):
+        _check(self.lib.gala_encrypt_batch(self.h, _stream(stream), sk.h, _dev(slots_dev), _dev(seeds_dev), count,
+                                           _dev(ct_dev)), "gala_encrypt_batch")
+
+    def decrypt_batch(self, sk, ct_dev, count, slots_dev, stream=None):
+        _check(self.lib.gala_decrypt_batch(self.h, _stream(stream), sk.h, _dev(ct_dev), count, _dev(slots_dev)),
+               "gala_decrypt_batch")
 
     def rotate(self, gk, ct_in, count, rot, ct_out, stream=None):
         _check(self.lib.gala_rotate(self.h, _stream(stream), gk.h, _dev(ct_in), count, Rot(*rot), _dev(ct_out)),

@@ -78,6 +78,19 @@ extern "C" int gala_ct_export(const gala_ctx *c, void *stream, const uint64_t *s
     return launch_ntt(c, stream, src, dst, (size_t)count * 2, 1) ? GALA_EHIP : GALA_OK;
 }
 
+extern "C" int gala_encrypt_batch(const gala_ctx *c, void *stream, const gala_sk *sk, const uint64_t *slots,
+                                  const uint64_t *seeds, int count, uint64_t *ct) {
+    if (!c || !sk || !slots || !seeds || !ct || count < 0) return GALA_EARG;
+    if (!c->has_device || !sk->d_s_hat) return GALA_EHIP;
+    return launch_encrypt(c, stream, sk->d_s_hat, slots, seeds, count, ct) ? GALA_EHIP : GALA_OK;
+}
+extern "C" int gala_decrypt_batch(const gala_ctx *c, void *stream, const gala_sk *sk, const uint64_t *ct, int count,
+                                  uint64_t *slots) {
+    if (!c || !sk || !slots || !ct || count < 0) return GALA_EARG;
+    if (!c->has_device || !sk->d_s_hat) return GALA_EHIP;
+    return launch_decrypt(c, stream, sk->d_s_hat, ct, count, slots) ? GALA_EHIP : GALA_OK;
+}
+
 extern "C" int gala_rotate(const gala_ctx *c, void *stream, const gala_gk *gk, const uint64_t *ct_in, int count,
                            gala_rot rot, uint64_t *ct_out) {
     if (!c || !gk || !ct_in || !ct_out || count < 0 || rot.step < 0 || rot.step >= c->n / 2 || (rot.swap & ~1))

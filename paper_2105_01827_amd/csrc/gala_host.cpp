@@ -378,10 +378,18 @@ extern "C" int gala_keygen(const gala_ctx *c, uint64_t seed, gala_sk **out) {
     for (int i = 0; i < c->n; ++i) sk->s[i] = lift_signed(draw_ternary(seed, kStreamSk, (u64)i), c->q);
     sk->s_hat = sk->s;
     c->ntt_q.forward(sk->s_hat.data());
+    if (c->has_device && upload(&sk->d_s_hat, sk->s_hat)) {
+        gala_sk_destroy(sk);
+        return GALA_EHIP;
+    }
     *out = sk;
     return GALA_OK;
 }
-extern "C" void gala_sk_destroy(gala_sk *sk) { delete sk; }
+extern "C" void gala_sk_destroy(gala_sk *sk) {
+    if (!sk) return;
+    if (sk->d_s_hat) hipFree(sk->d_s_hat);
+    delete sk;
+}
 extern "C" int gala_sk_export(const gala_ctx *c, const gala_sk *sk, uint64_t *s_host) {
     if (!c || !sk || !s_host) return GALA_EARG;
     std::memcpy(s_host, sk->s.data(), sizeof(u64) * c->n);

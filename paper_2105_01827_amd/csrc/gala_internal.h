@@ -83,6 +83,7 @@ struct gala_ctx {
 struct gala_sk {
     std::vector<gala::u64> s;          // coefficients mod q (0, 1, q-1)
     std::vector<gala::u64> s_hat;      // forward transform of s
+    gala::u64 *d_s_hat = nullptr;      // device copy of s_hat (null on a host without a device)
 };
 
 struct gala_gk {
@@ -150,6 +151,12 @@ namespace gala {
 int launch_ntt(const gala_ctx *ctx, void *stream, const u64 *src, u64 *dst, size_t count, int inverse);
 // the same with the tables of another modulus of the context (dev_q, dev_p or dev_P)
 int launch_ntt_mod(const gala_ctx *ctx, void *stream, const u64 *src, u64 *dst, size_t count, int inverse, const NttDev &T);
+
+// Batched client steps on internal-form ciphertexts (one workgroup per ciphertext).
+int launch_encrypt(const gala_ctx *ctx, void *stream, const u64 *s_hat, const u64 *slots, const u64 *seeds, int count,
+                   u64 *ct_out);
+int launch_decrypt(const gala_ctx *ctx, void *stream, const u64 *s_hat, const u64 *ct_in, int count, u64 *slots);
+const u64 *gauss_cdf_table();
 
 // key generation helper on `npairs` consecutive (t_hat, a_hat) pairs of n-word evaluation-domain
 // polynomials: t_hat <- t_hat - a_hat * s_hat in place (s_hat shared by all pairs).

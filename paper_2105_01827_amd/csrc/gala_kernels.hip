@@ -355,6 +355,96 @@ __global__ __launch_bounds__(NT) void finalize_kernel(FinalizeJob job, NttDev Tq
 }
 
 // ---------------------------------------------------------------------------
+// the client's steps, batched: one workgroup per ciphertext, internal (evaluation-domain) form
+// ---------------------------------------------------------------------------
+struct GaussCdf {
+    u64 t[2 * kGaussBound];   // floor(2^64 * P[X <= -bound + i])
+};
+__device__ __forceinline__ int draw_gauss_dev(const GaussCdf &cdf, u64 seed, u64 stream, u64 idx) {
+    const u64 u = rand64(seed, stream, idx, 0);
+    int x = -kGaussBound;
+#pragma unroll
+    for (int i = 0; i < 2 * kGaussBound; ++i) x += u >= cdf.t[i] ? 1 : 0;
+    return x;
+}
+// ct = (-a s + e + delta m, a) (Sec. II-C(1)): m = the plaintext polynomial of the slots, a uniform, e Gaussian,
+// everything drawn from the ciphertext's seed exactly as the host function does.
+template <int NT>
+__global__ __launch_bounds__(NT) void encrypt_kernel(const u64 *slots, const u64 *seeds, const u64 *s_hat, u64 *ct_out,
+                                                     NttDev Tq, NttDev Tp, const int *slot_to_idx, GaussCdf cdf, int n,
+                                                     int logn, int qbits, u64 delta, u64 delta_s) {
+    extern __shared__ u64 buf[];
+    const int tid = threadIdx.x;
+    const u64 q = Tq.mod.q, p = Tp.mod.q, seed = seeds[blockIdx.x];
+    const u64 *sl = slots + (size_t)blockIdx.x * n;
+    u64 *c0 = ct_out + (size_t)blockIdx.x * 2 * n, *c1 = c0 + n;
+    for (int s = tid; s < n; s += NT) {
+        const u64 v = sl[s];
+        buf[slot_to_idx[s]] = v >= p ? v % p : v;
+    }
+    __syncthreads();
+    ntt_inverse_lds<NT>(buf, n, logn, Tp);
+    u64 m[kMaxPer], a_hat[kMaxPer];
+#pragma unroll
+    for (int k = 0; k < kMaxPer; ++k) {
+        const int i = tid + k * NT;
+        m[k] = i < n ? buf[i] : 0;
+    }
+    __syncthreads();
+    for (int i = tid; i < n; i += NT) buf[i] = draw_uniform(q, qbits, seed, kStreamCtA, (u64)i);
+    __syncthreads();
+    ntt_forward_lds<NT>(buf, n, logn, Tq);
+#pragma unroll
+    for (int k = 0; k < kMaxPer; ++k) {
+        const int i = tid + k * NT;
+        if (i < n) {
+            a_hat[k] = csub(csub(buf[i], Tq.mod.q2), q);
+            c1[i] = a_hat[k];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kMaxPer; ++k) {
+        const int i = tid + k * NT;
+        if (i < n) {
+            const int e = draw_gauss_dev(cdf, seed, kStreamCtE, (u64)i);
+            const u64 el = e >= 0 ? (u64)e : q - (u64)(-e);
+            buf[i] = add_mod(el, mul_shoup(m[k], delta, delta_s, q), q);
+        }
+    }
+    __syncthreads();
+    ntt_forward_lds<NT>(buf, n, logn, Tq);
+#pragma unroll
+    for (int k = 0; k < kMaxPer; ++k) {
+        const int i = tid + k * NT;
+        if (i < n) c0[i] = sub_mod(csub(csub(buf[i], Tq.mod.q2), q), mul_mod(a_hat[k], s_hat[i], Tq.mod), q);
+    }
+}
+// slots = decode(round(p (c0 + c1 s) / q) mod p).  The rounded quotient of t = p v + floor(q/2) by q comes from
+// r = t mod q and the exact division (t - r) / q, which is the low word of (t - r) times q^-1 mod 2^64.
+template <int NT>
+__global__ __launch_bounds__(NT) void decrypt_kernel(const u64 *ct_in, const u64 *s_hat, u64 *slots, NttDev Tq, NttDev Tp,
+                                                     const int *slot_to_idx, int n, int logn, u64 q_inv64) {
+    extern __shared__ u64 buf[];
+    const int tid = threadIdx.x;
+    const u64 q = Tq.mod.q, p = Tp.mod.q;
+    const u64 *c0 = ct_in + (size_t)blockIdx.x * 2 * n, *c1 = c0 + n;
+    for (int i = tid; i < n; i += NT) buf[i] = add_mod(c0[i], mul_mod(c1[i], s_hat[i], Tq.mod), q);
+    __syncthreads();
+    ntt_inverse_lds<NT>(buf, n, logn, Tq);
+    for (int i = tid; i < n; i += NT) {
+        const u128 t = (u128)p * buf[i] + (q >> 1);
+        const u64 r = reduce128(t, Tq.mod);
+        const u64 quot = ((u64)t - r) * q_inv64;       // t - r is a multiple of q and the quotient is at most p
+        buf[i] = quot >= p ? quot - p : quot;
+    }
+    __syncthreads();
+    ntt_forward_lds<NT>(buf, n, logn, Tp);
+    u64 *out = slots + (size_t)blockIdx.x * n;
+    for (int s = tid; s < n; s += NT) out[s] = csub(csub(buf[slot_to_idx[s]], Tp.mod.q2), p);
+}
+
+// ---------------------------------------------------------------------------
 // convolution: hoisted input rotations and the multiply-accumulate
 // ---------------------------------------------------------------------------
 template <int NT>
@@ -528,6 +618,35 @@ int launch_ntt_mod(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, si
 }
 int launch_ntt(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, size_t count, int inverse) {
     return launch_ntt_mod(c, stream, src, dst, count, inverse, c->dev_q);
+}
+int launch_encrypt(const gala_ctx *c, void *stream, const u64 *s_hat, const u64 *slots, const u64 *seeds, int count,
+                   u64 *ct_out) {
+    if (!count) return 0;
+    GaussCdf cdf;
+    for (int i = 0; i < 2 * kGaussBound; ++i) cdf.t[i] = gauss_cdf_table()[i];
+    const size_t lds = sizeof(u64) * c->n;
+    hipStream_t st = (hipStream_t)stream;
+    if (block_threads(c->n) == 256)
+        hipLaunchKernelGGL(encrypt_kernel<256>, dim3((unsigned)count), dim3(256), lds, st, slots, seeds, s_hat, ct_out, c->dev_q,
+                           c->dev_p, c->d_slot_to_idx, cdf, c->n, c->logn, c->qbits, c->delta, c->delta_s);
+    else
+        hipLaunchKernelGGL(encrypt_kernel<64>, dim3((unsigned)count), dim3(64), lds, st, slots, seeds, s_hat, ct_out, c->dev_q,
+                           c->dev_p, c->d_slot_to_idx, cdf, c->n, c->logn, c->qbits, c->delta, c->delta_s);
+    return last_error();
+}
+int launch_decrypt(const gala_ctx *c, void *stream, const u64 *s_hat, const u64 *ct_in, int count, u64 *slots) {
+    if (!count) return 0;
+    u64 inv = c->q;                                   // Newton's iteration for q^-1 mod 2^64 (q is odd)
+    for (int i = 0; i < 6; ++i) inv *= 2 - c->q * inv;
+    const size_t lds = sizeof(u64) * c->n;
+    hipStream_t st = (hipStream_t)stream;
+    if (block_threads(c->n) == 256)
+        hipLaunchKernelGGL(decrypt_kernel<256>, dim3((unsigned)count), dim3(256), lds, st, ct_in, s_hat, slots, c->dev_q, c->dev_p,
+                           c->d_slot_to_idx, c->n, c->logn, inv);
+    else
+        hipLaunchKernelGGL(decrypt_kernel<64>, dim3((unsigned)count), dim3(64), lds, st, ct_in, s_hat, slots, c->dev_q, c->dev_p,
+                           c->d_slot_to_idx, c->n, c->logn, inv);
+    return last_error();
 }
 int launch_key_finish(const gala_ctx *c, void *stream, u64 *pairs, const u64 *s_hat, size_t npairs, const Modulus &mod) {
     if (!npairs) return 0;

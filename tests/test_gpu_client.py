@@ -1,0 +1,76 @@
+"""GPU parity of the batched client steps (encryption and decryption on the device, internal ciphertext form)
+against the CPU oracle's encrypt / decrypt (Sec. II-C(1)), bit for bit, through the C ABI."""
+import numpy as np
+import pytest
+
+from paper_2105_01827_amd import workloads as wl
+from tests.helpers import small_params
+from tests.test_gpu_parity import both, fc_case, harness, plain_matvec
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("n,count", [(8, 3), (64, 5), (512, 4), (2048, 7)])
+def test_encrypt_batch_matches_oracle_encrypt(n, count):
+    H = harness()
+    par = small_params(n) if n != 2048 else wl.DEFAULT
+    ctx, o = both(par)
+    sk, osk = ctx.keygen(9), o.keygen(9)
+    rng = np.random.default_rng(n)
+    slots = rng.integers(0, par.p, size=(count, n), dtype=np.uint64)
+    slots[0, :3] += np.uint64(par.p)                    # values are reduced mod p on the way in
+    seeds = np.array([11 + 1000 * i for i in range(count)], dtype=np.uint64)
+    d_ct = H.dev_empty(count * 2 * n)
+    ctx.encrypt_batch(sk, H.to_dev(slots), H.to_dev(seeds), count, d_ct)
+    got = H.export_cts(ctx, d_ct, count)
+    for i in range(count):
+        assert np.array_equal(got[i], o.encrypt(osk, slots[i] % np.uint64(par.p), int(seeds[i]))), i
+        assert np.array_equal(got[i], ctx.encrypt(sk, slots[i] % np.uint64(par.p), int(seeds[i])))
+    ctx.encrypt_batch(sk, H.to_dev(slots), H.to_dev(seeds), 0, d_ct)          # an empty batch is a no-op
+
+
+@pytest.mark.parametrize("n,count", [(8, 3), (64, 5), (512, 4), (2048, 7)])
+def test_decrypt_batch_matches_oracle_decrypt(n, count):
+    H = harness()
+    par = small_params(n) if n != 2048 else wl.DEFAULT
+    ctx, o = both(par)
+    sk, osk = ctx.keygen(4), o.keygen(4)
+    rng = np.random.default_rng(n + 1)
+    slots = rng.integers(0, par.p, size=(count, n), dtype=np.uint64)
+    cts = np.stack([o.encrypt(osk, slots[i], seed=5 + i) for i in range(count)])
+    # make the rounding matter: also decrypt arbitrary ring elements (results are whatever the formula gives)
+    junk = rng.integers(0, par.q, size=(2, 2 * n), dtype=np.uint64)
+    allc = np.concatenate([cts, junk])
+    d_slots = H.dev_empty((count + 2) * n)
+    ctx.decrypt_batch(sk, H.import_cts(ctx, allc), count + 2, d_slots)
+    got = H.to_host(d_slots).reshape(count + 2, n)
+    for i in range(count):
+        assert np.array_equal(got[i], slots[i])
+    for i in range(count + 2):
+        assert np.array_equal(got[i], o.decrypt(osk, allc[i])), i
+
+
+def test_client_and_server_on_the_device_end_to_end():
+    """encrypt_batch -> he_fc -> decrypt_batch without leaving the device; the shares add up to W x."""
+    import torch
+    H = harness()
+    par = wl.DEFAULT
+    ctx, o = both(par)
+    shape = wl.FcShape("t", 128, 1024, 6)
+    W, x, r = wl.fc_inputs(shape, seed=3)
+    sk = ctx.keygen(0)
+    plan = ctx.fc_plan(W)
+    plan.bind(ctx.galois_keygen(sk, plan.rotations(), seed=1))
+    slots = np.stack([plan.pack_input(x[b]) for b in range(shape.batch)])
+    seeds = np.arange(shape.batch, dtype=np.uint64)
+    d_in, d_out = H.dev_empty(shape.batch * 2 * par.n), H.dev_empty(shape.batch * 2 * par.n)
+    ctx.encrypt_batch(sk, H.to_dev(slots), H.to_dev(seeds), shape.batch, d_in)
+    wsb = plan.workspace_bytes(shape.batch)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    plan.he_fc(d_in, shape.batch, H.to_dev(r), 17, d_out, ws, wsb)
+    d_slots = H.dev_empty(shape.batch * par.n)
+    ctx.decrypt_batch(sk, d_out, shape.batch, d_slots)
+    dec = H.to_host(d_slots).reshape(shape.batch, par.n)
+    for b in range(shape.batch):
+        share = plan.unpack_share(dec[b])
+        assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_matvec(W, x[b], par.p))
