@@ -287,6 +287,21 @@ __device__ __forceinline__ void mask_role(const PermJob &job, const Tables2048 &
     }
 }
 
+// Workgroup -> (item, chunk).  Consecutive workgroup ids go to the eight XCDs in turn, each with an L2 of its own.
+// When the chunk count is a multiple of eight, chunk c is always given to XCD c % 8, so that an XCD only ever
+// reads the keys and weights of its own chunks and they stay in its L2.
+__device__ __forceinline__ void item_and_chunk(const PermJob &job, int &item, int &chunk) {
+    const int w = blockIdx.x;
+    if ((job.nchunks & 7) == 0) {
+        const int per = job.nchunks >> 3, s = w >> 3;
+        chunk = (w & 7) + 8 * (s % per);
+        item = s / per;
+    } else {
+        item = w / job.nchunks;
+        chunk = w % job.nchunks;
+    }
+}
+
 // Every product on this path is a multiplication by a constant that carries its precomputed
 // quotient (twiddles, encoded weights, key polynomials), so sums of products stay in 64-bit
 // registers: each product is below 2q, a running sum is kept below 8q and may take four more
@@ -301,7 +316,8 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
         mask_role(job, T, mj, (int)blockIdx.x - job.items * job.nchunks, bufA, bufB);
         return;
     }
-    const int item = blockIdx.x / job.nchunks, chunk = blockIdx.x % job.nchunks;
+    int item, chunk;
+    item_and_chunk(job, item, chunk);
     const int g0 = (int)((long)chunk * job.G / job.nchunks), g1 = (int)((long)(chunk + 1) * job.G / job.nchunks);
     const NegQ q = T.nq;
     const u64 q8 = 8 * T.mod.q;
@@ -589,7 +605,8 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
         mask_role(job, T, mj, (int)blockIdx.x - job.items * job.nchunks, bufA, bufB);
         return;
     }
-    const int item = blockIdx.x / job.nchunks, chunk = blockIdx.x % job.nchunks;
+    int item, chunk;
+    item_and_chunk(job, item, chunk);
     const int g0 = (int)((long)chunk * job.G / job.nchunks), g1 = (int)((long)(chunk + 1) * job.G / job.nchunks);
     const NegQ q = T.nq, qP = S.TP.nq;
     const u64 q8 = 8 * T.mod.q, P8 = 8 * S.TP.mod.q;
