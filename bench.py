@@ -415,8 +415,15 @@ def main():
                 outs, ocnt = o.he_fc_batch(wpoly, shape.n_o, shape.n_i, cts[:sample], ksk, r[:sample], 17)
             c1 = time.perf_counter()
             assert np.array_equal(got[:sample], outs), "HIP result differs from the oracle"
+            # the same oracle on one thread: two inputs, one after the other
+            mask0 = [o.fc_mask_slots(shape.n_o, shape.n_i, r[b], 17, b) for b in range(2)]
+            s0 = time.perf_counter()
+            single = [o.he_fc(wpoly, cts[b], ksk, mask0[b]) for b in range(2)]
+            s1 = time.perf_counter()
+            assert all(np.array_equal(got[b], single[b][0]) for b in range(2))
             out["cpu_baseline"] = {"value": args.cpu_repeat * ocnt["perm"] / (c1 - c0), "unit": "rotations/s",
                                    "cores": o.max_threads(), "kind": "oracle",
+                                   "one_thread_value": sum(c["perm"] for _, c in single) / (s1 - s0),
                                    "sample": f"{sample} of the {batch} inputs of {args.workload}, {args.cpu_repeat} passes "
                                              f"(he_fc_batch: {ocnt['perm']} Perm, {ocnt['scmult']} ScMult per pass), "
                                              f"{c1 - c0:.1f} s wall"}
