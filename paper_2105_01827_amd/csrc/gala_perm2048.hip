@@ -108,42 +108,49 @@ __device__ __forceinline__ void bf_inv(u64 &x, u64 &y, const ulonglong2 t, NegQ 
 //
 // Radix-8 forward pass on the three index bits held in the register number (bit 2 of k first).
 // FIRST = false skips the first stage (the last pass of the transform has only two stages).
-template <bool FIRST, bool CORRECT>
-__device__ __forceinline__ void fwd_pass(u64 (&a)[8], const ulonglong2 *__restrict__ blk, NegQ q, u64 q2) {
-    if (FIRST) {
-        const ulonglong2 t1 = blk[0];
+// The seven constants of a pass are fetched with tw_load() BEFORE the exchange that precedes the pass: a load
+// cannot move across the exchange's barrier, and issued after it its latency is fully exposed, pass after pass.
+struct Tw7 {
+    ulonglong2 t[7];
+};
+__device__ __forceinline__ Tw7 tw_load(const ulonglong2 *__restrict__ blk) {
+    Tw7 w;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) bf_fwd(a[k], a[k + 4], t1, q, q2);
+    for (int e = 0; e < 7; ++e) w.t[e] = blk[e];
+    return w;
+}
+template <bool FIRST, bool CORRECT>
+__device__ __forceinline__ void fwd_pass(u64 (&a)[8], const Tw7 &w, NegQ q, u64 q2) {
+    if (FIRST) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) bf_fwd(a[k], a[k + 4], w.t[0], q, q2);
     }
     if (CORRECT) {   // seven stages done: everything is below 15q, bring it below 8q
         const u64 q8 = 4 * q2;
 #pragma unroll
         for (int k = 0; k < 8; ++k) a[k] = csub_dev(a[k], q8);
     }
-    const ulonglong2 t2a = blk[1], t2b = blk[2];
-    bf_fwd(a[0], a[2], t2a, q, q2);
-    bf_fwd(a[1], a[3], t2a, q, q2);
-    bf_fwd(a[4], a[6], t2b, q, q2);
-    bf_fwd(a[5], a[7], t2b, q, q2);
-    bf_fwd(a[0], a[1], blk[3], q, q2);
-    bf_fwd(a[2], a[3], blk[4], q, q2);
-    bf_fwd(a[4], a[5], blk[5], q, q2);
-    bf_fwd(a[6], a[7], blk[6], q, q2);
+    bf_fwd(a[0], a[2], w.t[1], q, q2);
+    bf_fwd(a[1], a[3], w.t[1], q, q2);
+    bf_fwd(a[4], a[6], w.t[2], q, q2);
+    bf_fwd(a[5], a[7], w.t[2], q, q2);
+    bf_fwd(a[0], a[1], w.t[3], q, q2);
+    bf_fwd(a[2], a[3], w.t[4], q, q2);
+    bf_fwd(a[4], a[5], w.t[5], q, q2);
+    bf_fwd(a[6], a[7], w.t[6], q, q2);
 }
 // Radix-8 inverse pass (bit 0 of k first), same block layout on the inverse table.
-__device__ __forceinline__ void inv_pass(u64 (&a)[8], const ulonglong2 *__restrict__ blk, NegQ q, u64 q2) {
-    bf_inv(a[0], a[1], blk[3], q, q2);
-    bf_inv(a[2], a[3], blk[4], q, q2);
-    bf_inv(a[4], a[5], blk[5], q, q2);
-    bf_inv(a[6], a[7], blk[6], q, q2);
-    const ulonglong2 t2a = blk[1], t2b = blk[2];
-    bf_inv(a[0], a[2], t2a, q, q2);
-    bf_inv(a[1], a[3], t2a, q, q2);
-    bf_inv(a[4], a[6], t2b, q, q2);
-    bf_inv(a[5], a[7], t2b, q, q2);
-    const ulonglong2 t1 = blk[0];
+__device__ __forceinline__ void inv_pass(u64 (&a)[8], const Tw7 &w, NegQ q, u64 q2) {
+    bf_inv(a[0], a[1], w.t[3], q, q2);
+    bf_inv(a[2], a[3], w.t[4], q, q2);
+    bf_inv(a[4], a[5], w.t[5], q, q2);
+    bf_inv(a[6], a[7], w.t[6], q, q2);
+    bf_inv(a[0], a[2], w.t[1], q, q2);
+    bf_inv(a[1], a[3], w.t[1], q, q2);
+    bf_inv(a[4], a[6], w.t[2], q, q2);
+    bf_inv(a[5], a[7], w.t[2], q, q2);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) bf_inv(a[k], a[k + 4], t1, q, q2);
+    for (int k = 0; k < 4; ++k) bf_inv(a[k], a[k + 4], w.t[0], q, q2);
 }
 
 // Store the 8 registers at index(k) = base_out | (k << SH_OUT), barrier, load index(k) = base_in | (k << SH_IN).
@@ -182,13 +189,17 @@ __device__ __forceinline__ void forward_to_lds(u64 (&a)[8], u64 *res, u64 *other
     const int tid = fresh(tid_);
     const NegQ q = T.nq;
     const u64 q2 = T.mod.q2;
-    fwd_pass<true, false>(a, T.tw + 8 * 1, q, q2);                                   // bits 8-10
+    Tw7 w = tw_load(T.tw + 8 * 1);
+    fwd_pass<true, false>(a, w, q, q2);                                              // bits 8-10
+    w = tw_load(T.tw + 8 * (8 + (tid >> 5)));
     exchange<8, 5>(a, other, tid, ((tid >> 5) << 8) | (tid & 31));
-    fwd_pass<true, false>(a, T.tw + 8 * (8 + (tid >> 5)), q, q2);                    // bits 5-7
+    fwd_pass<true, false>(a, w, q, q2);                                              // bits 5-7
+    w = tw_load(T.tw + 8 * (64 + (tid >> 2)));
     exchange<5, 2>(a, res, ((tid >> 5) << 8) | (tid & 31), ((tid >> 2) << 5) | (tid & 3));
-    fwd_pass<true, true>(a, T.tw + 8 * (64 + (tid >> 2)), q, q2);                    // bits 2-4
+    fwd_pass<true, true>(a, w, q, q2);                                               // bits 2-4
+    w = tw_load(T.tw + 8 * (256 + tid));
     exchange<2, 0>(a, other, ((tid >> 2) << 5) | (tid & 3), tid << 3);
-    fwd_pass<false, false>(a, T.tw + 8 * (256 + tid), q, q2);                        // bits 0-1
+    fwd_pass<false, false>(a, w, q, q2);                                             // bits 0-1
     u64 *po = res + pad(tid << 3);
 #pragma unroll
     for (int k = 0; k < 8; ++k) po[k] = a[k];
@@ -201,14 +212,17 @@ __device__ __forceinline__ void inverse_in_regs(u64 (&a)[8], u64 *bufA, u64 *buf
     const int tid = fresh(tid_);
     const NegQ q = T.nq;
     const u64 q2 = T.mod.q2;
-    inv_pass(a, T.itw + 8 * (256 + tid), q, q2);                                     // bits 0-2
+    Tw7 w = tw_load(T.itw + 8 * (256 + tid));
+    inv_pass(a, w, q, q2);                                                           // bits 0-2
+    w = tw_load(T.itw + 8 * (32 + (tid >> 3)));
     exchange<0, 3>(a, bufA, tid << 3, ((tid >> 3) << 6) | (tid & 7));
-    inv_pass(a, T.itw + 8 * (32 + (tid >> 3)), q, q2);                               // bits 3-5
+    inv_pass(a, w, q, q2);                                                           // bits 3-5
+    w = tw_load(T.itw + 8 * (4 + (tid >> 6)));
     exchange<3, 6>(a, bufB, ((tid >> 3) << 6) | (tid & 7), ((tid >> 6) << 9) | (tid & 63));
-    inv_pass(a, T.itw + 8 * (4 + (tid >> 6)), q, q2);                                // bits 6-8
+    inv_pass(a, w, q, q2);                                                           // bits 6-8
+    const ulonglong2 t2a = T.itw[8 * 1 + 1], t2b = T.itw[8 * 1 + 2];
     exchange<6, 8>(a, bufA, ((tid >> 6) << 9) | (tid & 63), tid);
     // bits 9-10 (register bits 1,2; register bit 0 is index bit 8), n^-1 folded into the last stage
-    const ulonglong2 t2a = T.itw[8 * 1 + 1], t2b = T.itw[8 * 1 + 2];
     bf_inv(a[0], a[2], t2a, q, q2);
     bf_inv(a[1], a[3], t2a, q, q2);
     bf_inv(a[4], a[6], t2b, q, q2);
