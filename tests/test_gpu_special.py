@@ -123,7 +123,7 @@ def test_he_conv_3x3_decrypts_at_the_papers_parameters():
 
 
 def test_he_conv_config4_decrypts_at_full_size():
-    """16x16x128 input, 128 kernels of 3x3, batch 16, n = 2048, p ~ 2^20: the convolution of BASELINE's fourth
+    """16x16x128 input, 128 kernels of 3x3, batch 16, n = 2048, p ~ 2^20: the convolution of the fourth benchmark
     configuration.  One output ciphertext is recomputed by the oracle; the plain convolution is recovered for two
     of the inputs from all their output ciphertexts."""
     par = params(2048)
