@@ -307,3 +307,49 @@ def test_61_bit_modulus_runs_on_the_generic_kernels():
         share = plan.unpack_share(ctx2.decrypt(sk2, got[b]))
         assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_matvec(W, x[b], par.p))
     conv_case(par, (16, 8, 1, 1, 16, 16), 2, [(0, 0), (1, 1)], seed=9)
+
+
+def test_error_paths_return_codes_and_launch_nothing():
+    """Unsupported shapes, unbound plans, short workspaces and bad arguments come back as error codes."""
+    import torch
+    H = harness()
+    par = small_params(64)
+    ctx, o = both(par)
+    sk = ctx.keygen(1)
+    rng = np.random.default_rng(0)
+
+    def code(fn):
+        with pytest.raises(binding.GalaError) as e:
+            fn()
+        return e.value.code
+
+    # shapes one ciphertext block cannot hold
+    assert code(lambda: ctx.fc_plan(rng.integers(0, par.p, size=(4, 128), dtype=np.uint64))) == binding.GALA_ESHAPE
+    assert code(lambda: ctx.conv_plan(rng.integers(0, par.p, size=(2, 2, 2, 2), dtype=np.uint64), 4, 4)) == binding.GALA_ESHAPE
+    assert code(lambda: ctx.conv_plan(rng.integers(0, par.p, size=(2, 2, 3, 3), dtype=np.uint64), 8, 8)) == binding.GALA_ESHAPE
+    # he_fc: plan not bound to keys, workspace too small, empty batch
+    W = rng.integers(0, par.p, size=(8, 32), dtype=np.uint64)
+    plan = ctx.fc_plan(W)
+    d_in, d_out = H.dev_empty(2 * 2 * par.n), H.dev_empty(2 * 2 * par.n)
+    d_r = H.to_dev(rng.integers(0, par.p, size=(2, 8), dtype=np.uint64))
+    wsb = plan.workspace_bytes(2)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    assert code(lambda: plan.he_fc(d_in, 2, d_r, 1, d_out, ws, wsb)) == binding.GALA_ENOKEY
+    plan.bind(ctx.galois_keygen(sk, plan.rotations(), seed=1))
+    assert code(lambda: plan.he_fc(d_in, 2, d_r, 1, d_out, ws, wsb - 256)) == binding.GALA_ENOMEM
+    assert code(lambda: plan.he_fc(d_in, 0, d_r, 1, d_out, ws, wsb)) == binding.GALA_EARG
+    # a plan cannot be bound to keys that lack one of its rotations
+    assert code(lambda: plan.bind(ctx.galois_keygen(sk, plan.rotations()[:-1], seed=1))) == binding.GALA_ENOKEY
+    # rotate: in place, step out of range
+    gk = ctx.galois_keygen(sk, [(0, 1)], seed=2)
+    assert code(lambda: ctx.rotate(gk, d_in, 1, (0, 1), d_in)) == binding.GALA_EARG
+    assert code(lambda: ctx.rotate(gk, d_in, 1, (0, par.n // 2), d_out)) == binding.GALA_EARG
+    # he_conv: unbound plan with taps
+    K = rng.integers(0, par.p, size=(4, 4, 3, 3), dtype=np.uint64)
+    cplan = ctx.conv_plan(K, 2, 4)
+    cwsb = cplan.workspace_bytes(1)
+    cws = torch.empty(max(cwsb, 8), dtype=torch.uint8, device="cuda")
+    d_cin = H.dev_empty(cplan.nin * 2 * par.n)
+    d_cout = H.dev_empty(cplan.nout * 2 * par.n)
+    d_cr = H.to_dev(rng.integers(0, par.p, size=(1, 4, 2, 4), dtype=np.uint64))
+    assert code(lambda: cplan.he_conv(d_cin, 1, d_cr, 1, d_cout, cws, cwsb)) == binding.GALA_ENOKEY
