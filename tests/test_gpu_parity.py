@@ -353,3 +353,13 @@ def test_error_paths_return_codes_and_launch_nothing():
     d_cout = H.dev_empty(cplan.nout * 2 * par.n)
     d_cr = H.to_dev(rng.integers(0, par.p, size=(1, 4, 2, 4), dtype=np.uint64))
     assert code(lambda: cplan.he_conv(d_cin, 1, d_cr, 1, d_cout, cws, cwsb)) == binding.GALA_ENOKEY
+
+
+def test_he_conv_matrix_cores_with_a_half_filled_column_tile():
+    """Four inputs (8 columns of a 16-column tile) on the matrix cores: the shape of the first ResNet stage,
+    64 -> 64 channels, 3x3, one 32x32 tile per input (c_n = 2, 288 terms, 64 rows)."""
+    par = wl.DEFAULT
+    shape = (64, 64, 3, 3, 32, 32)
+    ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, shape, 4, [(1, 5), (3, 31)], seed=4, matrix_cores=True)
+    assert plan.cn == 2 and plan.nin == 32 and plan.nout == 32
+    assert cnt["scmult"] == 4 * 32 * 2 * 32 * 9 and cnt["perm"] == 4 * 32
