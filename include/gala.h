@@ -152,6 +152,30 @@ int gala_encrypt_batch(const gala_ctx *ctx, void *stream, const gala_sk *sk, con
 int gala_decrypt_batch(const gala_ctx *ctx, void *stream, const gala_sk *sk, const uint64_t *ct_dev, int count,
                        uint64_t *slots_dev);
 
+/* ---- Add, ScMult and plaintext operands on their own (Sec. II-C(1)) --------- */
+/* The layers fuse these operations into their kernels; the stand-alone forms are for composing layers the
+ * plans do not cover (for example a matrix wider than n, split into blocks whose outputs are added, Sec. III-A).
+ * All buffers are device memory in the internal form and may alias where noted; work is enqueued on `stream`.
+ *
+ * gala_encode_plain: count slot vectors (count x n values, reduced mod p) -> count plaintext polynomials of n
+ * words in the evaluation domain.  mode 0: coefficients lifted to (-p/2, p/2] -- the operand of ScMult (the same
+ * encoding the plans use for weights).  mode 1: coefficients in [0,p) times delta -- the operand of
+ * gala_add_plain / gala_sub_plain, i.e. what encryption adds to c0. */
+int gala_encode_plain(const gala_ctx *ctx, void *stream, const uint64_t *slots_dev, int count, int mode,
+                      uint64_t *plain_dev);
+/* out[i] = a[i] + b[i] slot-wise (both polynomials mod q); out may be a or b. */
+int gala_add(const gala_ctx *ctx, void *stream, const uint64_t *a, const uint64_t *b, int count, uint64_t *out);
+/* out[i] = ct[i] (.) plain[i * plain_stride]: both polynomials times a mode-0 plaintext; plain_stride is n for
+ * one plaintext per ciphertext or 0 to use the same one for all; out may be ct. */
+int gala_scmult(const gala_ctx *ctx, void *stream, const uint64_t *ct, const uint64_t *plain, size_t plain_stride,
+                int count, uint64_t *out);
+/* out[i] = ct[i] -/+ plain[i * plain_stride] with a mode-1 plaintext (only c0 changes); out may be ct.  The
+ * subtraction is the share generation of Sec. III-A(3) on its own. */
+int gala_sub_plain(const gala_ctx *ctx, void *stream, const uint64_t *ct, const uint64_t *plain, size_t plain_stride,
+                   int count, uint64_t *out);
+int gala_add_plain(const gala_ctx *ctx, void *stream, const uint64_t *ct, const uint64_t *plain, size_t plain_stride,
+                   int count, uint64_t *out);
+
 /* ---- Perm: one slot rotation per ciphertext (Sec. II-C(1)) ----------------- */
 /* ct_out[i] = Perm_rot(ct_in[i]) for i < count, internal form, device.  A Perm
  * is a DecPerm (inverse transform of c1, base-2^gadget_bits digits, forward

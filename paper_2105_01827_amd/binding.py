@@ -78,6 +78,11 @@ SIGNATURES = {
     "gala_ct_export": (_I, [_VP, _VP, _U64P, _I, _U64P]),
     "gala_encrypt_batch": (_I, [_VP, _VP, _VP, _U64P, _U64P, _I, _U64P]),
     "gala_decrypt_batch": (_I, [_VP, _VP, _VP, _U64P, _I, _U64P]),
+    "gala_encode_plain": (_I, [_VP, _VP, _U64P, _I, _I, _U64P]),
+    "gala_add": (_I, [_VP, _VP, _U64P, _U64P, _I, _U64P]),
+    "gala_scmult": (_I, [_VP, _VP, _U64P, _U64P, C.c_size_t, _I, _U64P]),
+    "gala_sub_plain": (_I, [_VP, _VP, _U64P, _U64P, C.c_size_t, _I, _U64P]),
+    "gala_add_plain": (_I, [_VP, _VP, _U64P, _U64P, C.c_size_t, _I, _U64P]),
     "gala_rotate": (_I, [_VP, _VP, _VP, _U64P, _I, Rot, _U64P]),
     "gala_fc_plan_create": (_I, [_VP, _U64P, _I, _I, C.POINTER(_VP)]),
     "gala_fc_plan_destroy": (None, [_VP]),
@@ -229,6 +234,25 @@ class Context:
     def decrypt_batch(self, sk, ct_dev, count, slots_dev, stream=None):
         _check(self.lib.gala_decrypt_batch(self.h, _stream(stream), sk.h, _dev(ct_dev), count, _dev(slots_dev)),
                "gala_decrypt_batch")
+
+    def encode_plain(self, slots_dev, count, mode, plain_dev, stream=None):
+        _check(self.lib.gala_encode_plain(self.h, _stream(stream), _dev(slots_dev), count, mode, _dev(plain_dev)),
+               "gala_encode_plain")
+
+    def add(self, a, b, count, out, stream=None):
+        _check(self.lib.gala_add(self.h, _stream(stream), _dev(a), _dev(b), count, _dev(out)), "gala_add")
+
+    def scmult(self, ct, plain, count, out, shared=False, stream=None):
+        _check(self.lib.gala_scmult(self.h, _stream(stream), _dev(ct), _dev(plain), 0 if shared else self.n, count,
+                                    _dev(out)), "gala_scmult")
+
+    def sub_plain(self, ct, plain, count, out, shared=False, stream=None):
+        _check(self.lib.gala_sub_plain(self.h, _stream(stream), _dev(ct), _dev(plain), 0 if shared else self.n, count,
+                                       _dev(out)), "gala_sub_plain")
+
+    def add_plain(self, ct, plain, count, out, shared=False, stream=None):
+        _check(self.lib.gala_add_plain(self.h, _stream(stream), _dev(ct), _dev(plain), 0 if shared else self.n, count,
+                                       _dev(out)), "gala_add_plain")
 
     def rotate(self, gk, ct_in, count, rot, ct_out, stream=None):
         _check(self.lib.gala_rotate(self.h, _stream(stream), gk.h, _dev(ct_in), count, Rot(*rot), _dev(ct_out)),

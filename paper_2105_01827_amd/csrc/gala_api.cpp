@@ -91,6 +91,38 @@ extern "C" int gala_decrypt_batch(const gala_ctx *c, void *stream, const gala_sk
     return launch_decrypt(c, stream, sk->d_s_hat, ct, count, slots) ? GALA_EHIP : GALA_OK;
 }
 
+extern "C" int gala_encode_plain(const gala_ctx *c, void *stream, const uint64_t *slots, int count, int mode,
+                                 uint64_t *plain) {
+    if (!c || !slots || !plain || count < 0 || (mode != 0 && mode != 1)) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    return launch_encode_plain(c, stream, slots, count, mode, plain) ? GALA_EHIP : GALA_OK;
+}
+extern "C" int gala_add(const gala_ctx *c, void *stream, const uint64_t *a, const uint64_t *b, int count, uint64_t *out) {
+    if (!c || !a || !b || !out || count < 0) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    return launch_ct_op(c, stream, 0, a, b, 2 * (size_t)c->n, count, out) ? GALA_EHIP : GALA_OK;
+}
+namespace {
+int plain_op(const gala_ctx *c, void *stream, int op, const uint64_t *ct, const uint64_t *plain, size_t stride, int count,
+             uint64_t *out) {
+    if (!c || !ct || !plain || !out || count < 0 || (stride != 0 && stride != (size_t)c->n)) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    return launch_ct_op(c, stream, op, ct, plain, stride, count, out) ? GALA_EHIP : GALA_OK;
+}
+}  // namespace
+extern "C" int gala_scmult(const gala_ctx *c, void *stream, const uint64_t *ct, const uint64_t *plain, size_t stride,
+                           int count, uint64_t *out) {
+    return plain_op(c, stream, 1, ct, plain, stride, count, out);
+}
+extern "C" int gala_sub_plain(const gala_ctx *c, void *stream, const uint64_t *ct, const uint64_t *plain, size_t stride,
+                              int count, uint64_t *out) {
+    return plain_op(c, stream, 2, ct, plain, stride, count, out);
+}
+extern "C" int gala_add_plain(const gala_ctx *c, void *stream, const uint64_t *ct, const uint64_t *plain, size_t stride,
+                              int count, uint64_t *out) {
+    return plain_op(c, stream, 3, ct, plain, stride, count, out);
+}
+
 extern "C" int gala_rotate(const gala_ctx *c, void *stream, const gala_gk *gk, const uint64_t *ct_in, int count,
                            gala_rot rot, uint64_t *ct_out) {
     if (!c || !gk || !ct_in || !ct_out || count < 0 || rot.step < 0 || rot.step >= c->n / 2 || (rot.swap & ~1))

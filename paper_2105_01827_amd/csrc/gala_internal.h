@@ -158,6 +158,10 @@ int launch_encrypt(const gala_ctx *ctx, void *stream, const u64 *s_hat, const u6
 int launch_decrypt(const gala_ctx *ctx, void *stream, const u64 *s_hat, const u64 *ct_in, int count, u64 *slots);
 const u64 *gauss_cdf_table();
 
+// Stand-alone Add / ScMult / plaintext operations on internal-form buffers (op: 0 add ct, 1 scmult, 2 sub plain, 3 add plain).
+int launch_encode_plain(const gala_ctx *ctx, void *stream, const u64 *slots, int count, int mode, u64 *plain);
+int launch_ct_op(const gala_ctx *ctx, void *stream, int op, const u64 *a, const u64 *b, size_t b_stride, int count, u64 *out);
+
 // key generation helper on `npairs` consecutive (t_hat, a_hat) pairs of n-word evaluation-domain
 // polynomials: t_hat <- t_hat - a_hat * s_hat in place (s_hat shared by all pairs).
 int launch_key_finish(const gala_ctx *ctx, void *stream, u64 *pairs, const u64 *s_hat, size_t npairs, const Modulus &mod);

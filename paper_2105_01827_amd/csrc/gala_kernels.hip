@@ -355,6 +355,49 @@ __global__ __launch_bounds__(NT) void finalize_kernel(FinalizeJob job, NttDev Tq
 }
 
 // ---------------------------------------------------------------------------
+// Add, ScMult and plaintext operands on their own
+// ---------------------------------------------------------------------------
+// slots -> plaintext polynomial mod p -> lifted (mode 0: centred; mode 1: times delta) -> evaluation domain mod q
+template <int NT>
+__global__ __launch_bounds__(NT) void encode_plain_kernel(const u64 *slots, u64 *plain, NttDev Tq, NttDev Tp,
+                                                          const int *slot_to_idx, int n, int logn, int mode, u64 delta,
+                                                          u64 delta_s) {
+    extern __shared__ u64 buf[];
+    const int tid = threadIdx.x;
+    const u64 q = Tq.mod.q, p = Tp.mod.q;
+    const u64 *sl = slots + (size_t)blockIdx.x * n;
+    for (int s = tid; s < n; s += NT) {
+        const u64 v = sl[s];
+        buf[slot_to_idx[s]] = v >= p ? v % p : v;
+    }
+    __syncthreads();
+    ntt_inverse_lds<NT>(buf, n, logn, Tp);
+    for (int i = tid; i < n; i += NT) {
+        const u64 m = buf[i];
+        buf[i] = mode ? mul_shoup(m, delta, delta_s, q) : (m > p / 2 ? q - (p - m) : m);
+    }
+    __syncthreads();
+    ntt_forward_lds<NT>(buf, n, logn, Tq);
+    u64 *out = plain + (size_t)blockIdx.x * n;
+    for (int i = tid; i < n; i += NT) out[i] = csub(csub(buf[i], Tq.mod.q2), q);
+}
+// one thread per word of a ciphertext: op 0 ct + ct, 1 ct (.) plain, 2 ct - plain (c0 only), 3 ct + plain
+__global__ void ct_op_kernel(int op, const u64 *a, const u64 *b, size_t b_stride, size_t words, int n, u64 *out, Modulus mod) {
+    const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= words) return;
+    const size_t item = id / (2 * (size_t)n);
+    const int e = (int)(id % (2 * (size_t)n)), i = e % n;
+    const u64 x = a[id];
+    u64 r;
+    if (op == 0) r = add_mod(x, b[item * b_stride + e], mod.q);
+    else if (op == 1) r = mul_mod(x, b[item * b_stride + i], mod);
+    else if (e >= n) r = x;
+    else if (op == 2) r = sub_mod(x, b[item * b_stride + i], mod.q);
+    else r = add_mod(x, b[item * b_stride + i], mod.q);
+    out[id] = r;
+}
+
+// ---------------------------------------------------------------------------
 // the client's steps, batched: one workgroup per ciphertext, internal (evaluation-domain) form
 // ---------------------------------------------------------------------------
 struct GaussCdf {
@@ -618,6 +661,25 @@ int launch_ntt_mod(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, si
 }
 int launch_ntt(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, size_t count, int inverse) {
     return launch_ntt_mod(c, stream, src, dst, count, inverse, c->dev_q);
+}
+int launch_encode_plain(const gala_ctx *c, void *stream, const u64 *slots, int count, int mode, u64 *plain) {
+    if (!count) return 0;
+    const size_t lds = sizeof(u64) * c->n;
+    hipStream_t st = (hipStream_t)stream;
+    if (block_threads(c->n) == 256)
+        hipLaunchKernelGGL(encode_plain_kernel<256>, dim3((unsigned)count), dim3(256), lds, st, slots, plain, c->dev_q, c->dev_p,
+                           c->d_slot_to_idx, c->n, c->logn, mode, c->delta, c->delta_s);
+    else
+        hipLaunchKernelGGL(encode_plain_kernel<64>, dim3((unsigned)count), dim3(64), lds, st, slots, plain, c->dev_q, c->dev_p,
+                           c->d_slot_to_idx, c->n, c->logn, mode, c->delta, c->delta_s);
+    return last_error();
+}
+int launch_ct_op(const gala_ctx *c, void *stream, int op, const u64 *a, const u64 *b, size_t b_stride, int count, u64 *out) {
+    if (!count) return 0;
+    const size_t words = (size_t)count * 2 * c->n;
+    hipLaunchKernelGGL(ct_op_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, (hipStream_t)stream, op, a, b, b_stride,
+                       words, c->n, out, c->dev_q.mod);
+    return last_error();
 }
 int launch_encrypt(const gala_ctx *c, void *stream, const u64 *s_hat, const u64 *slots, const u64 *seeds, int count,
                    u64 *ct_out) {
