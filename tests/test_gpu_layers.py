@@ -99,3 +99,61 @@ def test_resnet18_shaped_layer_list():
     share = plan.unpack_share(ctx.decrypt(sk, got[0]))
     assert np.array_equal((share + r[0]) % np.uint64(par.p), (W @ x[0]) % np.uint64(par.p))
     print("ResNet-18 conv op totals:", total, flush=True)
+
+
+def test_he_fc_and_he_conv_replay_from_a_hip_graph():
+    """The layer entry points allocate nothing, wait for nothing and clear memory with kernels only, so a caller
+    can capture them in a HIP graph.  Captured once, replayed three times on fresh inputs with eager work and
+    synchronisations in between; every replay must equal the eager result of the same inputs."""
+    import torch
+    from tests import gpu_harness as Hn
+    par = small_params(256, p_limit=1 << 13, gadget_bits=8)
+    ctx = binding.Context(par.n, par.q, par.p, par.gadget_bits)
+    sk = ctx.keygen(0)
+    rng = np.random.default_rng(3)
+    n, batch = par.n, 4
+    W = rng.integers(0, par.p, size=(16, 64), dtype=np.uint64)
+    fplan = ctx.fc_plan(W)
+    fplan.bind(ctx.galois_keygen(sk, fplan.rotations(), seed=1))
+    K = rng.integers(0, par.p, size=(8, 8, 3, 3), dtype=np.uint64)
+    cplan = ctx.conv_plan(K, 4, 4)
+    cplan.bind(ctx.galois_keygen(sk, cplan.rotations(), seed=2))
+    cplan.prepare_batched()
+    d_fin, d_fout = Hn.dev_empty(batch * 2 * n), Hn.dev_empty(batch * 2 * n)
+    d_cin, d_cout = Hn.dev_empty(batch * cplan.nin * 2 * n), Hn.dev_empty(batch * cplan.nout * 2 * n)
+    d_fr = Hn.to_dev(rng.integers(0, par.p, size=(batch, 16), dtype=np.uint64))
+    d_cr = Hn.to_dev(rng.integers(0, par.p, size=(batch, 8, 4, 4), dtype=np.uint64))
+    fwsb, cwsb = fplan.workspace_bytes(batch), cplan.workspace_bytes(batch)
+    fws = torch.empty(fwsb, dtype=torch.uint8, device="cuda")
+    cws = torch.empty(cwsb, dtype=torch.uint8, device="cuda")
+
+    def layers(stream):
+        fplan.he_fc(d_fin, batch, d_fr, 5, d_fout, fws, fwsb, stream=stream)
+        cplan.he_conv(d_cin, batch, d_cr, 6, d_cout, cws, cwsb, stream=stream)
+
+    def fresh_inputs(seed):
+        g = np.random.default_rng(seed)
+        d_fin.copy_(Hn.to_dev(g.integers(0, par.q, size=batch * 2 * n, dtype=np.uint64)))
+        d_cin.copy_(Hn.to_dev(g.integers(0, par.q, size=batch * cplan.nin * 2 * n, dtype=np.uint64)))
+
+    fresh_inputs(0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        layers(side)                                     # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        layers(torch.cuda.current_stream())
+    for rep in range(3):
+        fresh_inputs(100 + rep)
+        layers(None)                                     # eager, default stream
+        torch.cuda.synchronize()
+        want_f, want_c = Hn.to_host(d_fout).copy(), Hn.to_host(d_cout).copy()
+        d_fout.zero_(); d_cout.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(Hn.to_host(d_fout), want_f), rep
+        assert np.array_equal(Hn.to_host(d_cout), want_c), rep
