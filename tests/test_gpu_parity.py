@@ -363,3 +363,18 @@ def test_he_conv_matrix_cores_with_a_half_filled_column_tile():
     ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, shape, 4, [(1, 5), (3, 31)], seed=4, matrix_cores=True)
     assert plan.cn == 2 and plan.nin == 32 and plan.nout == 32
     assert cnt["scmult"] == 4 * 32 * 2 * 32 * 9 and cnt["perm"] == 4 * 32
+
+
+@pytest.mark.parametrize("batch", [5, 17])
+def test_he_conv_matrix_cores_with_ragged_column_tiles(batch):
+    """Column counts that are not a multiple of the 16-column tile (10 and 34 columns: one and three tiles, the
+    last workgroup of the grid with a single valid tile), rows and terms ragged as well."""
+    par = small_params(128, p_limit=1 << 9, gadget_bits=4)
+    shape = (6, 10, 3, 3, 4, 4)
+    picks = [(0, 0), (batch // 2, 0), (batch - 1, 0)]
+    ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, shape, batch, picks, seed=batch, matrix_cores=True)
+    for b in (0, batch - 1):
+        share = np.zeros(r[b].shape, np.uint64)
+        for O in range(plan.nout):
+            plan.unpack_share(O, ctx.decrypt(sk, got[b, O]), share)
+        assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_conv(K, x[b], par.p))
