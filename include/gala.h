@@ -227,7 +227,8 @@ void gala_conv_plan_destroy(gala_conv_plan *plan);
  * whenever a call brings at least 4 inputs.  Costs about 1.3x the plan's device memory again;
  * results are bit-identical either way.  Needs n >= 16. */
 int gala_conv_plan_prepare_batched(gala_conv_plan *plan);
-/* geometry[0..4] = T, c_n, input ciphertexts per image, output ciphertexts, taps. */
+/* geometry[0..5] = T, c_n, input ciphertexts per image, output ciphertexts, taps, terms: the (input ciphertext,
+   tap) pairs whose encoded kernels are not all zero; only these are rotated and multiplied. */
 int gala_conv_plan_geometry(const gala_conv_plan *plan, int32_t *geometry);
 int gala_conv_plan_rotations(const gala_conv_plan *plan, gala_rot *rots, int *nrots);
 int gala_conv_plan_bind(gala_conv_plan *plan, const gala_gk *gk);

@@ -386,9 +386,9 @@ class ConvPlan:
         _check(ctx.lib.gala_conv_plan_create(ctx.h, kp, self.c_o, self.c_i, self.k_h, self.k_w, u_h, u_w, C.byref(h)),
                "gala_conv_plan_create")
         self.h = h
-        g = (C.c_int32 * 5)()
+        g = (C.c_int32 * 6)()
         _check(ctx.lib.gala_conv_plan_geometry(h, g), "gala_conv_plan_geometry")
-        self.T, self.cn, self.nin, self.nout, self.ntap = (int(v) for v in g)
+        self.T, self.cn, self.nin, self.nout, self.ntap, self.nterm = (int(v) for v in g)
 
     def rotations(self):
         n = C.c_int()

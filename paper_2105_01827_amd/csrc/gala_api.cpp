@@ -210,14 +210,14 @@ ConvWorkspace conv_workspace(const gala_conv_plan *pl, int batch) {
     ws.chunks = choose_chunks(batch * pl->nout, pl->cn);
     ws.digits = 0;
     ws.xrot = ws.digits + align_up((size_t)batch * pl->nin * c->ndigits * n * w * (c->special ? 2 : 1));
-    ws.acc = ws.xrot + align_up((size_t)batch * pl->nin * pl->ntap * 2 * n * w);
+    ws.acc = ws.xrot + align_up((size_t)batch * pl->nterm * 2 * n * w);
     ws.partial = ws.acc + align_up((size_t)batch * pl->nout * pl->cn * 2 * n * w);
     ws.xl = ws.partial + align_up((size_t)batch * pl->nout * (ws.chunks + 1) * 2 * n * w);
     ws.mfma = pl->d_wl && 2 * batch >= 8;    // from four inputs on, half a column tile is enough to win
     size_t xl_bytes = 0, tmp_bytes = 0;
     if (ws.mfma) {
         int mt, nt, kb;
-        conv_mfma_geometry(pl->nout * pl->cn, 2 * batch, pl->nin * pl->ntap, &mt, &nt, &kb);
+        conv_mfma_geometry(pl->nout * pl->cn, 2 * batch, pl->nterm, &mt, &nt, &kb);
         xl_bytes = conv_mfma_image_bytes(c->n, nt, kb);
         tmp_bytes = conv_mfma_tmp_bytes(c->n, mt, nt);
     }
@@ -236,7 +236,7 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
                             size_t workspace_bytes, gala_opcount *counts) {
     if (!c || !pl || pl->ctx != c || !ct_in || !ct_out || !r || batch <= 0) return GALA_EARG;
     if (!c->has_device) return GALA_EHIP;
-    if ((pl->ntap > 1 || pl->cn > 1) && !pl->bound) return GALA_ENOKEY;
+    if ((pl->nrot_terms > 0 || pl->cn > 1) && !pl->bound) return GALA_ENOKEY;
     const ConvWorkspace ws = conv_workspace(pl, batch);
     if (!workspace || workspace_bytes < ws.total) return GALA_ENOMEM;
     char *base = (char *)workspace;
@@ -245,11 +245,13 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
     const int n = c->n;
     const size_t nct_in = (size_t)batch * pl->nin;
     const u64 *keys = pl->bound ? pl->bound->d_keys : nullptr;
-    // 1. input rotations: one DecPerm per input ciphertext, one HstPerm per non-central tap
+    // 1. input rotations: one DecPerm per input ciphertext, one HstPerm per term off the central tap
     // 2. ScMult and Add first: one sum per (output block, kernel order)
-    const bool fast_hoist = uses_fast_hoist(c) && (pl->ntap == 1 || (pl->bound && pl->bound->d_keys2));
+    const bool rotates = pl->nrot_terms > 0;
+    const bool fast_hoist = uses_fast_hoist(c) && (!rotates || (pl->bound && pl->bound->d_keys2));
     const u64 *keys2 = pl->bound ? pl->bound->d_keys2 : nullptr;
-    const int nterm = pl->nin * pl->ntap, groups = pl->nout * pl->cn;
+    const int nterm = pl->nterm, groups = pl->nout * pl->cn;
+    const TermList terms{pl->nin, nterm, pl->d_term_ct, pl->d_term_gal, pl->d_term_key};
     const bool timed = c->prof_which == 1 && (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
     auto mark = [&](int end) {
         if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used + end], (hipStream_t)stream);
@@ -258,7 +260,7 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
     if (ws.mfma && fast_hoist && !c->special) {
         // the rotated inputs go straight into the column image of the matrix-core product
         u64 *xl = (u64 *)(base + ws.xl), *tmp = (u64 *)(base + ws.tmp);
-        if (launch_hstperm_pack_2048(c, stream, ct_in, digits, batch, pl->nin, pl->ntap, pl->d_tap_gal, pl->d_tap_key, keys2, xl))
+        if (launch_hstperm_pack_2048(c, stream, ct_in, digits, batch, terms, rotates, keys2, xl))
             return GALA_EHIP;
         mark(0);
         if (launch_conv_mfma(c, stream, pl->d_wl, xl, batch, groups, nterm, tmp)) return GALA_EHIP;
@@ -266,18 +268,19 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
         if (launch_conv_untranspose(c, stream, tmp, batch, groups, acc)) return GALA_EHIP;
     } else {
         if (c->special && fast_hoist) {
-            if (launch_hoist_taps_2048(c, stream, ct_in, nct_in, pl->ntap, pl->d_tap_gal, pl->d_tap_key, keys2, digits, xrot))
+            if (launch_hoist_taps_2048(c, stream, ct_in, batch, terms, rotates, keys2, digits, xrot))
                 return GALA_EHIP;
         } else if (c->special) {
-            // every tap as a Perm of its own: xrot[ct][tap] = Perm_{tap}(ct), one workgroup per (ct, tap)
+            // every term as a Perm of its own: xrot[b][e] = Perm_e(ct of term e), one workgroup per (b, e)
             PermJob taps{};
             taps.ct_in = ct_in;
-            taps.in_item_stride = 2 * (size_t)n;
-            taps.in_g_stride = 0;
+            taps.in_item_stride = (size_t)pl->nin * 2 * n;
+            taps.in_g_stride = 2 * (size_t)n;
+            taps.in_g_index = pl->d_term_ct;
             taps.w = nullptr;
-            taps.gal = pl->d_tap_gal; taps.key_idx = pl->d_tap_key;
+            taps.gal = pl->d_term_gal; taps.key_idx = pl->d_term_key;
             taps.keys = keys; taps.keys2 = keys2;
-            taps.G = pl->ntap; taps.items = (int)nct_in; taps.nchunks = pl->ntap; taps.slots = pl->ntap;
+            taps.G = nterm; taps.items = batch; taps.nchunks = nterm; taps.slots = nterm;
             taps.partial = xrot;
             const int which = c->prof_which;     // these launches are not the ones the events are for
             c->prof_which = -1;
@@ -285,11 +288,11 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
             c->prof_which = which;
             if (rc) return GALA_EHIP;
         } else if (fast_hoist) {
-            if (launch_hoist_taps_2048(c, stream, ct_in, nct_in, pl->ntap, pl->d_tap_gal, pl->d_tap_key, keys2, digits, xrot))
+            if (launch_hoist_taps_2048(c, stream, ct_in, batch, terms, rotates, keys2, digits, xrot))
                 return GALA_EHIP;
         } else {
-            if (pl->ntap > 1 && launch_decperm(c, stream, ct_in, nct_in, digits)) return GALA_EHIP;
-            if (launch_hstperm_taps(c, stream, ct_in, digits, nct_in, pl->ntap, pl->d_tap_gal, pl->d_tap_key, keys, xrot))
+            if (rotates && launch_decperm(c, stream, ct_in, nct_in, digits)) return GALA_EHIP;
+            if (launch_hstperm_taps(c, stream, ct_in, digits, batch, terms, keys, xrot))
                 return GALA_EHIP;
         }
         if (ws.mfma) {
@@ -301,7 +304,7 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
             if (launch_conv_untranspose(c, stream, tmp, batch, groups, acc)) return GALA_EHIP;
         } else {
             mark(0);
-            if (launch_conv_mac(c, stream, pl->d_w, xrot, batch, pl->nout, pl->cn, pl->nin, pl->ntap, acc)) return GALA_EHIP;
+            if (launch_conv_mac(c, stream, pl->d_w, xrot, batch, pl->nout, pl->cn, nterm, acc)) return GALA_EHIP;
             mark(1);
         }
     }
@@ -325,12 +328,12 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
     fin.ct_out = ct_out;
     if (launch_perm_finalize(c, stream, job, fin)) return GALA_EHIP;
     if (counts) {
-        const int64_t terms = (int64_t)pl->nin * pl->ntap;
-        counts->decperm_in = pl->ntap > 1 ? (int64_t)batch * pl->nin : 0;
-        counts->hstperm_in = (int64_t)batch * pl->nin * (pl->ntap - 1);
-        counts->scmult = (int64_t)batch * pl->nout * pl->cn * terms;
+        const int64_t nt = nterm;
+        counts->decperm_in = (int64_t)batch * pl->nrot_cts;
+        counts->hstperm_in = (int64_t)batch * pl->nrot_terms;
+        counts->scmult = (int64_t)batch * pl->nout * pl->cn * nt;
         counts->perm = (int64_t)batch * pl->nout * (pl->cn - 1);
-        counts->add = (int64_t)batch * pl->nout * (pl->cn * (terms - 1) + (pl->cn - 1));
+        counts->add = (int64_t)batch * pl->nout * (pl->cn * (nt - 1) + (pl->cn - 1));
     }
     return GALA_OK;
 }

@@ -729,12 +729,27 @@ extern "C" int gala_conv_plan_create(gala_ctx *c, const uint64_t *K, int c_o, in
     pl->grp_gal.resize(cn);
     for (int gam = 0; gam < cn; ++gam) pl->grp_gal[gam] = galois_element(n, gam / hpos, (gam % hpos) * T);
 
-    const size_t npoly = (size_t)nout * cn * nin * ntap;
+    // Terms: an (input ciphertext, tap) pair takes part when some kernel value it carries is non-zero mod p and the
+    // tap reaches inside the image; every (input channel, output channel) pair sits in exactly one kernel order, so
+    // this is the set of pairs with a non-zero encoded kernel.  An all-zero layer keeps one term.
+    for (int I = 0; I < nin; ++I)
+        for (int tap = 0; tap < ntap; ++tap) {
+            const int dy = tap / k_w - k_h / 2, dx = tap % k_w - k_w / 2;
+            bool active = false;
+            if (std::abs(dy) < u_h && std::abs(dx) < u_w)
+                for (int in_ch = I * cn; in_ch < std::min(c_i, (I + 1) * cn) && !active; ++in_ch)
+                    for (int out_ch = 0; out_ch < c_o && !active; ++out_ch)
+                        active = K[((size_t)out_ch * c_i + in_ch) * ntap + tap] % c->p != 0;
+            if (active) { pl->term_ct.push_back(I); pl->term_tap.push_back(tap); }
+        }
+    if (pl->term_ct.empty()) { pl->term_ct.push_back(0); pl->term_tap.push_back(pl->centre); }
+    const int nterm = pl->nterm = (int)pl->term_ct.size();
+    const size_t npoly = (size_t)nout * cn * nterm;
     std::vector<u64> w;
     try { w.resize(npoly * n); } catch (...) { delete pl; return GALA_ENOMEM; }
     parallel_for(npoly, [&](size_t id) {
-        const int tap = (int)(id % ntap), I = (int)(id / ntap % nin), gam = (int)(id / ntap / nin % cn),
-                  O = (int)(id / ntap / nin / cn);
+        const int e = (int)(id % nterm), tap = pl->term_tap[e], I = pl->term_ct[e], gam = (int)(id / nterm % cn),
+                  O = (int)(id / nterm / cn);
         const int gs = gam / hpos, gt = gam % hpos, dy = tap / k_w - k_h / 2, dx = tap % k_w - k_w / 2;
         std::vector<u64> slots(n, 0);
         for (int h = 0; h < 2; ++h)
@@ -772,11 +787,18 @@ extern "C" int gala_conv_plan_create(gala_ctx *c, const uint64_t *K, int c_o, in
         for (int t = rows; t <= n; ++t) mh.row_ptr[(size_t)O * (n + 1) + t] = rows;
         mh.nrows[O] = rows;
     }
-    std::vector<int> tap_key(ntap, -1), grp_key(cn, -1);
+    std::vector<int> term_key(nterm, -1), grp_key(cn, -1), term_gal(nterm);
+    std::vector<char> ct_rotates(nin, 0);
+    for (int e = 0; e < nterm; ++e) {
+        term_gal[e] = pl->tap_gal[pl->term_tap[e]];
+        if (term_gal[e] != 1) { ++pl->nrot_terms; ct_rotates[pl->term_ct[e]] = 1; }
+    }
+    for (char f : ct_rotates) pl->nrot_cts += f;
     int rc = upload(&pl->d_w, w);
-    if (!rc) rc = upload(&pl->d_tap_gal, pl->tap_gal);
+    if (!rc) rc = upload(&pl->d_term_ct, pl->term_ct);
+    if (!rc) rc = upload(&pl->d_term_gal, term_gal);
+    if (!rc) rc = upload(&pl->d_term_key, term_key);
     if (!rc) rc = upload(&pl->d_grp_gal, pl->grp_gal);
-    if (!rc) rc = upload(&pl->d_tap_key, tap_key);
     if (!rc) rc = upload(&pl->d_grp_key, grp_key);
     if (!rc) rc = upload_mask_layout(mh, &pl->mask_d);
     if (rc) { gala_conv_plan_destroy(pl); return rc; }
@@ -788,7 +810,7 @@ extern "C" int gala_conv_plan_prepare_batched(gala_conv_plan *pl) {
     if (pl->d_wl) return GALA_OK;
     const gala_ctx *c = pl->ctx;
     if (c->n < 16) return GALA_ESHAPE;
-    const int groups = pl->nout * pl->cn, nterm = pl->nin * pl->ntap;
+    const int groups = pl->nout * pl->cn, nterm = pl->nterm;
     int mt, nt, kb;
     conv_mfma_geometry(groups, groups, nterm, &mt, &nt, &kb);
     if (hipMalloc((void **)&pl->d_wl, conv_mfma_image_bytes(c->n, mt, kb)) != hipSuccess) return GALA_ENOMEM;
@@ -801,13 +823,14 @@ extern "C" int gala_conv_plan_prepare_batched(gala_conv_plan *pl) {
 }
 extern "C" void gala_conv_plan_destroy(gala_conv_plan *pl) {
     if (!pl) return;
-    hipFree(pl->d_w); hipFree(pl->d_wl); hipFree(pl->d_tap_gal); hipFree(pl->d_grp_gal); hipFree(pl->d_tap_key); hipFree(pl->d_grp_key);
+    hipFree(pl->d_w); hipFree(pl->d_wl); hipFree(pl->d_term_ct); hipFree(pl->d_term_gal); hipFree(pl->d_term_key);
+    hipFree(pl->d_grp_gal); hipFree(pl->d_grp_key);
     free_mask_layout(&pl->mask_d);
     delete pl;
 }
 extern "C" int gala_conv_plan_geometry(const gala_conv_plan *pl, int32_t *g) {
     if (!pl || !g) return GALA_EARG;
-    g[0] = pl->T; g[1] = pl->cn; g[2] = pl->nin; g[3] = pl->nout; g[4] = pl->ntap;
+    g[0] = pl->T; g[1] = pl->cn; g[2] = pl->nin; g[3] = pl->nout; g[4] = pl->ntap; g[5] = pl->nterm;
     return GALA_OK;
 }
 namespace {
@@ -828,7 +851,10 @@ gala_rot rot_of(const gala_ctx *c, int g) {
 extern "C" int gala_conv_plan_rotations(const gala_conv_plan *pl, gala_rot *rots, int *nrots) {
     if (!pl || !nrots) return GALA_EARG;
     std::vector<int> els;
-    for (int g : pl->tap_gal) if (g != 1 && std::find(els.begin(), els.end(), g) == els.end()) els.push_back(g);
+    for (int t : pl->term_tap) {
+        const int g = pl->tap_gal[t];
+        if (g != 1 && std::find(els.begin(), els.end(), g) == els.end()) els.push_back(g);
+    }
     for (int g : pl->grp_gal) if (g != 1 && std::find(els.begin(), els.end(), g) == els.end()) els.push_back(g);
     *nrots = (int)els.size();
     if (rots)
@@ -837,12 +863,13 @@ extern "C" int gala_conv_plan_rotations(const gala_conv_plan *pl, gala_rot *rots
 }
 extern "C" int gala_conv_plan_bind(gala_conv_plan *pl, const gala_gk *gk) {
     if (!pl || !gk) return GALA_EARG;
-    std::vector<int> tk(pl->ntap, -1), gkey(pl->cn, -1);
-    for (int t = 0; t < pl->ntap; ++t) {
-        if (pl->tap_gal[t] == 1) continue;
-        auto it = gk->index_of.find(pl->tap_gal[t]);
+    std::vector<int> tk(pl->nterm, -1), gkey(pl->cn, -1);
+    for (int e = 0; e < pl->nterm; ++e) {
+        const int g = pl->tap_gal[pl->term_tap[e]];
+        if (g == 1) continue;
+        auto it = gk->index_of.find(g);
         if (it == gk->index_of.end()) return GALA_ENOKEY;
-        tk[t] = it->second;
+        tk[e] = it->second;
     }
     for (int g = 0; g < pl->cn; ++g) {
         if (pl->grp_gal[g] == 1) continue;
@@ -850,7 +877,7 @@ extern "C" int gala_conv_plan_bind(gala_conv_plan *pl, const gala_gk *gk) {
         if (it == gk->index_of.end()) return GALA_ENOKEY;
         gkey[g] = it->second;
     }
-    if (hipMemcpy(pl->d_tap_key, tk.data(), sizeof(int) * pl->ntap, hipMemcpyHostToDevice) != hipSuccess ||
+    if (hipMemcpy(pl->d_term_key, tk.data(), sizeof(int) * pl->nterm, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(pl->d_grp_key, gkey.data(), sizeof(int) * pl->cn, hipMemcpyHostToDevice) != hipSuccess)
         return GALA_EHIP;
     pl->bound = gk;

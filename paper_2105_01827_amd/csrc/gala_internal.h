@@ -133,9 +133,13 @@ struct gala_conv_plan {
     int c_o = 0, c_i = 0, k_h = 0, k_w = 0, u_h = 0, u_w = 0;
     int T = 0, cn = 0, hpos = 0, nin = 0, nout = 0, ntap = 0, centre = 0;
     std::vector<int> tap_gal, grp_gal; // Galois elements of taps (ntap) and kernel orders (cn)
-    gala::u64 *d_w = nullptr;          // nout x cn x nin x ntap x n encoded kernels, evaluation domain
+    // Terms of the multiply-accumulate: the (input ciphertext, tap) pairs whose encoded kernels are not all zero,
+    // in (input, tap) order.  A dense kernel has nin*ntap of them.
+    int nterm = 0, nrot_terms = 0, nrot_cts = 0;   // terms; those that rotate; input ciphertexts with a rotating term
+    std::vector<int> term_ct, term_tap;
+    int *d_term_ct = nullptr, *d_term_gal = nullptr, *d_term_key = nullptr;   // nterm each (key valid once bound)
+    gala::u64 *d_w = nullptr;          // nout x cn x nterm x n encoded kernels, evaluation domain
     gala::u64 *d_wl = nullptr;         // the same as balanced base-256 digit planes for the matrix-core path, or null
-    int *d_tap_gal = nullptr, *d_tap_key = nullptr;   // ntap
     int *d_grp_gal = nullptr, *d_grp_key = nullptr;   // cn
     const gala_gk *bound = nullptr;
     MaskLayoutHost mask_h;
@@ -184,6 +188,7 @@ struct PermJob {
     const int *gal, *key_idx;
     const u64 *keys;
     const u64 *w2, *keys2;   // (value, companion) pair images of w and keys (n = 2048 kernel only)
+    const int *in_g_index;   // optional: rotation g reads input number in_g_index[g] instead of g
     int G, items, nchunks;
     int slots;               // partial ciphertexts reserved per item (>= nchunks)
     u64 *partial;            // items x slots x 2n
@@ -214,13 +219,18 @@ int launch_perm_accumulate_2048_masked(const gala_ctx *ctx, void *stream, const 
 
 // DecPerm of `count` ciphertexts: digits[c][j] = forward(digit_j(inverse(c1))), j < ndigits.
 int launch_decperm(const gala_ctx *ctx, void *stream, const u64 *ct_in, size_t count, u64 *digits);
+// The convolution's rotated inputs, one per (batch element, term): the description of the terms of a plan.
+struct TermList {
+    int nin, nterm;               // input ciphertexts per batch element, terms
+    const int *ct, *gal, *key;    // per term: input ciphertext, Galois element of its tap, key index (device)
+};
 // HstPerm for the convolution's input rotations:
-//   xrot[c][tap] = HstPerm_{tap_gal[tap]}(ct_in[c], digits[c]) ; the tap with Galois element 1 is a copy.
-int launch_hstperm_taps(const gala_ctx *ctx, void *stream, const u64 *ct_in, const u64 *digits, size_t count,
-                        int ntap, const int *tap_gal, const int *tap_key, const u64 *keys, u64 *xrot);
+//   xrot[b][e] = HstPerm_{gal[e]}(ct_in[b*nin + ct[e]], its digits) ; a term with Galois element 1 is a copy.
+int launch_hstperm_taps(const gala_ctx *ctx, void *stream, const u64 *ct_in, const u64 *digits, int batch,
+                        const TermList &terms, const u64 *keys, u64 *xrot);
 // acc[b][O][gam] = sum_{I,tap} w[O][gam][I][tap] (.) xrot[b][I][tap]   (both polynomials)
 int launch_conv_mac(const gala_ctx *ctx, void *stream, const u64 *w, const u64 *xrot, int batch, int nout, int cn,
-                    int nin, int ntap, u64 *acc);
+                    int nterm, u64 *acc);
 
 // Matrix-core path of the convolution's multiply-accumulate (gala_conv_mfma.hip): digit-plane images of the
 // encoded kernels (built once per plan) and of the rotated inputs (built per call), then one MFMA kernel.
@@ -228,13 +238,13 @@ void conv_mfma_geometry(int groups, int cols, int nterm, int *mtiles, int *ntile
 size_t conv_mfma_image_bytes(int n, int tiles, int kblocks);
 int launch_limb_pack(const gala_ctx *ctx, void *stream, const u64 *src, int mode, int rows, int nterm, u64 *dst);
 bool uses_fast_hoist(const gala_ctx *ctx);
-int launch_hoist_taps_2048(const gala_ctx *ctx, void *stream, const u64 *ct_in, size_t count, int ntap,
-                           const int *tap_gal, const int *tap_key, const u64 *keys2, u64 *digits, u64 *xrot);
+int launch_hoist_taps_2048(const gala_ctx *ctx, void *stream, const u64 *ct_in, int batch, const TermList &terms,
+                           bool any_rotation, const u64 *keys2, u64 *digits, u64 *xrot);
 size_t conv_mfma_tmp_bytes(int n, int mtiles, int ntiles);
 int launch_conv_mfma(const gala_ctx *ctx, void *stream, const u64 *wl, const u64 *xl, int batch, int groups,
                      int nterm, u64 *tmp);
 int launch_conv_untranspose(const gala_ctx *ctx, void *stream, const u64 *tmp, int batch, int groups, u64 *acc);
-int launch_hstperm_pack_2048(const gala_ctx *ctx, void *stream, const u64 *ct_in, u64 *digits, int batch, int nin,
-                             int ntap, const int *tap_gal, const int *tap_key, const u64 *keys2, u64 *xl);
+int launch_hstperm_pack_2048(const gala_ctx *ctx, void *stream, const u64 *ct_in, u64 *digits, int batch,
+                             const TermList &terms, bool any_rotation, const u64 *keys2, u64 *xl);
 
 }  // namespace gala

@@ -141,7 +141,8 @@ __global__ __launch_bounds__(NT) void perm_accumulate_kernel(PermJob job, NttDev
     int terms = 0;   // products (each below q^2 < 2^122) summed into the accumulators so far
 
     for (int g = g0; g < g1; ++g) {
-        const u64 *c0 = job.ct_in + (size_t)item * job.in_item_stride + (size_t)g * job.in_g_stride;
+        const u64 *c0 = job.ct_in + (size_t)item * job.in_item_stride +
+                        (size_t)(job.in_g_index ? job.in_g_index[g] : g) * job.in_g_stride;
         const u64 *c1 = c0 + n;
         const u64 *w = job.w ? job.w + (size_t)g * n : nullptr;
         const int gal = job.gal[g];
@@ -521,14 +522,14 @@ __global__ __launch_bounds__(NT) void decperm_kernel(const u64 *ct_in, u64 *digi
     }
 }
 
-__global__ void hstperm_taps_kernel(const u64 *ct_in, const u64 *digits, int ntap, const int *tap_gal,
-                                    const int *tap_key, const u64 *keys, u64 *xrot, Modulus mod, int n, int logn,
-                                    int ndigits) {
-    const int c = blockIdx.x / ntap, tap = blockIdx.x % ntap;
-    const u64 *c0 = ct_in + (size_t)c * 2 * n, *c1 = c0 + n;
-    const u64 *dig = digits + (size_t)c * ndigits * n;
-    u64 *out = xrot + ((size_t)c * ntap + tap) * 2 * n;
-    const int gal = tap_gal[tap];
+__global__ void hstperm_taps_kernel(const u64 *ct_in, const u64 *digits, TermList terms, const u64 *keys, u64 *xrot,
+                                    Modulus mod, int n, int logn, int ndigits) {
+    const int b = blockIdx.x / terms.nterm, e = blockIdx.x % terms.nterm;
+    const size_t c = (size_t)b * terms.nin + terms.ct[e];
+    const u64 *c0 = ct_in + c * 2 * n, *c1 = c0 + n;
+    const u64 *dig = digits + c * ndigits * n;
+    u64 *out = xrot + (size_t)blockIdx.x * 2 * n;
+    const int gal = terms.gal[e];
     if (gal == 1) {
         for (int i = threadIdx.x; i < n; i += blockDim.x) {
             out[i] = c0[i];
@@ -536,7 +537,7 @@ __global__ void hstperm_taps_kernel(const u64 *ct_in, const u64 *digits, int nta
         }
         return;
     }
-    const u64 *key = keys + (size_t)tap_key[tap] * ndigits * 2 * n;
+    const u64 *key = keys + (size_t)terms.key[e] * ndigits * 2 * n;
     for (int i = threadIdx.x; i < n; i += blockDim.x) {
         const int pi = galois_index(i, gal, logn, n);
         u128 a0 = c0[pi], a1 = 0;
@@ -584,7 +585,7 @@ __device__ __forceinline__ void mac128(u64 &lo, u64 &hi, u64 x, u64 w) {
 // Per coefficient the convolution's ScMult/Add step is a small dense product: (O,gam) x (I,tap) weights
 // times (I,tap) x (input, polynomial) rotated ciphertext words.  One thread owns one coefficient and a
 // TM x TN register tile of 128-bit sums, so each loaded word feeds TN (weights) or TM (inputs) products.
-// nterm = nin*ntap; groups = nout*cn; cols = 2*batch (input-major, c0 then c1).
+// nterm terms (the plan's active (input ciphertext, tap) pairs); groups = nout*cn; cols = 2*batch (input-major, c0 then c1).
 // A workgroup is WM x WN wavefronts on the same 64 coefficients: the wavefronts of a row read the same
 // weight words and those of a column the same input words, so those reads hit in the CU's vector cache.
 template <int TM, int TN, int WM, int WN>
@@ -735,7 +736,7 @@ int launch_perm_accumulate(const gala_ctx *c, void *stream, const PermJob &job) 
     const dim3 grid((unsigned)(job.items * job.nchunks));
     const bool timed = c->prof_which == 0 && (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
     if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used], st);
-    if (uses_fast_perm(c)) {
+    if (uses_fast_perm(c) && !job.in_g_index) {   // the n = 2048 kernels take consecutive inputs only
         const int rc = launch_perm_accumulate_2048(c, stream, job);
         if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used++ + 1], st);
         return rc;
@@ -788,21 +789,19 @@ int launch_decperm(const gala_ctx *c, void *stream, const u64 *ct_in, size_t cou
                            c->logn, c->gadget_bits, c->ndigits);
     return last_error();
 }
-int launch_hstperm_taps(const gala_ctx *c, void *stream, const u64 *ct_in, const u64 *digits, size_t count, int ntap,
-                        const int *tap_gal, const int *tap_key, const u64 *keys, u64 *xrot) {
-    if (!count) return 0;
-    hipLaunchKernelGGL(hstperm_taps_kernel, dim3((unsigned)(count * ntap)), dim3(block_threads(c->n)), 0,
-                       (hipStream_t)stream, ct_in, digits, ntap, tap_gal, tap_key, keys, xrot, c->dev_q.mod, c->n,
-                       c->logn, c->ndigits);
+int launch_hstperm_taps(const gala_ctx *c, void *stream, const u64 *ct_in, const u64 *digits, int batch,
+                        const TermList &terms, const u64 *keys, u64 *xrot) {
+    if (batch <= 0 || terms.nterm <= 0) return 0;
+    hipLaunchKernelGGL(hstperm_taps_kernel, dim3((unsigned)((size_t)batch * terms.nterm)), dim3(block_threads(c->n)), 0,
+                       (hipStream_t)stream, ct_in, digits, terms, keys, xrot, c->dev_q.mod, c->n, c->logn, c->ndigits);
     return last_error();
 }
 int launch_conv_mac(const gala_ctx *c, void *stream, const u64 *w, const u64 *xrot, int batch, int nout, int cn,
-                    int nin, int ntap, u64 *acc) {
+                    int nterm, u64 *acc) {
     if (batch <= 0) return 0;
     const int groups = nout * cn, cols = 2 * batch;
     // products are below q^2: 255 of them fit 128 bits when q < 2^60, 63 when q < 2^61
     const int flush_every = c->q < (1ull << 60) ? 255 : 63;
-    const int nterm = nin * ntap;
     hipStream_t st = (hipStream_t)stream;
     // The tile's width follows the number of (input, polynomial) columns (a single input is 2 columns); its
     // height is halved until the launch has a few workgroups per compute unit: with few columns the kernel is

@@ -475,14 +475,14 @@ __global__ __launch_bounds__(NT) void decperm_2048(const u64 *ct_in, u64 *digits
 // HstPerm: one workgroup per (ciphertext, tap).  c0 and the digits are read through the automorphism's index
 // map straight from memory: the map sends every aligned block of 64 indices onto another such block, so a
 // wavefront's gather still touches whole cache lines.  Output: xrot[ct][tap][c0|c1][i], canonical.
-__global__ __launch_bounds__(NT) void hstperm_taps_2048(const u64 *ct_in, const u64 *digits, int ntap, const int *tap_gal,
-                                                        const int *tap_key, const u64 *keys2, u64 *xrot, Tables2048 T,
-                                                        int ndigits) {
+__global__ __launch_bounds__(NT) void hstperm_taps_2048(const u64 *ct_in, const u64 *digits, TermList terms,
+                                                        const u64 *keys2, u64 *xrot, Tables2048 T, int ndigits) {
     const int tid = threadIdx.x;
-    const int ct = blockIdx.x / ntap, tap = blockIdx.x % ntap;
-    const u64 *c0 = ct_in + (size_t)ct * 2 * N, *c1 = c0 + N;
-    u64 *out = xrot + ((size_t)ct * ntap + tap) * 2 * N;
-    const int gal = tap_gal[tap];
+    const int b = blockIdx.x / terms.nterm, e = blockIdx.x % terms.nterm;
+    const size_t ct = (size_t)b * terms.nin + terms.ct[e];
+    const u64 *c0 = ct_in + ct * 2 * N, *c1 = c0 + N;
+    u64 *out = xrot + (size_t)blockIdx.x * 2 * N;
+    const int gal = terms.gal[e];
     if (gal == 1) {
 #pragma unroll
         for (int k = 0; k < PER; ++k) {
@@ -493,8 +493,8 @@ __global__ __launch_bounds__(NT) void hstperm_taps_2048(const u64 *ct_in, const 
         return;
     }
     const NegQ q = T.nq;
-    const u64 *dsrc = digits + (size_t)ct * ndigits * N;
-    const ulonglong2 *key = reinterpret_cast<const ulonglong2 *>(keys2) + (size_t)tap_key[tap] * ndigits * 2 * N;
+    const u64 *dsrc = digits + ct * ndigits * N;
+    const ulonglong2 *key = reinterpret_cast<const ulonglong2 *>(keys2) + (size_t)terms.key[e] * ndigits * 2 * N;
     // two batches of four coefficients keep the loads of a batch in flight together at a modest register count
 #pragma unroll 1
     for (int half = 0; half < 2; ++half) {
@@ -538,11 +538,10 @@ __global__ __launch_bounds__(NT) void hstperm_taps_2048(const u64 *ct_in, const 
 // consecutive terms (input ciphertext, tap), so a chunk is assembled in registers and the eight digit
 // chunks of a coefficient leave as 128 contiguous bytes.
 typedef int v4i_t __attribute__((ext_vector_type(4)));
-__global__ __launch_bounds__(NT) void hstperm_pack_2048(const u64 *ct_in, const u64 *digits, int nin, int ntap, int kblocks,
-                                                        const int *tap_gal, const int *tap_key, const u64 *keys2,
-                                                        v4i_t *xl, Tables2048 T, int ndigits) {
+__global__ __launch_bounds__(NT) void hstperm_pack_2048(const u64 *ct_in, const u64 *digits, TermList terms, int kblocks,
+                                                        const u64 *keys2, v4i_t *xl, Tables2048 T, int ndigits) {
     const int i = blockIdx.x * NT + threadIdx.x, eb = blockIdx.y, b = blockIdx.z;
-    const int nterm = nin * ntap;
+    const int nterm = terms.nterm;
     const NegQ q = T.nq;
     const size_t key_pairs = (size_t)ndigits * 2 * N;
     u64 D0[16], D1[16];     // balanced digits of the 16 terms' c0 and c1 values
@@ -551,14 +550,14 @@ __global__ __launch_bounds__(NT) void hstperm_pack_2048(const u64 *ct_in, const 
         const int e = eb * 16 + t;
         u64 v0 = 0, v1 = 0;
         if (e < nterm) {
-            const int I = e / ntap, tap = e - I * ntap, gal = tap_gal[tap];
-            const size_t ct = (size_t)b * nin + I;
+            const int gal = terms.gal[e];
+            const size_t ct = (size_t)b * terms.nin + terms.ct[e];
             const u64 *c0 = ct_in + ct * 2 * N;
             if (gal == 1) {
                 v0 = c0[i];
                 v1 = c0[N + i];
             } else {
-                const ulonglong2 *key = reinterpret_cast<const ulonglong2 *>(keys2) + (size_t)tap_key[tap] * key_pairs;
+                const ulonglong2 *key = reinterpret_cast<const ulonglong2 *>(keys2) + (size_t)terms.key[e] * key_pairs;
                 const u64 *dsrc = digits + ct * ndigits * N;
                 const int src = galois_index11(i, gal);
                 u64 s0 = c0[src], s1 = 0;
@@ -809,15 +808,16 @@ __global__ __launch_bounds__(NT) void decperm_special_2048(const u64 *ct_in, u64
 // HstPerm: one workgroup per (ciphertext, tap): inner products in both moduli from the stored digits, the sums
 // modulo P back to coefficients, lifted, reduced modulo q and transformed forward again, then
 // out = (P c0(X^g) + t_b - NTT(r_b)) / P, (t_a - NTT(r_a)) / P.  Output: xrot[ct][tap][c0|c1][i], canonical.
-__global__ __launch_bounds__(NT) void hstperm_special_2048(const u64 *ct_in, const u64 *digits, int ntap, const int *tap_gal,
-                                                           const int *tap_key, const u64 *keys2, u64 *xrot, Tables2048 T,
-                                                           SpecialJob S, int ndigits) {
+__global__ __launch_bounds__(NT) void hstperm_special_2048(const u64 *ct_in, const u64 *digits, TermList terms,
+                                                           const u64 *keys2, u64 *xrot, Tables2048 T, SpecialJob S,
+                                                           int ndigits) {
     __shared__ u64 bufA[LDS_WORDS], bufB[LDS_WORDS];
     const int tid = threadIdx.x;
-    const int ct = blockIdx.x / ntap, tap = blockIdx.x % ntap;
-    const u64 *c0 = ct_in + (size_t)ct * 2 * N, *c1 = c0 + N;
-    u64 *out = xrot + ((size_t)ct * ntap + tap) * 2 * N;
-    const int gal = tap_gal[tap];
+    const int b = blockIdx.x / terms.nterm, e = blockIdx.x % terms.nterm;
+    const size_t ct = (size_t)b * terms.nin + terms.ct[e];
+    const u64 *c0 = ct_in + ct * 2 * N, *c1 = c0 + N;
+    u64 *out = xrot + (size_t)blockIdx.x * 2 * N;
+    const int gal = terms.gal[e];
     if (gal == 1) {
 #pragma unroll
         for (int k = 0; k < PER; ++k) {
@@ -828,8 +828,8 @@ __global__ __launch_bounds__(NT) void hstperm_special_2048(const u64 *ct_in, con
         return;
     }
     const NegQ q = T.nq, qP = S.TP.nq;
-    const u64 *dsrc = digits + (size_t)ct * ndigits * 2 * N;
-    const ulonglong2 *key = reinterpret_cast<const ulonglong2 *>(keys2) + (size_t)tap_key[tap] * ndigits * 4 * N;
+    const u64 *dsrc = digits + ct * ndigits * 2 * N;
+    const ulonglong2 *key = reinterpret_cast<const ulonglong2 *>(keys2) + (size_t)terms.key[e] * ndigits * 4 * N;
     int src[PER];
     u64 sum0[PER], sum1[PER], tp0[PER], tp1[PER];
 #pragma unroll
@@ -958,52 +958,52 @@ int launch_perm_accumulate_2048_masked(const gala_ctx *c, void *stream, const Pe
 }
 
 bool uses_fast_hoist(const gala_ctx *c) { return uses_fast_perm(c) && c->ndigits <= HOIST_DIGITS; }
-int launch_hoist_taps_2048(const gala_ctx *c, void *stream, const u64 *ct_in, size_t count, int ntap, const int *tap_gal,
-                           const int *tap_key, const u64 *keys2, u64 *digits, u64 *xrot) {
-    if (!count) return 0;
+int launch_hoist_taps_2048(const gala_ctx *c, void *stream, const u64 *ct_in, int batch, const TermList &terms,
+                           bool any_rotation, const u64 *keys2, u64 *digits, u64 *xrot) {
+    if (batch <= 0 || terms.nterm <= 0) return 0;
+    const size_t count = (size_t)batch * terms.nin;
     const Tables2048 T = make_tables(c, c->d_tw2, c->dev_q);
     hipStream_t st = (hipStream_t)stream;
+    const dim3 per_term((unsigned)((size_t)batch * terms.nterm));
     if (c->special) {     // digits[ct][j][modulus][N]: twice the digit storage of the one-prime form
         SpecialJob S;
         S.TP = make_tables(c, c->d_tw2P, c->dev_P);
         S.Pq = make_ulonglong2(c->Pq, c->Pq_s);
         S.Pinv = make_ulonglong2(c->Pinv, c->Pinv_s);
-        if (ntap > 1) {
+        if (any_rotation) {
             hipLaunchKernelGGL(decperm_special_2048, dim3((unsigned)(count * c->ndigits * 2)), dim3(NT), 0, st, ct_in, digits,
                                T, S.TP, c->gadget_bits, c->ndigits);
             const int rc = (int)hipGetLastError();
             if (rc) return rc;
         }
-        hipLaunchKernelGGL(hstperm_special_2048, dim3((unsigned)(count * ntap)), dim3(NT), 0, st, ct_in, digits, ntap,
-                           tap_gal, tap_key, keys2, xrot, T, S, c->ndigits);
+        hipLaunchKernelGGL(hstperm_special_2048, per_term, dim3(NT), 0, st, ct_in, digits, terms, keys2, xrot, T, S, c->ndigits);
         return (int)hipGetLastError();
     }
-    if (ntap > 1) {
+    if (any_rotation) {
         hipLaunchKernelGGL(decperm_2048, dim3((unsigned)(count * c->ndigits)), dim3(NT), 0, st, ct_in, digits, T,
                            c->gadget_bits, c->ndigits);
         const int rc = (int)hipGetLastError();
         if (rc) return rc;
     }
-    hipLaunchKernelGGL(hstperm_taps_2048, dim3((unsigned)(count * ntap)), dim3(NT), 0, st, ct_in, digits, ntap, tap_gal,
-                       tap_key, keys2, xrot, T, c->ndigits);
+    hipLaunchKernelGGL(hstperm_taps_2048, per_term, dim3(NT), 0, st, ct_in, digits, terms, keys2, xrot, T, c->ndigits);
     return (int)hipGetLastError();
 }
 
-// DecPerm (when there is more than one tap) followed by the HstPerm of every tap, written as the column image
-int launch_hstperm_pack_2048(const gala_ctx *c, void *stream, const u64 *ct_in, u64 *digits, int batch, int nin, int ntap,
-                             const int *tap_gal, const int *tap_key, const u64 *keys2, u64 *xl) {
-    if (batch <= 0) return 0;
+// DecPerm (when any term rotates) followed by the HstPerm of every term, written as the column image
+int launch_hstperm_pack_2048(const gala_ctx *c, void *stream, const u64 *ct_in, u64 *digits, int batch,
+                             const TermList &terms, bool any_rotation, const u64 *keys2, u64 *xl) {
+    if (batch <= 0 || terms.nterm <= 0) return 0;
     const Tables2048 T = make_tables(c, c->d_tw2, c->dev_q);
     hipStream_t st = (hipStream_t)stream;
-    if (ntap > 1) {
-        hipLaunchKernelGGL(decperm_2048, dim3((unsigned)((size_t)batch * nin * c->ndigits)), dim3(NT), 0, st, ct_in, digits, T,
-                           c->gadget_bits, c->ndigits);
+    if (any_rotation) {
+        hipLaunchKernelGGL(decperm_2048, dim3((unsigned)((size_t)batch * terms.nin * c->ndigits)), dim3(NT), 0, st, ct_in,
+                           digits, T, c->gadget_bits, c->ndigits);
         const int rc = (int)hipGetLastError();
         if (rc) return rc;
     }
-    const int nterm = nin * ntap, eblocks = (nterm + 15) / 16, kblocks = (nterm + 63) / 64;
-    hipLaunchKernelGGL(hstperm_pack_2048, dim3(N / NT, (unsigned)eblocks, (unsigned)batch), dim3(NT), 0, st, ct_in, digits, nin,
-                       ntap, kblocks, tap_gal, tap_key, keys2, reinterpret_cast<v4i_t *>(xl), T, c->ndigits);
+    const int eblocks = (terms.nterm + 15) / 16, kblocks = (terms.nterm + 63) / 64;
+    hipLaunchKernelGGL(hstperm_pack_2048, dim3(N / NT, (unsigned)eblocks, (unsigned)batch), dim3(NT), 0, st, ct_in, digits, terms,
+                       kblocks, keys2, reinterpret_cast<v4i_t *>(xl), T, c->ndigits);
     return (int)hipGetLastError();
 }
 

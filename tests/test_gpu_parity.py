@@ -164,13 +164,16 @@ def test_he_fc_config3_1000x2048_batch64_sampled():
         assert np.array_equal((share + r[b]) % np.uint64(par.p), want), b
 
 
-def conv_case(par, shape, batch, oracle_outputs, seed=0, matrix_cores=False):
+def conv_case(par, shape, batch, oracle_outputs, seed=0, matrix_cores=False, edit_kernel=None):
     """oracle_outputs: list of (b, O) ciphertexts the oracle recomputes.  matrix_cores: keep the digit-plane
-    image of the kernels so that the multiply-accumulate runs on the MFMA units (needs batch >= 4)."""
+    image of the kernels so that the multiply-accumulate runs on the MFMA units (needs batch >= 4).
+    edit_kernel: a function that changes the seeded kernel tensor in place before either side sees it."""
     H = harness()
     ctx, o = both(par)
     co, ci, kh, kw, uh, uw = shape
     K, x, r = wl.conv_inputs(wl.ConvShape("t", co, ci, kh, kw, uh, uw, batch), p=par.p, seed=seed)
+    if edit_kernel:
+        edit_kernel(K)
     sk, osk = ctx.keygen(0), o.keygen(0)
     plan = ctx.conv_plan(K, uh, uw)
     geo = o.conv_geometry(*shape)
@@ -254,6 +257,59 @@ def test_he_conv_on_matrix_cores_small_rings(n, p_limit, gb, shape, batch):
         for O in range(plan.nout):
             plan.unpack_share(O, ctx.decrypt(sk, got[b, O]), share)
         assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_conv(K, x[b], par.p))
+
+
+def _punch_holes(K):
+    """Zero three taps everywhere, every tap but the centre for the second half of the input channels, and a
+    multiple of p (zero mod p) in one more tap: the plan drops such (input ciphertext, tap) terms."""
+    co, ci, kh, kw = K.shape
+    K[:, :, 0, 0] = 0
+    K[:, :, kh - 1, kw // 2] = 0
+    K[:, :, kh // 2, 0] = 0
+    centre = K[:, ci // 2:, kh // 2, kw // 2].copy()
+    K[:, ci // 2:] = 0
+    K[:, ci // 2:, kh // 2, kw // 2] = centre
+
+
+@pytest.mark.parametrize("n,p_limit,gb,shape,batch,matrix_cores", [
+    (64, 1 << 9, 4, (8, 16, 3, 3, 2, 4), 3, False),      # two input ciphertexts; the second keeps its centre tap only
+    (64, 1 << 9, 4, (8, 16, 3, 3, 2, 4), 9, True),
+    (512, 1 << 14, 8, (20, 24, 3, 3, 5, 6), 5, True),
+    (128, 1 << 9, 4, (6, 6, 5, 5, 2, 2), 2, False),      # 5x5 taps on 2x2 images: the outer ring never lands inside
+])
+def test_he_conv_skips_zero_terms(n, p_limit, gb, shape, batch, matrix_cores):
+    """Terms whose kernels are all zero are left out of the rotations and of the multiply-accumulate; the
+    ciphertexts stay those of the oracle, which adds the zero products."""
+    par = small_params(n, p_limit=p_limit, gadget_bits=gb)
+    co, ci, kh, kw, uh, uw = shape
+    o = Oracle(par.n, par.q, par.p, par.gadget_bits)
+    geo = o.conv_geometry(*shape)
+    picks = [(b, O) for b in (0, batch - 1) for O in range(geo["nout"])]
+    edit = _punch_holes if uh > 2 or kh == 3 else None
+    ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, shape, batch, picks, seed=n + 7, matrix_cores=matrix_cores,
+                                                    edit_kernel=edit)
+    assert plan.nterm < plan.nin * plan.ntap
+    if edit:
+        assert plan.nterm == (plan.ntap - 3) * ((plan.nin + 1) // 2) + plan.nin // 2
+    else:
+        assert plan.nterm == plan.nin * 9              # |dy|, |dx| <= 1 of the 5x5 taps
+    assert cnt["hstperm_in"] == batch * (plan.nterm - plan.nin)
+    assert cnt["scmult"] == batch * plan.nout * plan.cn * plan.nterm
+    for b in range(batch):
+        share = np.zeros((co, uh, uw), np.uint64)
+        for O in range(plan.nout):
+            plan.unpack_share(O, ctx.decrypt(sk, got[b, O]), share)
+        assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_conv(K, x[b], par.p))
+
+
+def test_he_conv_skips_zero_terms_n2048():
+    """The same on the n = 2048 kernels: vector multiply-accumulate (batch 2) and matrix cores (batch 6)."""
+    par = wl.DEFAULT
+    shape = (8, 32, 3, 3, 16, 16)                         # c_n = 8: four input ciphertexts, one output
+    for batch, mc in ((2, False), (6, True)):
+        ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, shape, batch, [(0, 0), (batch - 1, 0)], seed=77,
+                                                        matrix_cores=mc, edit_kernel=_punch_holes)
+        assert plan.nterm == 6 * 2 + 2      # (decryption to the plain result needs the special prime at this size)
 
 
 def test_he_conv_config4_matrix_cores_equals_vector_path():

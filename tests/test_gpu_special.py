@@ -8,7 +8,7 @@ import pytest
 
 from paper_2105_01827_amd import binding, workloads as wl
 from tests.helpers import rotate_slots, small_params
-from tests.test_gpu_parity import both, conv_case, fc_case, harness, plain_conv, plain_matvec
+from tests.test_gpu_parity import _punch_holes, both, conv_case, fc_case, harness, plain_conv, plain_matvec
 
 pytestmark = pytest.mark.gpu
 
@@ -101,6 +101,22 @@ def test_he_conv_small_rings(n, p_limit, gb, shape, batch, mc):
     outs = [(b, O) for b in range(min(batch, 3)) for O in range(nout)]
     ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, shape, batch, outs, seed=n, matrix_cores=mc)
     for b in range(batch):     # with the special prime the identity holds even at large gadget bases
+        share = np.zeros(r[b].shape, np.uint64)
+        for O in range(plan.nout):
+            plan.unpack_share(O, ctx.decrypt(sk, got[b, O]), share)
+        assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_conv(K, x[b], par.p))
+
+
+@pytest.mark.parametrize("n,p_limit,gb,shape,batch", [
+    (64, 1 << 9, 20, (8, 16, 3, 3, 2, 4), 3),            # any-n kernels: every term a Perm of its own
+    (2048, None, 20, (8, 32, 3, 3, 16, 16), 2),          # n = 2048 kernels
+])
+def test_he_conv_skips_zero_terms(n, p_limit, gb, shape, batch):
+    par = params(n, p_limit=p_limit, gadget_bits=gb) if p_limit else params(2048)
+    ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, shape, batch, [(0, 0), (batch - 1, 0)], seed=5,
+                                                    edit_kernel=_punch_holes)
+    assert plan.nterm == 6 * (plan.nin // 2) + plan.nin // 2
+    for b in range(batch):
         share = np.zeros(r[b].shape, np.uint64)
         for O in range(plan.nout):
             plan.unpack_share(O, ctx.decrypt(sk, got[b, O]), share)
