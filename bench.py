@@ -164,7 +164,13 @@ def resnet18_workload(ctx, sk, H, torch, args):
     ctx.profile_select(1)
     for L in layers:
         K = rng.integers(0, par.p, size=(L.c_o, L.c_i, L.k, L.k), dtype=np.uint64)
-        t = ctx.conv_tiling(L.in_hw, L.in_hw, L.k, L.k, L.stride)
+        if L.stride > 1 and not args.stride_by_subsampling:
+            # stride as a stride-1 layer over the phase images: only the outputs that are kept get computed
+            pp = ctx.conv_polyphase(L.c_i, L.in_hw, L.in_hw, L.k, L.k, L.stride)
+            K = ctx.polyphase_kernel(pp, K)
+            t = ctx.conv_tiling(pp.out_h, pp.out_w, pp.k_h_poly, pp.k_w_poly, 1)
+        else:
+            t = ctx.conv_tiling(L.in_hw, L.in_hw, L.k, L.k, L.stride)
         plan = ctx.conv_plan(K, t.tile_h, t.tile_w)
         gk = ctx.galois_keygen(sk, plan.rotations(), seed=8)
         plan.bind(gk)
@@ -185,10 +191,10 @@ def resnet18_workload(ctx, sk, H, torch, args):
         dt = timed(conv, torch, steps, 0)
         kms = ctx.profile_collect(steps)
         ctx.profile_enable(0)
-        groups, nterm = plan.nout * plan.cn, plan.nin * plan.ntap
+        groups, nterm = plan.nout * plan.cn, plan.nterm
         weight_bytes += 8.0 * par.n * groups * nterm
         mac_ms += float(np.mean(kms)) if kms else 0.0
-        per_layer.append({"layer": L.name, "tiles": t.tiles, "c_n": plan.cn, "ms": dt * 1e3,
+        per_layer.append({"layer": L.name, "tiles": t.tiles, "c_n": plan.cn, "terms": nterm, "ms": dt * 1e3,
                           "multiply_accumulate_ms": float(np.mean(kms)) if kms else None})
         total_ms += dt * 1e3
         for k in total:
@@ -228,6 +234,8 @@ def main():
     ap.add_argument("--special-prime", action="store_true",
                     help="key switching with the special prime (keys modulo q*P, exact division by P): the mode in "
                          "which 3x3 convolutions decrypt at the 20-bit plaintext modulus")
+    ap.add_argument("--stride-by-subsampling", action="store_true",
+                    help="resnet18_b1: evaluate strided layers at stride 1 and drop outputs instead of the polyphase split")
     ap.add_argument("--no-secondary", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device copy of this size (calibrates rocprofv3 HBM byte counters)")
@@ -258,6 +266,7 @@ def main():
             "ms_per_step": total_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64",
             "data": "synthetic",
             "config": {"workload": "resnet18_b1", "layers": len(per_layer), "n": par.n, "batch": 1,
+                       "stride": "subsampling" if args.stride_by_subsampling else "polyphase",
                        "note": "each layer timed on its own; a step is one pass over the 21 linear layers"},
             "layers_per_s": len(per_layer) * 1e3 / total_ms, "networks_per_s": 1e3 / total_ms, "ops_per_step": total,
             "per_layer": per_layer,

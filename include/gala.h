@@ -271,6 +271,28 @@ int gala_conv_tile_mask(const gala_conv_tiling *t, int ch, const uint64_t *r, in
 /* Writes the outputs this tile keeps from tile_vals (ch x tile_h x tile_w) into out (ch x out_h x out_w). */
 int gala_conv_tile_scatter(const gala_conv_tiling *t, int ch, const uint64_t *tile_vals, int tile, uint64_t *out);
 
+/* ---- stride as a polyphase split (host) ----
+ * The paper never mentions stride.  A stride-s "same" convolution, out[Y][X] = sum K[dy][dx] * x[sY+dy][sX+dx]
+ * over |dy| <= k_h/2, |dx| <= k_w/2, equals a stride-1 convolution (Sec. III-B) over the phase images
+ * x_(a,b)[Y][X] = x[sY+a][sX+b] taken as input channels, with the kernel of phase (a,b) holding K[sm+a][sl+b] at
+ * tap (m,l).  Only phases that some tap reads are kept (a 1x1 kernel reads phase (0,0) alone), in phase-major
+ * channel order: channel = (ia*phases_x + ib)*c_i + ch, where ia, ib index phase_y[], phase_x[].  The rearranged
+ * kernel is mostly zero taps, which convolution plans leave out; the layer's output comes out at its final size,
+ * nothing is computed and dropped.  1 <= stride <= 8. */
+typedef struct {
+    int32_t c_i, in_h, in_w, k_h, k_w, stride;
+    int32_t phases_y, phases_x;          /* number of row / column phases kept                     */
+    int32_t phase_y[8], phase_x[8];      /* their residues a, b in [0, stride), ascending          */
+    int32_t c_i_poly;                    /* c_i * phases_y * phases_x input channels of the plan   */
+    int32_t k_h_poly, k_w_poly;          /* odd sizes of the stride-1 kernel                       */
+    int32_t out_h, out_w;                /* ceil(in/stride): size of every phase image and of the output */
+} gala_conv_polyphase;
+int gala_conv_polyphase_plan(int c_i, int in_h, int in_w, int k_h, int k_w, int stride, gala_conv_polyphase *out);
+/* K (c_o x c_i x k_h x k_w) -> K_poly (c_o x c_i_poly x k_h_poly x k_w_poly), values copied unchanged. */
+int gala_conv_polyphase_kernel(const gala_conv_polyphase *pp, int c_o, const uint64_t *K, uint64_t *K_poly);
+/* x (c_i x in_h x in_w) -> x_poly (c_i_poly x out_h x out_w), zero where a phase runs past the image. */
+int gala_conv_polyphase_input(const gala_conv_polyphase *pp, const uint64_t *x, uint64_t *x_poly);
+
 #ifdef __cplusplus
 }
 #endif

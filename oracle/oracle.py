@@ -279,3 +279,58 @@ class Oracle:
                                  _p(xrot) if xrot is not None else None,
                                  C.byref(ready) if ready is not None else None, _p(out), C.byref(cnt))
         return out, cnt.as_dict()
+
+
+# ---------------------------------------------------------------------------
+# Stride.  The paper's convolution (Sec. III-B) is stride 1; a strided layer is defined here by the usual
+# "same"-padded sum and reduced to the stride-1 form by splitting the image into its phases.
+# ---------------------------------------------------------------------------
+def strided_conv_plain(K, x, p, stride):
+    """out[o][Y][X] = sum_{c,dy,dx} K[o][c][dy+kh//2][dx+kw//2] * x[c][stride*Y+dy][stride*X+dx] mod p, x zero
+    outside the image; the definition written out with Python integers (small cases only)."""
+    co, ci, kh, kw = K.shape
+    _, H, W = x.shape
+    oh, ow = -(-H // stride), -(-W // stride)
+    out = np.zeros((co, oh, ow), np.uint64)
+    for o in range(co):
+        for Y in range(oh):
+            for X in range(ow):
+                acc = 0
+                for c in range(ci):
+                    for dy in range(-(kh // 2), kh // 2 + 1):
+                        for dx in range(-(kw // 2), kw // 2 + 1):
+                            y, xx = stride * Y + dy, stride * X + dx
+                            if 0 <= y < H and 0 <= xx < W:
+                                acc += int(K[o, c, dy + kh // 2, dx + kw // 2]) * int(x[c, y, xx])
+                out[o, Y, X] = acc % p
+    return out
+
+
+def polyphase_split(K, x, stride):
+    """(K_poly, x_poly): the stride-1 convolution of x_poly with K_poly equals the stride-`stride` convolution of
+    x with K.  Phase (a, b) of the image, x[:, a::s, b::s], becomes a block of c_i input channels (phase-major,
+    only phases that a tap reads); tap (dy, dx) = (s*m + a, s*l + b) of K becomes tap (m, l) of that block."""
+    K, x = np.asarray(K, np.uint64), np.asarray(x, np.uint64)
+    co, ci, kh, kw = K.shape
+    _, H, W = x.shape
+    s = stride
+
+    def axis(k):
+        taps = range(-(k // 2), k // 2 + 1)
+        return sorted({d % s for d in taps}), 2 * max(abs(d // s) for d in taps) + 1     # // floors
+
+    ry, khp = axis(kh)
+    rx, kwp = axis(kw)
+    oh, ow = -(-H // s), -(-W // s)
+    Kp = np.zeros((co, len(ry) * len(rx) * ci, khp, kwp), np.uint64)
+    xp = np.zeros((len(ry) * len(rx) * ci, oh, ow), np.uint64)
+    for ia, a in enumerate(ry):
+        for ib, b in enumerate(rx):
+            base = (ia * len(rx) + ib) * ci
+            sub = x[:, a::s, b::s]
+            xp[base:base + ci, :sub.shape[1], :sub.shape[2]] = sub
+            for dy in range(-(kh // 2), kh // 2 + 1):
+                for dx in range(-(kw // 2), kw // 2 + 1):
+                    if dy % s == a and dx % s == b:
+                        Kp[:, base:base + ci, dy // s + khp // 2, dx // s + kwp // 2] = K[:, :, dy + kh // 2, dx + kw // 2]
+    return Kp, xp

@@ -45,6 +45,12 @@ class ConvTiling(C.Structure):
         return self.tiles_y * self.tiles_x
 
 
+class ConvPolyphase(C.Structure):
+    _fields_ = ([(k, C.c_int32) for k in ("c_i", "in_h", "in_w", "k_h", "k_w", "stride", "phases_y", "phases_x")] +
+                [("phase_y", C.c_int32 * 8), ("phase_x", C.c_int32 * 8)] +
+                [(k, C.c_int32) for k in ("c_i_poly", "k_h_poly", "k_w_poly", "out_h", "out_w")])
+
+
 class OpCount(C.Structure):
     _fields_ = [("perm", C.c_int64), ("decperm_in", C.c_int64), ("hstperm_in", C.c_int64),
                 ("scmult", C.c_int64), ("add", C.c_int64)]
@@ -107,6 +113,9 @@ SIGNATURES = {
     "gala_conv_tile_extract": (_I, [C.POINTER(ConvTiling), _I, _U64P, _I, _U64P]),
     "gala_conv_tile_mask": (_I, [C.POINTER(ConvTiling), _I, _U64P, _I, _U64P]),
     "gala_conv_tile_scatter": (_I, [C.POINTER(ConvTiling), _I, _U64P, _I, _U64P]),
+    "gala_conv_polyphase_plan": (_I, [_I, _I, _I, _I, _I, _I, C.POINTER(ConvPolyphase)]),
+    "gala_conv_polyphase_kernel": (_I, [C.POINTER(ConvPolyphase), _I, _U64P, _U64P]),
+    "gala_conv_polyphase_input": (_I, [C.POINTER(ConvPolyphase), _U64P, _U64P]),
 }
 
 _lib = None
@@ -284,6 +293,29 @@ class Context:
         assert out.dtype == np.uint64 and out.flags["C_CONTIGUOUS"] and out.shape == (ch, t.out_h, t.out_w)
         _check(self.lib.gala_conv_tile_scatter(C.byref(t), ch, ap, tile, out.ctypes.data_as(C.c_void_p)),
                "gala_conv_tile_scatter")
+
+    # ---- stride as a polyphase split (host)
+    def conv_polyphase(self, c_i, in_h, in_w, k_h, k_w, stride):
+        pp = ConvPolyphase()
+        _check(self.lib.gala_conv_polyphase_plan(c_i, in_h, in_w, k_h, k_w, stride, C.byref(pp)),
+               "gala_conv_polyphase_plan")
+        return pp
+
+    def polyphase_kernel(self, pp, K):
+        a, ap = _host(K); c_o = a.shape[0]
+        assert a.shape[1:] == (pp.c_i, pp.k_h, pp.k_w)
+        out = np.empty((c_o, pp.c_i_poly, pp.k_h_poly, pp.k_w_poly), np.uint64)
+        _check(self.lib.gala_conv_polyphase_kernel(C.byref(pp), c_o, ap, out.ctypes.data_as(C.c_void_p)),
+               "gala_conv_polyphase_kernel")
+        return out
+
+    def polyphase_input(self, pp, x):
+        a, ap = _host(x)
+        assert a.shape == (pp.c_i, pp.in_h, pp.in_w)
+        out = np.empty((pp.c_i_poly, pp.out_h, pp.out_w), np.uint64)
+        _check(self.lib.gala_conv_polyphase_input(C.byref(pp), ap, out.ctypes.data_as(C.c_void_p)),
+               "gala_conv_polyphase_input")
+        return out
 
     def conv_plan(self, K, u_h, u_w):
         return ConvPlan(self, K, u_h, u_w)

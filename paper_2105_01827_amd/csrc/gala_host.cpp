@@ -985,3 +985,68 @@ extern "C" int gala_conv_tile_scatter(const gala_conv_tiling *t, int ch, const u
                     out[((size_t)c * t->out_h + yo) * t->out_w + xo] = vals[((size_t)c * t->tile_h + ty) * t->tile_w + tx];
     return GALA_OK;
 }
+
+// ===========================================================================
+// stride as a polyphase split (host)
+// ===========================================================================
+namespace {
+inline int floor_div(int a, int b) { return a >= 0 ? a / b : -((-a + b - 1) / b); }
+// phases read by taps d in [-half, half]: residues of d modulo s, ascending
+int phases_of(int half, int s, int32_t *list) {
+    int cnt = 0;
+    for (int a = 0; a < s; ++a)
+        for (int d = -half; d <= half; ++d)
+            if (((d % s) + s) % s == a) { list[cnt++] = a; break; }
+    return cnt;
+}
+}  // namespace
+extern "C" int gala_conv_polyphase_plan(int c_i, int in_h, int in_w, int k_h, int k_w, int stride,
+                                        gala_conv_polyphase *pp) {
+    if (!pp || c_i < 1 || in_h < 1 || in_w < 1 || k_h < 1 || k_w < 1 || stride < 1 || stride > 8) return GALA_EARG;
+    if (!(k_h & 1) || !(k_w & 1)) return GALA_ESHAPE;
+    std::memset(pp, 0, sizeof *pp);
+    pp->c_i = c_i; pp->in_h = in_h; pp->in_w = in_w; pp->k_h = k_h; pp->k_w = k_w; pp->stride = stride;
+    pp->phases_y = phases_of(k_h / 2, stride, pp->phase_y);
+    pp->phases_x = phases_of(k_w / 2, stride, pp->phase_x);
+    pp->c_i_poly = c_i * pp->phases_y * pp->phases_x;
+    // tap d = s*m + a with m = floor(d/s): the most negative m sets the (symmetric) window
+    pp->k_h_poly = 2 * -floor_div(-(k_h / 2), stride) + 1;
+    pp->k_w_poly = 2 * -floor_div(-(k_w / 2), stride) + 1;
+    pp->out_h = (in_h + stride - 1) / stride;
+    pp->out_w = (in_w + stride - 1) / stride;
+    return GALA_OK;
+}
+extern "C" int gala_conv_polyphase_kernel(const gala_conv_polyphase *pp, int c_o, const uint64_t *K, uint64_t *Kp) {
+    if (!pp || !K || !Kp || c_o < 1) return GALA_EARG;
+    const int s = pp->stride, kh = pp->k_h, kw = pp->k_w, khp = pp->k_h_poly, kwp = pp->k_w_poly, ci = pp->c_i;
+    std::fill(Kp, Kp + (size_t)c_o * pp->c_i_poly * khp * kwp, 0);
+    for (int o = 0; o < c_o; ++o)
+        for (int ch = 0; ch < ci; ++ch)
+            for (int ty = 0; ty < kh; ++ty)
+                for (int tx = 0; tx < kw; ++tx) {
+                    const int dy = ty - kh / 2, dx = tx - kw / 2;
+                    const int m = floor_div(dy, s), l = floor_div(dx, s), a = dy - m * s, b = dx - l * s;
+                    const int ia = (int)(std::find(pp->phase_y, pp->phase_y + pp->phases_y, a) - pp->phase_y);
+                    const int ib = (int)(std::find(pp->phase_x, pp->phase_x + pp->phases_x, b) - pp->phase_x);
+                    const int chp = (ia * pp->phases_x + ib) * ci + ch;
+                    Kp[(((size_t)o * pp->c_i_poly + chp) * khp + (m + khp / 2)) * kwp + (l + kwp / 2)] =
+                        K[(((size_t)o * ci + ch) * kh + ty) * kw + tx];
+                }
+    return GALA_OK;
+}
+extern "C" int gala_conv_polyphase_input(const gala_conv_polyphase *pp, const uint64_t *x, uint64_t *xp) {
+    if (!pp || !x || !xp) return GALA_EARG;
+    const int s = pp->stride, ci = pp->c_i, oh = pp->out_h, ow = pp->out_w;
+    for (int ia = 0; ia < pp->phases_y; ++ia)
+        for (int ib = 0; ib < pp->phases_x; ++ib)
+            for (int ch = 0; ch < ci; ++ch) {
+                uint64_t *dst = xp + (size_t)((ia * pp->phases_x + ib) * ci + ch) * oh * ow;
+                const uint64_t *src = x + (size_t)ch * pp->in_h * pp->in_w;
+                for (int Y = 0; Y < oh; ++Y)
+                    for (int X = 0; X < ow; ++X) {
+                        const int y = s * Y + pp->phase_y[ia], xx = s * X + pp->phase_x[ib];
+                        dst[(size_t)Y * ow + X] = (y < pp->in_h && xx < pp->in_w) ? src[(size_t)y * pp->in_w + xx] : 0;
+                    }
+            }
+    return GALA_OK;
+}

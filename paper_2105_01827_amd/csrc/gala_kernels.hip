@@ -588,7 +588,7 @@ __device__ __forceinline__ void mac128(u64 &lo, u64 &hi, u64 x, u64 w) {
 // nterm terms (the plan's active (input ciphertext, tap) pairs); groups = nout*cn; cols = 2*batch (input-major, c0 then c1).
 // A workgroup is WM x WN wavefronts on the same 64 coefficients: the wavefronts of a row read the same
 // weight words and those of a column the same input words, so those reads hit in the CU's vector cache.
-template <int TM, int TN, int WM, int WN>
+template <int TM, int TN, int WM, int WN, int U>
 __global__ __launch_bounds__(64 * WM * WN) void conv_mac_kernel(const u64 *w, const u64 *xrot, int cols, int groups,
                                                                 int nterm, u64 *acc, Modulus mod, int n,
                                                                 int flush_every) {
@@ -610,18 +610,26 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mac_kernel(const u64 *w, co
     for (int a = 0; a < TM; ++a)
 #pragma unroll
         for (int b = 0; b < TN; ++b) lo[a][b] = hi[a][b] = 0;
-    int pending = 0;
-    for (int e = 0; e < nterm; ++e) {
-        u64 wv[TM], xv[TN];
+    // U terms per step, all their loads issued before the first product: a wavefront that waits for one load at
+    // a time reaches about half of the memory rate that several loads in flight do.
+    int pending = 0, e = 0;
+    for (; e + U <= nterm; e += U) {
+        u64 wv[U][TM], xv[U][TN];
 #pragma unroll
-        for (int a = 0; a < TM; ++a) wv[a] = wp[a][(size_t)e * n];
+        for (int u = 0; u < U; ++u) {
 #pragma unroll
-        for (int b = 0; b < TN; ++b) xv[b] = xp[b][(size_t)e * 2 * n];
+            for (int a = 0; a < TM; ++a) wv[u][a] = wp[a][(size_t)(e + u) * n];
 #pragma unroll
-        for (int a = 0; a < TM; ++a)
+            for (int b = 0; b < TN; ++b) xv[u][b] = xp[b][(size_t)(e + u) * 2 * n];
+        }
 #pragma unroll
-            for (int b = 0; b < TN; ++b) mac128(lo[a][b], hi[a][b], xv[b], wv[a]);
-        if (++pending == flush_every) {   // keep the 128-bit sums of products below q^2 from overflowing
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b) mac128(lo[a][b], hi[a][b], xv[u][b], wv[u][a]);
+        pending += U;
+        if (pending + U > flush_every) {   // keep the 128-bit sums of products below q^2 from overflowing
 #pragma unroll
             for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -632,6 +640,17 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mac_kernel(const u64 *w, co
             pending = 1;
         }
     }
+    for (; e < nterm; ++e) {               // fewer than U terms left: there is room for them (pending + U <= flush_every)
+        u64 wv[TM], xv[TN];
+#pragma unroll
+        for (int a = 0; a < TM; ++a) wv[a] = wp[a][(size_t)e * n];
+#pragma unroll
+        for (int b = 0; b < TN; ++b) xv[b] = xp[b][(size_t)e * 2 * n];
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) mac128(lo[a][b], hi[a][b], xv[b], wv[a]);
+    }
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -639,6 +658,109 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mac_kernel(const u64 *w, co
             const int m = m0 + a, col = c0 + b;
             if (m < groups && col < cols)
                 acc[(((size_t)(col >> 1) * groups + m) * 2 + (col & 1)) * n + i] = reduce128(hi[a][b], lo[a][b], mod);
+        }
+}
+
+// The same sums for a single input (two columns: c0 and c1), where the kernel is bound by streaming the encoded
+// kernels out of HBM once.  A workgroup is 4 x KS wavefronts on the same 64 coefficients: four consecutive tiles
+// of TM rows (their input words are shared through the vector cache) times KS slices of the terms, whose partial
+// sums meet in LDS at the end.  The words of the next U terms are requested before the products of the current U
+// terms are formed, so every wavefront keeps U*TM weight words in flight all the time.
+template <int TM, int U, int KS>
+__global__ __launch_bounds__(256 * KS) void conv_mac_stream_kernel(const u64 *w, const u64 *xrot, int groups, int nterm,
+                                                                   u64 *acc, Modulus mod, int n, int flush_every) {
+    __shared__ u64 part[KS > 1 ? (KS - 1) * 4 * TM * 2 * 64 : 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r = wave & 3, ks = wave >> 2;
+    const int i = min(blockIdx.x * 64 + lane, n - 1);          // lanes past the ring repeat the last coefficient
+    const bool live = blockIdx.x * 64 + lane < n;
+    const int m0 = (blockIdx.y * 4 + r) * TM;
+    const int per = (nterm + KS * U - 1) / (KS * U) * U;       // terms per slice, a multiple of U
+    const int e0 = min(ks * per, nterm), e1 = min(e0 + per, nterm);
+    const u64 *wp[TM];
+#pragma unroll
+    for (int a = 0; a < TM; ++a) wp[a] = w + ((size_t)min(m0 + a, groups - 1) * nterm + e0) * n + i;
+    const u64 *xp = xrot + (size_t)e0 * 2 * n + i;
+    u64 lo[TM][2], hi[TM][2];
+#pragma unroll
+    for (int a = 0; a < TM; ++a) lo[a][0] = lo[a][1] = hi[a][0] = hi[a][1] = 0;
+    const int nblk = (e1 - e0) / U;
+    u64 wa[U][TM], xa[U][2], wb[U][TM], xb[U][2];
+    auto load = [&](u64 (&wv)[U][TM], u64 (&xv)[U][2], int blk) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t e = (size_t)blk * U + u;
+#pragma unroll
+            for (int a = 0; a < TM; ++a) wv[u][a] = wp[a][e * n];
+            xv[u][0] = xp[e * 2 * n];
+            xv[u][1] = xp[e * 2 * n + n];
+        }
+    };
+    int pending = 0;
+    if (nblk > 0) load(wa, xa, 0);
+    for (int k = 0; k < nblk; ++k) {
+        load(wb, xb, min(k + 1, nblk - 1));         // the last step reads its own block again instead of branching
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+                mac128(lo[a][0], hi[a][0], xa[u][0], wa[u][a]);
+                mac128(lo[a][1], hi[a][1], xa[u][1], wa[u][a]);
+            }
+        pending += U;
+        if (pending + U > flush_every) {            // keep the 128-bit sums of products below q^2 from overflowing
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    lo[a][b] = reduce128(hi[a][b], lo[a][b], mod);
+                    hi[a][b] = 0;
+                }
+            pending = 1;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a) wa[u][a] = wb[u][a];
+            xa[u][0] = xb[u][0];
+            xa[u][1] = xb[u][1];
+        }
+    }
+    for (int e = nblk * U; e < e1 - e0; ++e) {      // fewer than U terms left: pending + U <= flush_every holds
+        const u64 x0 = xp[(size_t)e * 2 * n], x1 = xp[(size_t)e * 2 * n + n];
+#pragma unroll
+        for (int a = 0; a < TM; ++a) {
+            const u64 wv = wp[a][(size_t)e * n];
+            mac128(lo[a][0], hi[a][0], x0, wv);
+            mac128(lo[a][1], hi[a][1], x1, wv);
+        }
+    }
+    u64 sum[TM][2];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) sum[a][b] = reduce128(hi[a][b], lo[a][b], mod);
+    if (KS > 1) {
+        if (ks > 0) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) part[((((ks - 1) * 4 + r) * TM + a) * 2 + b) * 64 + lane] = sum[a][b];
+        }
+        __syncthreads();
+        if (ks > 0) return;
+#pragma unroll
+        for (int s2 = 1; s2 < KS; ++s2)
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    sum[a][b] = add_mod(sum[a][b], part[((((s2 - 1) * 4 + r) * TM + a) * 2 + b) * 64 + lane], mod.q);
+    }
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+        if (live && m0 + a < groups) {
+            acc[((size_t)(m0 + a) * 2) * n + i] = sum[a][0];
+            acc[((size_t)(m0 + a) * 2 + 1) * n + i] = sum[a][1];
         }
 }
 
@@ -803,23 +925,30 @@ int launch_conv_mac(const gala_ctx *c, void *stream, const u64 *w, const u64 *xr
     // products are below q^2: 255 of them fit 128 bits when q < 2^60, 63 when q < 2^61
     const int flush_every = c->q < (1ull << 60) ? 255 : 63;
     hipStream_t st = (hipStream_t)stream;
-    // The tile's width follows the number of (input, polynomial) columns (a single input is 2 columns); its
-    // height is halved until the launch has a few workgroups per compute unit: with few columns the kernel is
-    // bound by streaming the encoded kernels and needs the whole chip's loads in flight more than it needs reuse.
+    // The tile's width follows the number of (input, polynomial) columns; its height is halved until the launch
+    // has a few workgroups per compute unit: with few columns the kernel is bound by streaming the encoded kernels
+    // and needs the whole chip's loads in flight more than it needs reuse.  A single input (2 columns) has a
+    // kernel of its own.
     const unsigned iblocks = (unsigned)((c->n + 63) / 64);
     auto wgs = [&](int tm, int tn, int wm, int wn) {
         return (size_t)iblocks * ((groups + tm * wm - 1) / (tm * wm)) * ((cols + tn * wn - 1) / (tn * wn));
     };
     const size_t enough = 1024;
 #define GALA_MAC(TM, TN, WM, WN)                                                                                      \
-    hipLaunchKernelGGL((conv_mac_kernel<TM, TN, WM, WN>),                                                            \
+    hipLaunchKernelGGL((conv_mac_kernel<TM, TN, WM, WN, 1>),                                                         \
                        dim3(iblocks, (unsigned)((groups + TM * WM - 1) / (TM * WM)), (unsigned)((cols + TN * WN - 1) / (TN * WN))), \
                        dim3(64 * WM * WN), 0, st, w, xrot, cols, groups, nterm, acc, c->dev_q.mod, c->n, flush_every)
     if (cols <= 2) {
-        if (wgs(8, 2, 4, 1) >= enough) GALA_MAC(8, 2, 4, 1);
-        else if (wgs(4, 2, 4, 1) >= enough) GALA_MAC(4, 2, 4, 1);
-        else if (wgs(2, 2, 4, 1) >= enough) GALA_MAC(2, 2, 4, 1);
-        else GALA_MAC(1, 2, 4, 1);
+        // one input: the streaming kernel, with the tallest row tile that still gives every compute unit a workgroup
+        const size_t per_cu = 256;
+#define GALA_MACS(TM, KS)                                                                                             \
+    hipLaunchKernelGGL((conv_mac_stream_kernel<TM, 2, KS>), dim3(iblocks, (unsigned)((groups + TM * 4 - 1) / (TM * 4))), \
+                       dim3(256 * KS), 0, st, w, xrot, groups, nterm, acc, c->dev_q.mod, c->n, flush_every)
+        if (wgs(8, 2, 4, 1) >= per_cu) GALA_MACS(8, 2);
+        else if (wgs(4, 2, 4, 1) >= per_cu) GALA_MACS(4, 2);
+        else if (wgs(2, 2, 4, 1) >= per_cu) GALA_MACS(2, 1);
+        else GALA_MACS(1, 1);
+#undef GALA_MACS
     } else if (cols <= 4) {
         if (wgs(4, 4, 4, 1) >= enough) GALA_MAC(4, 4, 4, 1);
         else if (wgs(2, 4, 4, 1) >= enough) GALA_MAC(2, 4, 4, 1);

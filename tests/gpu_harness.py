@@ -58,7 +58,14 @@ def gpu_he_conv(ctx, plan, cts_coeff, r, mask_seed):
     return export_cts(ctx, d_out, batch * plan.nout).reshape(batch, plan.nout, 2 * ctx.n), cnt
 
 
-def gpu_conv_layer(ctx, sk, K, image, r_layer, stride, mask_seed, key_seed=8, enc_seed=0):
+def polyphase_layer(ctx, K, image, stride):
+    """(K_poly, image_poly) of the library: the stride-1 layer that computes the strided one."""
+    c_o, c_i, k_h, k_w = K.shape
+    pp = ctx.conv_polyphase(c_i, image.shape[1], image.shape[2], k_h, k_w, stride)
+    return ctx.polyphase_kernel(pp, K), ctx.polyphase_input(pp, image)
+
+
+def gpu_conv_layer(ctx, sk, K, image, r_layer, stride, mask_seed, key_seed=8, enc_seed=0, matrix_cores=False):
     """A whole convolution layer on one image (c_i x H x W) through the library: spatial tiling, stride,
     he_conv over the tiles.  Returns (tiling, plan, tile inputs, tile masks, input cts, output cts, counts)."""
     c_o, c_i, k_h, k_w = K.shape
@@ -68,6 +75,8 @@ def gpu_conv_layer(ctx, sk, K, image, r_layer, stride, mask_seed, key_seed=8, en
     gk = ctx.galois_keygen(sk, plan.rotations(), seed=key_seed)
     plan.bind(gk)
     tiles = t.tiles
+    if matrix_cores and tiles >= 4:
+        plan.prepare_batched()
     x_tiles = np.stack([ctx.tile_extract(t, image, b) for b in range(tiles)])
     r_tiles = np.stack([ctx.tile_mask(t, r_layer, b) for b in range(tiles)])
     slots = np.stack([plan.pack_input(x_tiles[b]) for b in range(tiles)])          # (tiles, nin, n)

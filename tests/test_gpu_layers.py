@@ -51,6 +51,43 @@ def test_tiled_strided_layer_matches_plain_convolution(n, p_limit, gb, c_o, c_i,
     assert np.array_equal(got[b, O], oracle_block(o, shape, K, cts[b], r_tiles[b], 5, b, O, osk))
 
 
+@pytest.mark.parametrize("n,p_limit,gb,c_o,c_i,k,stride,H,W,special", [
+    (64, 1 << 9, 4, 4, 2, 3, 2, 12, 12, False),     # 6x6 phases tiled; four phases of two channels
+    (64, 1 << 9, 4, 6, 4, 1, 2, 9, 5, False),       # 1x1: phase (0,0) alone, odd image
+    (256, 1 << 13, 4, 8, 4, 3, 2, 10, 10, False),   # 5x5 phases in one tile
+    (256, 1 << 13, 4, 4, 3, 7, 2, 20, 20, False),   # 7x7/2: 5x5 window on 10x10 phases
+    (256, 1 << 13, 20, 4, 2, 3, 3, 13, 11, True),   # stride 3, special prime
+])
+def test_polyphase_strided_layer(n, p_limit, gb, c_o, c_i, k, stride, H, W, special):
+    """A strided layer as a stride-1 he_conv over the phase images: the share decrypts to the strided convolution
+    written out by definition, the ciphertexts equal the oracle's on its own rearrangement of kernel and image, and
+    the plan multiplies only by the taps that exist."""
+    from oracle.oracle import polyphase_split, strided_conv_plain
+    from tests import gpu_harness as Hn
+    from tests.test_gpu_special import with_special
+    par = small_params(n, p_limit=p_limit, gadget_bits=gb)
+    if special:
+        par = with_special(par)
+    ctx = binding.Context(par.n, par.q, par.p, par.gadget_bits, par.special)
+    o = Oracle(par.n, par.q, par.p, par.gadget_bits, par.special)
+    rng = np.random.default_rng(n + H + k)
+    K = rng.integers(1, par.p, size=(c_o, c_i, k, k), dtype=np.uint64)
+    image = rng.integers(0, par.p, size=(c_i, H, W), dtype=np.uint64)
+    sk, osk = ctx.keygen(0), o.keygen(0)
+    Kp, xp = Hn.polyphase_layer(ctx, K, image, stride)
+    Kp_o, xp_o = polyphase_split(K, image, stride)
+    assert np.array_equal(Kp, Kp_o) and np.array_equal(xp, xp_o)
+    r = rng.integers(0, par.p, size=(c_o, xp.shape[1], xp.shape[2]), dtype=np.uint64)
+    t, plan, x_tiles, r_tiles, cts, got, cnt = Hn.gpu_conv_layer(ctx, sk, Kp, xp, r, 1, mask_seed=5, matrix_cores=True)
+    assert (t.out_h, t.out_w) == (-(-H // stride), -(-W // stride))
+    assert plan.nterm < plan.nin * plan.ntap or k == 1
+    share = Hn.stitch_layer_share(ctx, sk, t, plan, got, c_o)
+    assert np.array_equal((share + r) % np.uint64(par.p), strided_conv_plain(K, image, par.p, stride))
+    shape = (c_o, Kp.shape[1], Kp.shape[2], Kp.shape[3], t.tile_h, t.tile_w)
+    b, O = t.tiles - 1, plan.nout - 1
+    assert np.array_equal(got[b, O], oracle_block(o, shape, Kp_o, cts[b], r_tiles[b], 5, b, O, osk))
+
+
 def test_resnet18_shaped_layer_list():
     """Config 5: every linear layer of an ImageNet-shaped ResNet-18, one input, random weights mod p.
     Each layer runs in full on the GPU; the oracle recomputes one output ciphertext per layer (a sampled

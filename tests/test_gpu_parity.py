@@ -312,6 +312,17 @@ def test_he_conv_skips_zero_terms_n2048():
         assert plan.nterm == 6 * 2 + 2      # (decryption to the plain result needs the special prime at this size)
 
 
+@pytest.mark.parametrize("c_o,c_i,u", [(6, 4, 23), (70, 2, 24), (130, 2, 32)])
+def test_he_conv_single_input_n2048(c_o, c_i, u):
+    """One input at n = 2048 (c_n = 2): the streaming multiply-accumulate with 6, 70 and 130 rows (row tiles of 1,
+    2 and 4 rows per wavefront, each with a ragged last tile)."""
+    par = wl.DEFAULT
+    shape = (c_o, c_i, 3, 3, u, u)
+    nout = (c_o + 1) // 2
+    ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, shape, 1, [(0, 0), (0, nout // 2), (0, nout - 1)], seed=c_o)
+    assert plan.cn == 2 and plan.nout == nout
+
+
 def test_he_conv_config4_matrix_cores_equals_vector_path():
     """Both implementations of the multiply-accumulate give the same ciphertexts on the whole config-4 batch."""
     par = wl.DEFAULT
