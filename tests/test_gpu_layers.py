@@ -138,6 +138,46 @@ def test_resnet18_shaped_layer_list():
     print("ResNet-18 conv op totals:", total, flush=True)
 
 
+def test_resnet18_strided_layers_as_polyphase_layers():
+    """The seven strided layers of the list (7x7/2, three 3x3/2, three 1x1/2) through the polyphase split at full
+    size: one output ciphertext per layer against the oracle on its own rearrangement, the operation counts of the
+    terms that exist, and for the 1x1 layers the decrypted share against the subsampled plain convolution."""
+    from oracle.oracle import polyphase_split
+    from tests import gpu_harness as Hn
+    par = wl.DEFAULT
+    ctx = binding.Context(par.n, par.q, par.p, par.gadget_bits)
+    o = Oracle(par.n, par.q, par.p, par.gadget_bits)
+    sk, osk = ctx.keygen(0), o.keygen(0)
+    layers, _ = wl.resnet18_layers()
+    # taps that exist per original channel after the split: 49 of 4*25, 9 of 4*9, 1 of 1
+    scmult_per_pair = {7: 49, 3: 9, 1: 1}
+    for li, L in enumerate(layers):
+        if L.stride == 1:
+            continue
+        rng = np.random.default_rng(2000 + li)
+        K = rng.integers(1, par.p, size=(L.c_o, L.c_i, L.k, L.k), dtype=np.uint64)
+        image = rng.integers(0, par.p, size=(L.c_i, L.in_hw, L.in_hw), dtype=np.uint64)
+        Kp, xp = Hn.polyphase_layer(ctx, K, image, L.stride)
+        Kp_o, xp_o = polyphase_split(K, image, L.stride)
+        assert np.array_equal(Kp, Kp_o) and np.array_equal(xp, xp_o)
+        out_hw = L.in_hw // L.stride
+        r = rng.integers(0, par.p, size=(L.c_o, out_hw, out_hw), dtype=np.uint64)
+        t, plan, x_tiles, r_tiles, cts, got, cnt = Hn.gpu_conv_layer(ctx, sk, Kp, xp, r, 1, mask_seed=li, matrix_cores=True)
+        print(f"layer {L.name}: {Kp.shape[1]} phase channels, {Kp.shape[2]}x{Kp.shape[3]} window, tiles {t.tiles}, "
+              f"terms {plan.nterm} of {plan.nin * plan.ntap}", flush=True)
+        assert (t.out_h, t.out_w) == (out_hw, out_hw)
+        if L.c_i % plan.cn == 0:          # every input ciphertext holds one phase: exactly the taps that exist
+            assert cnt["scmult"] == t.tiles * plan.nout * plan.cn * (L.c_i // plan.cn) * scmult_per_pair[L.k]
+        shape = (L.c_o, Kp.shape[1], Kp.shape[2], Kp.shape[3], t.tile_h, t.tile_w)
+        b, O = (li * 7) % t.tiles, (li * 5) % plan.nout
+        want = oracle_block(o, shape, Kp_o, cts[b], r_tiles[b], li, b, O, osk)
+        assert np.array_equal(got[b, O], want), f"{L.name}: ciphertext mismatch at tile {b}, block {O}"
+        if L.k == 1:
+            share = Hn.stitch_layer_share(ctx, sk, t, plan, got, L.c_o)
+            assert np.array_equal((share + r) % np.uint64(par.p), strided_conv(K, image, par.p, L.stride)), L.name
+        del plan
+
+
 def test_he_fc_and_he_conv_replay_from_a_hip_graph():
     """The layer entry points allocate nothing, wait for nothing and clear memory with kernels only, so a caller
     can capture them in a HIP graph.  Captured once, replayed three times on fresh inputs with eager work and
