@@ -86,6 +86,16 @@ def secondary_workloads(ctx, sk, H, torch):
     t = timed(lambda: ctx.rotate(gk, d_in, count, (0, 1), d_out), torch, 100, 20)
     res["rotate_4096_cts"] = {"ms": t * 1e3, "rotations_per_s": count / t}
     del d_in, d_out
+    # gala_rotate_hoisted: 512 ciphertexts x 8 rotations each, one DecPerm per ciphertext (HstPerm-dominated)
+    hc, hr = 512, 8
+    gk8 = ctx.galois_keygen(sk, [(0, 1 + k) for k in range(hr)], seed=4)
+    d_in = H.to_dev(rng.integers(0, par.q, size=(hc, 2 * par.n), dtype=np.uint64))
+    d_out = H.dev_empty(hc * hr * 2 * par.n)
+    hwsb = ctx.rotate_hoisted_workspace(hc)
+    hws = torch.empty(hwsb, dtype=torch.uint8, device="cuda")
+    t = timed(lambda: ctx.rotate_hoisted(gk8, d_in, hc, d_out, hws, hwsb), torch, 100, 20)
+    res["rotate_hoisted_512_cts_x8"] = {"ms": t * 1e3, "rotations_per_s": hc * hr / t}
+    del d_in, d_out, hws, gk8
     # the client's steps on the device: 4096 encryptions and decryptions (internal ciphertext form)
     d_slots = H.to_dev(rng.integers(0, par.p, size=(count, par.n), dtype=np.uint64))
     d_seeds = H.to_dev(np.arange(count, dtype=np.uint64))

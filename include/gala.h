@@ -184,6 +184,17 @@ int gala_add_plain(const gala_ctx *ctx, void *stream, const uint64_t *ct, const 
 int gala_rotate(const gala_ctx *ctx, void *stream, const gala_gk *gk, const uint64_t *ct_in, int count,
                 gala_rot rot, uint64_t *ct_out);
 
+/* Hoisted rotations (Sec. III-B(1): the k_w k_h - 1 rotations of one input ciphertext; Sec. II-C(1): a Perm is a
+ * DecPerm followed by a HstPerm): ct_out[i][k] = Perm_k(ct_in[i]) for every key k of gk, in the order of
+ * gala_galois_keygen's list (distinct rotations, the identity left out; gala_gk_count of them), with ONE DecPerm
+ * per input shared by all its HstPerm.  Internal form, device; ct_out holds count * gala_gk_count ciphertexts and
+ * must not overlap ct_in.  workspace: device scratch of gala_rotate_hoisted_workspace(ctx, count) bytes for the
+ * decompositions, caller-owned.  Errors: GALA_EARG, GALA_ENOMEM (workspace too small), GALA_EHIP. */
+int gala_gk_count(const gala_gk *gk);
+size_t gala_rotate_hoisted_workspace(const gala_ctx *ctx, int count);
+int gala_rotate_hoisted(const gala_ctx *ctx, void *stream, const gala_gk *gk, const uint64_t *ct_in, int count,
+                        uint64_t *ct_out, void *workspace, size_t workspace_bytes);
+
 /* ---- he_fc: row-encoding-share-RaS matrix-vector product (Sec. III-A(3)) --- */
 /* "encode-rowwise" (offline): W is n_o x n_i row-major on the host, entries
  * mod p.  n_o and n_i are padded to powers of two; supported in one block:

@@ -90,6 +90,9 @@ SIGNATURES = {
     "gala_sub_plain": (_I, [_VP, _VP, _U64P, _U64P, C.c_size_t, _I, _U64P]),
     "gala_add_plain": (_I, [_VP, _VP, _U64P, _U64P, C.c_size_t, _I, _U64P]),
     "gala_rotate": (_I, [_VP, _VP, _VP, _U64P, _I, Rot, _U64P]),
+    "gala_gk_count": (_I, [_VP]),
+    "gala_rotate_hoisted_workspace": (C.c_size_t, [_VP, _I]),
+    "gala_rotate_hoisted": (_I, [_VP, _VP, _VP, _U64P, _I, _U64P, _VP, C.c_size_t]),
     "gala_fc_plan_create": (_I, [_VP, _U64P, _I, _I, C.POINTER(_VP)]),
     "gala_fc_plan_destroy": (None, [_VP]),
     "gala_fc_plan_G": (_I, [_VP]),
@@ -267,6 +270,13 @@ class Context:
         _check(self.lib.gala_rotate(self.h, _stream(stream), gk.h, _dev(ct_in), count, Rot(*rot), _dev(ct_out)),
                "gala_rotate")
 
+    def rotate_hoisted_workspace(self, count):
+        return int(self.lib.gala_rotate_hoisted_workspace(self.h, count))
+
+    def rotate_hoisted(self, gk, ct_in, count, ct_out, workspace, workspace_bytes, stream=None):
+        _check(self.lib.gala_rotate_hoisted(self.h, _stream(stream), gk.h, _dev(ct_in), count, _dev(ct_out),
+                                            _dev(workspace), workspace_bytes), "gala_rotate_hoisted")
+
     def fc_plan(self, W):
         return FcPlan(self, W)
 
@@ -345,6 +355,10 @@ class GaloisKeys:
         h = C.c_void_p()
         _check(ctx.lib.gala_galois_keygen(ctx.h, sk.h, _rots(rots), len(rots), seed, C.byref(h)), "gala_galois_keygen")
         self.h = h
+
+    @property
+    def count(self):
+        return int(self.ctx.lib.gala_gk_count(self.h))
 
     def export(self, rot):
         out = np.empty(self.ctx.ksk_words, np.uint64)

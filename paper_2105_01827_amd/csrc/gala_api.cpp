@@ -150,6 +150,56 @@ extern "C" int gala_rotate(const gala_ctx *c, void *stream, const gala_gk *gk, c
     return launch_perm_accumulate(c, stream, job) ? GALA_EHIP : GALA_OK;
 }
 
+namespace {
+// xrot[b][e] = HstPerm_e(ct of term e of item b) for every term, one DecPerm per input ciphertext that rotates
+// (Sec. III-B(1): the rotations of one input share its decomposition).  digits: scratch for the decompositions.
+int hoist_terms(const gala_ctx *c, void *stream, const u64 *ct_in, int batch, const TermList &terms, bool rotates,
+                const u64 *keys, const u64 *keys2, u64 *digits, u64 *xrot) {
+    const int n = c->n;
+    const bool fast = uses_fast_hoist(c) && (!rotates || keys2);
+    if (fast) return launch_hoist_taps_2048(c, stream, ct_in, batch, terms, rotates, keys2, digits, xrot);
+    if (c->special) {
+        // every term as a Perm of its own: one workgroup per (item, term)
+        PermJob taps{};
+        taps.ct_in = ct_in;
+        taps.in_item_stride = (size_t)terms.nin * 2 * n;
+        taps.in_g_stride = 2 * (size_t)n;
+        taps.in_g_index = terms.ct;
+        taps.w = nullptr;
+        taps.gal = terms.gal; taps.key_idx = terms.key;
+        taps.keys = keys; taps.keys2 = keys2;
+        taps.G = terms.nterm; taps.items = batch; taps.nchunks = terms.nterm; taps.slots = terms.nterm;
+        taps.partial = xrot;
+        const int which = c->prof_which;     // these launches are not the ones the events are for
+        c->prof_which = -1;
+        const int rc = launch_perm_accumulate(c, stream, taps);
+        c->prof_which = which;
+        return rc;
+    }
+    if (rotates && launch_decperm(c, stream, ct_in, (size_t)batch * terms.nin, digits)) return 1;
+    return launch_hstperm_taps(c, stream, ct_in, digits, batch, terms, keys, xrot);
+}
+size_t hoist_digit_bytes(const gala_ctx *c, size_t ncts) {
+    return align_up(ncts * c->ndigits * c->n * sizeof(u64) * (c->special ? 2 : 1));
+}
+}  // namespace
+
+extern "C" int gala_gk_count(const gala_gk *gk) { return gk ? (int)gk->elements.size() : GALA_EARG; }
+extern "C" size_t gala_rotate_hoisted_workspace(const gala_ctx *c, int count) {
+    return (!c || count <= 0) ? 0 : hoist_digit_bytes(c, (size_t)count);
+}
+extern "C" int gala_rotate_hoisted(const gala_ctx *c, void *stream, const gala_gk *gk, const uint64_t *ct_in, int count,
+                                   uint64_t *ct_out, void *workspace, size_t workspace_bytes) {
+    if (!c || !gk || !ct_in || !ct_out || count < 0 || ct_in == ct_out) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    const int nkeys = (int)gk->elements.size();
+    if (!count || !nkeys) return GALA_OK;
+    if (!workspace || workspace_bytes < hoist_digit_bytes(c, (size_t)count)) return GALA_ENOMEM;
+    const TermList terms{1, nkeys, gk->d_zeros, gk->d_elements, gk->d_iota};
+    return hoist_terms(c, stream, ct_in, count, terms, true, gk->d_keys, gk->d_keys2, (u64 *)workspace, ct_out) ? GALA_EHIP
+                                                                                                                : GALA_OK;
+}
+
 // ---------------------------------------------------------------------------
 // he_fc
 // ---------------------------------------------------------------------------
@@ -209,7 +259,7 @@ ConvWorkspace conv_workspace(const gala_conv_plan *pl, int batch) {
     ConvWorkspace ws{};
     ws.chunks = choose_chunks(batch * pl->nout, pl->cn);
     ws.digits = 0;
-    ws.xrot = ws.digits + align_up((size_t)batch * pl->nin * c->ndigits * n * w * (c->special ? 2 : 1));
+    ws.xrot = ws.digits + hoist_digit_bytes(c, (size_t)batch * pl->nin);
     ws.acc = ws.xrot + align_up((size_t)batch * pl->nterm * 2 * n * w);
     ws.partial = ws.acc + align_up((size_t)batch * pl->nout * pl->cn * 2 * n * w);
     ws.xl = ws.partial + align_up((size_t)batch * pl->nout * (ws.chunks + 1) * 2 * n * w);
@@ -243,7 +293,6 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
     u64 *digits = (u64 *)(base + ws.digits), *xrot = (u64 *)(base + ws.xrot), *acc = (u64 *)(base + ws.acc),
         *partial = (u64 *)(base + ws.partial);
     const int n = c->n;
-    const size_t nct_in = (size_t)batch * pl->nin;
     const u64 *keys = pl->bound ? pl->bound->d_keys : nullptr;
     // 1. input rotations: one DecPerm per input ciphertext, one HstPerm per term off the central tap
     // 2. ScMult and Add first: one sum per (output block, kernel order)
@@ -267,34 +316,7 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
         mark(1);
         if (launch_conv_untranspose(c, stream, tmp, batch, groups, acc)) return GALA_EHIP;
     } else {
-        if (c->special && fast_hoist) {
-            if (launch_hoist_taps_2048(c, stream, ct_in, batch, terms, rotates, keys2, digits, xrot))
-                return GALA_EHIP;
-        } else if (c->special) {
-            // every term as a Perm of its own: xrot[b][e] = Perm_e(ct of term e), one workgroup per (b, e)
-            PermJob taps{};
-            taps.ct_in = ct_in;
-            taps.in_item_stride = (size_t)pl->nin * 2 * n;
-            taps.in_g_stride = 2 * (size_t)n;
-            taps.in_g_index = pl->d_term_ct;
-            taps.w = nullptr;
-            taps.gal = pl->d_term_gal; taps.key_idx = pl->d_term_key;
-            taps.keys = keys; taps.keys2 = keys2;
-            taps.G = nterm; taps.items = batch; taps.nchunks = nterm; taps.slots = nterm;
-            taps.partial = xrot;
-            const int which = c->prof_which;     // these launches are not the ones the events are for
-            c->prof_which = -1;
-            const int rc = launch_perm_accumulate(c, stream, taps);
-            c->prof_which = which;
-            if (rc) return GALA_EHIP;
-        } else if (fast_hoist) {
-            if (launch_hoist_taps_2048(c, stream, ct_in, batch, terms, rotates, keys2, digits, xrot))
-                return GALA_EHIP;
-        } else {
-            if (rotates && launch_decperm(c, stream, ct_in, nct_in, digits)) return GALA_EHIP;
-            if (launch_hstperm_taps(c, stream, ct_in, digits, batch, terms, keys, xrot))
-                return GALA_EHIP;
-        }
+        if (hoist_terms(c, stream, ct_in, batch, terms, rotates, keys, keys2, digits, xrot)) return GALA_EHIP;
         if (ws.mfma) {
             u64 *xl = (u64 *)(base + ws.xl), *tmp = (u64 *)(base + ws.tmp);
             if (launch_limb_pack(c, stream, xrot, 1, 2 * batch, nterm, xl)) return GALA_EHIP;

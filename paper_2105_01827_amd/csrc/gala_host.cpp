@@ -413,9 +413,10 @@ extern "C" int gala_galois_keygen(gala_ctx *c, const gala_sk *sk, const gala_rot
     }
     const size_t nkeys = gk->elements.size(), kw = gk->key_words();
     {
-        std::vector<int> iota(nkeys), one(1, 1);
+        std::vector<int> iota(nkeys), one(1, 1), zeros(std::max<size_t>(nkeys, 1), 0);
         for (size_t k = 0; k < nkeys; ++k) iota[k] = (int)k;
-        if (upload(&gk->d_elements, gk->elements) || upload(&gk->d_iota, iota) || upload(&gk->d_one, one)) {
+        if (upload(&gk->d_elements, gk->elements) || upload(&gk->d_iota, iota) || upload(&gk->d_one, one) ||
+            upload(&gk->d_zeros, zeros)) {
             gala_gk_destroy(gk);
             return GALA_EHIP;
         }
@@ -488,7 +489,7 @@ extern "C" int gala_galois_keygen(gala_ctx *c, const gala_sk *sk, const gala_rot
 }
 extern "C" void gala_gk_destroy(gala_gk *gk) {
     if (!gk) return;
-    hipFree(gk->d_keys); hipFree(gk->d_keys2); hipFree(gk->d_elements); hipFree(gk->d_iota); hipFree(gk->d_one);
+    hipFree(gk->d_keys); hipFree(gk->d_keys2); hipFree(gk->d_elements); hipFree(gk->d_iota); hipFree(gk->d_one); hipFree(gk->d_zeros);
     delete gk;
 }
 extern "C" int gala_gk_export(gala_ctx *c, const gala_gk *gk, gala_rot rot, uint64_t *ksk_host) {

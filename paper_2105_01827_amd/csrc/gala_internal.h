@@ -95,6 +95,7 @@ struct gala_gk {
     int *d_elements = nullptr;         // nkeys Galois elements, device
     int *d_iota = nullptr;             // 0,1,2,... (key index of element k is k), device
     int *d_one = nullptr;              // the single value 1 (Galois element of the identity), device
+    int *d_zeros = nullptr;            // nkeys zeros (every hoisted rotation reads input ciphertext 0 of its item), device
     size_t key_words() const { return (size_t)ndigits * polys * n; }
 };
 

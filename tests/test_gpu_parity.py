@@ -97,6 +97,49 @@ def test_rotate_matches_oracle_perm(n, gb, rots):
     assert e.value.code == binding.GALA_ENOKEY
 
 
+@pytest.mark.parametrize("n,gb,special", [(16, 4, False), (64, 7, False), (512, 20, False), (2048, 20, False),
+                                          (64, 20, True), (2048, 30, True)])
+def test_rotate_hoisted_matches_decperm_then_hstperm(n, gb, special):
+    """Every key of a key set applied to each input with one shared decomposition: DecPerm once, then a HstPerm
+    per rotation (Sec. III-B(1), Sec. II-C(1)), against the oracle's two steps called one after the other."""
+    import dataclasses
+    import torch
+    H = harness()
+    if n == 2048:
+        par = wl.DEFAULT_SPECIAL if special else wl.DEFAULT
+    else:
+        par = small_params(n, gadget_bits=gb)
+        if special:
+            P = wl.find_prime_below(1 << 60, 2 * n)
+            par = dataclasses.replace(par, special=P if P != par.q else wl.find_prime_below(P, 2 * n))
+    ctx, o = both(par)
+    sk, osk = ctx.keygen(3), o.keygen(3)
+    rng = np.random.default_rng(n)
+    count = 3
+    rots = [(0, 1), (1, 0), (0, n // 2 - 1), (1, 3 % (n // 2)), (0, 0), (0, 1)]      # identity and a repeat are skipped
+    slots = rng.integers(0, par.p, size=(count, n), dtype=np.uint64)
+    cts = np.stack([ctx.encrypt(sk, slots[i], seed=20 + i) for i in range(count)])
+    gk = ctx.galois_keygen(sk, rots, seed=42)
+    kept = rots[:4]
+    assert gk.count == len(kept)
+    d_in = H.import_cts(ctx, cts)
+    d_out = H.dev_empty(count * len(kept) * 2 * n)
+    wsb = ctx.rotate_hoisted_workspace(count)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    ctx.rotate_hoisted(gk, d_in, count, d_out, ws, wsb)
+    got = H.export_cts(ctx, d_out, count * len(kept)).reshape(count, len(kept), 2 * n)
+    for i in range(count):
+        digits = o.decperm(cts[i][n:])
+        for k, (swap, step) in enumerate(kept):
+            g = o.galois_elt(swap, step)
+            want = o.hstperm(cts[i][:n], digits, g, o.galois_key(osk, g, 42))
+            assert np.array_equal(got[i, k], want), (i, swap, step)
+            assert np.array_equal(ctx.decrypt(sk, got[i, k]), rotate_slots(slots[i], step, bool(swap)))
+    with pytest.raises(binding.GalaError) as e:
+        ctx.rotate_hoisted(gk, d_in, count, d_out, ws, wsb - 1)
+    assert e.value.code == binding.GALA_ENOMEM
+
+
 def fc_case(par, n_o, n_i, batch, oracle_items, seed=0):
     """Run he_fc on the GPU for the whole batch and on the oracle for the chosen items; compare exactly."""
     H = harness()
