@@ -78,18 +78,29 @@ __global__ __launch_bounds__(256) void limb_pack_kernel(const u64 *src, int mode
     for (int limb = 0; limb < 8; ++limb) dst[base + (size_t)limb * step] = digit_chunk(d, limb);
 }
 
-// sum_s 256^s * c[s] for 15 signed 32-bit diagonals, as an unsigned 128-bit value (the true sum is non-negative)
+// sum_s 256^s * c[s] for 15 signed 32-bit diagonals, as an unsigned 128-bit value (the true sum is non-negative).
+// Four diagonals at a time fit a signed 64-bit word (|e| < 2^56); the four words, 32 bits apart, are then added
+// with 32-bit carries.
 __device__ __forceinline__ u128 recombine(const int (&c)[15]) {
-    i64 d[8];
-#pragma unroll
-    for (int t = 0; t < 7; ++t) d[t] = (i64)c[2 * t] + ((i64)c[2 * t + 1] << 8);
-    d[7] = (i64)c[14];
+    // the multipliers are hidden from the optimiser so that each term is one 32x32+64 multiply-add instead of a
+    // sign extension, a 64-bit shift and a 64-bit addition
+    int m8 = 256, m16 = 65536, m24 = 16777216;
+    asm volatile("" : "+s"(m8), "+s"(m16), "+s"(m24));
     i64 e[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) e[u] = d[2 * u] + (d[2 * u + 1] << 16);
-    typedef __int128 i128;
-    const i128 v = (i128)e[0] + ((i128)e[1] << 32) + ((i128)e[2] << 64) + ((i128)e[3] << 96);
-    return (u128)v;
+    for (int j = 0; j < 4; ++j) {
+        e[j] = (i64)c[4 * j] + (i64)c[4 * j + 1] * m8 + (i64)c[4 * j + 2] * m16;
+        if (j < 3) e[j] += (i64)c[4 * j + 3] * m24;
+    }
+    i64 t = e[0];
+    const u64 w0 = (uint32_t)t;
+    t = (t >> 32) + e[1];
+    const u64 w1 = (uint32_t)t;
+    t = (t >> 32) + e[2];
+    const u64 w2 = (uint32_t)t;
+    t = (t >> 32) + e[3];
+    const u64 w3 = (uint32_t)t;
+    return ((u128)(w2 | (w3 << 32)) << 64) | (w0 | (w1 << 32));
 }
 
 // One workgroup = one coefficient, WAVES row tiles (one per wavefront) and 2 column tiles.  The column
@@ -102,7 +113,8 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void conv_mfma_kernel(const 
                                                                int ntiles, int kblocks, int nblk16, int n, Modulus mod) {
     constexpr int NT = 64 * WAVES, BLOADS = 1024 / NT;
     __shared__ v4i bsm[2][2][8][64];     // [buffer][column tile][digit][lane], 32 KiB
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // the wavefront's number is the same in all its lanes: kept in a scalar register, with everything derived from it
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const size_t i = blockIdx.x;
     const int mt = blockIdx.y * WAVES + wave, nt0 = blockIdx.z * 2;
     const bool live = mt < mtiles;
