@@ -218,16 +218,34 @@ static int upload(T **dst, const std::vector<T> &src) {
     if (hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice) != hipSuccess) return GALA_EHIP;
     return GALA_OK;
 }
-static int upload_mask_layout(const MaskLayoutHost &h, MaskLayoutDev *d) {
+static int upload_mask_layout(const gala_ctx *c, const MaskLayoutHost &h, MaskLayoutDev *d) {
     int rc;
     if ((rc = upload(&d->row_ptr, h.row_ptr))) return rc;
     if ((rc = upload(&d->row_slots, h.row_slots))) return rc;
     if ((rc = upload(&d->row_rindex, h.row_rindex))) return rc;
     if ((rc = upload(&d->nrows, h.nrows))) return rc;
-    return upload(&d->is_first, h.is_first);
+    if ((rc = upload(&d->is_first, h.is_first))) return rc;
+    // the same CSR seen from its entries, with the slot -> transform-position map applied
+    const int n = c->n;
+    std::vector<int> entry_row((size_t)h.nout * n, -1), entry_idx((size_t)h.nout * n, 0), first_idx((size_t)h.nout * n, 0);
+    for (int O = 0; O < h.nout; ++O) {
+        const int *rp = h.row_ptr.data() + (size_t)O * (n + 1), *rs = h.row_slots.data() + (size_t)O * n;
+        for (int t = 0; t < h.nrows[O]; ++t) {
+            if (rp[t + 1] <= rp[t]) continue;
+            first_idx[(size_t)O * n + t] = c->slot_to_idx[rs[rp[t]]];
+            for (int e = rp[t] + 1; e < rp[t + 1]; ++e) {
+                entry_row[(size_t)O * n + e] = t;
+                entry_idx[(size_t)O * n + e] = c->slot_to_idx[rs[e]];
+            }
+        }
+    }
+    if ((rc = upload(&d->entry_row, entry_row))) return rc;
+    if ((rc = upload(&d->entry_idx, entry_idx))) return rc;
+    return upload(&d->first_idx, first_idx);
 }
 static void free_mask_layout(MaskLayoutDev *d) {
     hipFree(d->row_ptr); hipFree(d->row_slots); hipFree(d->row_rindex); hipFree(d->nrows); hipFree(d->is_first);
+    hipFree(d->entry_row); hipFree(d->entry_idx); hipFree(d->first_idx);
 }
 
 }  // namespace gala
@@ -652,7 +670,7 @@ extern "C" int gala_fc_plan_create(gala_ctx *c, const uint64_t *W, int n_o, int 
     }
     if (!rc) rc = upload(&pl->d_gal, pl->gal);
     if (!rc) rc = upload(&pl->d_key_idx, key_idx);
-    if (!rc) rc = upload_mask_layout(mh, &pl->mask_d);
+    if (!rc) rc = upload_mask_layout(c, mh, &pl->mask_d);
     if (rc) { gala_fc_plan_destroy(pl); return rc; }
     *out = pl;
     return GALA_OK;
@@ -801,7 +819,7 @@ extern "C" int gala_conv_plan_create(gala_ctx *c, const uint64_t *K, int c_o, in
     if (!rc) rc = upload(&pl->d_term_key, term_key);
     if (!rc) rc = upload(&pl->d_grp_gal, pl->grp_gal);
     if (!rc) rc = upload(&pl->d_grp_key, grp_key);
-    if (!rc) rc = upload_mask_layout(mh, &pl->mask_d);
+    if (!rc) rc = upload_mask_layout(c, mh, &pl->mask_d);
     if (rc) { gala_conv_plan_destroy(pl); return rc; }
     *out = pl;
     return GALA_OK;

@@ -112,6 +112,9 @@ struct MaskLayoutHost {
 struct MaskLayoutDev {
     int *row_ptr = nullptr, *row_slots = nullptr, *row_rindex = nullptr, *nrows = nullptr;
     unsigned char *is_first = nullptr;
+    // per entry e of the CSR (nout x n): its row, or -1 for the first entry of a row, and the position of its slot
+    // in the mod-p transform's input; per row (nout x n): that position for the row's first slot
+    int *entry_row = nullptr, *entry_idx = nullptr, *first_idx = nullptr;
 };
 
 struct gala_fc_plan {

@@ -261,7 +261,6 @@ __device__ __forceinline__ void mask_role(const PermJob &job, const Tables2048 &
     const int b = item / mj.nout, O = item % mj.nout;
     const u64 p = mj.Tp.mod.q, q = T.mod.q;
     const int *row_ptr = mj.layout.row_ptr + (size_t)O * (N + 1);
-    const int *row_slots = mj.layout.row_slots + (size_t)O * N;
     const int *row_rindex = mj.layout.row_rindex + (size_t)O * N;
     const unsigned char *is_first = mj.layout.is_first + (size_t)O * N;
     // every slot but the first of each real output is a draw from the mask stream; values go to the
@@ -272,15 +271,39 @@ __device__ __forceinline__ void mask_role(const PermJob &job, const Tables2048 &
         bufB[mj.slot_to_idx[s]] = v;
     }
     __syncthreads();
+    // the first slot of every real row absorbs r minus the row's other slots.  The row sums are formed by all
+    // threads: a thread adds up its strip of consecutive entries and flushes to the row's cell in LDS whenever the
+    // row changes (plain integer sums of values below p: at most n of them, far from 64 bits).
     const int nrows = mj.layout.nrows[O];
+    const int *entry_row = mj.layout.entry_row + (size_t)O * N, *entry_idx = mj.layout.entry_idx + (size_t)O * N;
+    const int *first_idx = mj.layout.first_idx + (size_t)O * N;
+    unsigned long long *rowsum = reinterpret_cast<unsigned long long *>(bufA);
+    for (int t = tid; t < nrows; t += NT) rowsum[t] = 0;
+    __syncthreads();
+    {
+        const int nent = row_ptr[nrows];
+        int cur = -1;
+        u64 acc = 0;
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int e = PER * tid + k;
+            const int t = e < nent ? entry_row[e] : -1;
+            if (t < 0) continue;
+            if (t != cur) {
+                if (cur >= 0) atomicAdd(&rowsum[cur], acc);
+                cur = t;
+                acc = 0;
+            }
+            acc += bufB[entry_idx[e]];
+        }
+        if (cur >= 0) atomicAdd(&rowsum[cur], acc);
+    }
+    __syncthreads();
     for (int t = tid; t < nrows; t += NT) {
-        const int e0 = row_ptr[t], e1 = row_ptr[t + 1];
-        if (e1 <= e0) continue;
-        u64 sum = 0;
-        for (int e = e0 + 1; e < e1; ++e) sum = add_mod(sum, bufB[mj.slot_to_idx[row_slots[e]]], p);
+        if (row_ptr[t + 1] <= row_ptr[t]) continue;
         u64 rv = mj.r[(size_t)b * mj.r_stride + row_rindex[t]];
         if (rv >= p) rv %= p;
-        bufB[mj.slot_to_idx[row_slots[e0]]] = sub_mod(rv, sum, p);
+        bufB[first_idx[t]] = sub_mod(rv, rowsum[t] % p, p);
     }
     __syncthreads();
     // slots -> plaintext polynomial (inverse transform mod p) -> delta * m mod q -> evaluation domain mod q
