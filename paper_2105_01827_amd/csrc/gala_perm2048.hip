@@ -278,10 +278,11 @@ __device__ __forceinline__ void mask_role(const PermJob &job, const Tables2048 &
     const int *entry_row = mj.layout.entry_row + (size_t)O * N, *entry_idx = mj.layout.entry_idx + (size_t)O * N;
     const int *first_idx = mj.layout.first_idx + (size_t)O * N;
     unsigned long long *rowsum = reinterpret_cast<unsigned long long *>(bufA);
-    for (int t = tid; t < nrows; t += NT) rowsum[t] = 0;
-    __syncthreads();
-    {
-        const int nent = row_ptr[nrows];
+    const int nent = row_ptr[nrows];
+    const bool sums = nent > nrows;      // rows of a single slot (convolutions) have nothing to add up
+    if (sums) {
+        for (int t = tid; t < nrows; t += NT) rowsum[t] = 0;
+        __syncthreads();
         int cur = -1;
         u64 acc = 0;
 #pragma unroll
@@ -297,13 +298,13 @@ __device__ __forceinline__ void mask_role(const PermJob &job, const Tables2048 &
             acc += bufB[entry_idx[e]];
         }
         if (cur >= 0) atomicAdd(&rowsum[cur], acc);
+        __syncthreads();
     }
-    __syncthreads();
     for (int t = tid; t < nrows; t += NT) {
         if (row_ptr[t + 1] <= row_ptr[t]) continue;
         u64 rv = mj.r[(size_t)b * mj.r_stride + row_rindex[t]];
         if (rv >= p) rv %= p;
-        bufB[first_idx[t]] = sub_mod(rv, rowsum[t] % p, p);
+        bufB[first_idx[t]] = sub_mod(rv, sums ? rowsum[t] % p : 0, p);
     }
     __syncthreads();
     // slots -> plaintext polynomial (inverse transform mod p) -> delta * m mod q -> evaluation domain mod q
