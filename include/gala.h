@@ -152,6 +152,16 @@ int gala_encrypt_batch(const gala_ctx *ctx, void *stream, const gala_sk *sk, con
 int gala_decrypt_batch(const gala_ctx *ctx, void *stream, const gala_sk *sk, const uint64_t *ct_dev, int count,
                        uint64_t *slots_dev);
 
+/* The plaintext half of share generation for a batch, on the device (Sec. III-A(3): the slots of one output are
+ * added up after decryption, by the client and by the server on its mask alike; the outputs of a convolution are
+ * single slots, Sec. III-B).  slots_dev: decrypted slot vectors, count x n for he_fc, count x (output ciphertexts
+ * of the plan) x n for he_conv; out_dev: count x n_o, resp. count x c_o x u_h x u_w values mod p.  The same
+ * values as gala_fc_unpack_share / gala_conv_unpack_share on every item.  Device pointers, caller-owned. */
+int gala_fc_unpack_share_batch(const gala_fc_plan *plan, void *stream, const uint64_t *slots_dev, int count,
+                               uint64_t *out_dev);
+int gala_conv_unpack_share_batch(const gala_conv_plan *plan, void *stream, const uint64_t *slots_dev, int count,
+                                 uint64_t *out_dev);
+
 /* ---- Add, ScMult and plaintext operands on their own (Sec. II-C(1)) --------- */
 /* The layers fuse these operations into their kernels; the stand-alone forms are for composing layers the
  * plans do not cover (for example a matrix wider than n, split into blocks whose outputs are added, Sec. III-A).

@@ -84,6 +84,8 @@ SIGNATURES = {
     "gala_ct_export": (_I, [_VP, _VP, _U64P, _I, _U64P]),
     "gala_encrypt_batch": (_I, [_VP, _VP, _VP, _U64P, _U64P, _I, _U64P]),
     "gala_decrypt_batch": (_I, [_VP, _VP, _VP, _U64P, _I, _U64P]),
+    "gala_fc_unpack_share_batch": (_I, [_VP, _VP, _U64P, _I, _U64P]),
+    "gala_conv_unpack_share_batch": (_I, [_VP, _VP, _U64P, _I, _U64P]),
     "gala_encode_plain": (_I, [_VP, _VP, _U64P, _I, _I, _U64P]),
     "gala_add": (_I, [_VP, _VP, _U64P, _U64P, _I, _U64P]),
     "gala_scmult": (_I, [_VP, _VP, _U64P, _U64P, C.c_size_t, _I, _U64P]),
@@ -405,6 +407,10 @@ class FcPlan:
         _check(self.ctx.lib.gala_fc_unpack_share(self.h, sp, out.ctypes.data_as(C.c_void_p)), "gala_fc_unpack_share")
         return out
 
+    def unpack_share_batch(self, slots_dev, count, out_dev, stream=None):
+        _check(self.ctx.lib.gala_fc_unpack_share_batch(self.h, _stream(stream), _dev(slots_dev), count, _dev(out_dev)),
+               "gala_fc_unpack_share_batch")
+
     def workspace_bytes(self, batch):
         return int(self.ctx.lib.gala_he_fc_workspace(self.h, batch))
 
@@ -460,6 +466,10 @@ class ConvPlan:
         assert out.dtype == np.uint64 and out.flags["C_CONTIGUOUS"]
         _check(self.ctx.lib.gala_conv_unpack_share(self.h, O, sp, out.ctypes.data_as(C.c_void_p)),
                "gala_conv_unpack_share")
+
+    def unpack_share_batch(self, slots_dev, count, out_dev, stream=None):
+        _check(self.ctx.lib.gala_conv_unpack_share_batch(self.h, _stream(stream), _dev(slots_dev), count, _dev(out_dev)),
+               "gala_conv_unpack_share_batch")
 
     def workspace_bytes(self, batch):
         return int(self.ctx.lib.gala_he_conv_workspace(self.h, batch))

@@ -91,6 +91,21 @@ extern "C" int gala_decrypt_batch(const gala_ctx *c, void *stream, const gala_sk
     return launch_decrypt(c, stream, sk->d_s_hat, ct, count, slots) ? GALA_EHIP : GALA_OK;
 }
 
+extern "C" int gala_fc_unpack_share_batch(const gala_fc_plan *pl, void *stream, const uint64_t *slots, int count,
+                                          uint64_t *out) {
+    if (!pl || !slots || !out || count < 0) return GALA_EARG;
+    if (!pl->ctx->has_device) return GALA_EHIP;
+    return launch_unpack_share(pl->ctx, stream, slots, count, 1, pl->mask_d, (size_t)pl->n_o, out) ? GALA_EHIP : GALA_OK;
+}
+extern "C" int gala_conv_unpack_share_batch(const gala_conv_plan *pl, void *stream, const uint64_t *slots, int count,
+                                            uint64_t *out) {
+    if (!pl || !slots || !out || count < 0) return GALA_EARG;
+    if (!pl->ctx->has_device) return GALA_EHIP;
+    return launch_unpack_share(pl->ctx, stream, slots, count, pl->nout, pl->mask_d, (size_t)pl->c_o * pl->u_h * pl->u_w, out)
+               ? GALA_EHIP
+               : GALA_OK;
+}
+
 extern "C" int gala_encode_plain(const gala_ctx *c, void *stream, const uint64_t *slots, int count, int mode,
                                  uint64_t *plain) {
     if (!c || !slots || !plain || count < 0 || (mode != 0 && mode != 1)) return GALA_EARG;

@@ -228,11 +228,13 @@ static int upload_mask_layout(const gala_ctx *c, const MaskLayoutHost &h, MaskLa
     // the same CSR seen from its entries, with the slot -> transform-position map applied
     const int n = c->n;
     std::vector<int> entry_row((size_t)h.nout * n, -1), entry_idx((size_t)h.nout * n, 0), first_idx((size_t)h.nout * n, 0);
+    std::vector<int> slot_rowid((size_t)h.nout * n, -1);
     for (int O = 0; O < h.nout; ++O) {
         const int *rp = h.row_ptr.data() + (size_t)O * (n + 1), *rs = h.row_slots.data() + (size_t)O * n;
         for (int t = 0; t < h.nrows[O]; ++t) {
             if (rp[t + 1] <= rp[t]) continue;
             first_idx[(size_t)O * n + t] = c->slot_to_idx[rs[rp[t]]];
+            for (int e = rp[t]; e < rp[t + 1]; ++e) slot_rowid[(size_t)O * n + rs[e]] = t;
             for (int e = rp[t] + 1; e < rp[t + 1]; ++e) {
                 entry_row[(size_t)O * n + e] = t;
                 entry_idx[(size_t)O * n + e] = c->slot_to_idx[rs[e]];
@@ -241,11 +243,12 @@ static int upload_mask_layout(const gala_ctx *c, const MaskLayoutHost &h, MaskLa
     }
     if ((rc = upload(&d->entry_row, entry_row))) return rc;
     if ((rc = upload(&d->entry_idx, entry_idx))) return rc;
+    if ((rc = upload(&d->slot_rowid, slot_rowid))) return rc;
     return upload(&d->first_idx, first_idx);
 }
 static void free_mask_layout(MaskLayoutDev *d) {
     hipFree(d->row_ptr); hipFree(d->row_slots); hipFree(d->row_rindex); hipFree(d->nrows); hipFree(d->is_first);
-    hipFree(d->entry_row); hipFree(d->entry_idx); hipFree(d->first_idx);
+    hipFree(d->entry_row); hipFree(d->entry_idx); hipFree(d->first_idx); hipFree(d->slot_rowid);
 }
 
 }  // namespace gala

@@ -115,6 +115,7 @@ struct MaskLayoutDev {
     // per entry e of the CSR (nout x n): its row, or -1 for the first entry of a row, and the position of its slot
     // in the mod-p transform's input; per row (nout x n): that position for the row's first slot
     int *entry_row = nullptr, *entry_idx = nullptr, *first_idx = nullptr;
+    int *slot_rowid = nullptr;         // nout x n: the row a slot belongs to, -1 for slots outside every row
 };
 
 struct gala_fc_plan {
@@ -169,6 +170,9 @@ const u64 *gauss_cdf_table();
 // Stand-alone Add / ScMult / plaintext operations on internal-form buffers (op: 0 add ct, 1 scmult, 2 sub plain, 3 add plain).
 int launch_encode_plain(const gala_ctx *ctx, void *stream, const u64 *slots, int count, int mode, u64 *plain);
 int launch_ct_op(const gala_ctx *ctx, void *stream, int op, const u64 *a, const u64 *b, size_t b_stride, int count, u64 *out);
+// out[b][rindex of row t] = sum of the row's slots mod p, for `count` items of nout slot vectors each
+int launch_unpack_share(const gala_ctx *ctx, void *stream, const u64 *slots, int count, int nout, const MaskLayoutDev &layout,
+                        size_t out_stride, u64 *out);
 
 // key generation helper on `npairs` consecutive (t_hat, a_hat) pairs of n-word evaluation-domain
 // polynomials: t_hat <- t_hat - a_hat * s_hat in place (s_hat shared by all pairs).

@@ -764,6 +764,24 @@ __global__ __launch_bounds__(256 * KS) void conv_mac_stream_kernel(const u64 *w,
         }
 }
 
+// The plaintext half of share generation: every output is the sum of its row's slots mod p (Sec. III-A(3); a
+// convolution's rows are single slots).  One workgroup per slot vector; the row sums meet in LDS as plain integers.
+__global__ void unpack_share_kernel(const u64 *slots, int nout, int n, u64 p, const int *slot_rowid, const int *row_rindex,
+                                    const int *nrows, size_t out_stride, u64 *out) {
+    extern __shared__ u64 lds[];
+    unsigned long long *acc = reinterpret_cast<unsigned long long *>(lds);
+    const int b = blockIdx.x / nout, O = blockIdx.x % nout;
+    const u64 *v = slots + (size_t)blockIdx.x * n;
+    for (int t = threadIdx.x; t < n; t += blockDim.x) acc[t] = 0;
+    __syncthreads();
+    for (int s = threadIdx.x; s < n; s += blockDim.x) {
+        const int t = slot_rowid[(size_t)O * n + s];
+        if (t >= 0) atomicAdd(&acc[t], (unsigned long long)(v[s] % p));
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < nrows[O]; t += blockDim.x) out[(size_t)b * out_stride + row_rindex[(size_t)O * n + t]] = acc[t] % p;
+}
+
 inline int block_threads(int n) { return n >= 512 ? 256 : 64; }
 inline int last_error() { return (int)hipGetLastError(); }
 
@@ -802,6 +820,14 @@ int launch_ct_op(const gala_ctx *c, void *stream, int op, const u64 *a, const u6
     const size_t words = (size_t)count * 2 * c->n;
     hipLaunchKernelGGL(ct_op_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, (hipStream_t)stream, op, a, b, b_stride,
                        words, c->n, out, c->dev_q.mod);
+    return last_error();
+}
+int launch_unpack_share(const gala_ctx *c, void *stream, const u64 *slots, int count, int nout, const MaskLayoutDev &layout,
+                        size_t out_stride, u64 *out) {
+    if (count <= 0) return 0;
+    hipLaunchKernelGGL(unpack_share_kernel, dim3((unsigned)((size_t)count * nout)), dim3(block_threads(c->n)), sizeof(u64) * c->n,
+                       (hipStream_t)stream, slots, nout, c->n, c->p, layout.slot_rowid, layout.row_rindex, layout.nrows, out_stride,
+                       out);
     return last_error();
 }
 int launch_encrypt(const gala_ctx *c, void *stream, const u64 *s_hat, const u64 *slots, const u64 *seeds, int count,

@@ -74,3 +74,49 @@ def test_client_and_server_on_the_device_end_to_end():
     for b in range(shape.batch):
         share = plan.unpack_share(dec[b])
         assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_matvec(W, x[b], par.p))
+
+
+@pytest.mark.parametrize("n,n_o,n_i", [(64, 4, 16), (64, 16, 8), (512, 10, 100), (2048, 16, 128), (2048, 128, 1024),
+                                       (2048, 1000, 2048)])
+def test_fc_unpack_share_batch_matches_oracle(n, n_o, n_i):
+    """The plaintext sum of every output's slots (Sec. III-A(3)) on the device, against the oracle's and the
+    library's host function, on arbitrary slot vectors (values above p are reduced on the way in)."""
+    H = harness()
+    par = small_params(n) if n != 2048 else wl.DEFAULT
+    ctx, o = both(par)
+    rng = np.random.default_rng(n_o * n_i)
+    W = rng.integers(0, par.p, size=(n_o, n_i), dtype=np.uint64)
+    plan = ctx.fc_plan(W)
+    count = 3
+    slots = rng.integers(0, 2 * par.p, size=(count, n), dtype=np.uint64)
+    d_out = H.dev_empty(count * n_o)
+    plan.unpack_share_batch(H.to_dev(slots), count, d_out)
+    got = H.to_host(d_out).reshape(count, n_o)
+    for i in range(count):
+        assert np.array_equal(got[i], o.fc_unpack_share(n_o, n_i, slots[i] % np.uint64(par.p))), i
+        assert np.array_equal(got[i], plan.unpack_share(slots[i]))
+    plan.unpack_share_batch(H.to_dev(slots), 0, d_out)
+
+
+@pytest.mark.parametrize("n,shape", [(64, (5, 3, 3, 1, 3, 2)), (256, (20, 4, 3, 3, 4, 4)), (2048, (70, 4, 3, 3, 24, 24)),
+                                     (2048, (128, 8, 1, 1, 7, 7))])
+def test_conv_unpack_share_batch_matches_oracle(n, shape):
+    H = harness()
+    par = small_params(n) if n != 2048 else wl.DEFAULT
+    ctx, o = both(par)
+    co, ci, kh, kw, uh, uw = shape
+    rng = np.random.default_rng(co + n)
+    K = rng.integers(0, par.p, size=(co, ci, kh, kw), dtype=np.uint64)
+    plan = ctx.conv_plan(K, uh, uw)
+    count = 2
+    slots = rng.integers(0, 2 * par.p, size=(count, plan.nout, n), dtype=np.uint64)
+    d_out = H.dev_empty(count * co * uh * uw)
+    plan.unpack_share_batch(H.to_dev(slots), count, d_out)
+    got = H.to_host(d_out).reshape(count, co, uh, uw)
+    for i in range(count):
+        want = np.zeros((co, uh, uw), np.uint64)
+        mine = np.zeros((co, uh, uw), np.uint64)
+        for O in range(plan.nout):
+            o.conv_unpack_share(shape, O, slots[i, O] % np.uint64(par.p), want)
+            plan.unpack_share(O, slots[i, O], mine)
+        assert np.array_equal(got[i], want) and np.array_equal(mine, want), i
