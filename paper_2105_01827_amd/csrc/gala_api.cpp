@@ -15,19 +15,30 @@ int galois_element(int n, int swap, int step);
 
 namespace {
 
-// Workgroups the rotate-and-accumulate launch aims for: what the chip holds at once (256 CUs, three
-// workgroups each at this kernel's register count), so that the launch has no partly filled last round.
-int target_workgroups() {
+// Workgroups the rotate-and-accumulate launch aims for.  Short sums (G < 32: a convolution's kernel orders) get
+// what the chip holds at once (256 CUs, three workgroups each at this kernel's register count): every further
+// chunk costs a partial ciphertext and a mask round.  Long sums (an FC layer's G rotations) are cut finer, into
+// about 2048 workgroups: chunks of equal length matter more there than a single round (63 rotations in 12 chunks
+// leave a third of the workgroups with 6 instead of 5), and a chunk count that is a multiple of eight lets the
+// XCD-aware mapping keep every chunk's keys in one L2.  Measured on he_fc 128x1024 and 1000x2048 at batch 64:
+// 32 chunks are 4 % and 6 % faster than 12.
+int target_override() {
     static int v = [] {
         const char *e = std::getenv("GALA_WG_TARGET");
-        int t = e ? std::atoi(e) : 0;
-        return t > 0 ? t : 768;
+        return e ? std::atoi(e) : 0;
     }();
     return v;
 }
 // The G rotations of one item are split into this many chunks, each summed by one workgroup.
 int choose_chunks(int items, int G) {
-    int c = (target_workgroups() + items - 1) / std::max(items, 1);
+    items = std::max(items, 1);
+    const int forced = target_override();
+    if (forced > 0 || G < 32) {
+        const int c = ((forced > 0 ? forced : 768) + items - 1) / items;
+        return std::max(1, std::min(c, G));
+    }
+    int c = (2048 + items - 1) / items;
+    c = (c + 7) / 8 * 8;
     return std::max(1, std::min(c, G));
 }
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
