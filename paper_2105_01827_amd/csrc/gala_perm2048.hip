@@ -562,48 +562,70 @@ __global__ __launch_bounds__(NT) void hstperm_taps_2048(const u64 *ct_in, const 
 // consecutive terms (input ciphertext, tap), so a chunk is assembled in registers and the eight digit
 // chunks of a coefficient leave as 128 contiguous bytes.
 typedef int v4i_t __attribute__((ext_vector_type(4)));
+// ND: the number of digits when it is 3 (unrolled), else 0 (run-time loop).  ANY_ROT false: no term rotates, there
+// are no keys and no digits to read.
+template <int ND, bool ANY_ROT>
 __global__ __launch_bounds__(NT) void hstperm_pack_2048(const u64 *ct_in, const u64 *digits, TermList terms, int kblocks,
-                                                        const u64 *keys2, v4i_t *xl, Tables2048 T, int ndigits) {
-    const int i = blockIdx.x * NT + threadIdx.x, eb = blockIdx.y, b = blockIdx.z;
-    const int nterm = terms.nterm;
+                                                        const u64 *keys2, v4i_t *xl, Tables2048 T, int ndigits_rt, int batch) {
+    // a workgroup is 64 coefficients x 4 inputs: its wavefronts read the same key words, which then come out of
+    // the vector cache for three of them
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + lane, eb = blockIdx.y;
+    const bool b_live = (int)blockIdx.z * 4 + wave < batch;
+    const int b = min((int)blockIdx.z * 4 + wave, batch - 1);
+    const int nterm = terms.nterm, ndigits = ND ? ND : ndigits_rt;
     const NegQ q = T.nq;
     const size_t key_pairs = (size_t)ndigits * 2 * N;
+    // A term past the end repeats the last one and is zeroed; a rotation by zero reads its own digits and the
+    // first key and multiplies by zero: every term runs the same straight code with the digit loop unrolled.
     u64 D0[16], D1[16];     // balanced digits of the 16 terms' c0 and c1 values
 #pragma unroll
     for (int t = 0; t < 16; ++t) {
-        const int e = eb * 16 + t;
-        u64 v0 = 0, v1 = 0;
-        if (e < nterm) {
-            const int gal = terms.gal[e];
-            const size_t ct = (size_t)b * terms.nin + terms.ct[e];
-            const u64 *c0 = ct_in + ct * 2 * N;
-            if (gal == 1) {
-                v0 = c0[i];
-                v1 = c0[N + i];
-            } else {
-                const ulonglong2 *key = reinterpret_cast<const ulonglong2 *>(keys2) + (size_t)terms.key[e] * key_pairs;
-                const u64 *dsrc = digits + ct * ndigits * N;
-                const int src = galois_index11(i, gal);
-                u64 s0 = c0[src], s1 = 0;
-                for (int j = 0; j < ndigits; ++j) {
-                    const u64 d = dsrc[(size_t)j * N + src];
+        const int e = min(eb * 16 + t, nterm - 1);
+        const bool live = eb * 16 + t < nterm;
+        const int gal = terms.gal[e];
+        const bool ident = gal == 1;
+        const size_t ct = (size_t)b * terms.nin + terms.ct[e];
+        const u64 *c0 = ct_in + ct * 2 * N;
+        const ulonglong2 *key = reinterpret_cast<const ulonglong2 *>(keys2) + (size_t)max(terms.key[e], 0) * key_pairs;
+        const u64 *dsrc = digits + ct * ndigits * N;
+        const int src = ident ? i : galois_index11(i, gal);
+        u64 s0 = c0[src], s1 = ident ? c0[N + i] : 0;
+        if (ANY_ROT) {
+            if (ND) {
+#pragma unroll
+                for (int j = 0; j < (ND ? ND : 1); ++j) {
+                    const u64 dl = dsrc[(size_t)j * N + src];
+                    const u64 d = ident ? 0 : dl;
                     const ulonglong2 kb = key[(size_t)(2 * j) * N + i], ka = key[(size_t)(2 * j + 1) * N + i];
                     s0 += mul_const(d, kb.x, kb.y, q);      // each product is below 2q: at most 7q in all
                     s1 += mul_const(d, ka.x, ka.y, q);
                 }
-                v0 = reduce64(s0, T.mod);
-                v1 = reduce64(s1, T.mod);
+            } else {
+                for (int j = 0; j < ndigits; ++j) {
+                    const u64 dl = dsrc[(size_t)j * N + src];
+                    const u64 d = ident ? 0 : dl;
+                    const ulonglong2 kb = key[(size_t)(2 * j) * N + i], ka = key[(size_t)(2 * j + 1) * N + i];
+                    s0 += mul_const(d, kb.x, kb.y, q);
+                    s1 += mul_const(d, ka.x, ka.y, q);
+                }
             }
         }
+        const u64 v0 = live ? reduce64(s0, T.mod) : 0, v1 = live ? reduce64(s1, T.mod) : 0;
         const u64 k80 = 0x8080808080808080ull;   // bytes of x + 0x80..80 are the balanced digits plus 128
         D0[t] = (v0 + k80) ^ k80;
         D1[t] = (v1 + k80) ^ k80;
     }
+    // A thread holds the eight 16-byte chunks of its coefficient (128 contiguous bytes); stored straight from
+    // the registers, every store instruction would touch 64 different lines with 16 bytes each.  The chunks go
+    // through LDS instead (row = lane, padded to 144 bytes), so that instruction k of a wavefront writes the
+    // 1 KiB of coefficients 8k..8k+7.
+    __shared__ v4i_t tr[NT / 64][64][9];
     const int kb = eb >> 2, g = eb & 3;
+    const int i_wave = blockIdx.x * 64;
 #pragma unroll
     for (int poly = 0; poly < 2; ++poly) {
-        const int col = 2 * b + poly, lane = g * 16 + (col & 15);
-        v4i_t *dst = xl + ((((size_t)(col >> 4) * kblocks + kb) * 64 + lane) * N + i) * 8;
+        const int col = 2 * b + poly, row = g * 16 + (col & 15);
 #pragma unroll
         for (int limb = 0; limb < 8; ++limb) {
             v4i_t c;
@@ -615,10 +637,17 @@ __global__ __launch_bounds__(NT) void hstperm_pack_2048(const u64 *ct_in, const 
                     wd |= (u32)(((poly ? D1[4 * w + t] : D0[4 * w + t]) >> (8 * limb)) & 0xff) << (8 * t);
                 c[w] = (int)wd;
             }
-            dst[limb] = c;
+            tr[wave][lane][limb] = c;
         }
+        __syncthreads();
+        v4i_t *dst = xl + ((((size_t)(col >> 4) * kblocks + kb) * 64 + row) * N + i_wave) * 8;
+        if (b_live)
+#pragma unroll
+            for (int k = 0; k < 8; ++k) dst[64 * k + lane] = tr[wave][8 * k + (lane >> 3)][lane & 7];
+        __syncthreads();
     }
 }
+
 
 // ---- key switching with a special prime P -------------------------------------------------------------
 // Keys hold four polynomials per digit ((b, a) modulo q, then modulo P).  Per rotation the digits are
@@ -1026,8 +1055,16 @@ int launch_hstperm_pack_2048(const gala_ctx *c, void *stream, const u64 *ct_in, 
         if (rc) return rc;
     }
     const int eblocks = (terms.nterm + 15) / 16, kblocks = (terms.nterm + 63) / 64;
-    hipLaunchKernelGGL(hstperm_pack_2048, dim3(N / NT, (unsigned)eblocks, (unsigned)batch), dim3(NT), 0, st, ct_in, digits, terms,
-                       kblocks, keys2, reinterpret_cast<v4i_t *>(xl), T, c->ndigits);
+    const dim3 grid(N / 64, (unsigned)eblocks, (unsigned)((batch + 3) / 4));
+    v4i_t *out = reinterpret_cast<v4i_t *>(xl);
+    if (!any_rotation)
+        hipLaunchKernelGGL((hstperm_pack_2048<0, false>), grid, dim3(NT), 0, st, ct_in, digits, terms, kblocks, keys2, out, T, c->ndigits, batch);
+    else if (!keys2)
+        return (int)hipErrorInvalidValue;
+    else if (c->ndigits == 3)
+        hipLaunchKernelGGL((hstperm_pack_2048<3, true>), grid, dim3(NT), 0, st, ct_in, digits, terms, kblocks, keys2, out, T, c->ndigits, batch);
+    else
+        hipLaunchKernelGGL((hstperm_pack_2048<0, true>), grid, dim3(NT), 0, st, ct_in, digits, terms, kblocks, keys2, out, T, c->ndigits, batch);
     return (int)hipGetLastError();
 }
 
