@@ -30,11 +30,14 @@ int target_override() {
     return v;
 }
 // The G rotations of one item are split into this many chunks, each summed by one workgroup.
-int choose_chunks(int items, int G) {
+int choose_chunks(const gala_ctx *ctx, int items, int G) {
     items = std::max(items, 1);
     const int forced = target_override();
-    if (forced > 0 || G < 32) {
-        const int c = ((forced > 0 ? forced : 768) + items - 1) / items;
+    // With a special prime the kernel holds two workgroups per CU, not three, and a rotation is twice the work:
+    // one round of 512 workgroups was the fastest cut for short and long sums alike (he_fc 128x1024: 0.43 ms
+    // against 0.48 ms with 2048 workgroups and 0.58 ms with 768).
+    if (forced > 0 || G < 32 || ctx->special) {
+        const int c = ((forced > 0 ? forced : ctx->special ? 512 : 768) + items - 1) / items;
         return std::max(1, std::min(c, G));
     }
     int c = (2048 + items - 1) / items;
@@ -231,7 +234,7 @@ extern "C" int gala_rotate_hoisted(const gala_ctx *c, void *stream, const gala_g
 // ---------------------------------------------------------------------------
 extern "C" size_t gala_he_fc_workspace(const gala_fc_plan *pl, int batch) {
     if (!pl || batch <= 0) return 0;
-    const int chunks = choose_chunks(batch, pl->G);
+    const int chunks = choose_chunks(pl->ctx, batch, pl->G);
     return align_up((size_t)batch * (chunks + 1) * 2 * pl->ctx->n * sizeof(u64));
 }
 extern "C" int gala_he_fc(const gala_ctx *c, void *stream, const gala_fc_plan *pl, const uint64_t *ct_in, int batch,
@@ -241,7 +244,7 @@ extern "C" int gala_he_fc(const gala_ctx *c, void *stream, const gala_fc_plan *p
     if (!c->has_device) return GALA_EHIP;
     if (pl->G > 1 && !pl->bound) return GALA_ENOKEY;
     if (!workspace || workspace_bytes < gala_he_fc_workspace(pl, batch)) return GALA_ENOMEM;
-    const int n = c->n, chunks = choose_chunks(batch, pl->G);
+    const int n = c->n, chunks = choose_chunks(pl->ctx, batch, pl->G);
     PermJob job{};
     job.ct_in = ct_in;
     job.in_item_stride = 2 * (size_t)n;
@@ -283,7 +286,7 @@ ConvWorkspace conv_workspace(const gala_conv_plan *pl, int batch) {
     const gala_ctx *c = pl->ctx;
     const size_t n = c->n, w = sizeof(u64);
     ConvWorkspace ws{};
-    ws.chunks = choose_chunks(batch * pl->nout, pl->cn);
+    ws.chunks = choose_chunks(c, batch * pl->nout, pl->cn);
     ws.digits = 0;
     ws.xrot = ws.digits + hoist_digit_bytes(c, (size_t)batch * pl->nin);
     ws.acc = ws.xrot + align_up((size_t)batch * pl->nterm * 2 * n * w);

@@ -884,32 +884,36 @@ __global__ __launch_bounds__(NT) void hstperm_special_2048(const u64 *ct_in, con
     const u64 *dsrc = digits + ct * ndigits * 2 * N;
     const ulonglong2 *key = reinterpret_cast<const ulonglong2 *>(keys2) + (size_t)terms.key[e] * ndigits * 4 * N;
     int src[PER];
-    u64 sum0[PER], sum1[PER], tp0[PER], tp1[PER];
 #pragma unroll
-    for (int k = 0; k < PER; ++k) {
-        src[k] = galois_index11(tid + k * NT, gal);
-        sum0[k] = mul_const(c0[src[k]], S.Pq.x, S.Pq.y, q);
-        sum1[k] = tp0[k] = tp1[k] = 0;
-    }
-    for (int j = 0; j < ndigits; ++j) {     // at most three digits: every sum stays below 8 moduli
-        const ulonglong2 *kb = key + (size_t)(4 * j) * N;
-#pragma unroll
-        for (int k = 0; k < PER; ++k) {
-            const int i = tid + k * NT;
-            const u64 dq = dsrc[(size_t)(2 * j) * N + src[k]], dP = dsrc[(size_t)(2 * j + 1) * N + src[k]];
-            const ulonglong2 b = kb[i], aa = kb[N + i], bP = kb[2 * N + i], aP = kb[3 * N + i];
-            sum0[k] += mul_const(dq, b.x, b.y, q);
-            sum1[k] += mul_const(dq, aa.x, aa.y, q);
-            tp0[k] += mul_const(dP, bP.x, bP.y, qP);
-            tp1[k] += mul_const(dP, aP.x, aP.y, qP);
-        }
-    }
+    for (int k = 0; k < PER; ++k) src[k] = galois_index11(tid + k * NT, gal);
+    // The two output polynomials one after the other (the digits are read twice, out of the L2): half the sums
+    // are alive at a time, and the products are formed four coefficients at a time so that no more than their
+    // operands are in flight - the kernel fits three workgroups per CU instead of one.
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
+        u64 sum[PER], tp[PER];      // modulo q and modulo P, below 8 moduli (at most three digits)
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            sum[k] = h ? 0 : mul_const(c0[src[k]], S.Pq.x, S.Pq.y, q);
+            tp[k] = 0;
+        }
+        for (int j = 0; j < ndigits; ++j) {
+            const ulonglong2 *kq = key + (size_t)(4 * j + h) * N, *kP = key + (size_t)(4 * j + 2 + h) * N;
+#pragma unroll
+            for (int k = 0; k < PER; ++k) {
+                const int i = tid + k * NT;
+                const u64 dq = dsrc[(size_t)(2 * j) * N + src[k]], dP = dsrc[(size_t)(2 * j + 1) * N + src[k]];
+                const ulonglong2 wq = kq[i], wP = kP[i];
+                sum[k] += mul_const(dq, wq.x, wq.y, q);
+                tp[k] += mul_const(dP, wP.x, wP.y, qP);
+                if (k == 3) __builtin_amdgcn_sched_barrier(0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
         u64 a[PER];
         // LDS phases: B (ownership change), A B A (inverse), B A B A (forward), then reads of A
 #pragma unroll
-        for (int k = 0; k < PER; ++k) bufB[pad(tid + k * NT)] = reduce64(h ? tp1[k] : tp0[k], S.TP.mod);
+        for (int k = 0; k < PER; ++k) bufB[pad(tid + k * NT)] = reduce64(tp[k], S.TP.mod);
         __syncthreads();
         {
             const u64 *pi = bufB + pad(tid << 3);
@@ -924,7 +928,7 @@ __global__ __launch_bounds__(NT) void hstperm_special_2048(const u64 *ct_in, con
         for (int k = 0; k < PER; ++k) {
             const int i = tid + k * NT;
             const u64 x = reduce64(bufA[pad(i)], T.mod);
-            const u64 t = reduce64(h ? sum1[k] : sum0[k], T.mod);
+            const u64 t = reduce64(sum[k], T.mod);
             const u64 dlt = t >= x ? t - x : t + T.mod.q - x;
             out[h * N + i] = csub_dev(mul_const(dlt, S.Pinv.x, S.Pinv.y, q), T.mod.q);
         }
