@@ -379,7 +379,7 @@ def main():
         kernel, units = "perm_accumulate_special_2048" if args.special_prime else "perm_accumulate_2048", batch * plan.G
         # HBM bytes per launch measured with rocprofv3 counters for the default workload
         # (profiles/perm_accumulate_fc_128x1024_b64_hbm_traffic.txt); not measured for the others
-        traffic = (47438 + 34816) * 1024.0 if args.workload == "fc_128x1024_b64" and not args.special_prime else None
+        traffic = (48155 + 67584) * 1024.0 if args.workload == "fc_128x1024_b64" and not args.special_prime else None
         config = {"workload": args.workload, "layer": "he_fc", "n": par.n, "n_o": shape.n_o, "n_i": shape.n_i,
                   "batch": batch, "G": plan.G, "gadget_digits": ctx.ndigits}
     config["key_switching"] = "special prime" if args.special_prime else "one prime"
