@@ -151,3 +151,34 @@ def test_he_conv_config4_decrypts_at_full_size():
         for O in range(plan.nout):
             plan.unpack_share(O, ctx.decrypt(sk, got[b, O]), share)
         assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_conv(K, x[b], par.p))
+
+
+def fast_plain_conv(K, x, p):
+    """The same "same"-padded convolution as plain_conv in uint64 (products below 2^40, at most 2^11 of them)."""
+    co, ci, kh, kw = K.shape
+    _, uh, uw = x.shape
+    out = np.zeros((co, uh, uw), np.uint64)
+    for dy in range(kh):
+        for dx in range(kw):
+            oy, ox = dy - kh // 2, dx - kw // 2
+            ys = slice(max(0, -oy), min(uh, uh - oy)); xs = slice(max(0, -ox), min(uw, uw - ox))
+            src = x[:, ys.start + oy:ys.stop + oy, xs.start + ox:xs.stop + ox]
+            out[:, ys, xs] += np.einsum("oc,cyx->oyx", K[:, :, dy, dx], src)
+    return out % np.uint64(p)
+
+
+@pytest.mark.parametrize("c,hw", [(128, 28), (512, 7)])
+def test_resnet_3x3_layers_decrypt_at_full_size(c, hw):
+    """3x3 layers of the ResNet-18-shaped list on one input (c_n = 2 with 576 terms; c_n = 32 with 144 terms): the
+    streaming multiply-accumulate and the special-prime rotations together; every output decrypts to the plain
+    convolution and one ciphertext is recomputed by the oracle."""
+    par = params(2048)
+    shape = (c, c, 3, 3, hw, hw)
+    ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, shape, 1, [(0, plan_o) for plan_o in (1,)], seed=c)
+    small = np.random.default_rng(1).integers(0, 50, size=(4, 3, 3, 3), dtype=np.uint64)
+    img = np.random.default_rng(2).integers(0, 50, size=(3, 5, 5), dtype=np.uint64)
+    assert np.array_equal(fast_plain_conv(small, img, par.p), plain_conv(small, img, par.p))
+    share = np.zeros(r[0].shape, np.uint64)
+    for O in range(plan.nout):
+        plan.unpack_share(O, ctx.decrypt(sk, got[0, O]), share)
+    assert np.array_equal((share + r[0]) % np.uint64(par.p), fast_plain_conv(K, x[0], par.p))
