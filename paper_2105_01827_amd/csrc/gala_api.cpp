@@ -18,7 +18,7 @@ namespace {
 // Workgroups the rotate-and-accumulate launch aims for.  Short sums (G < 32: a convolution's kernel orders) get
 // what the chip holds at once (256 CUs, three workgroups each at this kernel's register count): every further
 // chunk costs a partial ciphertext and a mask round.  Long sums (an FC layer's G rotations) are cut finer, into
-// about 2048 workgroups: chunks of equal length matter more there than a single round (63 rotations in 12 chunks
+// 1280 to 2560 workgroups: chunks of equal length matter more there than a single round (63 rotations in 12 chunks
 // leave a third of the workgroups with 6 instead of 5), and a chunk count that is a multiple of eight lets the
 // XCD-aware mapping keep every chunk's keys in one L2.  Measured on he_fc 128x1024 and 1000x2048 at batch 64:
 // 32 chunks are 4 % and 6 % faster than 12.
@@ -40,9 +40,13 @@ int choose_chunks(const gala_ctx *ctx, int items, int G) {
         const int c = ((forced > 0 ? forced : ctx->special ? 512 : 768) + items - 1) / items;
         return std::max(1, std::min(c, G));
     }
-    int c = (2048 + items - 1) / items;
-    c = (c + 7) / 8 * 8;
-    return std::max(1, std::min(c, G));
+    // a power of two (it divides the padded G, and from 8 on it keeps the XCD mapping): 1280 to 2560 workgroups,
+    // halved while a workgroup would be left with a single term and a round of the chip is still filled
+    int c = 1;
+    while (2 * c * items <= 2560) c *= 2;
+    c = std::min(c, G);
+    while (c > 1 && G / c < 2 && items * (c / 2) >= 768) c /= 2;
+    return std::max(1, c);
 }
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
