@@ -56,3 +56,35 @@ def test_client_side_functions_match_the_oracle_bit_for_bit(n):
     prod = o.scmult(ct, o.encode_weight(w))
     assert np.array_equal(ctx.decrypt(sk, prod), o.decrypt(osk, prod))
     assert np.array_equal(ctx.decrypt(sk, prod), v * w % np.uint64(par.p))
+
+
+def test_device_entry_points_reject_null_arguments_and_missing_devices():
+    """Argument checks come before any device work, so they can be exercised here; without a GPU every device
+    entry point answers GALA_EHIP instead of falling back to host code."""
+    import ctypes as C
+    import torch
+    lib = binding.load()
+    par = wl.DEFAULT
+    ctx = binding.Context(par.n, par.q, par.p, par.gadget_bits)
+    null = C.c_void_p(None)
+    one = C.c_void_p(8)          # a non-null placeholder that is never dereferenced on these paths
+    assert lib.gala_gk_count(null) == binding.GALA_EARG
+    assert lib.gala_rotate_hoisted(ctx.h, null, null, one, 1, one, one, 64) == binding.GALA_EARG
+    assert lib.gala_rotate_hoisted_workspace(null, 4) == 0 and lib.gala_rotate_hoisted_workspace(ctx.h, 0) == 0
+    assert lib.gala_rotate_hoisted_workspace(ctx.h, 3) >= 3 * 3 * par.n * 8
+    assert lib.gala_fc_unpack_share_batch(null, null, one, 1, one) == binding.GALA_EARG
+    assert lib.gala_conv_unpack_share_batch(null, null, one, 1, one) == binding.GALA_EARG
+    assert lib.gala_encrypt_batch(ctx.h, null, null, one, one, 1, one) == binding.GALA_EARG
+    assert lib.gala_add(ctx.h, null, null, one, 1, one) == binding.GALA_EARG
+    if not torch.cuda.is_available():
+        sk = ctx.keygen(1)
+        with pytest.raises(binding.GalaError) as e:
+            ctx.galois_keygen(sk, [(0, 1)], seed=1)
+        assert e.value.code == binding.GALA_EHIP
+        with pytest.raises(binding.GalaError) as e:
+            ctx.fc_plan(np.ones((4, 8), np.uint64))
+        assert e.value.code == binding.GALA_EHIP
+        with pytest.raises(binding.GalaError) as e:
+            ctx.conv_plan(np.ones((2, 2, 3, 3), np.uint64), 4, 4)
+        assert e.value.code == binding.GALA_EHIP
+        assert lib.gala_add(ctx.h, null, one, one, 1, one) == binding.GALA_EHIP
