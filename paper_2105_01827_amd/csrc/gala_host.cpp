@@ -767,26 +767,32 @@ extern "C" int gala_conv_plan_create(gala_ctx *c, const uint64_t *K, int c_o, in
     if (pl->term_ct.empty()) { pl->term_ct.push_back(0); pl->term_tap.push_back(pl->centre); }
     const int nterm = pl->nterm = (int)pl->term_ct.size();
     const size_t npoly = (size_t)nout * cn * nterm;
-    std::vector<u64> w;
-    try { w.resize(npoly * n); } catch (...) { delete pl; return GALA_ENOMEM; }
-    parallel_for(npoly, [&](size_t id) {
-        const int e = (int)(id % nterm), tap = pl->term_tap[e], I = pl->term_ct[e], gam = (int)(id / nterm % cn),
-                  O = (int)(id / nterm / cn);
-        const int gs = gam / hpos, gt = gam % hpos, dy = tap / k_w - k_h / 2, dx = tap % k_w - k_w / 2;
-        std::vector<u64> slots(n, 0);
-        for (int h = 0; h < 2; ++h)
-            for (int kap = 0; kap < hpos; ++kap) {
-                const int in_ch = I * cn + h * hpos + kap;
-                const int okap = ((kap - gt) % hpos + hpos) % hpos;
-                const int out_ch = O * cn + (h ^ gs) * hpos + okap;
-                if (in_ch >= c_i || out_ch >= c_o) continue;
-                const u64 *ker = K + ((size_t)out_ch * c_i + in_ch) * k_h * k_w;
-                for (int y = std::max(0, -dy); y < std::min(u_h, u_h - dy); ++y)
-                    for (int x = std::max(0, -dx); x < std::min(u_w, u_w - dx); ++x)
-                        slots[h * half + kap * T + y * u_w + x] = ker[tap] % c->p;
-            }
-        encode_weight_hat(c, slots.data(), w.data() + id * n);
-    });
+    // "encode" on the device: the slot vectors of a few thousand kernels at a time are written from K by one
+    // kernel and taken to the evaluation domain by the plaintext encoder (centred lift, as ScMult expects)
+    {
+        const ConvGeom geo{c_o, c_i, k_h, k_w, u_h, u_w, T, cn, hpos, nterm, n, c->p};
+        const size_t chunk = std::min<size_t>(npoly, 4096);
+        u64 *d_K = nullptr, *d_slots = nullptr;
+        int *d_tct = nullptr, *d_ttap = nullptr;
+        int rc = GALA_OK;
+        const size_t kwords = (size_t)c_o * c_i * k_h * k_w;
+        if (hipMalloc((void **)&d_K, kwords * sizeof(u64)) != hipSuccess ||
+            hipMalloc((void **)&d_slots, chunk * n * sizeof(u64)) != hipSuccess ||
+            hipMalloc((void **)&pl->d_w, npoly * n * sizeof(u64)) != hipSuccess)
+            rc = GALA_ENOMEM;
+        if (!rc) rc = upload(&d_tct, pl->term_ct);
+        if (!rc) rc = upload(&d_ttap, pl->term_tap);
+        if (!rc && hipMemcpy(d_K, K, kwords * sizeof(u64), hipMemcpyHostToDevice) != hipSuccess) rc = GALA_EHIP;
+        for (size_t first = 0; !rc && first < npoly; first += chunk) {
+            const size_t cnt = std::min(chunk, npoly - first);
+            if (launch_conv_weight_slots(c, nullptr, d_K, geo, d_tct, d_ttap, first, cnt, d_slots) ||
+                launch_encode_plain(c, nullptr, d_slots, (int)cnt, 0, pl->d_w + first * n))
+                rc = GALA_EHIP;
+        }
+        if (!rc && hipDeviceSynchronize() != hipSuccess) rc = GALA_EHIP;
+        hipFree(d_K); hipFree(d_slots); hipFree(d_tct); hipFree(d_ttap);
+        if (rc) { gala_conv_plan_destroy(pl); return rc; }
+    }
     // mask layout: every real output is a row of its own
     MaskLayoutHost &mh = pl->mask_h;
     mh.nout = nout;
@@ -816,8 +822,7 @@ extern "C" int gala_conv_plan_create(gala_ctx *c, const uint64_t *K, int c_o, in
         if (term_gal[e] != 1) { ++pl->nrot_terms; ct_rotates[pl->term_ct[e]] = 1; }
     }
     for (char f : ct_rotates) pl->nrot_cts += f;
-    int rc = upload(&pl->d_w, w);
-    if (!rc) rc = upload(&pl->d_term_ct, pl->term_ct);
+    int rc = upload(&pl->d_term_ct, pl->term_ct);
     if (!rc) rc = upload(&pl->d_term_gal, term_gal);
     if (!rc) rc = upload(&pl->d_term_key, term_key);
     if (!rc) rc = upload(&pl->d_grp_gal, pl->grp_gal);

@@ -170,6 +170,14 @@ const u64 *gauss_cdf_table();
 // Stand-alone Add / ScMult / plaintext operations on internal-form buffers (op: 0 add ct, 1 scmult, 2 sub plain, 3 add plain).
 int launch_encode_plain(const gala_ctx *ctx, void *stream, const u64 *slots, int count, int mode, u64 *plain);
 int launch_ct_op(const gala_ctx *ctx, void *stream, int op, const u64 *a, const u64 *b, size_t b_stride, int count, u64 *out);
+// "encode" of a convolution plan on the device (Sec. III-B(3), kernel grouping): slot vectors of the encoded kernels
+// `first` .. `first + count - 1` in (O, gamma, term) order, from the kernel tensor K (c_o x c_i x k_h x k_w, device)
+struct ConvGeom {
+    int c_o, c_i, k_h, k_w, u_h, u_w, T, cn, hpos, nterm, n;
+    u64 p;
+};
+int launch_conv_weight_slots(const gala_ctx *ctx, void *stream, const u64 *K, const ConvGeom &g, const int *term_ct,
+                             const int *term_tap, size_t first, size_t count, u64 *slots);
 // out[b][rindex of row t] = sum of the row's slots mod p, for `count` items of nout slot vectors each
 int launch_unpack_share(const gala_ctx *ctx, void *stream, const u64 *slots, int count, int nout, const MaskLayoutDev &layout,
                         size_t out_stride, u64 *out);

@@ -764,6 +764,31 @@ __global__ __launch_bounds__(256 * KS) void conv_mac_stream_kernel(const u64 *w,
         }
 }
 
+// Slot vectors of a convolution plan's encoded kernels (Sec. III-B(3)): polynomial (O, gamma, term) holds, at the
+// slot of pixel (y,x) of channel position (h,kappa), the tap's kernel value between the input channel at that
+// position and the output channel that kernel order gamma = (s,t) sends it to, or zero where the tap falls off
+// the image or a channel does not exist.  One workgroup per polynomial.
+__global__ void conv_weight_slots_kernel(const u64 *K, ConvGeom g, const int *term_ct, const int *term_tap, size_t first,
+                                         u64 *slots) {
+    const size_t id = first + blockIdx.x;
+    const int e = (int)(id % g.nterm), gam = (int)(id / g.nterm % g.cn), O = (int)(id / g.nterm / g.cn);
+    const int I = term_ct[e], tap = term_tap[e];
+    const int gs = gam / g.hpos, gt = gam % g.hpos, dy = tap / g.k_w - g.k_h / 2, dx = tap % g.k_w - g.k_w / 2;
+    const int half = g.n / 2;
+    u64 *out = slots + (size_t)blockIdx.x * g.n;
+    for (int s = threadIdx.x; s < g.n; s += blockDim.x) {
+        const int h = s / half, k = s % half, kap = k / g.T, off = k % g.T, y = off / g.u_w, x = off % g.u_w;
+        const int in_ch = I * g.cn + h * g.hpos + kap;
+        const int okap = ((kap - gt) % g.hpos + g.hpos) % g.hpos;
+        const int out_ch = O * g.cn + (h ^ gs) * g.hpos + okap;
+        u64 v = 0;
+        if (off < g.u_h * g.u_w && in_ch < g.c_i && out_ch < g.c_o && y + dy >= 0 && y + dy < g.u_h && x + dx >= 0 &&
+            x + dx < g.u_w)
+            v = K[((size_t)out_ch * g.c_i + in_ch) * g.k_h * g.k_w + tap] % g.p;
+        out[s] = v;
+    }
+}
+
 // The plaintext half of share generation: every output is the sum of its row's slots mod p (Sec. III-A(3); a
 // convolution's rows are single slots).  One workgroup per slot vector; the row sums meet in LDS as plain integers.
 __global__ void unpack_share_kernel(const u64 *slots, int nout, int n, u64 p, const int *slot_rowid, const int *row_rindex,
@@ -820,6 +845,13 @@ int launch_ct_op(const gala_ctx *c, void *stream, int op, const u64 *a, const u6
     const size_t words = (size_t)count * 2 * c->n;
     hipLaunchKernelGGL(ct_op_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, (hipStream_t)stream, op, a, b, b_stride,
                        words, c->n, out, c->dev_q.mod);
+    return last_error();
+}
+int launch_conv_weight_slots(const gala_ctx *c, void *stream, const u64 *K, const ConvGeom &g, const int *term_ct,
+                             const int *term_tap, size_t first, size_t count, u64 *slots) {
+    if (!count) return 0;
+    hipLaunchKernelGGL(conv_weight_slots_kernel, dim3((unsigned)count), dim3(block_threads(c->n)), 0, (hipStream_t)stream, K, g,
+                       term_ct, term_tap, first, slots);
     return last_error();
 }
 int launch_unpack_share(const gala_ctx *c, void *stream, const u64 *slots, int count, int nout, const MaskLayoutDev &layout,
