@@ -66,16 +66,33 @@ __global__ __launch_bounds__(256) void limb_pack_kernel(const u64 *src, int mode
     __syncthreads();
     // phase 2: mode 0 runs the row across the threads, mode 1 the coefficient
     const int rl = mode == 0 ? threadIdx.x & 15 : threadIdx.x >> 4, il = mode == 0 ? threadIdx.x >> 4 : threadIdx.x & 15;
-    if (i0 + il >= n) return;
+    const bool live = i0 + il < n;
     u64 d[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) d[j] = stage[(rl * 16 + j) * 17 + il];
     const size_t lane = (size_t)(g * 16 + rl);
-    const size_t base = mode == 0 ? ((((size_t)(i0 + il) * tiles + tile) * kblocks + kb) * 8) * 64 + lane
-                                  : ((((size_t)tile * kblocks + kb) * 64 + lane) * n + i0 + il) * 8;
-    const size_t step = mode == 0 ? 64 : 1;
+    if (mode == 0) {
+        if (!live) return;
+        // 16 threads (the rows of a tile) write 256 contiguous bytes per digit
+        const size_t base = ((((size_t)(i0 + il) * tiles + tile) * kblocks + kb) * 8) * 64 + lane;
 #pragma unroll
-    for (int limb = 0; limb < 8; ++limb) dst[base + (size_t)limb * step] = digit_chunk(d, limb);
+        for (int limb = 0; limb < 8; ++limb) dst[base + (size_t)limb * 64] = digit_chunk(d, limb);
+        return;
+    }
+    // mode 1: a row's 16 coefficients x 8 digits are 2 KiB contiguous in the image, but a thread owns the 128
+    // bytes of one coefficient: the chunks change owner in LDS so that the 16 threads of a row write 256
+    // contiguous bytes per instruction instead of 16 bytes in each of 16 lines
+    __syncthreads();                                   // everybody has read its digits out of `stage`
+    v4i *tr = reinterpret_cast<v4i *>(stage);          // [row][coefficient][digit], 32 KiB
+#pragma unroll
+    for (int limb = 0; limb < 8; ++limb) tr[(rl * 16 + il) * 8 + limb] = digit_chunk(d, limb);
+    __syncthreads();
+    const size_t base = ((((size_t)tile * kblocks + kb) * 64 + lane) * n + i0) * 8;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int c = k * 16 + il;                     // chunk c of the row: coefficient c / 8, digit c % 8
+        if (i0 + (c >> 3) < n) dst[base + c] = tr[rl * 128 + c];
+    }
 }
 
 // sum_s 256^s * c[s] for 15 signed 32-bit diagonals, as an unsigned 128-bit value (the true sum is non-negative).
