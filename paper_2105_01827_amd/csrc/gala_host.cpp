@@ -667,8 +667,11 @@ extern "C" int gala_fc_plan_create(gala_ctx *c, const uint64_t *W, int n_o, int 
     std::vector<int> key_idx(G, -1);
     int rc = upload(&pl->d_w, w);
     if (!rc && uses_fast_perm(c)) {
-        if (hipMalloc((void **)&pl->d_w2, 2 * w.size() * sizeof(u64)) != hipSuccess) rc = GALA_ENOMEM;
-        if (!rc && (launch_pair_pack(c, nullptr, pl->d_w, pl->d_w2, w.size(), 2) || hipDeviceSynchronize() != hipSuccess))
+        // pairs in natural order, then once more in the order the Perm kernel's threads own them
+        if (hipMalloc((void **)&pl->d_w2, 4 * w.size() * sizeof(u64)) != hipSuccess) rc = GALA_ENOMEM;
+        if (!rc && (launch_pair_pack(c, nullptr, pl->d_w, pl->d_w2, w.size(), 2) ||
+                    launch_owner_order_2048(nullptr, pl->d_w2, pl->d_w2 + 2 * w.size(), (size_t)G) ||
+                    hipDeviceSynchronize() != hipSuccess))
             rc = GALA_EHIP;
     }
     if (!rc) rc = upload(&pl->d_gal, pl->gal);

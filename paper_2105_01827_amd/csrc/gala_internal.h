@@ -125,7 +125,8 @@ struct gala_fc_plan {
     std::vector<int> slot_row;         // padded row of each slot, -1 if it carries no weight
     std::vector<int> gal;              // Galois element of rotation g (gal[0] = 1)
     gala::u64 *d_w = nullptr;          // G x n encoded weights, evaluation domain
-    gala::u64 *d_w2 = nullptr;         // the same as (value, companion) pairs for the n = 2048 kernel, or null
+    gala::u64 *d_w2 = nullptr;         // the same as (value, companion) pairs for the n = 2048 kernel, or null: G polynomials in
+                                       // natural order, then the same G in the threads' ownership order
     int *d_gal = nullptr;              // G Galois elements
     int *d_key_idx = nullptr;          // G key indices (valid once bound)
     const gala_gk *bound = nullptr;
@@ -190,6 +191,10 @@ int launch_key_finish(const gala_ctx *ctx, void *stream, u64 *pairs, const u64 *
 // With a special prime the polynomials alternate (b, a) mod q, (b, a) mod P: `polys` = 4 selects the modulus
 // by polynomial index, `polys` = 2 uses q throughout.
 int launch_pair_pack(const gala_ctx *ctx, void *stream, const u64 *src, u64 *dst, size_t count, int polys);
+// dst[poly][512*(t/64) + 64*k + t%64] = src[poly][8*t + k] on 16-byte pairs of n = 2048 polynomials: the order in which
+// the threads of the Perm kernel read the 8 consecutive coefficients they own - one coalesced load per k, the eight of
+// a wavefront within 8 KiB
+int launch_owner_order_2048(void *stream, const u64 *src_pairs, u64 *dst_pairs, size_t npolys);
 // whether launch_perm_accumulate will use the n = 2048 kernel for this context
 bool uses_fast_perm(const gala_ctx *ctx);
 

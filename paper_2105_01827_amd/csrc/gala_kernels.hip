@@ -898,6 +898,19 @@ int launch_key_finish(const gala_ctx *c, void *stream, u64 *pairs, const u64 *s_
                        s_hat, c->n, total, mod);
     return last_error();
 }
+__global__ void owner_order_2048_kernel(const ulonglong2 *src, ulonglong2 *dst) {
+    const size_t base = (size_t)blockIdx.x * 2048;
+    for (int j = threadIdx.x; j < 2048; j += blockDim.x) {
+        const int t = j >> 3, k = j & 7;      // owner thread t, its k-th coefficient
+        dst[base + (size_t)(t >> 6) * 512 + k * 64 + (t & 63)] = src[base + j];
+    }
+}
+int launch_owner_order_2048(void *stream, const u64 *src, u64 *dst, size_t npolys) {
+    if (!npolys) return 0;
+    hipLaunchKernelGGL(owner_order_2048_kernel, dim3((unsigned)npolys), dim3(256), 0, (hipStream_t)stream,
+                       reinterpret_cast<const ulonglong2 *>(src), reinterpret_cast<ulonglong2 *>(dst));
+    return (int)hipGetLastError();
+}
 int launch_pair_pack(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, size_t count, int polys) {
     if (!count) return 0;
     hipLaunchKernelGGL(pair_pack_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, (hipStream_t)stream, src,

@@ -370,6 +370,9 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
         const u64 *c0 = job.ct_in + (size_t)item * job.in_item_stride + (size_t)g * job.in_g_stride;
         const u64 *c1 = c0 + N;
         const ulonglong2 *w = HAS_W ? reinterpret_cast<const ulonglong2 *>(job.w2) + (size_t)g * N : nullptr;
+        // middle of this wavefront's 8 KiB in the ownership-order copy: all eight loads are immediate offsets of it
+        const char *wo = HAS_W ? reinterpret_cast<const char *>(w + (size_t)job.G * N) : nullptr;
+        const unsigned wmid = ((unsigned)(fresh(tid) >> 6) * 512u + 256u + (unsigned)(tid & 63)) * 16u;
         const int gal = job.gal[g];
         if (gal == 1) {   // rotation by zero: ScMult and Add only
 #pragma unroll
@@ -402,8 +405,9 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const ulonglong2 cv = c1v[k];
-                if (HAS_W) {
-                    const ulonglong2 wa = w[8 * tid + 2 * k], wb = w[8 * tid + 2 * k + 1];
+                if (HAS_W) {     // the copy in ownership order: 64 lanes read 1 KiB of whole lines
+                    const ulonglong2 wa = *reinterpret_cast<const ulonglong2 *>(wo + (wmid + (unsigned)((2 * k - 4) * 1024))),
+                                     wb = *reinterpret_cast<const ulonglong2 *>(wo + (wmid + (unsigned)((2 * k - 3) * 1024)));
                     a[2 * k] = mul_const(cv.x, wa.x, wa.y, q);
                     a[2 * k + 1] = mul_const(cv.y, wb.x, wb.y, q);
                 } else {
