@@ -322,7 +322,12 @@ extern "C" int gala_ctx_create(const gala_params *par, gala_ctx **out) {
     std::vector<u64> pairs, pairs_p, pairs_P, hostP;
     if (n == 2048) {
         auto build = [&](const NttHost &h, std::vector<u64> &out) {
-            out.assign(2 * 2 * 8 * (size_t)512, 0);
+            // ... followed, for each direction, by the same pairs level by level with the constant's number before
+            // the block's: level c (blocks c .. 2c-1, c = 1, 4, 8, 32, 64, 256) is [e][j] = block (c + j), pair e, so
+            // that a wavefront's load of constant e reads neighbouring pairs (2555 pairs per direction)
+            static const int kLevels[6] = {1, 4, 8, 32, 64, 256};
+            const size_t blocks_words = 2 * 2 * 8 * (size_t)512, level_pairs = 7 * (1 + 4 + 8 + 32 + 64 + 256);
+            out.assign(blocks_words + 2 * 2 * level_pairs, 0);
             for (int inv = 0; inv < 2; ++inv) {
                 const std::vector<u64> &w = inv ? h.itw : h.tw, &ws = inv ? h.itws : h.tws;
                 u64 *base = out.data() + (size_t)inv * 2 * 8 * 512;
@@ -332,6 +337,16 @@ extern "C" int gala_ctx_create(const gala_params *par, gala_ctx **out) {
                         base[2 * (8 * T + e)] = w[idx[e]];
                         base[2 * (8 * T + e) + 1] = ws[idx[e]];
                     }
+                }
+                u64 *lev = out.data() + blocks_words + (size_t)inv * 2 * level_pairs;
+                for (int L = 0; L < 6; ++L) {
+                    const int cnt = kLevels[L];
+                    for (int e = 0; e < 7; ++e)
+                        for (int j = 0; j < cnt; ++j) {
+                            lev[2 * ((size_t)e * cnt + j)] = base[2 * (8 * (cnt + j) + e)];
+                            lev[2 * ((size_t)e * cnt + j) + 1] = base[2 * (8 * (cnt + j) + e) + 1];
+                        }
+                    lev += 2 * 7 * (size_t)cnt;
                 }
             }
         };

@@ -101,22 +101,33 @@ __device__ __forceinline__ void bf_inv(u64 &x, u64 &y, const ulonglong2 t, NegQ 
     y = mul_const(d, t.x, t.y, nq);
 }
 
-// Twiddles are stored pass-major: the seven constants one thread needs for a radix-8 pass sit in
-// one 128-byte block {t1, t2a, t2b, t4[0..3], unused}; block T of the natural table order
-// tw[T], tw[2T], tw[2T+1], tw[4T..4T+3]  (T = (n >> (B+3)) + (index >> (B+3)) for a pass on bits B..B+2).
-// Block numbering: T itself (1 <= T < 512), so the table has 512 blocks of 8 pairs.
+// The seven constants one thread needs for a radix-8 pass on index bits B..B+2 are tw[T], tw[2T], tw[2T+1],
+// tw[4T..4T+3] of the natural table order, with T = (n >> (B+3)) + (index >> (B+3)): "block" T.  A pass uses the
+// blocks c .. 2c-1 of one level c (1, 8, 64, 256 forward; 256, 32, 4, 1 inverse).  The table is stored level by
+// level with the constant's number before the block's: level c is [e][j] = constant e of block c + j.  Constant e
+// of the 64 lanes of a wavefront is then 16 to 1024 contiguous bytes; stored block by block (128 bytes per block)
+// the same load touched up to 64 different lines, and the twiddles were two thirds of all the lines the Perm
+// kernel asked its vector cache for.
 //
 // Radix-8 forward pass on the three index bits held in the register number (bit 2 of k first).
 // FIRST = false skips the first stage (the last pass of the transform has only two stages).
-// The seven constants of a pass are fetched with tw_load() BEFORE the exchange that precedes the pass: a load
+// The seven constants of a pass are fetched with tw_level() BEFORE the exchange that precedes the pass: a load
 // cannot move across the exchange's barrier, and issued after it its latency is fully exposed, pass after pass.
 struct Tw7 {
     ulonglong2 t[7];
 };
-__device__ __forceinline__ Tw7 tw_load(const ulonglong2 *__restrict__ blk) {
+// offset, in pairs, of level c inside a direction's table (levels 1, 4, 8, 32, 64, 256 in this order)
+__device__ __forceinline__ constexpr int level_offset(int c) {
+    return 7 * (c > 1 ? 1 : 0) + 7 * (c > 4 ? 4 : 0) + 7 * (c > 8 ? 8 : 0) + 7 * (c > 32 ? 32 : 0) + 7 * (c > 64 ? 64 : 0);
+}
+// constants of block COUNT + j: the level's start is uniform, j*16 a 32-bit offset
+template <int COUNT>
+__device__ __forceinline__ Tw7 tw_level(const ulonglong2 *__restrict__ table, unsigned j) {
+    const char *level = reinterpret_cast<const char *>(table + level_offset(COUNT));
+    const unsigned off = j * 16u;
     Tw7 w;
 #pragma unroll
-    for (int e = 0; e < 7; ++e) w.t[e] = blk[e];
+    for (int e = 0; e < 7; ++e) w.t[e] = *reinterpret_cast<const ulonglong2 *>(level + (size_t)(e * COUNT * 16) + off);
     return w;
 }
 template <bool FIRST, bool CORRECT>
@@ -170,7 +181,7 @@ __device__ __forceinline__ void exchange(u64 (&a)[8], u64 *buf, int base_out, in
 }
 
 struct Tables2048 {
-    const ulonglong2 *tw, *itw;   // pass-major blocks of (w, companion) pairs, forward and inverse
+    const ulonglong2 *tw, *itw;   // level-major (w, companion) pairs, forward and inverse (see tw_level)
     ulonglong2 ninv, itw1n;       // n^-1 and itw[1]*n^-1 with companions
     Modulus mod;
     NegQ nq;                      // 2^64 - q
@@ -189,15 +200,15 @@ __device__ __forceinline__ void forward_to_lds(u64 (&a)[8], u64 *res, u64 *other
     const int tid = fresh(tid_);
     const NegQ q = T.nq;
     const u64 q2 = T.mod.q2;
-    Tw7 w = tw_load(T.tw + 8 * 1);
+    Tw7 w = tw_level<1>(T.tw, 0);
     fwd_pass<true, false>(a, w, q, q2);                                              // bits 8-10
-    w = tw_load(T.tw + 8 * (8 + (tid >> 5)));
+    w = tw_level<8>(T.tw, (unsigned)tid >> 5);
     exchange<8, 5>(a, other, tid, ((tid >> 5) << 8) | (tid & 31));
     fwd_pass<true, false>(a, w, q, q2);                                              // bits 5-7
-    w = tw_load(T.tw + 8 * (64 + (tid >> 2)));
+    w = tw_level<64>(T.tw, (unsigned)tid >> 2);
     exchange<5, 2>(a, res, ((tid >> 5) << 8) | (tid & 31), ((tid >> 2) << 5) | (tid & 3));
     fwd_pass<true, true>(a, w, q, q2);                                               // bits 2-4
-    w = tw_load(T.tw + 8 * (256 + tid));
+    w = tw_level<256>(T.tw, (unsigned)tid);
     exchange<2, 0>(a, other, ((tid >> 2) << 5) | (tid & 3), tid << 3);
     fwd_pass<false, false>(a, w, q, q2);                                             // bits 0-1
     u64 *po = res + pad(tid << 3);
@@ -212,15 +223,15 @@ __device__ __forceinline__ void inverse_in_regs(u64 (&a)[8], u64 *bufA, u64 *buf
     const int tid = fresh(tid_);
     const NegQ q = T.nq;
     const u64 q2 = T.mod.q2;
-    Tw7 w = tw_load(T.itw + 8 * (256 + tid));
+    Tw7 w = tw_level<256>(T.itw, (unsigned)tid);
     inv_pass(a, w, q, q2);                                                           // bits 0-2
-    w = tw_load(T.itw + 8 * (32 + (tid >> 3)));
+    w = tw_level<32>(T.itw, (unsigned)tid >> 3);
     exchange<0, 3>(a, bufA, tid << 3, ((tid >> 3) << 6) | (tid & 7));
     inv_pass(a, w, q, q2);                                                           // bits 3-5
-    w = tw_load(T.itw + 8 * (4 + (tid >> 6)));
+    w = tw_level<4>(T.itw, (unsigned)tid >> 6);
     exchange<3, 6>(a, bufB, ((tid >> 3) << 6) | (tid & 7), ((tid >> 6) << 9) | (tid & 63));
     inv_pass(a, w, q, q2);                                                           // bits 6-8
-    const ulonglong2 t2a = T.itw[8 * 1 + 1], t2b = T.itw[8 * 1 + 2];
+    const ulonglong2 t2a = T.itw[1], t2b = T.itw[2];      // level 1: constants 1 and 2 of block 1
     exchange<6, 8>(a, bufA, ((tid >> 6) << 9) | (tid & 63), tid);
     // bits 9-10 (register bits 1,2; register bit 0 is index bit 8), n^-1 folded into the last stage
     bf_inv(a[0], a[2], t2a, q, q2);
@@ -954,8 +965,10 @@ __global__ void sum_partials_kernel(const u64 *partial, int slots, int used, u64
 
 static Tables2048 make_tables(const gala_ctx *c, const u64 *blocks, const NttDev &dev) {
     Tables2048 T;
-    T.tw = reinterpret_cast<const ulonglong2 *>(blocks);
-    T.itw = reinterpret_cast<const ulonglong2 *>(blocks + 2 * 8 * (size_t)512);
+    // the level-major tables follow the two block tables (512 blocks of 8 pairs each)
+    const ulonglong2 *levels = reinterpret_cast<const ulonglong2 *>(blocks) + 2 * 8 * (size_t)512;
+    T.tw = levels;
+    T.itw = levels + 7 * (1 + 4 + 8 + 32 + 64 + 256);
     T.ninv = make_ulonglong2(dev.ninv, dev.ninvs);
     T.itw1n = make_ulonglong2(dev.itw1n, dev.itw1ns);
     T.mod = dev.mod;
