@@ -14,6 +14,18 @@ constexpr int kMaxDigits = 32;
 constexpr int kMaxN = 2048;
 constexpr int kGaussBound = 19;
 
+// Cumulative table of the discrete Gaussian (passed to kernels by value) and the draw from it: one 64-bit word
+// of the counter-based generator compared with the 38 thresholds.
+struct GaussCdf {
+    u64 t[2 * kGaussBound];   // floor(2^64 * P[X <= -bound + i])
+};
+GALA_HD int draw_gauss_cdf(const GaussCdf &cdf, u64 seed, u64 stream, u64 idx) {
+    const u64 u = rand64(seed, stream, idx, 0);
+    int x = -kGaussBound;
+    for (int i = 0; i < 2 * kGaussBound; ++i) x += u >= cdf.t[i] ? 1 : 0;
+    return x;
+}
+
 // ---------------------------------------------------------------------------
 // Negacyclic number-theoretic transform tables for one modulus.
 // Forward: natural-order coefficients -> values a(psi^(2*brev(i)+1)) at index i.
@@ -167,6 +179,10 @@ int launch_encrypt(const gala_ctx *ctx, void *stream, const u64 *s_hat, const u6
                    u64 *ct_out);
 int launch_decrypt(const gala_ctx *ctx, void *stream, const u64 *s_hat, const u64 *ct_in, int count, u64 *slots);
 const u64 *gauss_cdf_table();
+// the same two steps with the radix-8 transforms of the n = 2048 kernels
+int launch_encrypt_2048(const gala_ctx *ctx, void *stream, const u64 *s_hat, const u64 *slots, const u64 *seeds, int count,
+                        u64 *ct_out);
+int launch_decrypt_2048(const gala_ctx *ctx, void *stream, const u64 *s_hat, const u64 *ct_in, int count, u64 *slots);
 
 // Stand-alone Add / ScMult / plaintext operations on internal-form buffers (op: 0 add ct, 1 scmult, 2 sub plain, 3 add plain).
 int launch_encode_plain(const gala_ctx *ctx, void *stream, const u64 *slots, int count, int mode, u64 *plain);

@@ -401,16 +401,6 @@ __global__ void ct_op_kernel(int op, const u64 *a, const u64 *b, size_t b_stride
 // ---------------------------------------------------------------------------
 // the client's steps, batched: one workgroup per ciphertext, internal (evaluation-domain) form
 // ---------------------------------------------------------------------------
-struct GaussCdf {
-    u64 t[2 * kGaussBound];   // floor(2^64 * P[X <= -bound + i])
-};
-__device__ __forceinline__ int draw_gauss_dev(const GaussCdf &cdf, u64 seed, u64 stream, u64 idx) {
-    const u64 u = rand64(seed, stream, idx, 0);
-    int x = -kGaussBound;
-#pragma unroll
-    for (int i = 0; i < 2 * kGaussBound; ++i) x += u >= cdf.t[i] ? 1 : 0;
-    return x;
-}
 // ct = (-a s + e + delta m, a) (Sec. II-C(1)): m = the plaintext polynomial of the slots, a uniform, e Gaussian,
 // everything drawn from the ciphertext's seed exactly as the host function does.
 template <int NT>
@@ -451,7 +441,7 @@ __global__ __launch_bounds__(NT) void encrypt_kernel(const u64 *slots, const u64
     for (int k = 0; k < kMaxPer; ++k) {
         const int i = tid + k * NT;
         if (i < n) {
-            const int e = draw_gauss_dev(cdf, seed, kStreamCtE, (u64)i);
+            const int e = draw_gauss_cdf(cdf, seed, kStreamCtE, (u64)i);
             const u64 el = e >= 0 ? (u64)e : q - (u64)(-e);
             buf[i] = add_mod(el, mul_shoup(m[k], delta, delta_s, q), q);
         }
@@ -865,6 +855,7 @@ int launch_unpack_share(const gala_ctx *c, void *stream, const u64 *slots, int c
 int launch_encrypt(const gala_ctx *c, void *stream, const u64 *s_hat, const u64 *slots, const u64 *seeds, int count,
                    u64 *ct_out) {
     if (!count) return 0;
+    if (uses_fast_perm(c)) return launch_encrypt_2048(c, stream, s_hat, slots, seeds, count, ct_out);
     GaussCdf cdf;
     for (int i = 0; i < 2 * kGaussBound; ++i) cdf.t[i] = gauss_cdf_table()[i];
     const size_t lds = sizeof(u64) * c->n;
@@ -879,6 +870,7 @@ int launch_encrypt(const gala_ctx *c, void *stream, const u64 *s_hat, const u64 
 }
 int launch_decrypt(const gala_ctx *c, void *stream, const u64 *s_hat, const u64 *ct_in, int count, u64 *slots) {
     if (!count) return 0;
+    if (uses_fast_perm(c)) return launch_decrypt_2048(c, stream, s_hat, ct_in, count, slots);
     u64 inv = c->q;                                   // Newton's iteration for q^-1 mod 2^64 (q is odd)
     for (int i = 0; i < 6; ++i) inv *= 2 - c->q * inv;
     const size_t lds = sizeof(u64) * c->n;

@@ -664,6 +664,73 @@ __global__ __launch_bounds__(NT) void hstperm_pack_2048(const u64 *ct_in, const 
 }
 
 
+// ---- the client's two steps with the radix-8 transforms (one workgroup per ciphertext) ------------------------
+// ct = (-a s + e + delta m, a) (Sec. II-C(1)), bit for bit the any-n kernel: m = the plaintext polynomial of the
+// slots, a uniform, e Gaussian, all drawn from the ciphertext's seed by coefficient index.
+__global__ __launch_bounds__(NT) void encrypt_2048(const u64 *slots, const u64 *seeds, const u64 *s_hat, u64 *ct_out,
+                                                   Tables2048 T, Tables2048 Tp, const int *slot_to_idx, GaussCdf cdf,
+                                                   int qbits, ulonglong2 delta) {
+    __shared__ u64 bufA[LDS_WORDS], bufB[LDS_WORDS];
+    const int tid = threadIdx.x;
+    const u64 q = T.mod.q, p = Tp.mod.q, seed = seeds[blockIdx.x];
+    const u64 *sl = slots + (size_t)blockIdx.x * N;
+    u64 *c0 = ct_out + (size_t)blockIdx.x * 2 * N, *c1 = c0 + N;
+    for (int s = tid; s < N; s += NT) {
+        const u64 v = sl[s];
+        bufB[slot_to_idx[s]] = v >= p ? v % p : v;
+    }
+    __syncthreads();
+    u64 a[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) a[k] = bufB[8 * tid + k];
+    inverse_in_regs(a, bufA, bufB, Tp, tid);          // m, coefficient tid + 256k, canonical mod p
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int e = draw_gauss_cdf(cdf, seed, kStreamCtE, (u64)(tid + k * NT));
+        const u64 el = e >= 0 ? (u64)e : q - (u64)(-e);
+        a[k] = csub_dev(el + csub_dev(mul_const(a[k], delta.x, delta.y, T.nq), q), q);
+    }
+    forward_to_lds(a, bufA, bufB, T, tid);            // (e + delta m) in the evaluation domain, in bufA
+    u64 t0[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) t0[k] = reduce64(bufA[pad(tid + k * NT)], T.mod);
+#pragma unroll
+    for (int k = 0; k < PER; ++k) a[k] = draw_uniform(q, qbits, seed, kStreamCtA, (u64)(tid + k * NT));
+    forward_to_lds(a, bufA, bufB, T, tid);            // its first barrier comes after every read of bufA above
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int i = tid + k * NT;
+        const u64 ah = reduce64(bufA[pad(i)], T.mod);
+        c1[i] = ah;
+        c0[i] = sub_mod(t0[k], mul_mod(ah, s_hat[i], T.mod), q);
+    }
+}
+// slots = decode(round(p (c0 + c1 s) / q) mod p); the rounded quotient through the exact division by q (q^-1 mod 2^64).
+__global__ __launch_bounds__(NT) void decrypt_2048(const u64 *ct_in, const u64 *s_hat, u64 *slots, Tables2048 T,
+                                                   Tables2048 Tp, const int *slot_to_idx, u64 q_inv64) {
+    __shared__ u64 bufA[LDS_WORDS], bufB[LDS_WORDS];
+    const int tid = threadIdx.x;
+    const u64 q = T.mod.q, p = Tp.mod.q;
+    const u64 *c0 = ct_in + (size_t)blockIdx.x * 2 * N, *c1 = c0 + N;
+    u64 a[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int i = 8 * tid + k;
+        a[k] = add_mod(c0[i], mul_mod(c1[i], s_hat[i], T.mod), q);
+    }
+    inverse_in_regs(a, bufA, bufB, T, tid);           // c0 + c1 s, coefficient tid + 256k, canonical
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const u128 t = (u128)p * a[k] + (q >> 1);
+        const u64 r = reduce128(t, T.mod);
+        const u64 quot = ((u64)t - r) * q_inv64;      // t - r is a multiple of q and the quotient is at most p
+        a[k] = quot >= p ? quot - p : quot;
+    }
+    forward_to_lds(a, bufA, bufB, Tp, tid);           // the slots' values at their transform positions, in bufA
+    u64 *out = slots + (size_t)blockIdx.x * N;
+    for (int s = tid; s < N; s += NT) out[s] = reduce64(bufA[pad(slot_to_idx[s])], Tp.mod);
+}
+
 // ---- key switching with a special prime P -------------------------------------------------------------
 // Keys hold four polynomials per digit ((b, a) modulo q, then modulo P).  Per rotation the digits are
 // transformed in both moduli and multiplied into sums modulo q and modulo P; the sums modulo P go back to
@@ -1086,6 +1153,25 @@ int launch_hstperm_pack_2048(const gala_ctx *c, void *stream, const u64 *ct_in, 
         hipLaunchKernelGGL((hstperm_pack_2048<3, true>), grid, dim3(NT), 0, st, ct_in, digits, terms, kblocks, keys2, out, T, c->ndigits, batch);
     else
         hipLaunchKernelGGL((hstperm_pack_2048<0, true>), grid, dim3(NT), 0, st, ct_in, digits, terms, kblocks, keys2, out, T, c->ndigits, batch);
+    return (int)hipGetLastError();
+}
+
+int launch_encrypt_2048(const gala_ctx *c, void *stream, const u64 *s_hat, const u64 *slots, const u64 *seeds, int count,
+                        u64 *ct_out) {
+    if (!count) return 0;
+    GaussCdf cdf;
+    for (int i = 0; i < 2 * kGaussBound; ++i) cdf.t[i] = gauss_cdf_table()[i];
+    hipLaunchKernelGGL(encrypt_2048, dim3((unsigned)count), dim3(NT), 0, (hipStream_t)stream, slots, seeds, s_hat, ct_out,
+                       make_tables(c, c->d_tw2, c->dev_q), make_tables(c, c->d_tw2p, c->dev_p), c->d_slot_to_idx, cdf, c->qbits,
+                       make_ulonglong2(c->delta, c->delta_s));
+    return (int)hipGetLastError();
+}
+int launch_decrypt_2048(const gala_ctx *c, void *stream, const u64 *s_hat, const u64 *ct_in, int count, u64 *slots) {
+    if (!count) return 0;
+    u64 inv = c->q;                                   // Newton's iteration for q^-1 mod 2^64 (q is odd)
+    for (int i = 0; i < 6; ++i) inv *= 2 - c->q * inv;
+    hipLaunchKernelGGL(decrypt_2048, dim3((unsigned)count), dim3(NT), 0, (hipStream_t)stream, ct_in, s_hat, slots,
+                       make_tables(c, c->d_tw2, c->dev_q), make_tables(c, c->d_tw2p, c->dev_p), c->d_slot_to_idx, inv);
     return (int)hipGetLastError();
 }
 
