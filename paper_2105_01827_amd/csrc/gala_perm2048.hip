@@ -1017,14 +1017,25 @@ __global__ __launch_bounds__(NT) void hstperm_special_2048(const u64 *ct_in, con
     }
 }
 
-// out[item] = sum over the first `used` partial ciphertexts of the item (mod q); one thread per word pair
-__global__ void sum_partials_kernel(const u64 *partial, int slots, int used, u64 *out, size_t words, u64 q) {
-    const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (id >= words) return;
+// out[item] = sum over the first `used` partial ciphertexts of the item (mod q).  A workgroup owns 64 consecutive
+// words; its SG wavefronts each add every SG-th partial (independent loads, several in flight) and the SG sums
+// meet in LDS: with one input and a few hundred partials a single thread per word would wait for them one by one.
+template <int SG>
+__global__ __launch_bounds__(64 * SG) void sum_partials_kernel(const u64 *partial, int slots, int used, u64 *out, size_t words,
+                                                               u64 q) {
+    __shared__ u64 red[SG][64];
+    const int lane = threadIdx.x & 63, sg = threadIdx.x >> 6;
+    const size_t id = (size_t)blockIdx.x * 64 + lane;          // words is a multiple of 2N, so of 64
     const size_t item = id / (2 * N), e = id % (2 * N);
     const u64 *src = partial + item * slots * 2 * N + e;
     u64 acc = 0;
-    for (int s = 0; s < used; ++s) acc = add_mod(acc, src[(size_t)s * 2 * N], q);
+#pragma unroll 4
+    for (int s = sg; s < used; s += SG) acc = add_mod(acc, src[(size_t)s * 2 * N], q);
+    red[sg][lane] = acc;
+    __syncthreads();
+    if (sg) return;
+#pragma unroll
+    for (int g = 1; g < SG; ++g) acc = add_mod(acc, red[g][lane], q);
     out[id] = acc;
 }
 
@@ -1093,8 +1104,13 @@ int launch_perm_accumulate_2048_masked(const gala_ctx *c, void *stream, const Pe
     if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used++ + 1], st);
     if (rc) return rc;
     const size_t words = (size_t)job.items * 2 * N;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, job.partial, job.slots,
-                       job.nchunks + 1, fin.ct_out, words, c->q);
+    // many partials of few items: more wavefronts per word
+    if (job.nchunks + 1 > 64 && words / 64 < 2048)
+        hipLaunchKernelGGL(sum_partials_kernel<16>, dim3((unsigned)(words / 64)), dim3(1024), 0, st, job.partial, job.slots,
+                           job.nchunks + 1, fin.ct_out, words, c->q);
+    else
+        hipLaunchKernelGGL(sum_partials_kernel<4>, dim3((unsigned)(words / 64)), dim3(256), 0, st, job.partial, job.slots,
+                           job.nchunks + 1, fin.ct_out, words, c->q);
     return (int)hipGetLastError();
 }
 
