@@ -184,7 +184,7 @@ def resnet18_workload(ctx, sk, H, torch, args):
         plan = ctx.conv_plan(K, t.tile_h, t.tile_w)
         gk = ctx.galois_keygen(sk, plan.rotations(), seed=8)
         plan.bind(gk)
-        if 2 * t.tiles >= 8:
+        if t.tiles >= 2:
             plan.prepare_batched()
         d_in = H.to_dev(rng.integers(0, par.q, size=(t.tiles * plan.nin, 2 * par.n), dtype=np.uint64))
         d_out = H.dev_empty(t.tiles * plan.nout * 2 * par.n)

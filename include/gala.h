@@ -245,7 +245,7 @@ int gala_conv_plan_create(gala_ctx *ctx, const uint64_t *K, int c_o, int c_i, in
 void gala_conv_plan_destroy(gala_conv_plan *plan);
 /* Optional, offline: also keeps the encoded kernels as base-256 digit planes so that gala_he_conv
  * runs its ScMult/Add step (a dense per-coefficient matrix product, Sec. III-B) on the matrix cores
- * whenever a call brings at least 4 inputs.  Costs about 1.3x the plan's device memory again;
+ * whenever a call brings at least 2 inputs.  Costs about 1.3x the plan's device memory again;
  * results are bit-identical either way.  Needs n >= 16. */
 int gala_conv_plan_prepare_batched(gala_conv_plan *plan);
 /* geometry[0..5] = T, c_n, input ciphertexts per image, output ciphertexts, taps, terms: the (input ciphertext,

@@ -75,7 +75,7 @@ def gpu_conv_layer(ctx, sk, K, image, r_layer, stride, mask_seed, key_seed=8, en
     gk = ctx.galois_keygen(sk, plan.rotations(), seed=key_seed)
     plan.bind(gk)
     tiles = t.tiles
-    if matrix_cores and tiles >= 4:
+    if matrix_cores and tiles >= 2:
         plan.prepare_batched()
     x_tiles = np.stack([ctx.tile_extract(t, image, b) for b in range(tiles)])
     r_tiles = np.stack([ctx.tile_mask(t, r_layer, b) for b in range(tiles)])

@@ -355,6 +355,18 @@ def test_he_conv_skips_zero_terms_n2048():
         assert plan.nterm == 6 * 2 + 2      # (decryption to the plain result needs the special prime at this size)
 
 
+@pytest.mark.parametrize("batch", [2, 3])
+def test_he_conv_two_and_three_inputs_on_matrix_cores_n2048(batch):
+    """4 and 6 columns of the 16-column tile: the smallest calls that take the matrix-core multiply-accumulate
+    (a single input goes to the streaming kernel), every output ciphertext of the first and the last input."""
+    par = wl.DEFAULT
+    shape = (24, 16, 3, 3, 16, 16)                        # c_n = 8: two input and three output ciphertexts
+    picks = [(b, O) for b in (0, batch - 1) for O in range(3)]
+    ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, shape, batch, picks, seed=batch, matrix_cores=True)
+    assert plan.cn == 8 and plan.nin == 2 and plan.nout == 3
+    assert cnt["scmult"] == batch * 3 * 8 * 18
+
+
 @pytest.mark.parametrize("c_o,c_i,u", [(6, 4, 23), (70, 2, 24), (130, 2, 32)])
 def test_he_conv_single_input_n2048(c_o, c_i, u):
     """One input at n = 2048 (c_n = 2): the streaming multiply-accumulate with 6, 70 and 130 rows (row tiles of 1,
