@@ -1039,6 +1039,17 @@ __global__ __launch_bounds__(64 * SG) void sum_partials_kernel(const u64 *partia
     out[id] = acc;
 }
 
+// the same with one thread per word, for a handful of partials
+__global__ void sum_few_partials_kernel(const u64 *partial, int slots, int used, u64 *out, size_t words, u64 q) {
+    const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= words) return;
+    const size_t item = id / (2 * N), e = id % (2 * N);
+    const u64 *src = partial + item * slots * 2 * N + e;
+    u64 acc = 0;
+    for (int s = 0; s < used; ++s) acc = add_mod(acc, src[(size_t)s * 2 * N], q);
+    out[id] = acc;
+}
+
 }  // namespace
 
 static Tables2048 make_tables(const gala_ctx *c, const u64 *blocks, const NttDev &dev) {
@@ -1105,7 +1116,10 @@ int launch_perm_accumulate_2048_masked(const gala_ctx *c, void *stream, const Pe
     if (rc) return rc;
     const size_t words = (size_t)job.items * 2 * N;
     // many partials of few items: more wavefronts per word
-    if (job.nchunks + 1 > 64 && words / 64 < 2048)
+    if (job.nchunks + 1 <= 8)
+        hipLaunchKernelGGL(sum_few_partials_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, job.partial, job.slots,
+                           job.nchunks + 1, fin.ct_out, words, c->q);
+    else if (job.nchunks + 1 > 64 && words / 64 < 2048)
         hipLaunchKernelGGL(sum_partials_kernel<16>, dim3((unsigned)(words / 64)), dim3(1024), 0, st, job.partial, job.slots,
                            job.nchunks + 1, fin.ct_out, words, c->q);
     else
