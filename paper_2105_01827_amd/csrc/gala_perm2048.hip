@@ -748,6 +748,9 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
                                                                       int gadget_bits, int ndigits) {
     __shared__ u64 bufA[LDS_WORDS], bufB[LDS_WORDS];
     __shared__ u64 stash[N];
+    // Sums of the lifted remainders (coefficient domain modulo q, canonical, index tid + 256k): 15 of a thread's 16
+    // words live in LDS slots of its own (no barrier), which is what two workgroups per CU leave room for.
+    __shared__ u64 Rl[15 * NT];
     const int tid = threadIdx.x;
     if ((int)blockIdx.x >= job.items * job.nchunks) {   // only launched when mj.enabled
         mask_role(job, T, mj, (int)blockIdx.x - job.items * job.nchunks, bufA, bufB);
@@ -762,9 +765,11 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
     const size_t key_pairs = (size_t)ndigits * 4 * N;
 
     u64 sum0[PER], sum1[PER];   // evaluation domain modulo q, below 8q between products
-    u64 R0[PER], R1[PER];       // coefficient domain modulo q, canonical, index tid + 256k
+    u64 Rlast = 0;              // the sixteenth word of the remainder sums
 #pragma unroll
-    for (int k = 0; k < PER; ++k) sum0[k] = sum1[k] = R0[k] = R1[k] = 0;
+    for (int k = 0; k < PER; ++k) sum0[k] = sum1[k] = 0;
+#pragma unroll
+    for (int s = 0; s < 15; ++s) Rl[s * NT + tid] = 0;
 
     for (int g = g0; g < g1; ++g) {
         const u64 *c0 = job.ct_in + (size_t)item * job.in_item_stride + (size_t)g * job.in_g_stride;
@@ -890,7 +895,12 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
 #pragma unroll
             for (int k = 0; k < PER; ++k) {
                 const u64 r = csub_dev(a[k], T.mod.q);
-                if (h) R1[k] = csub_dev(R1[k] + r, T.mod.q); else R0[k] = csub_dev(R0[k] + r, T.mod.q);
+                if (h && k == PER - 1) {
+                    Rlast = csub_dev(Rlast + r, T.mod.q);
+                } else {
+                    u64 *slot = Rl + (h * PER + k) * NT + tid;
+                    *slot = csub_dev(*slot + r, T.mod.q);
+                }
             }
         }
     }
@@ -900,7 +910,7 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
     for (int h = 0; h < 2; ++h) {
         u64 a[PER];
 #pragma unroll
-        for (int k = 0; k < PER; ++k) a[k] = h ? R1[k] : R0[k];
+        for (int k = 0; k < PER; ++k) a[k] = (h && k == PER - 1) ? Rlast : Rl[(h * PER + k) * NT + tid];
         forward_to_lds(a, bufA, bufB, T, tid);
 #pragma unroll
         for (int k = 0; k < PER; ++k) {
