@@ -37,41 +37,50 @@ __device__ __forceinline__ int galois_index11(int i, int gal) {
 // v_mad_u64_u32 (32x32 + 64 -> 64 with carry-out) issues at the full VALU rate, so everything is built
 // from it.  The compiler's own lowering of 64x64 products spends a quarter of its instructions on
 // register moves; the sequences below are written out so that it cannot re-associate them.
+// CM = true writes the multiply-adds in C instead: the compiler then knows the instruction and leaves out the wait
+// state it puts after every inline-asm result, at the price of choosing the registers and the order itself.  The
+// special-prime kernels are faster that way, the one-prime kernels are not.
+template <bool CM = false>
 __device__ __forceinline__ u64 mad_u64(u32 a, u32 b, u64 c) {
+    if (CM) return (u64)a * b + c;
     u64 r, carry;
     asm("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(r), "=s"(carry) : "v"(a), "v"(b), "v"(c));
     return r;
 }
+template <bool CM = false>
 __device__ __forceinline__ u64 mul_u64(u32 a, u32 b) {
+    if (CM) return (u64)a * b;
     u64 r, carry;
     asm("v_mad_u64_u32 %0, %1, %2, %3, 0" : "=v"(r), "=s"(carry) : "v"(a), "v"(b));
     return r;
 }
 // high 64 bits of y*s in 6 instructions: with A1 = hi32(y0 s0), B = y0 s1 + A1 and
 // S = y1 s0 + B (65 bits: C plus the carry-out), the result is y1 s1 + floor(S / 2^32).
+template <bool CM = false>
 __device__ __forceinline__ u64 mulhi64_dev(u64 y, u64 s) {
     const u32 y0 = (u32)y, y1 = (u32)(y >> 32), s0 = (u32)s, s1 = (u32)(s >> 32);
-    const u64 B = mad_u64(y0, s1, (u64)__umulhi(y0, s0));
+    const u64 B = mad_u64<CM>(y0, s1, (u64)__umulhi(y0, s0));
     u64 C, carry;
     asm("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(C), "=s"(carry) : "v"(y1), "v"(s0), "v"(B));
     u32 top;
     asm("v_cndmask_b32_e64 %0, 0, 1, %1" : "=v"(top) : "s"(carry));
-    return mad_u64(y1, s1, ((u64)top << 32) | (u32)(C >> 32));
+    return mad_u64<CM>(y1, s1, ((u64)top << 32) | (u32)(C >> 32));
 }
 // negated modulus split in two VGPR words, set up once per kernel
 struct NegQ { u32 lo, hi; };
 // y*w mod q up to one extra q (a value in [0,2q)) for any 64-bit y, w a constant with companion ws:
 // y*w - h*q = y*w + h*(-q) mod 2^64 as one chain for the low word and one for the high word.
+template <bool CM = false>
 __device__ __forceinline__ u64 mul_const(u64 y, u64 w, u64 ws, NegQ nq) {
-    const u64 h = mulhi64_dev(y, ws);
+    const u64 h = mulhi64_dev<CM>(y, ws);
     const u32 y0 = (u32)y, y1 = (u32)(y >> 32), w0 = (u32)w, w1 = (u32)(w >> 32);
     const u32 h0 = (u32)h, h1 = (u32)(h >> 32);
-    u64 u = mul_u64(y0, w1);          // only the low word of this chain is used
-    u = mad_u64(y1, w0, u);
-    u = mad_u64(h0, nq.hi, u);
-    u = mad_u64(h1, nq.lo, u);
-    u64 t = mul_u64(y0, w0);
-    t = mad_u64(h0, nq.lo, t);
+    u64 u = mul_u64<CM>(y0, w1);          // only the low word of this chain is used
+    u = mad_u64<CM>(y1, w0, u);
+    u = mad_u64<CM>(h0, nq.hi, u);
+    u = mad_u64<CM>(h1, nq.lo, u);
+    u64 t = mul_u64<CM>(y0, w0);
+    t = mad_u64<CM>(h0, nq.lo, t);
     u32 hi;
     asm("v_add_u32 %0, %1, %2" : "=v"(hi) : "v"((u32)(t >> 32)), "v"((u32)u));
     return ((u64)hi << 32) | (u32)t;
@@ -89,16 +98,18 @@ __device__ __forceinline__ u64 csub_dev(u64 x, u64 c) {
 }
 
 // x,y -> x + w*y, x - w*y + 2q  without any correction (bound grows by 2q per stage)
+template <bool CM = false>
 __device__ __forceinline__ void bf_fwd(u64 &x, u64 &y, const ulonglong2 t, NegQ nq, u64 q2) {
-    const u64 v = mul_const(y, t.x, t.y, nq);
+    const u64 v = mul_const<CM>(y, t.x, t.y, nq);
     y = x - v + q2;
     x = x + v;
 }
 // x,y in [0,2q) -> x + y (below 2q), (x - y)*w (below 2q)
+template <bool CM = false>
 __device__ __forceinline__ void bf_inv(u64 &x, u64 &y, const ulonglong2 t, NegQ nq, u64 q2) {
     const u64 s = x + y, d = x - y + q2;
     x = csub_dev(s, q2);
-    y = mul_const(d, t.x, t.y, nq);
+    y = mul_const<CM>(d, t.x, t.y, nq);
 }
 
 // The seven constants one thread needs for a radix-8 pass on index bits B..B+2 are tw[T], tw[2T], tw[2T+1],
@@ -130,38 +141,39 @@ __device__ __forceinline__ Tw7 tw_level(const ulonglong2 *__restrict__ table, un
     for (int e = 0; e < 7; ++e) w.t[e] = *reinterpret_cast<const ulonglong2 *>(level + (size_t)(e * COUNT * 16) + off);
     return w;
 }
-template <bool FIRST, bool CORRECT>
+template <bool FIRST, bool CORRECT, bool CM = false>
 __device__ __forceinline__ void fwd_pass(u64 (&a)[8], const Tw7 &w, NegQ q, u64 q2) {
     if (FIRST) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) bf_fwd(a[k], a[k + 4], w.t[0], q, q2);
+        for (int k = 0; k < 4; ++k) bf_fwd<CM>(a[k], a[k + 4], w.t[0], q, q2);
     }
     if (CORRECT) {   // seven stages done: everything is below 15q, bring it below 8q
         const u64 q8 = 4 * q2;
 #pragma unroll
         for (int k = 0; k < 8; ++k) a[k] = csub_dev(a[k], q8);
     }
-    bf_fwd(a[0], a[2], w.t[1], q, q2);
-    bf_fwd(a[1], a[3], w.t[1], q, q2);
-    bf_fwd(a[4], a[6], w.t[2], q, q2);
-    bf_fwd(a[5], a[7], w.t[2], q, q2);
-    bf_fwd(a[0], a[1], w.t[3], q, q2);
-    bf_fwd(a[2], a[3], w.t[4], q, q2);
-    bf_fwd(a[4], a[5], w.t[5], q, q2);
-    bf_fwd(a[6], a[7], w.t[6], q, q2);
+    bf_fwd<CM>(a[0], a[2], w.t[1], q, q2);
+    bf_fwd<CM>(a[1], a[3], w.t[1], q, q2);
+    bf_fwd<CM>(a[4], a[6], w.t[2], q, q2);
+    bf_fwd<CM>(a[5], a[7], w.t[2], q, q2);
+    bf_fwd<CM>(a[0], a[1], w.t[3], q, q2);
+    bf_fwd<CM>(a[2], a[3], w.t[4], q, q2);
+    bf_fwd<CM>(a[4], a[5], w.t[5], q, q2);
+    bf_fwd<CM>(a[6], a[7], w.t[6], q, q2);
 }
 // Radix-8 inverse pass (bit 0 of k first), same block layout on the inverse table.
+template <bool CM = false>
 __device__ __forceinline__ void inv_pass(u64 (&a)[8], const Tw7 &w, NegQ q, u64 q2) {
-    bf_inv(a[0], a[1], w.t[3], q, q2);
-    bf_inv(a[2], a[3], w.t[4], q, q2);
-    bf_inv(a[4], a[5], w.t[5], q, q2);
-    bf_inv(a[6], a[7], w.t[6], q, q2);
-    bf_inv(a[0], a[2], w.t[1], q, q2);
-    bf_inv(a[1], a[3], w.t[1], q, q2);
-    bf_inv(a[4], a[6], w.t[2], q, q2);
-    bf_inv(a[5], a[7], w.t[2], q, q2);
+    bf_inv<CM>(a[0], a[1], w.t[3], q, q2);
+    bf_inv<CM>(a[2], a[3], w.t[4], q, q2);
+    bf_inv<CM>(a[4], a[5], w.t[5], q, q2);
+    bf_inv<CM>(a[6], a[7], w.t[6], q, q2);
+    bf_inv<CM>(a[0], a[2], w.t[1], q, q2);
+    bf_inv<CM>(a[1], a[3], w.t[1], q, q2);
+    bf_inv<CM>(a[4], a[6], w.t[2], q, q2);
+    bf_inv<CM>(a[5], a[7], w.t[2], q, q2);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) bf_inv(a[k], a[k + 4], w.t[0], q, q2);
+    for (int k = 0; k < 4; ++k) bf_inv<CM>(a[k], a[k + 4], w.t[0], q, q2);
 }
 
 // Store the 8 registers at index(k) = base_out | (k << SH_OUT), barrier, load index(k) = base_in | (k << SH_IN).
@@ -196,21 +208,22 @@ __device__ __forceinline__ int fresh(int tid) {
 
 // Forward transform of the 8 registers (ownership t + 256k, values below q); the result is left in
 // LDS buffer `res` (natural index, padded), values below 16q.  LDS phases: other, res, other, res.
+template <bool CM = false>
 __device__ __forceinline__ void forward_to_lds(u64 (&a)[8], u64 *res, u64 *other, const Tables2048 &T, int tid_) {
     const int tid = fresh(tid_);
     const NegQ q = T.nq;
     const u64 q2 = T.mod.q2;
     Tw7 w = tw_level<1>(T.tw, 0);
-    fwd_pass<true, false>(a, w, q, q2);                                              // bits 8-10
+    fwd_pass<true, false, CM>(a, w, q, q2);                                              // bits 8-10
     w = tw_level<8>(T.tw, (unsigned)tid >> 5);
     exchange<8, 5>(a, other, tid, ((tid >> 5) << 8) | (tid & 31));
-    fwd_pass<true, false>(a, w, q, q2);                                              // bits 5-7
+    fwd_pass<true, false, CM>(a, w, q, q2);                                              // bits 5-7
     w = tw_level<64>(T.tw, (unsigned)tid >> 2);
     exchange<5, 2>(a, res, ((tid >> 5) << 8) | (tid & 31), ((tid >> 2) << 5) | (tid & 3));
-    fwd_pass<true, true>(a, w, q, q2);                                               // bits 2-4
+    fwd_pass<true, true, CM>(a, w, q, q2);                                               // bits 2-4
     w = tw_level<256>(T.tw, (unsigned)tid);
     exchange<2, 0>(a, other, ((tid >> 2) << 5) | (tid & 3), tid << 3);
-    fwd_pass<false, false>(a, w, q, q2);                                             // bits 0-1
+    fwd_pass<false, false, CM>(a, w, q, q2);                                             // bits 0-1
     u64 *po = res + pad(tid << 3);
 #pragma unroll
     for (int k = 0; k < 8; ++k) po[k] = a[k];
@@ -219,30 +232,31 @@ __device__ __forceinline__ void forward_to_lds(u64 (&a)[8], u64 *res, u64 *other
 
 // Inverse transform: registers hold index 8t + k (values below 2q) on entry and index t + 256k,
 // canonical, on return.
+template <bool CM = false>
 __device__ __forceinline__ void inverse_in_regs(u64 (&a)[8], u64 *bufA, u64 *bufB, const Tables2048 &T, int tid_) {
     const int tid = fresh(tid_);
     const NegQ q = T.nq;
     const u64 q2 = T.mod.q2;
     Tw7 w = tw_level<256>(T.itw, (unsigned)tid);
-    inv_pass(a, w, q, q2);                                                           // bits 0-2
+    inv_pass<CM>(a, w, q, q2);                                                           // bits 0-2
     w = tw_level<32>(T.itw, (unsigned)tid >> 3);
     exchange<0, 3>(a, bufA, tid << 3, ((tid >> 3) << 6) | (tid & 7));
-    inv_pass(a, w, q, q2);                                                           // bits 3-5
+    inv_pass<CM>(a, w, q, q2);                                                           // bits 3-5
     w = tw_level<4>(T.itw, (unsigned)tid >> 6);
     exchange<3, 6>(a, bufB, ((tid >> 3) << 6) | (tid & 7), ((tid >> 6) << 9) | (tid & 63));
-    inv_pass(a, w, q, q2);                                                           // bits 6-8
+    inv_pass<CM>(a, w, q, q2);                                                           // bits 6-8
     const ulonglong2 t2a = T.itw[1], t2b = T.itw[2];      // level 1: constants 1 and 2 of block 1
     exchange<6, 8>(a, bufA, ((tid >> 6) << 9) | (tid & 63), tid);
     // bits 9-10 (register bits 1,2; register bit 0 is index bit 8), n^-1 folded into the last stage
-    bf_inv(a[0], a[2], t2a, q, q2);
-    bf_inv(a[1], a[3], t2a, q, q2);
-    bf_inv(a[4], a[6], t2b, q, q2);
-    bf_inv(a[5], a[7], t2b, q, q2);
+    bf_inv<CM>(a[0], a[2], t2a, q, q2);
+    bf_inv<CM>(a[1], a[3], t2a, q, q2);
+    bf_inv<CM>(a[4], a[6], t2b, q, q2);
+    bf_inv<CM>(a[5], a[7], t2b, q, q2);
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const u64 x = a[k], y = a[k + 4];
-        a[k] = csub_dev(mul_const(x + y, T.ninv.x, T.ninv.y, q), T.mod.q);
-        a[k + 4] = csub_dev(mul_const(x - y + q2, T.itw1n.x, T.itw1n.y, q), T.mod.q);
+        a[k] = csub_dev(mul_const<CM>(x + y, T.ninv.x, T.ninv.y, q), T.mod.q);
+        a[k + 4] = csub_dev(mul_const<CM>(x - y + q2, T.itw1n.x, T.itw1n.y, q), T.mod.q);
     }
 }
 
@@ -783,11 +797,11 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
                 u64 x0 = c0[i], x1 = c1[i];
                 if (HAS_W) {
                     const ulonglong2 ww = w[i];
-                    x0 = mul_const(x0, ww.x, ww.y, q);
-                    x1 = mul_const(x1, ww.x, ww.y, q);
+                    x0 = mul_const<true>(x0, ww.x, ww.y, q);
+                    x1 = mul_const<true>(x1, ww.x, ww.y, q);
                 }
-                sum0[k] = csub_dev(sum0[k] + mul_const(x0, S.Pq.x, S.Pq.y, q), q8);
-                sum1[k] = csub_dev(sum1[k] + mul_const(x1, S.Pq.x, S.Pq.y, q), q8);
+                sum0[k] = csub_dev(sum0[k] + mul_const<true>(x0, S.Pq.x, S.Pq.y, q), q8);
+                sum1[k] = csub_dev(sum1[k] + mul_const<true>(x1, S.Pq.x, S.Pq.y, q), q8);
             }
             continue;
         }
@@ -804,15 +818,15 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
                 const ulonglong2 cv = c1v[k];
                 if (HAS_W) {
                     const ulonglong2 wa = w[8 * tid + 2 * k], wb = w[8 * tid + 2 * k + 1];
-                    a[2 * k] = mul_const(cv.x, wa.x, wa.y, q);
-                    a[2 * k + 1] = mul_const(cv.y, wb.x, wb.y, q);
+                    a[2 * k] = mul_const<true>(cv.x, wa.x, wa.y, q);
+                    a[2 * k + 1] = mul_const<true>(cv.y, wb.x, wb.y, q);
                 } else {
                     a[2 * k] = cv.x;
                     a[2 * k + 1] = cv.y;
                 }
             }
         }
-        inverse_in_regs(a, bufA, bufB, T, tid);
+        inverse_in_regs<true>(a, bufA, bufB, T, tid);
 #pragma unroll
         for (int k = 0; k < PER; ++k) stash[tid + k * NT] = a[k];
         // the c0 part, times P
@@ -821,9 +835,9 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
             u64 x = c0[src[k]];
             if (HAS_W) {
                 const ulonglong2 ww = w[src[k]];
-                x = mul_const(x, ww.x, ww.y, q);
+                x = mul_const<true>(x, ww.x, ww.y, q);
             }
-            sum0[k] += mul_const(x, S.Pq.x, S.Pq.y, q);
+            sum0[k] += mul_const<true>(x, S.Pq.x, S.Pq.y, q);
         }
         int pending = 1, pendingP = 0;
         u64 tp0[PER], tp1[PER];   // this rotation's sums modulo P, below 8P between products
@@ -832,7 +846,7 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
         for (int j = 0; j < ndigits; ++j) {
 #pragma unroll
             for (int k = 0; k < PER; ++k) a[k] = (stash[tid + k * NT] >> (j * gadget_bits)) & digit_mask;
-            forward_to_lds(a, bufA, bufB, T, tid);
+            forward_to_lds<true>(a, bufA, bufB, T, tid);
             const ulonglong2 *kb = key + (size_t)(4 * j) * N, *ka = kb + N;
             if (pending == 4) {
 #pragma unroll
@@ -847,14 +861,14 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
                 const int i = tid + k * NT;
                 const u64 d = bufA[pad(src[k])];
                 const ulonglong2 b = kb[i], aa = ka[i];
-                sum0[k] += mul_const(d, b.x, b.y, q);
-                sum1[k] += mul_const(d, aa.x, aa.y, q);
+                sum0[k] += mul_const<true>(d, b.x, b.y, q);
+                sum1[k] += mul_const<true>(d, aa.x, aa.y, q);
             }
             ++pending;
             // the same digit modulo P
 #pragma unroll
             for (int k = 0; k < PER; ++k) a[k] = (stash[tid + k * NT] >> (j * gadget_bits)) & digit_mask;
-            forward_to_lds(a, bufA, bufB, S.TP, tid);
+            forward_to_lds<true>(a, bufA, bufB, S.TP, tid);
             const ulonglong2 *kbP = kb + 2 * (size_t)N, *kaP = kbP + N;
             if (pendingP == 4) {
 #pragma unroll
@@ -869,8 +883,8 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
                 const int i = tid + k * NT;
                 const u64 d = bufA[pad(src[k])];
                 const ulonglong2 b = kbP[i], aa = kaP[i];
-                tp0[k] += mul_const(d, b.x, b.y, qP);
-                tp1[k] += mul_const(d, aa.x, aa.y, qP);
+                tp0[k] += mul_const<true>(d, b.x, b.y, qP);
+                tp1[k] += mul_const<true>(d, aa.x, aa.y, qP);
             }
             ++pendingP;
         }
@@ -891,7 +905,7 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
 #pragma unroll
                 for (int k = 0; k < PER; ++k) a[k] = pi[k];
             }
-            inverse_in_regs(a, bufA, bufB, S.TP, tid);
+            inverse_in_regs<true>(a, bufA, bufB, S.TP, tid);
 #pragma unroll
             for (int k = 0; k < PER; ++k) {
                 const u64 r = csub_dev(a[k], T.mod.q);
@@ -911,14 +925,14 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
         u64 a[PER];
 #pragma unroll
         for (int k = 0; k < PER; ++k) a[k] = (h && k == PER - 1) ? Rlast : Rl[(h * PER + k) * NT + tid];
-        forward_to_lds(a, bufA, bufB, T, tid);
+        forward_to_lds<true>(a, bufA, bufB, T, tid);
 #pragma unroll
         for (int k = 0; k < PER; ++k) {
             const int i = tid + k * NT;
             const u64 x = reduce64(bufA[pad(i)], T.mod);
             const u64 t = reduce64(h ? sum1[k] : sum0[k], T.mod);
             const u64 dlt = t >= x ? t - x : t + T.mod.q - x;
-            out[h * N + i] = csub_dev(mul_const(dlt, S.Pinv.x, S.Pinv.y, q), T.mod.q);
+            out[h * N + i] = csub_dev(mul_const<true>(dlt, S.Pinv.x, S.Pinv.y, q), T.mod.q);
         }
     }
 }
