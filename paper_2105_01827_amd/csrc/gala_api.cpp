@@ -38,7 +38,7 @@ int choose_chunks(const gala_ctx *ctx, int items, int G) {
     // against 0.48 ms with 2048 workgroups and 0.58 ms with 768).
     if (forced > 0 || G < 32 || ctx->special) {
         const int c = ((forced > 0 ? forced : ctx->special ? 512 : 768) + items - 1) / items;
-        return std::max(1, std::min(c, G));
+        return std::max(1, std::min(c, G - 1));     // G-1 entries cost a key switch (chunk_range)
     }
     // a power of two (it divides the padded G, and from 8 on it keeps the XCD mapping): 1280 to 2560 workgroups,
     // halved while a workgroup would be left with a single term and a round of the chip is still filled

@@ -26,6 +26,14 @@ GALA_HD int draw_gauss_cdf(const GaussCdf &cdf, u64 seed, u64 stream, u64 idx) {
     return x;
 }
 
+// Entries g0 .. g1-1 of a rotate-and-accumulate sum that chunk `chunk` of `nchunks` takes.  The first entry is the
+// rotation by zero in he_fc and he_conv (a ScMult and no key switch): it rides with chunk 0, and the G-1 entries
+// after it are spread evenly, so that no workgroup is launched for the cheap entry alone.
+GALA_HD void chunk_range(int chunk, int nchunks, int G, int &g0, int &g1) {
+    g0 = chunk ? 1 + (int)((long)chunk * (G - 1) / nchunks) : 0;
+    g1 = 1 + (int)((long)(chunk + 1) * (G - 1) / nchunks);
+}
+
 // ---------------------------------------------------------------------------
 // Negacyclic number-theoretic transform tables for one modulus.
 // Forward: natural-order coefficients -> values a(psi^(2*brev(i)+1)) at index i.

@@ -125,7 +125,8 @@ __global__ __launch_bounds__(NT) void perm_accumulate_kernel(PermJob job, NttDev
     extern __shared__ u64 buf[];
     const int tid = threadIdx.x;
     const int item = blockIdx.x / job.nchunks, chunk = blockIdx.x % job.nchunks;
-    const int g0 = (int)((long)chunk * job.G / job.nchunks), g1 = (int)((long)(chunk + 1) * job.G / job.nchunks);
+    int g0, g1;
+    chunk_range(chunk, job.nchunks, job.G, g0, g1);
     const u64 q = T.mod.q, q2 = T.mod.q2;
     const u64 digit_mask = (1ull << gadget_bits) - 1;
     constexpr int POLYS = SPECIAL ? 4 : 2;

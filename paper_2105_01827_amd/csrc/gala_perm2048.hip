@@ -381,7 +381,8 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
     }
     int item, chunk;
     item_and_chunk(job, item, chunk);
-    const int g0 = (int)((long)chunk * job.G / job.nchunks), g1 = (int)((long)(chunk + 1) * job.G / job.nchunks);
+    int g0, g1;
+    chunk_range(chunk, job.nchunks, job.G, g0, g1);
     const NegQ q = T.nq;
     const u64 q8 = 8 * T.mod.q;
     const u64 digit_mask = (1ull << gadget_bits) - 1;
@@ -772,7 +773,8 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
     }
     int item, chunk;
     item_and_chunk(job, item, chunk);
-    const int g0 = (int)((long)chunk * job.G / job.nchunks), g1 = (int)((long)(chunk + 1) * job.G / job.nchunks);
+    int g0, g1;
+    chunk_range(chunk, job.nchunks, job.G, g0, g1);
     const NegQ q = T.nq, qP = S.TP.nq;
     const u64 q8 = 8 * T.mod.q, P8 = 8 * S.TP.mod.q;
     const u64 digit_mask = (1ull << gadget_bits) - 1;
