@@ -365,7 +365,7 @@ def main():
             roof = {"bound": "hbm", "kernel": "conv_mfma_kernel", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
                     # HBM bytes per launch from rocprofv3 counters (profiles/he_conv_16x16x128_3x3x128_b16_hbm_traffic.txt)
-                    "traffic": (450327 + 73728) * 1024.0 if not args.special_prime else None, "kernel_ms_avg": kavg_ms,
+                    "traffic": (442524 + 66449) * 1024.0 if not args.special_prime else None, "kernel_ms_avg": kavg_ms,
                     "units_per_launch": macs, "bytes_per_unit": alg_bytes / macs,
                     "int8_mfma_top_s": macs * 64 * 2 / (kavg_ms * 1e-3) / 1e12}
             ops, unit_ops, kernel, units, traffic = 0, 0, "conv_mfma_kernel", macs, None

@@ -339,15 +339,20 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
         if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used + end], (hipStream_t)stream);
         if (timed && end) ++c->prof_used;
     };
+    // With a mask to subtract the sums go to the n = 2048 Perm kernel, which reads the product's own blocks of eight
+    // coefficients: no transposition pass in between.
+    const bool in8 = ws.mfma && fast_hoist && !c->special && r != nullptr;
+    const u64 *perm_in = acc;
     if (ws.mfma && fast_hoist && !c->special) {
         // the rotated inputs go straight into the column image of the matrix-core product
         u64 *xl = (u64 *)(base + ws.xl), *tmp = (u64 *)(base + ws.tmp);
         if (launch_hstperm_pack_2048(c, stream, ct_in, digits, batch, terms, rotates, keys2, xl))
             return GALA_EHIP;
         mark(0);
-        if (launch_conv_mfma(c, stream, pl->d_wl, xl, batch, groups, nterm, tmp)) return GALA_EHIP;
+        if (launch_conv_mfma(c, stream, pl->d_wl, xl, batch, groups, nterm, tmp, in8)) return GALA_EHIP;
         mark(1);
-        if (launch_conv_untranspose(c, stream, tmp, batch, groups, acc)) return GALA_EHIP;
+        if (in8) perm_in = tmp;
+        else if (launch_conv_untranspose(c, stream, tmp, batch, groups, acc)) return GALA_EHIP;
     } else {
         if (hoist_terms(c, stream, ct_in, batch, terms, rotates, keys, keys2, digits, xrot)) return GALA_EHIP;
         if (ws.mfma) {
@@ -365,9 +370,18 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
     }
     // 3. Perm second: rotate each kernel order into place and add, then subtract the mask
     PermJob job{};
-    job.ct_in = acc;
+    job.ct_in = perm_in;
     job.in_item_stride = (size_t)pl->cn * 2 * n;
     job.in_g_stride = 2 * (size_t)n;
+    if (in8) {
+        int mt, nt, kb;
+        conv_mfma_geometry(groups, 2 * batch, nterm, &mt, &nt, &kb);
+        const size_t rowsP = (size_t)mt * 16, colsP = (size_t)nt * 16;
+        job.in8_S = rowsP * colsP * 8;                       // the next eight coefficients
+        job.in_g_stride = colsP * 8;                         // the next row of the product
+        job.in8_o_stride = (size_t)pl->cn * colsP * 8;       // the rows of the next output ciphertext
+        job.in8_nout = pl->nout;
+    }
     job.w = nullptr;
     job.gal = pl->d_grp_gal; job.key_idx = pl->d_grp_key;
     job.keys = keys;

@@ -124,15 +124,18 @@ __device__ __forceinline__ u128 recombine(const int (&c)[15]) {
 // operand (rotated inputs) of a term block is staged once in LDS and read by all wavefronts; every wavefront
 // streams its own row operand (encoded kernels) from memory, so each operand byte is fetched once per
 // workgroup.  Loads of the next term block are issued before the MFMAs of the current one.
-// Output: tmp[i][row][column] (rows and columns padded to tiles), transposed afterwards.
-template <int WAVES>
+// Output: tmp[i][row][column] (rows and columns padded to tiles), transposed afterwards; or, BLK8, in blocks of
+// eight coefficients tmp[i/8][row][column][i%8], which the n = 2048 Perm kernel reads as they are (a thread's eight
+// consecutive coefficients of c0 and of c1 are the two halves of one 128-byte line).
+template <int WAVES, bool BLK8 = false>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void conv_mfma_kernel(const v4i *wl, const v4i *xl, u64 *tmp, int mtiles,
                                                                int ntiles, int kblocks, int nblk16, int n, Modulus mod) {
     constexpr int NT = 64 * WAVES, BLOADS = 1024 / NT;
     __shared__ v4i bsm[2][2][8][64];     // [buffer][column tile][digit][lane], 32 KiB
     // the wavefront's number is the same in all its lanes: kept in a scalar register, with everything derived from it
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const size_t i = blockIdx.x;
+    // BLK8: eight consecutive coefficients are handled by workgroups 8 apart, which run on the same XCD
+    const size_t i = BLK8 ? (size_t)(blockIdx.x & 7) * (n >> 3) + (blockIdx.x >> 3) : (size_t)blockIdx.x;
     const int mt = blockIdx.y * WAVES + wave, nt0 = blockIdx.z * 2;
     const bool live = mt < mtiles;
     const int mtc = live ? mt : mtiles - 1;
@@ -200,7 +203,8 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void conv_mfma_kernel(const 
             for (int k = 0; k < 15; ++k) c[k] = s[t][k][r];
             const u64 val = reduce128(recombine(c), mod);
             const int m = mt * 16 + 4 * (lane >> 4) + r, col = (nt0 + t) * 16 + (lane & 15);
-            tmp[(i * rowsP + m) * colsP + col] = val;
+            if (BLK8) tmp[(((i >> 3) * rowsP + m) * colsP + col) * 8 + (i & 7)] = val;
+            else tmp[(i * rowsP + m) * colsP + col] = val;
         }
     }
 }
@@ -245,14 +249,19 @@ int launch_limb_pack(const gala_ctx *c, void *stream, const u64 *src, int mode, 
     return (int)hipGetLastError();
 }
 int launch_conv_mfma(const gala_ctx *c, void *stream, const u64 *wl, const u64 *xl, int batch, int groups, int nterm,
-                     u64 *tmp) {
+                     u64 *tmp, bool blocks_of_eight) {
     int mtiles, ntiles, kblocks;
     conv_mfma_geometry(groups, 2 * batch, nterm, &mtiles, &ntiles, &kblocks);
     constexpr int WAVES = 4;
     const dim3 grid((unsigned)c->n, (unsigned)((mtiles + WAVES - 1) / WAVES), (unsigned)((ntiles + 1) / 2));
-    hipLaunchKernelGGL(conv_mfma_kernel<WAVES>, grid, dim3(64 * WAVES), 0, (hipStream_t)stream,
-                       reinterpret_cast<const v4i *>(wl), reinterpret_cast<const v4i *>(xl), tmp, mtiles, ntiles, kblocks,
-                       (nterm + 15) / 16, c->n, c->dev_q.mod);
+    if (blocks_of_eight)
+        hipLaunchKernelGGL((conv_mfma_kernel<WAVES, true>), grid, dim3(64 * WAVES), 0, (hipStream_t)stream,
+                           reinterpret_cast<const v4i *>(wl), reinterpret_cast<const v4i *>(xl), tmp, mtiles, ntiles, kblocks,
+                           (nterm + 15) / 16, c->n, c->dev_q.mod);
+    else
+        hipLaunchKernelGGL(conv_mfma_kernel<WAVES>, grid, dim3(64 * WAVES), 0, (hipStream_t)stream,
+                           reinterpret_cast<const v4i *>(wl), reinterpret_cast<const v4i *>(xl), tmp, mtiles, ntiles, kblocks,
+                           (nterm + 15) / 16, c->n, c->dev_q.mod);
     return (int)hipGetLastError();
 }
 int launch_conv_untranspose(const gala_ctx *c, void *stream, const u64 *tmp, int batch, int groups, u64 *acc) {

@@ -234,6 +234,11 @@ struct PermJob {
     const u64 *keys;
     const u64 *w2, *keys2;   // (value, companion) pair images of w and keys (n = 2048 kernel only)
     const int *in_g_index;   // optional: rotation g reads input number in_g_index[g] instead of g
+    // n = 2048 kernel only, in8_S != 0: the inputs are the matrix-core product's sums in blocks of eight coefficients,
+    // word (i/8)*in8_S + i%8 of a polynomial, c1 eight words after c0; item = b*in8_nout + O starts at
+    // ct_in + O*in8_o_stride + 16*b and rotation g in_g_stride words further.
+    size_t in8_S, in8_o_stride;
+    int in8_nout;
     int G, items, nchunks;
     int slots;               // partial ciphertexts reserved per item (>= nchunks)
     u64 *partial;            // items x slots x 2n
@@ -286,8 +291,9 @@ bool uses_fast_hoist(const gala_ctx *ctx);
 int launch_hoist_taps_2048(const gala_ctx *ctx, void *stream, const u64 *ct_in, int batch, const TermList &terms,
                            bool any_rotation, const u64 *keys2, u64 *digits, u64 *xrot);
 size_t conv_mfma_tmp_bytes(int n, int mtiles, int ntiles);
+// blocks_of_eight: tmp[(i/8)][row][column][i%8] instead of tmp[i][row][column] (what PermJob::in8_S describes)
 int launch_conv_mfma(const gala_ctx *ctx, void *stream, const u64 *wl, const u64 *xl, int batch, int groups,
-                     int nterm, u64 *tmp);
+                     int nterm, u64 *tmp, bool blocks_of_eight = false);
 int launch_conv_untranspose(const gala_ctx *ctx, void *stream, const u64 *tmp, int batch, int groups, u64 *acc);
 int launch_hstperm_pack_2048(const gala_ctx *ctx, void *stream, const u64 *ct_in, u64 *digits, int batch,
                              const TermList &terms, bool any_rotation, const u64 *keys2, u64 *xl);

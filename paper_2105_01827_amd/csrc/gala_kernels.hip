@@ -960,6 +960,7 @@ int launch_finalize(const gala_ctx *c, void *stream, const FinalizeJob &job) {
 }
 int launch_perm_finalize(const gala_ctx *c, void *stream, const PermJob &job, const FinalizeJob &fin) {
     if (uses_fast_perm(c) && fin.r && job.slots > job.nchunks) return launch_perm_accumulate_2048_masked(c, stream, job, fin);
+    if (job.in8_S) return (int)hipErrorInvalidValue;     // only the n = 2048 kernel reads blocks of eight
     const int rc = launch_perm_accumulate(c, stream, job);
     return rc ? rc : launch_finalize(c, stream, fin);
 }

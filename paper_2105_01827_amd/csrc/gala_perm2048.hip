@@ -369,7 +369,8 @@ __device__ __forceinline__ void item_and_chunk(const PermJob &job, int &item, in
 // quotient (twiddles, encoded weights, key polynomials), so sums of products stay in 64-bit
 // registers: each product is below 2q, a running sum is kept below 8q and may take four more
 // products before one conditional subtraction of 8q.
-template <bool HAS_W>
+// IN8: the inputs lie in blocks of eight coefficients (PermJob::in8_S), as the matrix-core product leaves them.
+template <bool HAS_W, bool IN8 = false>
 __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables2048 T, MaskJob mj, int gadget_bits,
                                                            int ndigits) {
     __shared__ u64 bufA[LDS_WORDS], bufB[LDS_WORDS];
@@ -393,8 +394,16 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
     for (int k = 0; k < PER; ++k) sum0[k] = sum1[k] = 0;
 
     for (int g = g0; g < g1; ++g) {
-        const u64 *c0 = job.ct_in + (size_t)item * job.in_item_stride + (size_t)g * job.in_g_stride;
-        const u64 *c1 = c0 + N;
+        const u64 *c0 = IN8 ? job.ct_in + (size_t)(item % job.in8_nout) * job.in8_o_stride + (size_t)(item / job.in8_nout) * 16 +
+                                  (size_t)g * job.in_g_stride
+                            : job.ct_in + (size_t)item * job.in_item_stride + (size_t)g * job.in_g_stride;
+        const u64 *c1 = IN8 ? c0 + 8 : c0 + N;
+        const size_t S = IN8 ? job.in8_S : 0;
+        auto at = [&](const u64 *poly, int i) -> u64 { return IN8 ? poly[(size_t)(i >> 3) * S + (i & 7)] : poly[i]; };
+        // In blocks of eight a rotation's input is 256 separate lines: every thread touches the line it will start
+        // the next rotation from now, so that the line is in the L2 by then (one register, released below).
+        u32 touched = 0;
+        if (IN8 && g + 1 < g1) touched = *reinterpret_cast<const u32 *>(c1 + job.in_g_stride + (size_t)tid * S);
         const ulonglong2 *w = HAS_W ? reinterpret_cast<const ulonglong2 *>(job.w2) + (size_t)g * N : nullptr;
         // middle of this wavefront's 8 KiB in the ownership-order copy: all eight loads are immediate offsets of it
         const char *wo = HAS_W ? reinterpret_cast<const char *>(w + (size_t)job.G * N) : nullptr;
@@ -409,8 +418,8 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
                     sum0[k] = csub_dev(sum0[k] + mul_const(c0[i], ww.x, ww.y, q), q8);
                     sum1[k] = csub_dev(sum1[k] + mul_const(c1[i], ww.x, ww.y, q), q8);
                 } else {
-                    sum0[k] = csub_dev(sum0[k] + c0[i], q8);
-                    sum1[k] = csub_dev(sum1[k] + c1[i], q8);
+                    sum0[k] = csub_dev(sum0[k] + at(c0, i), q8);
+                    sum1[k] = csub_dev(sum1[k] + at(c1, i), q8);
                 }
             }
             continue;
@@ -427,7 +436,7 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
         // ScMult of c1 (8 consecutive coefficients per thread), then the inverse transform
         u64 a[PER];
         {
-            const ulonglong2 *c1v = reinterpret_cast<const ulonglong2 *>(c1 + 8 * tid);
+            const ulonglong2 *c1v = reinterpret_cast<const ulonglong2 *>(IN8 ? c1 + (size_t)tid * S : c1 + 8 * tid);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const ulonglong2 cv = c1v[k];
@@ -453,7 +462,7 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
                 const ulonglong2 ww = w[src[k]];
                 sum0[k] += mul_const(c0[src[k]], ww.x, ww.y, q);
             } else {
-                sum0[k] += c0[src[k]];
+                sum0[k] += at(c0, src[k]);
             }
         }
         int pending = 1;   // products added to sum0 since it was last brought below 8q
@@ -485,6 +494,7 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
             sum0[k] = csub_dev(sum0[k], q8);
             sum1[k] = csub_dev(sum1[k], q8);
         }
+        if (IN8) asm volatile("" ::"v"(touched));
     }
     u64 *out = job.partial + ((size_t)item * job.slots + chunk) * 2 * N;
 #pragma unroll
@@ -1099,6 +1109,7 @@ static int launch_2048(const gala_ctx *c, void *stream, const PermJob &job, cons
     const Tables2048 T = make_tables(c, c->d_tw2, c->dev_q);
     const dim3 grid((unsigned)(job.items * job.nchunks + (mj.enabled ? job.items : 0)));
     if (c->special) {
+        if (job.in8_S) return (int)hipErrorInvalidValue;
         SpecialJob S;
         S.TP = make_tables(c, c->d_tw2P, c->dev_P);
         S.Pq = make_ulonglong2(c->Pq, c->Pq_s);
@@ -1109,8 +1120,11 @@ static int launch_2048(const gala_ctx *c, void *stream, const PermJob &job, cons
             hipLaunchKernelGGL(perm_accumulate_special_2048<false>, grid, dim3(NT), 0, st, job, T, S, mj, c->gadget_bits, c->ndigits);
         return (int)hipGetLastError();
     }
+    if (job.in8_S && job.w) return (int)hipErrorInvalidValue;
     if (job.w)
         hipLaunchKernelGGL(perm_accumulate_2048<true>, grid, dim3(NT), 0, st, job, T, mj, c->gadget_bits, c->ndigits);
+    else if (job.in8_S)
+        hipLaunchKernelGGL((perm_accumulate_2048<false, true>), grid, dim3(NT), 0, st, job, T, mj, c->gadget_bits, c->ndigits);
     else
         hipLaunchKernelGGL(perm_accumulate_2048<false>, grid, dim3(NT), 0, st, job, T, mj, c->gadget_bits, c->ndigits);
     return (int)hipGetLastError();
