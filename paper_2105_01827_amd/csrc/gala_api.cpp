@@ -339,9 +339,9 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
         if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used + end], (hipStream_t)stream);
         if (timed && end) ++c->prof_used;
     };
-    // With a mask to subtract the sums go to the n = 2048 Perm kernel, which reads the product's own blocks of eight
-    // coefficients: no transposition pass in between.
-    const bool in8 = ws.mfma && fast_hoist && !c->special && r != nullptr;
+    // The one-prime n = 2048 Perm kernel reads the product's sums in their own blocks of eight coefficients: no
+    // transposition pass in between.
+    const bool in8 = ws.mfma && fast_hoist && !c->special;
     const u64 *perm_in = acc;
     if (ws.mfma && fast_hoist && !c->special) {
         // the rotated inputs go straight into the column image of the matrix-core product
