@@ -400,10 +400,6 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
         const u64 *c1 = IN8 ? c0 + 8 : c0 + N;
         const size_t S = IN8 ? job.in8_S : 0;
         auto at = [&](const u64 *poly, int i) -> u64 { return IN8 ? poly[(size_t)(i >> 3) * S + (i & 7)] : poly[i]; };
-        // In blocks of eight a rotation's input is 256 separate lines: every thread touches the line it will start
-        // the next rotation from now, so that the line is in the L2 by then (one register, released below).
-        u32 touched = 0;
-        if (IN8 && g + 1 < g1) touched = *reinterpret_cast<const u32 *>(c1 + job.in_g_stride + (size_t)tid * S);
         const ulonglong2 *w = HAS_W ? reinterpret_cast<const ulonglong2 *>(job.w2) + (size_t)g * N : nullptr;
         // middle of this wavefront's 8 KiB in the ownership-order copy: all eight loads are immediate offsets of it
         const char *wo = HAS_W ? reinterpret_cast<const char *>(w + (size_t)job.G * N) : nullptr;
@@ -494,7 +490,6 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
             sum0[k] = csub_dev(sum0[k], q8);
             sum1[k] = csub_dev(sum1[k], q8);
         }
-        if (IN8) asm volatile("" ::"v"(touched));
     }
     u64 *out = job.partial + ((size_t)item * job.slots + chunk) * 2 * N;
 #pragma unroll
