@@ -246,7 +246,8 @@ void gala_conv_plan_destroy(gala_conv_plan *plan);
 /* Optional, offline: also keeps the encoded kernels as base-256 digit planes so that gala_he_conv
  * runs its ScMult/Add step (a dense per-coefficient matrix product, Sec. III-B) on the matrix cores
  * whenever a call brings at least 2 inputs.  Costs about 1.3x the plan's device memory again;
- * results are bit-identical either way.  Needs n >= 16. */
+ * results are bit-identical either way for sums of any length (the running sums are reduced mod q every 192
+ * terms).  Needs n >= 16 and q < 2^60; otherwise GALA_ESHAPE, and gala_he_conv keeps using the vector ALU. */
 int gala_conv_plan_prepare_batched(gala_conv_plan *plan);
 /* geometry[0..5] = T, c_n, input ciphertexts per image, output ciphertexts, taps, terms: the (input ciphertext,
    tap) pairs whose encoded kernels are not all zero; only these are rotated and multiplied. */

@@ -296,7 +296,7 @@ ConvWorkspace conv_workspace(const gala_conv_plan *pl, int batch) {
     ws.acc = ws.xrot + align_up((size_t)batch * pl->nterm * 2 * n * w);
     ws.partial = ws.acc + align_up((size_t)batch * pl->nout * pl->cn * 2 * n * w);
     ws.xl = ws.partial + align_up((size_t)batch * pl->nout * (ws.chunks + 1) * 2 * n * w);
-    ws.mfma = pl->d_wl && batch >= 2;    // from two inputs on, an eighth of the two column tiles is enough to win    // from four inputs on, half a column tile is enough to win
+    ws.mfma = pl->d_wl && batch >= 2;    // from two inputs on (4 of a workgroup's 32 columns) the matrix cores win
     size_t xl_bytes = 0, tmp_bytes = 0;
     if (ws.mfma) {
         int mt, nt, kb;

@@ -5,7 +5,8 @@
 // exactly and reduced mod q once at the end.  It is mapped on the int8 MFMA units by writing every residue in
 // eight balanced base-256 digits d_0..d_7 in [-128,127] (x = sum d_u 256^u): then
 //     S = sum_{s=0..14} 256^s * D_s,   D_s[m][c] = sum_{u+v=s} sum_k W_u[m][k] * X_v[k][c]
-// and every D_s is an int8 x int8 -> int32 matrix product (|D_s| <= 8 * 144 * 2^14 < 2^31, exact).
+// and every D_s is an int8 x int8 -> int32 matrix product (|D_s| <= 8 * 192 * 2^14 < 2^31 and S < 192 * 2^120 < 2^128
+// for the at most 192 terms summed between two reductions mod q, given q < 2^60: exact).
 // One v_mfma_i32_16x16x64_i8 multiplies a 16x64 by a 64x16 digit tile; the 64 (u,v) digit pairs of a tile feed
 // 15 accumulators of four registers each.  The recombination of the 15 diagonals, the reduction mod q and the
 // transposition back to coefficient-major order run on the vector ALU in the same kernel.
@@ -24,6 +25,9 @@ namespace gala {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+
+// term blocks of 64 between two reductions of the running sums (conv_mfma_kernel); q < 2^60 is required
+constexpr int kFoldBlocks = 3;
 
 // balanced base-256 digits of x < 2^61, one per byte: the bytes of x + 0x80..80 are the digits plus 128
 __device__ __forceinline__ u64 balanced_digits(u64 x) {
@@ -127,7 +131,7 @@ __device__ __forceinline__ u128 recombine(const int (&c)[15]) {
 // Output: tmp[i][row][column] (rows and columns padded to tiles), transposed afterwards; or, BLK8, in blocks of
 // eight coefficients tmp[i/8][row][column][i%8], which the n = 2048 Perm kernel reads as they are (a thread's eight
 // consecutive coefficients of c0 and of c1 are the two halves of one 128-byte line).
-template <int WAVES, bool BLK8 = false>
+template <int WAVES, bool BLK8, bool FOLD>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void conv_mfma_kernel(const v4i *wl, const v4i *xl, u64 *tmp, int mtiles,
                                                                int ntiles, int kblocks, int nblk16, int n, Modulus mod) {
     constexpr int NT = 64 * WAVES, BLOADS = 1024 / NT;
@@ -189,6 +193,27 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void conv_mfma_kernel(const 
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) av[u] = an[u];
+        // The exact sum of K products of residues below 2^60 needs K * 2^120 < 2^128, and an int32 diagonal
+        // 8 * K * 2^14 < 2^31: after every kFoldBlocks term blocks (192 terms) the sums so far are reduced mod q
+        // and put back as three small non-negative diagonals (24 + 24 + 12 bits at 256^0, 256^3, 256^6), so sums
+        // of any length stay exact.  Layers of at most 192 terms run the instantiation without this branch (FOLD =
+        // false: the branch costs three spilled registers that the main loop reloads).
+        if (FOLD && kb % kFoldBlocks == kFoldBlocks - 1 && kb + 1 < kblocks) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    int c[15];
+#pragma unroll
+                    for (int k = 0; k < 15; ++k) c[k] = s[t][k][r];
+                    const u64 val = reduce128(recombine(c), mod);
+#pragma unroll
+                    for (int k = 0; k < 15; ++k) s[t][k][r] = 0;
+                    s[t][0][r] = (int)(val & 0xffffff);
+                    s[t][3][r] = (int)((val >> 24) & 0xffffff);
+                    s[t][6][r] = (int)(val >> 48);
+                }
+        }
     }
     if (!live) return;
     // lane holds rows 4*(lane/16) + r, column lane%16 of each 16x16 output tile
@@ -254,14 +279,14 @@ int launch_conv_mfma(const gala_ctx *c, void *stream, const u64 *wl, const u64 *
     conv_mfma_geometry(groups, 2 * batch, nterm, &mtiles, &ntiles, &kblocks);
     constexpr int WAVES = 4;
     const dim3 grid((unsigned)c->n, (unsigned)((mtiles + WAVES - 1) / WAVES), (unsigned)((ntiles + 1) / 2));
-    if (blocks_of_eight)
-        hipLaunchKernelGGL((conv_mfma_kernel<WAVES, true>), grid, dim3(64 * WAVES), 0, (hipStream_t)stream,
-                           reinterpret_cast<const v4i *>(wl), reinterpret_cast<const v4i *>(xl), tmp, mtiles, ntiles, kblocks,
-                           (nterm + 15) / 16, c->n, c->dev_q.mod);
-    else
-        hipLaunchKernelGGL(conv_mfma_kernel<WAVES>, grid, dim3(64 * WAVES), 0, (hipStream_t)stream,
-                           reinterpret_cast<const v4i *>(wl), reinterpret_cast<const v4i *>(xl), tmp, mtiles, ntiles, kblocks,
-                           (nterm + 15) / 16, c->n, c->dev_q.mod);
+    const bool fold = kblocks > kFoldBlocks;
+    auto go = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, grid, dim3(64 * WAVES), 0, (hipStream_t)stream, reinterpret_cast<const v4i *>(wl),
+                           reinterpret_cast<const v4i *>(xl), tmp, mtiles, ntiles, kblocks, (nterm + 15) / 16, c->n,
+                           c->dev_q.mod);
+    };
+    if (blocks_of_eight) fold ? go(conv_mfma_kernel<WAVES, true, true>) : go(conv_mfma_kernel<WAVES, true, false>);
+    else fold ? go(conv_mfma_kernel<WAVES, false, true>) : go(conv_mfma_kernel<WAVES, false, false>);
     return (int)hipGetLastError();
 }
 int launch_conv_untranspose(const gala_ctx *c, void *stream, const u64 *tmp, int batch, int groups, u64 *acc) {

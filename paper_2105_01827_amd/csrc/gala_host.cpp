@@ -854,7 +854,8 @@ extern "C" int gala_conv_plan_prepare_batched(gala_conv_plan *pl) {
     if (!pl) return GALA_EARG;
     if (pl->d_wl) return GALA_OK;
     const gala_ctx *c = pl->ctx;
-    if (c->n < 16) return GALA_ESHAPE;
+    // the matrix-core product keeps exact sums of 192 products in 128 bits, which needs q < 2^60
+    if (c->n < 16 || c->q >= (1ull << 60)) return GALA_ESHAPE;
     const int groups = pl->nout * pl->cn, nterm = pl->nterm;
     int mt, nt, kb;
     conv_mfma_geometry(groups, groups, nterm, &mt, &nt, &kb);

@@ -428,7 +428,11 @@ def test_61_bit_modulus_runs_on_the_generic_kernels():
     for b in range(3):
         share = plan.unpack_share(ctx2.decrypt(sk2, got[b]))
         assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_matvec(W, x[b], par.p))
-    conv_case(par, (16, 8, 1, 1, 16, 16), 2, [(0, 0), (1, 1)], seed=9)
+    res = conv_case(par, (16, 8, 1, 1, 16, 16), 2, [(0, 0), (1, 1)], seed=9)
+    # the matrix-core product's 128-bit sums of 192 products need q < 2^60: no digit-plane image for this modulus
+    with pytest.raises(binding.GalaError) as e:
+        res[2].prepare_batched()
+    assert e.value.code == binding.GALA_ESHAPE
 
 
 def test_error_paths_return_codes_and_launch_nothing():
@@ -500,3 +504,14 @@ def test_he_conv_matrix_cores_with_ragged_column_tiles(batch):
         for O in range(plan.nout):
             plan.unpack_share(O, ctx.decrypt(sk, got[b, O]), share)
         assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_conv(K, x[b], par.p))
+
+
+@pytest.mark.parametrize("n,c_i,u", [(16, 16 * 4096, 1), (2048, 8 * 2048, 16)])
+def test_he_conv_matrix_cores_long_sums_stay_exact(n, c_i, u):
+    """Sums of 4096 and 2048 products of 60-bit residues are far beyond 2^128 and their int32 digit sums beyond
+    2^31: the matrix-core product reduces its running sums mod q every 192 terms, so the ciphertexts are still the
+    oracle's.  1x1 kernels, one term per input ciphertext; n = 2048 takes the blocks-of-eight output layout."""
+    par = small_params(n, p_limit=1 << 7, gadget_bits=4) if n != 2048 else wl.DEFAULT
+    shape = (n // (u * u), c_i, 1, 1, u, u)
+    ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, shape, 2, [(0, 0), (1, 0)], seed=n, matrix_cores=True)
+    assert plan.nterm == c_i * u * u // n and plan.nterm >= 2048 and plan.nout == 1
