@@ -235,6 +235,18 @@ int gala_he_fc(const gala_ctx *ctx, void *stream, const gala_fc_plan *plan, cons
                const uint64_t *r, uint64_t mask_seed, uint64_t *ct_out, void *workspace, size_t workspace_bytes,
                gala_opcount *counts);
 
+/* gala_he_fc for callers that cannot allocate device memory or bring a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same computation and the same results as gala_he_fc,
+ * with the partial ciphertexts in a fixed array of gala_he_fc_static_capacity() bytes (32 MiB) that is part of the
+ * library's device code; each GPU the library runs on holds its copy until the process ends.  The call allocates
+ * nothing and only enqueues kernels on `stream`.  Returns GALA_ENOMEM when gala_he_fc_workspace(plan, batch)
+ * exceeds the capacity (nothing is launched), GALA_EARG when the current device is not the context's.  All calls
+ * on one GPU share the array: calls that overlap in time on one GPU (different streams or threads) race; calls
+ * on one stream are ordered and safe.  Nothing needs clearing between calls: a call reads only what it wrote. */
+size_t gala_he_fc_static_capacity(void);
+int gala_he_fc_static(const gala_ctx *ctx, void *stream, const gala_fc_plan *plan, const uint64_t *ct_in, int batch,
+                      const uint64_t *r, uint64_t mask_seed, uint64_t *ct_out, gala_opcount *counts);
+
 /* ---- he_conv: kernel-grouping convolution (Sec. III-B(3)) ------------------ */
 /* K is c_o x c_i x k_h x k_w row-major on the host, entries mod p; the image
  * is u_h x u_w per channel; stride 1, zero "same" padding, odd k_h and k_w.

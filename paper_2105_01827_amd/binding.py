@@ -104,6 +104,8 @@ SIGNATURES = {
     "gala_fc_unpack_share": (_I, [_VP, _U64P, _U64P]),
     "gala_he_fc_workspace": (C.c_size_t, [_VP, _I]),
     "gala_he_fc": (_I, [_VP, _VP, _VP, _U64P, _I, _U64P, C.c_uint64, _U64P, _VP, C.c_size_t, C.POINTER(OpCount)]),
+    "gala_he_fc_static_capacity": (C.c_size_t, []),
+    "gala_he_fc_static": (_I, [_VP, _VP, _VP, _U64P, _I, _U64P, C.c_uint64, _U64P, C.POINTER(OpCount)]),
     "gala_conv_plan_create": (_I, [_VP, _U64P, _I, _I, _I, _I, _I, _I, C.POINTER(_VP)]),
     "gala_conv_plan_destroy": (None, [_VP]),
     "gala_conv_plan_prepare_batched": (_I, [_VP]),
@@ -418,6 +420,12 @@ class FcPlan:
         cnt = OpCount()
         _check(self.ctx.lib.gala_he_fc(self.ctx.h, _stream(stream), self.h, _dev(ct_in), batch, _dev(r), mask_seed,
                                        _dev(ct_out), _dev(workspace), workspace_bytes, C.byref(cnt)), "gala_he_fc")
+        return cnt.as_dict()
+
+    def he_fc_static(self, ct_in, batch, r, mask_seed, ct_out, stream=None):
+        cnt = OpCount()
+        _check(self.ctx.lib.gala_he_fc_static(self.ctx.h, _stream(stream), self.h, _dev(ct_in), batch, _dev(r), mask_seed,
+                                              _dev(ct_out), C.byref(cnt)), "gala_he_fc_static")
         return cnt.as_dict()
 
     def __del__(self):

@@ -1,9 +1,10 @@
 // Device-side entry points of the C ABI: argument checks, workspace carving and
 // the kernel sequences of Perm, he_fc and he_conv.  No allocation happens here.
-#include <hip/hip_runtime_api.h>
+#include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cstdlib>
+#include <mutex>
 
 #include "gala_internal.h"
 
@@ -275,6 +276,54 @@ extern "C" int gala_he_fc(const gala_ctx *c, void *stream, const gala_fc_plan *p
         counts->decperm_in = counts->hstperm_in = 0;
     }
     return GALA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// he_fc for callers that cannot allocate: the partial ciphertexts live in a fixed array of the code object
+// ---------------------------------------------------------------------------
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+// In host code `scratch` is only a handle for hipGetSymbolAddress.  Every device has its own copy of the array at
+// its own address, resolved once per device and kept here; host code passes these pointers, never the name.
+constexpr int kMaxDevices = 64;
+void *scratch_ptr[kMaxDevices];
+std::mutex scratch_mu;
+}  // namespace
+
+namespace gala {
+// Resolves the device address of the fixed scratch array on the current device (called by gala_ctx_create).
+int static_scratch_init() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GALA_EHIP;
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (scratch_ptr[dev]) return GALA_OK;
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return GALA_EHIP;
+    scratch_ptr[dev] = ptr;
+    return GALA_OK;
+}
+}  // namespace gala
+
+extern "C" size_t gala_he_fc_static_capacity(void) { return kStaticScratchBytes; }
+extern "C" int gala_he_fc_static(const gala_ctx *c, void *stream, const gala_fc_plan *pl, const uint64_t *ct_in, int batch,
+                                 const uint64_t *r, uint64_t mask_seed, uint64_t *ct_out, gala_opcount *counts) {
+    if (!c || !pl || pl->ctx != c || batch <= 0) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    const size_t need = gala_he_fc_workspace(pl, batch);
+    if (need > kStaticScratchBytes) return GALA_ENOMEM;      // batch x (chunks + 1) partial ciphertexts do not fit
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return GALA_EHIP;
+    if (dev != c->device || dev < 0 || dev >= kMaxDevices) return GALA_EARG;
+    void *ptr;
+    {
+        std::lock_guard<std::mutex> lock(scratch_mu);
+        ptr = scratch_ptr[dev];
+    }
+    if (!ptr) return GALA_EHIP;                               // gala_ctx_create resolves it; no device, no address
+    // Every word of the partial ciphertexts that the summing kernel reads has been written by this call's
+    // rotate-and-accumulate and mask workgroups, so nothing left by an earlier call needs clearing.
+    return gala_he_fc(c, stream, pl, ct_in, batch, r, mask_seed, ct_out, ptr, kStaticScratchBytes, counts);
 }
 
 // ---------------------------------------------------------------------------

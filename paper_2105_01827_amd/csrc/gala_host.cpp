@@ -382,6 +382,11 @@ extern "C" int gala_ctx_create(const gala_params *par, gala_ctx **out) {
         dv[k]->itw1n = hs[k]->itw1n; dv[k]->itw1ns = hs[k]->itw1ns;
         dv[k]->mod = hs[k]->mod;
     }
+    // address of the fixed scratch array of gala_he_fc_static on this device (resolved once per device)
+    if (static_scratch_init() != GALA_OK) {
+        gala_ctx_destroy(c);
+        return GALA_EHIP;
+    }
     c->has_device = true;
     *out = c;
     return GALA_OK;

@@ -177,6 +177,9 @@ struct gala_conv_plan {
 // ---------------------------------------------------------------------------
 namespace gala {
 
+// resolves, once per device, the device address of the fixed scratch array behind gala_he_fc_static (gala_api.cpp)
+int static_scratch_init();
+
 // batched transform of `count` polynomials of n words: inverse=0 forward.
 int launch_ntt(const gala_ctx *ctx, void *stream, const u64 *src, u64 *dst, size_t count, int inverse);
 // the same with the tables of another modulus of the context (dev_q, dev_p or dev_P)
