@@ -73,7 +73,11 @@ typedef struct {
 /* Homomorphic operations executed by one call, in the paper's vocabulary.  A
  * full Perm is one DecPerm plus one HstPerm on a ciphertext of its own;
  * decperm_in / hstperm_in count the hoisted rotations of the convolution's
- * input ciphertexts (Sec. III-B). */
+ * input ciphertexts (Sec. III-B).  The numbers are computed on the host from the
+ * dimensions of the launches the call enqueued (items, sums, terms of the plan:
+ * the work of every workgroup is fixed by them); nothing is counted on the device.
+ * Terms of a convolution whose encoded kernels are all zero are not launched and
+ * not counted. */
 typedef struct {
     int64_t perm, decperm_in, hstperm_in, scmult, add;
 } gala_opcount;
@@ -104,7 +108,8 @@ const uint64_t *gala_gauss_cdf(void);
  * outside timed regions. */
 int gala_profile_enable(gala_ctx *ctx, int capacity);
 /* Which kernel the events bracket: 0 = rotate-and-accumulate (default), 1 = the convolution's
- * multiply-accumulate kernel inside gala_he_conv. */
+ * multiply-accumulate kernel inside gala_he_conv, 2 = the input rotations of gala_he_conv (DecPerm of the
+ * input ciphertexts and HstPerm of every term, one or two launches). */
 int gala_profile_select(gala_ctx *ctx, int which);
 int gala_profile_collect(gala_ctx *ctx, float *ms, int capacity, int *count);
 

@@ -34,28 +34,7 @@ def build(force=True, verbose=False):
     return LIB
 
 
-PROBES = ["probe_int_mul", "probe_butterfly_mix", "probe_hbm_read", "probe_mfma_i8"]
-
-
-def build_probes(verbose=False):
-    """Compile the stand-alone microbenchmarks (csrc/probe_*.hip) next to the library; run them on an MI355X."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    out = []
-    for name in PROBES:
-        exe = os.path.join(HERE, name)
-        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-value", "-Wno-unused-command-line-argument",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-o", exe, os.path.join(CSRC, name + ".hip")]
-        if verbose:
-            print(" ".join(cmd), flush=True)
-        subprocess.check_call(cmd)
-        out.append(exe)
-    return out
-
-
 if __name__ == "__main__":
     build(force=True, verbose=True)
     print("built", LIB)
-    if "--probes" in sys.argv[1:]:
-        for exe in build_probes(verbose=True):
-            print("built", exe)
     sys.exit(0)

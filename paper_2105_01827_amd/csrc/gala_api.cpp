@@ -23,22 +23,14 @@ namespace {
 // leave a third of the workgroups with 6 instead of 5), and a chunk count that is a multiple of eight lets the
 // XCD-aware mapping keep every chunk's keys in one L2.  Measured on he_fc 128x1024 and 1000x2048 at batch 64:
 // 32 chunks are 4 % and 6 % faster than 12.
-int target_override() {
-    static int v = [] {
-        const char *e = std::getenv("GALA_WG_TARGET");
-        return e ? std::atoi(e) : 0;
-    }();
-    return v;
-}
 // The G rotations of one item are split into this many chunks, each summed by one workgroup.
 int choose_chunks(const gala_ctx *ctx, int items, int G) {
     items = std::max(items, 1);
-    const int forced = target_override();
     // With a special prime the kernel holds two workgroups per CU, not three, and a rotation is twice the work:
     // one round of 512 workgroups was the fastest cut for short and long sums alike (he_fc 128x1024: 0.43 ms
     // against 0.48 ms with 2048 workgroups and 0.58 ms with 768).
-    if (forced > 0 || G < 32 || ctx->special) {
-        const int c = ((forced > 0 ? forced : ctx->special ? 512 : 768) + items - 1) / items;
+    if (G < 32 || ctx->special) {
+        const int c = ((ctx->special ? 512 : 768) + items - 1) / items;
         return std::max(1, std::min(c, G - 1));     // G-1 entries cost a key switch (chunk_range)
     }
     // a power of two (it divides the padded G, and from 8 on it keeps the XCD mapping): 1280 to 2560 workgroups,
@@ -70,7 +62,7 @@ extern "C" int gala_profile_enable(gala_ctx *c, int capacity) {
     return GALA_OK;
 }
 extern "C" int gala_profile_select(gala_ctx *c, int which) {
-    if (!c || (which != 0 && which != 1)) return GALA_EARG;
+    if (!c || which < 0 || which > 2) return GALA_EARG;
     c->prof_which = which;
     return GALA_OK;
 }
@@ -383,11 +375,14 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
     const u64 *keys2 = pl->bound ? pl->bound->d_keys2 : nullptr;
     const int nterm = pl->nterm, groups = pl->nout * pl->cn;
     const TermList terms{pl->nin, nterm, pl->d_term_ct, pl->d_term_gal, pl->d_term_key};
-    const bool timed = c->prof_which == 1 && (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
-    auto mark = [&](int end) {
-        if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used + end], (hipStream_t)stream);
-        if (timed && end) ++c->prof_used;
+    // measurement aid: events around the multiply-accumulate (selection 1) or around the input rotations (2)
+    const bool armed = (size_t)(2 * c->prof_used + 1) < c->prof_events.size();
+    auto mark_as = [&](int which, int end) {
+        if (!armed || c->prof_which != which) return;
+        (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used + end], (hipStream_t)stream);
+        if (end) ++c->prof_used;
     };
+    auto mark = [&](int end) { mark_as(1, end); };
     // The one-prime n = 2048 Perm kernel reads the product's sums in their own blocks of eight coefficients: no
     // transposition pass in between.
     const bool in8 = ws.mfma && fast_hoist && !c->special;
@@ -395,15 +390,19 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
     if (ws.mfma && fast_hoist && !c->special) {
         // the rotated inputs go straight into the column image of the matrix-core product
         u64 *xl = (u64 *)(base + ws.xl), *tmp = (u64 *)(base + ws.tmp);
+        mark_as(2, 0);
         if (launch_hstperm_pack_2048(c, stream, ct_in, digits, batch, terms, rotates, keys2, xl))
             return GALA_EHIP;
+        mark_as(2, 1);
         mark(0);
         if (launch_conv_mfma(c, stream, pl->d_wl, xl, batch, groups, nterm, tmp, in8)) return GALA_EHIP;
         mark(1);
         if (in8) perm_in = tmp;
         else if (launch_conv_untranspose(c, stream, tmp, batch, groups, acc)) return GALA_EHIP;
     } else {
+        mark_as(2, 0);
         if (hoist_terms(c, stream, ct_in, batch, terms, rotates, keys, keys2, digits, xrot)) return GALA_EHIP;
+        mark_as(2, 1);
         if (ws.mfma) {
             u64 *xl = (u64 *)(base + ws.xl), *tmp = (u64 *)(base + ws.tmp);
             if (launch_limb_pack(c, stream, xrot, 1, 2 * batch, nterm, xl)) return GALA_EHIP;

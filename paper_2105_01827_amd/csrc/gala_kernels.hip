@@ -911,8 +911,7 @@ int launch_pair_pack(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, 
     return last_error();
 }
 bool uses_fast_perm(const gala_ctx *c) {
-    static const bool generic_only = std::getenv("GALA_GENERIC_PERM") != nullptr;
-    return c->n == 2048 && c->q < (1ull << 60) && !generic_only &&
+    return c->n == 2048 && c->q < (1ull << 60) &&
            (!c->special || (c->special < (1ull << 60) && c->special < 2 * c->q));
 }
 int launch_perm_accumulate(const gala_ctx *c, void *stream, const PermJob &job) {
