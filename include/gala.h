@@ -99,6 +99,16 @@ uint64_t gala_ctx_delta(const gala_ctx *ctx);
 /* The 38 thresholds floor(2^64 * P[X <= -19+i]) of the error sampler (host). */
 const uint64_t *gala_gauss_cdf(void);
 
+/* The counter-based generator behind every seeded draw of the library (secret and key-switching keys, encryption
+ * randomness and noise, the expansion of the masks of gala_he_fc / gala_he_conv from mask_seed): gala_mix64 is the
+ * output function of SplitMix64, and
+ *   gala_rand64(seed, stream, idx, attempt) = mix64(mix64(mix64(mix64(seed + 0x9E3779B97F4A7C15) + stream) + idx) + attempt).
+ * It exists so that seeded runs can be reproduced bit for bit; it is NOT a cryptographic source.  The slots of a
+ * mask that are drawn from it are part of the server's secret share (Sec. II-C(2), Sec. III-A(3)): a deployment has
+ * to replace these draws by a cryptographic generator keyed with a secret seed. */
+uint64_t gala_mix64(uint64_t z);
+uint64_t gala_rand64(uint64_t seed, uint64_t stream, uint64_t idx, uint64_t attempt);
+
 /* Measurement aid.  After gala_profile_enable(ctx, capacity) the next `capacity`
  * launches of the rotate-and-accumulate kernel (the Perm kernel inside
  * gala_rotate, gala_he_fc and gala_he_conv) are bracketed by HIP events on the

@@ -279,6 +279,7 @@ static u64 mix64(u64 z) {   /* SplitMix64 output function */
     z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
     return z ^ (z >> 31);
 }
+u64 orc_mix64(u64 z) { return mix64(z); }
 u64 orc_rand64(u64 seed, u64 stream, u64 idx, u64 attempt) {
     u64 h = mix64(seed + 0x9E3779B97F4A7C15ull);
     h = mix64(h + stream);

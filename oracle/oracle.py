@@ -39,7 +39,7 @@ def lib():
         _lib = C.CDLL(build())
         _lib.orc_ctx_new.restype = C.c_void_p
         _lib.orc_ctx_new.argtypes = [C.c_int, C.c_uint64, C.c_uint64, C.c_int]
-        for name in ("orc_delta", "orc_zeta", "orc_psi", "orc_rand64", "orc_uniform", "orc_noise"):
+        for name in ("orc_delta", "orc_zeta", "orc_psi", "orc_rand64", "orc_mix64", "orc_uniform", "orc_noise"):
             getattr(_lib, name).restype = C.c_uint64
         _lib.orc_gauss_cdf.restype = C.POINTER(C.c_uint64)
     return _lib
@@ -110,6 +110,9 @@ class Oracle:
         self.L.orc_encode_weight(self.h, _p(s), _p(out)); return out
 
     # ---- samplers
+    def mix64(self, z):
+        return int(self.L.orc_mix64(C.c_uint64(z)))
+
     def rand64(self, seed, stream, idx, attempt=0):
         return int(self.L.orc_rand64(C.c_uint64(seed), C.c_uint64(stream), C.c_uint64(idx), C.c_uint64(attempt)))
 

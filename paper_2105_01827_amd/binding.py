@@ -67,6 +67,8 @@ SIGNATURES = {
     "gala_ctx_ndigits": (_I, [_VP]),
     "gala_ctx_delta": (C.c_uint64, [_VP]),
     "gala_gauss_cdf": (C.POINTER(C.c_uint64), []),
+    "gala_mix64": (C.c_uint64, [C.c_uint64]),
+    "gala_rand64": (C.c_uint64, [C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64]),
     "gala_profile_enable": (_I, [_VP, _I]),
     "gala_profile_select": (_I, [_VP, _I]),
     "gala_profile_collect": (_I, [_VP, C.POINTER(C.c_float), _I, C.POINTER(_I)]),

@@ -147,6 +147,12 @@ static const u64 kGaussCdf[38] = {
     0xffff40fa0088d11dull, 0xffffd2e835e1c57dull, 0xfffff6524386ff1eull, 0xfffffe1db4769da5ull,
     0xffffffac0a1dcb08ull, 0xfffffff428673853ull};
 const u64 *gauss_cdf_table() { return kGaussCdf; }
+}  // namespace gala
+extern "C" uint64_t gala_mix64(uint64_t z) { return gala::mix64(z); }
+extern "C" uint64_t gala_rand64(uint64_t seed, uint64_t stream, uint64_t idx, uint64_t attempt) {
+    return gala::rand64(seed, stream, idx, attempt);
+}
+namespace gala {
 
 static int draw_gauss(u64 seed, u64 stream, u64 idx) {
     const u64 u = rand64(seed, stream, idx, 0);

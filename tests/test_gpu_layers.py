@@ -1,4 +1,5 @@
 """GPU tests of whole layers: spatial tiling + stride on top of he_conv, and the ResNet-18-shaped list."""
+import concurrent.futures
 import ctypes
 
 import numpy as np
@@ -21,6 +22,22 @@ def oracle_block(o, shape, K, cts_b, r_tile, mask_seed, b, O, osk, key_seed=8):
     mask = o.conv_mask_slots(shape, r_tile, mask_seed, b, O)
     want, _ = o.he_conv_block(shape, K, O, cts_b, tk, gkk, mask)
     return want
+
+
+def check_sampled_blocks(o, osk, shape, K, cts, r_tiles, got, mask_seed, name, extra=()):
+    """The first, a middle and the last (tile, output block) of a layer, plus `extra`, recomputed by the oracle on a
+    host thread each; the ciphertexts must be equal."""
+    tiles, nout = got.shape[0], got.shape[1]
+    picks = sorted({(0, 0), (tiles // 2, nout // 2), (tiles - 1, nout - 1), *extra})
+    tk, gkk = o.conv_keys(osk, shape, seed=8)
+
+    def block(bO):
+        b, O = bO
+        return o.he_conv_block(shape, K, O, cts[b], tk, gkk, o.conv_mask_slots(shape, r_tiles[b], mask_seed, b, O))[0]
+
+    with concurrent.futures.ThreadPoolExecutor(len(picks)) as pool:
+        for (b, O), want in zip(picks, pool.map(block, picks)):
+            assert np.array_equal(got[b, O], want), f"{name}: ciphertext mismatch at tile {b}, block {O}"
 
 
 @pytest.mark.parametrize("n,p_limit,gb,c_o,c_i,k,stride,H,W", [
@@ -90,8 +107,8 @@ def test_polyphase_strided_layer(n, p_limit, gb, c_o, c_i, k, stride, H, W, spec
 
 def test_resnet18_shaped_layer_list():
     """Config 5: every linear layer of an ImageNet-shaped ResNet-18, one input, random weights mod p.
-    Each layer runs in full on the GPU; the oracle recomputes one output ciphertext per layer (a sampled
-    tile and output block) and the ciphertexts must agree exactly.  1x1 layers and the FC also decrypt
+    Each layer runs in full on the GPU; the oracle recomputes up to four output ciphertexts per layer (the first, a
+    middle and the last tile and output block, and one more) and the ciphertexts must agree exactly.  1x1 layers and the FC also decrypt
     (Sec. III-C noise budget) and are checked against the plain strided convolution / matrix product."""
     from tests import gpu_harness as Hn
     par = wl.DEFAULT
@@ -115,9 +132,7 @@ def test_resnet18_shaped_layer_list():
         assert cnt["perm"] == t.tiles * nout * (cn - 1) and cnt["scmult"] == t.tiles * nout * cn * nin * k2
         assert cnt["hstperm_in"] == t.tiles * nin * (k2 - 1)
         shape = (L.c_o, L.c_i, L.k, L.k, t.tile_h, t.tile_w)
-        b, O = (li * 7) % t.tiles, (li * 5) % nout
-        want = oracle_block(o, shape, K, cts[b], r_tiles[b], li, b, O, osk)
-        assert np.array_equal(got[b, O], want), f"{L.name}: ciphertext mismatch at tile {b}, block {O}"
+        check_sampled_blocks(o, osk, shape, K, cts, r_tiles, got, li, L.name, extra=[((li * 7) % t.tiles, (li * 5) % nout)])
         if L.k == 1:
             share = Hn.stitch_layer_share(ctx, sk, t, plan, got, L.c_o)
             assert np.array_equal((share + r) % np.uint64(par.p), strided_conv(K, image, par.p, L.stride)), L.name
@@ -140,7 +155,8 @@ def test_resnet18_shaped_layer_list():
 
 def test_resnet18_strided_layers_as_polyphase_layers():
     """The seven strided layers of the list (7x7/2, three 3x3/2, three 1x1/2) through the polyphase split at full
-    size: one output ciphertext per layer against the oracle on its own rearrangement, the operation counts of the
+    size: up to four output ciphertexts per layer (first, middle, last tile and block, one more) against the oracle on its
+    own rearrangement, the operation counts of the
     terms that exist, and for the 1x1 layers the decrypted share against the subsampled plain convolution."""
     from oracle.oracle import polyphase_split
     from tests import gpu_harness as Hn
@@ -169,9 +185,8 @@ def test_resnet18_strided_layers_as_polyphase_layers():
         if L.c_i % plan.cn == 0:          # every input ciphertext holds one phase: exactly the taps that exist
             assert cnt["scmult"] == t.tiles * plan.nout * plan.cn * (L.c_i // plan.cn) * scmult_per_pair[L.k]
         shape = (L.c_o, Kp.shape[1], Kp.shape[2], Kp.shape[3], t.tile_h, t.tile_w)
-        b, O = (li * 7) % t.tiles, (li * 5) % plan.nout
-        want = oracle_block(o, shape, Kp_o, cts[b], r_tiles[b], li, b, O, osk)
-        assert np.array_equal(got[b, O], want), f"{L.name}: ciphertext mismatch at tile {b}, block {O}"
+        check_sampled_blocks(o, osk, shape, Kp_o, cts, r_tiles, got, li, L.name,
+                             extra=[((li * 7) % t.tiles, (li * 5) % plan.nout)])
         if L.k == 1:
             share = Hn.stitch_layer_share(ctx, sk, t, plan, got, L.c_o)
             assert np.array_equal((share + r) % np.uint64(par.p), strided_conv(K, image, par.p, L.stride)), L.name

@@ -3,6 +3,7 @@
 Same seeded keys, noise and masks on both sides; ciphertexts are compared in
 interchange form (coefficient domain), so every comparison is exact equality.
 """
+import concurrent.futures
 import ctypes
 
 import numpy as np
@@ -161,9 +162,14 @@ def fc_case(par, n_o, n_i, batch, oracle_items, seed=0):
     assert cnt == dict(perm=batch * (G - 1), decperm_in=0, hstperm_in=0, scmult=batch * G, add=batch * (G - 1))
     wpoly = o.fc_encode_rowwise(W)
     ksk = o.fc_keys(osk, n_o, n_i, seed=1)
-    for b in oracle_items:
-        mask = o.fc_mask_slots(n_o, n_i, r[b], 17, b)
-        want, ocnt = o.he_fc(wpoly, cts[b], ksk, mask)
+
+    def item(b):
+        return o.he_fc(wpoly, cts[b], ksk, o.fc_mask_slots(n_o, n_i, r[b], 17, b))
+
+    # the oracle's items are independent: one host thread each (the C call releases the interpreter lock)
+    with concurrent.futures.ThreadPoolExecutor(max(1, min(16, len(oracle_items)))) as pool:
+        wants = list(pool.map(item, oracle_items))
+    for b, (want, ocnt) in zip(oracle_items, wants):
         assert np.array_equal(got[b], want), f"ciphertext mismatch at batch item {b}"
         assert ocnt["perm"] == G - 1 and ocnt["scmult"] == G
     return ctx, o, plan, sk, W, x, r, got
@@ -196,18 +202,18 @@ def test_he_fc_config2_128x1024_batch64():
         assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_matvec(W, x[b], par.p))
 
 
-def test_he_fc_config3_1000x2048_batch64_sampled():
-    """All 64 inputs run on the GPU; the oracle recomputes two of them in full (1023 Perms each) and
-    the decrypt identity is checked on every one."""
+def test_he_fc_config3_1000x2048_batch64():
+    """All 64 inputs run on the GPU and the oracle recomputes every one of them in full (1023 Perms each, on the
+    host threads); the decrypt identity is checked on every one."""
     par = wl.DEFAULT
-    ctx, o, plan, sk, W, x, r, got = fc_case(par, 1000, 2048, 64, [0, 41])
+    ctx, o, plan, sk, W, x, r, got = fc_case(par, 1000, 2048, 64, list(range(64)))
     for b in range(64):
         share = plan.unpack_share(ctx.decrypt(sk, got[b]))
         want = (W @ x[b]) % np.uint64(par.p)          # exact in uint64: 2048 products below 2^40
         assert np.array_equal((share + r[b]) % np.uint64(par.p), want), b
 
 
-def conv_case(par, shape, batch, oracle_outputs, seed=0, matrix_cores=False, edit_kernel=None):
+def conv_case(par, shape, batch, oracle_outputs, seed=0, matrix_cores=False, edit_kernel=None, split=1):
     """oracle_outputs: list of (b, O) ciphertexts the oracle recomputes.  matrix_cores: keep the digit-plane
     image of the kernels so that the multiply-accumulate runs on the MFMA units (needs batch >= 4).
     edit_kernel: a function that changes the seeded kernel tensor in place before either side sees it."""
@@ -230,14 +236,23 @@ def conv_case(par, shape, batch, oracle_outputs, seed=0, matrix_cores=False, edi
     cts = np.stack([[ctx.encrypt(sk, slots[b, I], seed=1000 * b + I) for I in range(plan.nin)] for b in range(batch)])
     got, cnt = H.gpu_he_conv(ctx, plan, cts, r, mask_seed=3)
     tk, gkk = o.conv_keys(osk, shape, seed=8)
-    cache = {}
+    # Output blocks of one input share its rotated inputs when they run one after the other; groups of blocks are
+    # independent and get a host thread each (split > 1 cuts one input's blocks into that many groups).
+    groups = {}
     for b, O in oracle_outputs:
-        if b not in cache:
-            cache = {b: (np.empty(plan.nin * plan.ntap * 2 * par.n, np.uint64), ctypes.c_int(0))}
-        xrot, ready = cache[b]
-        mask = o.conv_mask_slots(shape, r[b], 3, b, O)
-        want, _ = o.he_conv_block(shape, K, O, cts[b], tk, gkk, mask, xrot, ready)
-        assert np.array_equal(got[b, O], want), f"ciphertext mismatch at input {b}, output block {O}"
+        groups.setdefault((b, O % split), []).append(O)
+
+    def group(key):
+        b = key[0]
+        xrot, ready = np.empty(plan.nin * plan.ntap * 2 * par.n, np.uint64), ctypes.c_int(0)
+        return [(b, O, o.he_conv_block(shape, K, O, cts[b], tk, gkk, o.conv_mask_slots(shape, r[b], 3, b, O), xrot, ready)[0])
+                for O in groups[key]]
+
+    if groups:
+        with concurrent.futures.ThreadPoolExecutor(min(16, len(groups))) as pool:
+            for res in pool.map(group, list(groups)):
+                for b, O, want in res:
+                    assert np.array_equal(got[b, O], want), f"ciphertext mismatch at input {b}, output block {O}"
     return ctx, o, plan, sk, K, x, r, got, cnt
 
 
@@ -378,21 +393,25 @@ def test_he_conv_single_input_n2048(c_o, c_i, u):
     assert plan.cn == 2 and plan.nout == nout
 
 
-def test_he_conv_config4_matrix_cores_equals_vector_path():
-    """Both implementations of the multiply-accumulate give the same ciphertexts on the whole config-4 batch."""
+def test_he_conv_config4_every_output_on_matrix_cores_and_vector_path():
+    """The matrix-core multiply-accumulate against the oracle on all 256 output ciphertexts of config 4 (each recomputed
+    in full on the host threads), and against the vector path on all 256."""
     par = wl.DEFAULT
     s = wl.CONV_16x16_128_3x3
-    a = conv_case(par, s.tuple, s.batch, [(3, 9)], matrix_cores=True)
+    picks = [(b, O) for b in range(16) for O in range(16)]
+    a = conv_case(par, s.tuple, s.batch, picks, matrix_cores=True, split=2)
     b = conv_case(par, s.tuple, s.batch, [], matrix_cores=False)
     assert np.array_equal(a[7], b[7])
 
 
 def test_he_conv_config4_sampled():
-    """16x16x128 input, 128 kernels 3x3, batch 16 on the GPU; the oracle recomputes three of the 256 output
-    ciphertexts in full (1152 ScMult + 7 Perm each, plus the 144 input rotations of their inputs)."""
+    """16x16x128 input, 128 kernels 3x3, batch 16 on the GPU (vector multiply-accumulate); the oracle recomputes 31 of
+    the 256 output ciphertexts in full (1152 ScMult + 7 Perm each, plus the 144 input rotations of their inputs):
+    every output block of input 0 and one block of every other input."""
     par = wl.DEFAULT
     s = wl.CONV_16x16_128_3x3
-    ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, s.tuple, s.batch, [(0, 0), (0, 15), (11, 6)])
+    picks = [(0, O) for O in range(16)] + [(b, (7 * b) % 16) for b in range(1, 16)]
+    ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, s.tuple, s.batch, picks, split=16)
     # Table "Computation complexity of convolution", 16x16@128 with 3x3@128, per input
     assert (cnt["decperm_in"] + cnt["perm"], cnt["hstperm_in"] + cnt["perm"], cnt["scmult"], cnt["add"]) == \
            (16 * 128, 16 * 240, 16 * 18432, 16 * 18416)

@@ -88,3 +88,18 @@ def test_device_entry_points_reject_null_arguments_and_missing_devices():
             ctx.conv_plan(np.ones((2, 2, 3, 3), np.uint64), 4, 4)
         assert e.value.code == binding.GALA_EHIP
         assert lib.gala_add(ctx.h, null, one, one, 1, one) == binding.GALA_EHIP
+
+
+def test_library_generator_is_splitmix64_and_equals_the_oracles():
+    """The library's own copy of the seeded generator: the published SplitMix64 outputs for seed 0, and the same
+    words as the oracle's generator on a spread of (seed, stream, index, attempt)."""
+    lib = binding.load()
+    phi, mask = 0x9E3779B97F4A7C15, (1 << 64) - 1
+    assert [lib.gala_mix64((k * phi) & mask) for k in (1, 2, 3)] == [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
+    par = small_params(8)
+    o = Oracle(par.n, par.q, par.p, par.gadget_bits)
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        seed, stream, idx, attempt = (int(v) for v in rng.integers(0, 1 << 63, size=4, dtype=np.uint64))
+        stream %= 8
+        assert lib.gala_rand64(seed, stream, idx, attempt) == o.rand64(seed, stream, idx, attempt)

@@ -180,3 +180,37 @@ def test_sampler_statistics_and_ranges():
     # streams and seeds are independent inputs of the generator
     assert o.rand64(1, 2, 3) != o.rand64(1, 3, 2) and o.rand64(1, 2, 3) != o.rand64(2, 2, 3)
     assert o.rand64(1, 2, 3, 0) != o.rand64(1, 2, 3, 1)
+
+
+def _splitmix64_stream(seed, count):
+    """SplitMix64 as published (Steele, Lea, Flood 2014; the reference C version by Vigna): the state advances by the
+    golden-ratio constant, the output is the state through two xor-shift-multiply rounds and a final xor-shift."""
+    mask, out, state = (1 << 64) - 1, [], seed
+    for _ in range(count):
+        state = (state + 0x9E3779B97F4A7C15) & mask
+        z = state
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & mask
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & mask
+        out.append(z ^ (z >> 31))
+    return out
+
+
+# first outputs of SplitMix64 seeded with 0, as published with the reference implementation
+SPLITMIX64_SEED0 = [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
+
+
+def test_generator_is_splitmix64_output_function_composed_four_times():
+    """The samplers' bit recipe is this build's own, but its core is a published function with published outputs:
+    mix64 of the oracle against SplitMix64's test vector for seed 0, and rand64 against the stated composition."""
+    assert _splitmix64_stream(0, 3) == SPLITMIX64_SEED0
+    o = Oracle(8, small_params(8).q, small_params(8).p, 20)
+    phi, mask = 0x9E3779B97F4A7C15, (1 << 64) - 1
+    assert o.mix64(phi) == SPLITMIX64_SEED0[0]
+    assert o.mix64((2 * phi) & mask) == SPLITMIX64_SEED0[1] and o.mix64((3 * phi) & mask) == SPLITMIX64_SEED0[2]
+
+    def mix(z):      # one output of the published generator whose state was z - phi
+        return _splitmix64_stream((z - phi) & mask, 1)[0]
+
+    for seed, stream, idx, attempt in [(0, 0, 0, 0), (1, 2, 3, 0), (17, 6, (5 << 32) + (3 << 16) + 9, 2), (mask, mask, mask, mask)]:
+        want = mix((mix((mix((mix((seed + phi) & mask) + stream) & mask) + idx) & mask) + attempt) & mask)
+        assert o.rand64(seed, stream, idx, attempt) == want
