@@ -181,12 +181,24 @@ __device__ __forceinline__ void inv_pass(u64 (&a)[8], const Tw7 &w, NegQ q, u64 
 // register k is pad(base) plus a compile-time offset.
 template <int SH>
 __device__ __forceinline__ constexpr int reg_offset(int k) { return (k << SH) + ((k << SH) >> 5); }
-template <int SH_OUT, int SH_IN>
+// LOCAL: every word a thread loads was stored by a thread of its own wavefront (both index sets lie in the
+// wavefront's 512-word range of the buffer).  A wavefront's LDS instructions execute in order, so its loads see
+// its stores without a workgroup barrier; the fences only keep the compiler from moving the loads up.  Four of
+// the seven exchanges of an inverse + forward transform pair are of this kind: <5,2> and <2,0> move data inside
+// groups of 32 and 4 lanes, <0,3> and <3,6> inside groups of 8 and 64; <8,5>, <6,8> and the final store of the
+// forward transform cross wavefronts and keep the barrier.
+template <int SH_OUT, int SH_IN, bool LOCAL = false>
 __device__ __forceinline__ void exchange(u64 (&a)[8], u64 *buf, int base_out, int base_in) {
     u64 *po = buf + pad(base_out);
 #pragma unroll
     for (int k = 0; k < 8; ++k) po[reg_offset<SH_OUT>(k)] = a[k];
-    __syncthreads();
+    if (LOCAL) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    } else {
+        __syncthreads();
+    }
     const u64 *pi = buf + pad(base_in);
 #pragma unroll
     for (int k = 0; k < 8; ++k) a[k] = pi[reg_offset<SH_IN>(k)];
@@ -219,10 +231,10 @@ __device__ __forceinline__ void forward_to_lds(u64 (&a)[8], u64 *res, u64 *other
     exchange<8, 5>(a, other, tid, ((tid >> 5) << 8) | (tid & 31));
     fwd_pass<true, false, CM>(a, w, q, q2);                                              // bits 5-7
     w = tw_level<64>(T.tw, (unsigned)tid >> 2);
-    exchange<5, 2>(a, res, ((tid >> 5) << 8) | (tid & 31), ((tid >> 2) << 5) | (tid & 3));
+    exchange<5, 2, true>(a, res, ((tid >> 5) << 8) | (tid & 31), ((tid >> 2) << 5) | (tid & 3));
     fwd_pass<true, true, CM>(a, w, q, q2);                                               // bits 2-4
     w = tw_level<256>(T.tw, (unsigned)tid);
-    exchange<2, 0>(a, other, ((tid >> 2) << 5) | (tid & 3), tid << 3);
+    exchange<2, 0, true>(a, other, ((tid >> 2) << 5) | (tid & 3), tid << 3);
     fwd_pass<false, false, CM>(a, w, q, q2);                                             // bits 0-1
     u64 *po = res + pad(tid << 3);
 #pragma unroll
@@ -240,10 +252,10 @@ __device__ __forceinline__ void inverse_in_regs(u64 (&a)[8], u64 *bufA, u64 *buf
     Tw7 w = tw_level<256>(T.itw, (unsigned)tid);
     inv_pass<CM>(a, w, q, q2);                                                           // bits 0-2
     w = tw_level<32>(T.itw, (unsigned)tid >> 3);
-    exchange<0, 3>(a, bufA, tid << 3, ((tid >> 3) << 6) | (tid & 7));
+    exchange<0, 3, true>(a, bufA, tid << 3, ((tid >> 3) << 6) | (tid & 7));
     inv_pass<CM>(a, w, q, q2);                                                           // bits 3-5
     w = tw_level<4>(T.itw, (unsigned)tid >> 6);
-    exchange<3, 6>(a, bufB, ((tid >> 3) << 6) | (tid & 7), ((tid >> 6) << 9) | (tid & 63));
+    exchange<3, 6, true>(a, bufB, ((tid >> 3) << 6) | (tid & 7), ((tid >> 6) << 9) | (tid & 63));
     inv_pass<CM>(a, w, q, q2);                                                           // bits 6-8
     const ulonglong2 t2a = T.itw[1], t2b = T.itw[2];      // level 1: constants 1 and 2 of block 1
     exchange<6, 8>(a, bufA, ((tid >> 6) << 9) | (tid & 63), tid);
