@@ -753,6 +753,167 @@ void orc_he_conv_block(const orc_ctx *c, const u64 *K, int co, int ci, int kh, i
 }
 
 /* ------------------------------------------------------------------ */
+/* The comparison schedules of the paper, on the same operations:       */
+/* hybrid matrix-vector product (Sec. III-A(2)) and output-rotation     */
+/* MIMO convolution (Sec. III-B(2)).                                    */
+/* ------------------------------------------------------------------ */
+/* Hybrid FC.  The paper gives the method on one cycle of n slots and leaves the packed layout to a figure; on
+ * the 2 x n/2 torus it is read as follows (n_o, n_i padded to powers of two):
+ *  n_i <= n/2: every half-row holds n/(2 n_i) copies of x.  Copy c owns R = max(1, n_i n_o / n) output rows
+ *    c*R .. c*R+R-1 (no rows when n_i n_o < n and c >= n_o); slot (h,k) of copy c, j = k mod n_i, collects row
+ *    c*R + (j mod R).  G = R input rotations: w_g[(h,k)] = W[row(h,k)][(j+g) mod n_i] multiplies x_pack rotated
+ *    left by g.  After the sum over g slot (h,k) holds the partial product of its row over columns j .. j+R-1;
+ *    the rotate-and-sum steps by n_i/2, n_i/4, .., R add the n_i/R partial sums of a row, and row c*R + j ends up
+ *    in slot j < R of copy c.
+ *  n_i = n: half h holds x[h*n/2 ..]; slot (h,k) collects row k mod n_o over the columns of its half, G = n_o
+ *    input rotations, rotate-and-sum steps by n/4, .., n_o inside the rows and one row swap at the end; row t ends
+ *    up in slot (0,t).
+ * Counts: G ScMult, G-1 HstPerm of the input (one DecPerm), log2(n/n_o) Perm when n_i n_o >= n, as in Table
+ * "Complexity comparison of three methods". */
+typedef struct { int n, half, no, ni, nop, nip, G, R, big, steps; } hy_geom;
+static int hy_geometry(const orc_ctx *c, int n_o, int n_i, hy_geom *g) {
+    g->n = c->n; g->half = c->n / 2; g->no = n_o; g->ni = n_i;
+    g->nop = pow2ceil(n_o); g->nip = pow2ceil(n_i);
+    if (g->nip > g->n || g->nop > g->n) return -1;
+    g->big = g->nip == g->n;
+    if (g->big) {
+        if (g->nop > g->half) return -1;
+        g->G = g->R = g->nop; g->steps = ilog2(g->half / g->nop) + 1;
+    } else {
+        long prod = (long)g->nip * g->nop;
+        g->R = prod >= g->n ? (int)(prod / g->n) : 1;
+        g->G = g->R; g->steps = ilog2(g->nip / g->R);
+    }
+    return 0;
+}
+int orc_fc_hybrid_G(const orc_ctx *c, int n_o, int n_i) { hy_geom g; return hy_geometry(c, n_o, n_i, &g) ? -1 : g.G; }
+/* the rotate-and-sum rotations in order; returns their number */
+int orc_fc_hybrid_ras(const orc_ctx *c, int n_o, int n_i, int *swap, int *step) {
+    hy_geom g; if (hy_geometry(c, n_o, n_i, &g)) return -1;
+    int k = 0;
+    for (int rho = (g.big ? g.half : g.nip) / 2; rho >= g.R; rho /= 2) { swap[k] = 0; step[k] = rho; k++; }
+    if (g.big) { swap[k] = 1; step[k] = 0; k++; }
+    return k;
+}
+static int hy_row(const hy_geom *g, int h, int k) {
+    if (g->big) return k % g->nop;
+    int copy = h * (g->half / g->nip) + k / g->nip, j = k % g->nip;
+    if ((long)g->nip * g->nop < g->n && copy >= g->nop) return -1;
+    return copy * g->R + j % g->R;
+}
+/* the slot that holds output row t after the rotate-and-sum steps */
+static int hy_result_slot(const hy_geom *g, int t) {
+    if (g->big) return t;
+    int copy = t / g->R, per_row = g->half / g->nip;
+    return (copy / per_row) * g->half + (copy % per_row) * g->nip + t % g->R;
+}
+void orc_fc_hybrid_weight_slots(const orc_ctx *c, const u64 *W, int n_o, int n_i, int gi, u64 *slots) {
+    hy_geom g; hy_geometry(c, n_o, n_i, &g);
+    for (int h = 0; h < 2; h++)
+        for (int k = 0; k < g.half; k++) {
+            int row = hy_row(&g, h, k);
+            int col = g.big ? h * g.half + (k + gi) % g.half : (k % g.nip + gi) % g.nip;
+            slots[h * g.half + k] = (row >= 0 && row < n_o && col < n_i) ? W[(size_t)row * n_i + col] % c->p : 0;
+        }
+}
+void orc_fc_hybrid_encode(const orc_ctx *c, const u64 *W, int n_o, int n_i, u64 *wpoly) {
+    hy_geom g; hy_geometry(c, n_o, n_i, &g);
+    u64 *slots = malloc(sizeof(u64) * c->n);
+    for (int gi = 0; gi < g.G; gi++) {
+        orc_fc_hybrid_weight_slots(c, W, n_o, n_i, gi, slots);
+        orc_encode_weight(c, slots, wpoly + (size_t)gi * c->n);
+    }
+    free(slots);
+}
+void orc_fc_hybrid_unpack(const orc_ctx *c, int n_o, int n_i, const u64 *slots, u64 *out) {
+    hy_geom g; hy_geometry(c, n_o, n_i, &g);
+    for (int t = 0; t < n_o; t++) out[t] = slots[hy_result_slot(&g, t)] % c->p;
+}
+/* the server's random vector: its share r at the result slots, a draw from the mask stream everywhere else */
+void orc_fc_hybrid_mask_slots(const orc_ctx *c, int n_o, int n_i, const u64 *r, u64 seed, int b, u64 *slots) {
+    hy_geom g; hy_geometry(c, n_o, n_i, &g);
+    for (int s = 0; s < c->n; s++) slots[s] = orc_uniform(c->p, seed, STREAM_MASK, ((u64)b << 32) + (u64)s);
+    for (int t = 0; t < n_o; t++) slots[hy_result_slot(&g, t)] = r[t] % c->p;
+}
+/* out = RaS( sum_g ScMult( HstPerm_g(ct), w_g ) ) - mask, every rotate-and-sum step a Perm and an Add on the
+ * running ciphertext.  ksk_in: keys of the input rotations g = 1..G-1; ksk_ras: keys of orc_fc_hybrid_ras in order. */
+void orc_he_fc_hybrid(const orc_ctx *c, const u64 *wpoly, int n_o, int n_i, const u64 *ct, const u64 *ksk_in,
+                      const u64 *ksk_ras, const u64 *mask_slots, u64 *out, orc_counts *cnt) {
+    hy_geom g; hy_geometry(c, n_o, n_i, &g);
+    int n = c->n;
+    size_t ksz = (size_t)c->ndigits * orc_key_polys(c) * n;
+    u64 *digits = malloc(sizeof(u64) * (size_t)c->ndigits * n);
+    u64 *xr = malloc(sizeof(u64) * 2 * n), *u = malloc(sizeof(u64) * 2 * n), *acc = malloc(sizeof(u64) * 2 * n);
+    if (g.G > 1) { orc_decperm(c, ct + n, digits); if (cnt) cnt->decperm_in++; }
+    for (int gi = 0; gi < g.G; gi++) {
+        if (gi == 0) memcpy(xr, ct, sizeof(u64) * 2 * n);
+        else { orc_hstperm(c, ct, digits, orc_galois_elt(c, 0, gi), ksk_in + (size_t)(gi - 1) * ksz, xr); if (cnt) cnt->hstperm_in++; }
+        orc_scmult(c, xr, wpoly + (size_t)gi * n, u); if (cnt) cnt->scmult++;
+        if (gi == 0) memcpy(acc, u, sizeof(u64) * 2 * n);
+        else { orc_add(c, acc, u, acc); if (cnt) cnt->add++; }
+    }
+    int sw[32], st[32], steps = orc_fc_hybrid_ras(c, n_o, n_i, sw, st);
+    for (int k = 0; k < steps; k++) {
+        orc_perm(c, acc, orc_galois_elt(c, sw[k], st[k]), ksk_ras + (size_t)k * ksz, u); if (cnt) cnt->perm++;
+        orc_add(c, acc, u, acc); if (cnt) cnt->add++;
+    }
+    orc_sub_plain(c, acc, mask_slots, out);
+    free(digits); free(xr); free(u); free(acc);
+}
+
+/* Output-rotation MIMO convolution for ONE output ciphertext O (Sec. III-B(2)): the same encoded kernels, input
+ * rotations and kernel orders as orc_he_conv_block, but every (O, I) block is finished on its own:
+ *   block_I = sum_gam Perm_gam( sum_tap ScMult(Xrot[I][tap], pt[O][gam][I][tap]) ),   out = sum_I block_I - mask,
+ * i.e. c_n - 1 Perm per block instead of per output ciphertext. */
+void orc_he_conv_outrot_block(const orc_ctx *c, const u64 *K, int co, int ci, int kh, int kw, int uh, int uw,
+                              int O, const u64 *cts /* nin x 2n */, const u64 *tap_ksk, const u64 *grp_ksk,
+                              const u64 *mask_slots, u64 *xrot, int *xrot_ready, u64 *out, orc_counts *cnt) {
+    cv_geom g; cv_geometry(c, co, ci, kh, kw, uh, uw, &g);
+    int n = g.n, centre = (kh / 2) * kw + kw / 2;
+    size_t ksz = (size_t)c->ndigits * orc_key_polys(c) * n, ctsz = 2 * (size_t)n;
+    u64 *own = NULL;
+    if (!xrot) { own = malloc(sizeof(u64) * ctsz * g.nin * g.ntap); xrot = own; }
+    if (own || !*xrot_ready) {
+        u64 *digits = malloc(sizeof(u64) * (size_t)c->ndigits * n);
+        for (int I = 0; I < g.nin; I++) {
+            const u64 *ct = cts + I * ctsz;
+            if (g.ntap > 1) { orc_decperm(c, ct + n, digits); if (cnt) cnt->decperm_in++; }
+            for (int tap = 0, kidx = 0; tap < g.ntap; tap++) {
+                u64 *dst = xrot + ((size_t)I * g.ntap + tap) * ctsz;
+                if (tap == centre) { memcpy(dst, ct, sizeof(u64) * ctsz); continue; }
+                orc_hstperm(c, ct, digits, orc_galois_elt(c, 0, cv_tap_offset(&g, tap)), tap_ksk + kidx * ksz, dst);
+                if (cnt) cnt->hstperm_in++;
+                kidx++;
+            }
+        }
+        free(digits);
+        if (xrot_ready) *xrot_ready = 1;
+    }
+    u64 *slots = malloc(sizeof(u64) * n), *w = malloc(sizeof(u64) * n);
+    u64 *u = malloc(sizeof(u64) * ctsz), *acc = malloc(sizeof(u64) * ctsz), *blk = malloc(sizeof(u64) * ctsz);
+    u64 *tot = malloc(sizeof(u64) * ctsz);
+    for (int I = 0; I < g.nin; I++) {
+        for (int gam = 0; gam < g.cn; gam++) {
+            for (int tap = 0; tap < g.ntap; tap++) {
+                orc_conv_weight_slots(c, K, co, ci, kh, kw, uh, uw, O, gam, I, tap, slots);
+                orc_encode_weight(c, slots, w);
+                orc_scmult(c, xrot + ((size_t)I * g.ntap + tap) * ctsz, w, u); if (cnt) cnt->scmult++;
+                if (tap == 0) memcpy(acc, u, sizeof(u64) * ctsz);
+                else { orc_add(c, acc, u, acc); if (cnt) cnt->add++; }
+            }
+            if (gam == 0) { memcpy(blk, acc, sizeof(u64) * ctsz); continue; }
+            orc_perm(c, acc, orc_galois_elt(c, gam / g.hpos, (gam % g.hpos) * g.T), grp_ksk + (size_t)(gam - 1) * ksz, u);
+            if (cnt) cnt->perm++;
+            orc_add(c, blk, u, blk); if (cnt) cnt->add++;
+        }
+        if (I == 0) memcpy(tot, blk, sizeof(u64) * ctsz);
+        else { orc_add(c, tot, blk, tot); if (cnt) cnt->add++; }
+    }
+    orc_sub_plain(c, tot, mask_slots, out);
+    free(slots); free(w); free(u); free(acc); free(blk); free(tot); free(own);
+}
+
+/* ------------------------------------------------------------------ */
 /* batches: independent inputs, one OpenMP thread each                  */
 /* ------------------------------------------------------------------ */
 #ifdef _OPENMP

@@ -225,6 +225,57 @@ class Oracle:
                                C.c_uint64(mask_seed), _p(out), C.byref(cnt))
         return out, cnt.as_dict()
 
+    # ---- comparison schedules (Sec. III-A(2) hybrid FC, Sec. III-B(2) output-rotation convolution)
+    def fc_hybrid_G(self, n_o, n_i):
+        return int(self.L.orc_fc_hybrid_G(self.h, n_o, n_i))
+
+    def fc_hybrid_ras(self, n_o, n_i):
+        """The rotate-and-sum rotations (swap, step) in order."""
+        sw, st = (C.c_int * 32)(), (C.c_int * 32)()
+        k = self.L.orc_fc_hybrid_ras(self.h, n_o, n_i, sw, st)
+        if k < 0:
+            raise ValueError("oracle: FC shape not supported")
+        return [(sw[i], st[i]) for i in range(k)]
+
+    def fc_hybrid_weight_slots(self, W, g):
+        W = _u64(W); out = np.empty(self.n, np.uint64)
+        self.L.orc_fc_hybrid_weight_slots(self.h, _p(W), W.shape[0], W.shape[1], g, _p(out)); return out
+
+    def fc_hybrid_encode(self, W):
+        W = _u64(W); G = self.fc_hybrid_G(*W.shape); out = np.empty((G, self.n), np.uint64)
+        self.L.orc_fc_hybrid_encode(self.h, _p(W), W.shape[0], W.shape[1], _p(out)); return out
+
+    def fc_hybrid_unpack(self, n_o, n_i, slots):
+        s = _u64(slots); out = np.empty(n_o, np.uint64)
+        self.L.orc_fc_hybrid_unpack(self.h, n_o, n_i, _p(s), _p(out)); return out
+
+    def fc_hybrid_mask_slots(self, n_o, n_i, r, seed, b):
+        r = _u64(r); out = np.empty(self.n, np.uint64)
+        self.L.orc_fc_hybrid_mask_slots(self.h, n_o, n_i, _p(r), C.c_uint64(seed), int(b), _p(out)); return out
+
+    def fc_hybrid_keys(self, sk, n_o, n_i, seed):
+        """(keys of the input rotations g = 1..G-1, keys of the rotate-and-sum rotations), each concatenated."""
+        G = self.fc_hybrid_G(n_o, n_i)
+        cat = lambda l: np.concatenate(l) if l else np.zeros(0, np.uint64)
+        return (cat([self.galois_key(sk, self.galois_elt(0, g), seed) for g in range(1, G)]),
+                cat([self.galois_key(sk, self.galois_elt(s, t), seed) for s, t in self.fc_hybrid_ras(n_o, n_i)]))
+
+    def he_fc_hybrid(self, wpoly, n_o, n_i, ct, ksk_in, ksk_ras, mask_slots):
+        wpoly, ct, ki, kr, m = _u64(wpoly), _u64(ct), _u64(ksk_in), _u64(ksk_ras), _u64(mask_slots)
+        out = np.empty(2 * self.n, np.uint64); cnt = Counts()
+        self.L.orc_he_fc_hybrid(self.h, _p(wpoly), n_o, n_i, _p(ct), _p(ki), _p(kr), _p(m), _p(out), C.byref(cnt))
+        return out, cnt.as_dict()
+
+    def he_conv_outrot_block(self, shape, K, O, cts, tap_ksk, grp_ksk, mask_slots, xrot=None, ready=None):
+        """One output ciphertext O by the output-rotation schedule; arguments as he_conv_block."""
+        co, ci, kh, kw, uh, uw = shape
+        K, cts, tk, gk, m = _u64(K), _u64(cts), _u64(tap_ksk), _u64(grp_ksk), _u64(mask_slots)
+        out = np.empty(2 * self.n, np.uint64); cnt = Counts()
+        self.L.orc_he_conv_outrot_block(self.h, _p(K), co, ci, kh, kw, uh, uw, int(O), _p(cts), _p(tk), _p(gk), _p(m),
+                                        _p(xrot) if xrot is not None else None,
+                                        C.byref(ready) if ready is not None else None, _p(out), C.byref(cnt))
+        return out, cnt.as_dict()
+
     def max_threads(self):
         return int(self.L.orc_max_threads())
 
