@@ -201,7 +201,7 @@ def host_threads(o):
 
 # ---- he_fc -------------------------------------------------------------------------------------------------------
 def fc_config(ctx, sk, D, torch, par, shape, steps, prewarm_s, cpu_sample, cpu_repeat, special=False, mask_seed=17,
-              warmup=0):
+              warmup=0, compare=True):
     """One he_fc workload: wall time per layer, the rotate-and-accumulate kernel's HIP-event times, its roofline,
     and the oracle on `cpu_sample` of the inputs.  Returns (record, state for the headline)."""
     from paper_2105_01827_amd import workloads as wl
@@ -243,11 +243,36 @@ def fc_config(ctx, sk, D, torch, par, shape, steps, prewarm_s, cpu_sample, cpu_r
         roof = alu_roofline(kernel, kms, batch, 2 * par.n * OPS_CONST_MUL + inverse + forward + par.n * OPS_CONST_MUL,
                             11 * par.n + 3 * par.n,
                             note="latency-bound: one input is two workgroups of work; the figure is the launch's duration")
+    gazelle = None
+    if compare:
+        # the paper's comparison schedule (hybrid method, Sec. III-A(2)) on the same kernels and inputs
+        hplan = ctx.fc_hybrid_plan(W)
+        hgk = ctx.galois_keygen(sk, hplan.rotations(), seed=1)
+        hplan.bind(hgk)
+        h_out = D.dev_empty(batch * 2 * par.n)
+        h_wsb = hplan.workspace_bytes(batch)
+        h_ws = torch.empty(h_wsb, dtype=torch.uint8, device="cuda")
+        hcnt = {}
+
+        def hstep():
+            hcnt.update(hplan.he_fc_hybrid(d_in, batch, d_r, mask_seed, h_out, h_ws, h_wsb, stream=stream))
+
+        prewarm(hstep, torch, min(prewarm_s, 0.2))
+        hms = wall_ms(hstep, torch, max(5, steps // 4))
+        gazelle = {"schedule": "hybrid matrix-vector product (Sec. III-A(2)), same kernels, same inputs",
+                   "ms_per_layer": hms, "ops_per_layer": dict(hcnt), "gala_speedup": hms / ms,
+                   "decrypts": bool(special) or hplan.G == 1,
+                   "note": "the rotate-and-sum Perms of one input depend on each other: log2(n/n_o) launches of `batch` "
+                           "workgroups each"}
+        if shape.name == "fc_16x128_b1":
+            gazelle["paper_speedup"] = {"value": 19, "where": "Table 'Runtime cost of matrix-vector multiplication', "
+                                                              "16x128, LAN, Intel i7-8700 (another machine)"}
+        del hplan, hgk, h_out, h_ws
     rec = {"workload": shape.name, "layer": "he_fc", "n_o": shape.n_o, "n_i": shape.n_i, "batch": batch, "G": G,
            "key_switching": "special prime" if special else "one prime", "decrypts": True,
            "steps": steps, "prewarm_ms": pre, "ms_per_layer": ms, "layers_per_s": 1e3 / ms,
            "inputs_per_s": batch * 1e3 / ms, "rotations_per_s": cnt["perm"] * 1e3 / ms, "ops_per_layer": dict(cnt),
-           "roofline": roof, "cpu_baseline": None}
+           "roofline": roof, "cpu_baseline": None, "gazelle_schedule": gazelle}
     if cpu_sample:
         o, osk = oracle_for(par)
         got = D.export_cts(ctx, d_out, batch)
@@ -272,7 +297,8 @@ def fc_config(ctx, sk, D, torch, par, shape, steps, prewarm_s, cpu_sample, cpu_r
 
 
 # ---- he_conv -----------------------------------------------------------------------------------------------------
-def conv_config(ctx, sk, D, torch, par, shape, steps, prewarm_s, cpu_blocks, special=False, vector_mac=False, warmup=0):
+def conv_config(ctx, sk, D, torch, par, shape, steps, prewarm_s, cpu_blocks, special=False, vector_mac=False, warmup=0,
+                compare=True):
     from paper_2105_01827_amd import workloads as wl
     K, x, r = wl.conv_inputs(shape)
     plan = ctx.conv_plan(K, shape.u_h, shape.u_w)
@@ -330,6 +356,25 @@ def conv_config(ctx, sk, D, torch, par, shape, steps, prewarm_s, cpu_blocks, spe
         kernels.append(alu_roofline("perm_accumulate_2048", k_perm, cnt["perm"],
                                     ops_per_fused_perm(n, 11, nd) - 2 * n * OPS_CONST_MUL,      # no ScMult in these units
                                     modmuls_per_fused_perm(n, 11, nd, scmult=False)))
+    gazelle = None
+    if compare:
+        # the paper's comparison schedule (output rotation, Sec. III-B(2)) on the same plan, keys and inputs
+        o_out = D.dev_empty(batch * plan.nout * 2 * par.n)
+        o_wsb = plan.outrot_workspace_bytes(batch)
+        o_ws = torch.empty(o_wsb, dtype=torch.uint8, device="cuda")
+        ocnt_g = {}
+
+        def ostep():
+            ocnt_g.update(plan.he_conv_outrot(d_in, batch, d_r, 3, o_out, o_ws, o_wsb, stream=stream))
+
+        prewarm(ostep, torch, min(prewarm_s, 0.2))
+        oms = wall_ms(ostep, torch, max(5, steps // 4))
+        gazelle = {"schedule": "output-rotation MIMO convolution (Sec. III-B(2)), same plan, keys and inputs; "
+                               "multiply-accumulate on the vector ALU",
+                   "ms_per_layer": oms, "ops_per_layer": dict(ocnt_g), "gala_speedup": oms / ms,
+                   "paper_speedup": {"value": 2.6, "where": "Table 'Runtime cost of convolution', 16x16@128 with 3x3@128, "
+                                                            "LAN, Intel i7-8700 (another machine)"}}
+        del o_out, o_ws
     dominant = max(kernels, key=lambda k: k["kernel_ms_avg"] or 0.0)
     rotations = cnt["perm"] + cnt["hstperm_in"]
     rec = {"workload": shape.name, "layer": "he_conv", "c_o": shape.c_o, "c_i": shape.c_i, "k": shape.k_h,
@@ -341,7 +386,7 @@ def conv_config(ctx, sk, D, torch, par, shape, steps, prewarm_s, cpu_blocks, spe
            "decrypts": bool(special) or shape.k_h * shape.k_w == 1,
            "steps": steps, "prewarm_ms": pre, "ms_per_layer": ms, "layers_per_s": 1e3 / ms,
            "inputs_per_s": batch * 1e3 / ms, "rotations_per_s": rotations * 1e3 / ms, "ops_per_layer": dict(cnt),
-           "roofline": dominant, "kernels": kernels, "cpu_baseline": None}
+           "roofline": dominant, "kernels": kernels, "cpu_baseline": None, "gazelle_schedule": gazelle}
     if cpu_blocks:
         o, osk = oracle_for(par)
         got = D.export_cts(ctx, d_out, batch * plan.nout).reshape(batch, plan.nout, 2 * n)
@@ -646,7 +691,7 @@ def main():
            "config": cfg, "layers_per_s": head["layers_per_s"],
            "ops_per_step": head.get("ops_per_layer") or head.get("ops_per_network"),
            "roofline": head["roofline"], "cpu_baseline": head["cpu_baseline"]}
-    for k in ("inputs_per_s", "kernels", "per_layer", "ms_per_network_eager", "ms_per_network_graph_replay",
+    for k in ("inputs_per_s", "gazelle_schedule", "kernels", "per_layer", "ms_per_network_eager", "ms_per_network_graph_replay",
               "graph_replay_equals_eager", "ms_sum_of_layers_timed_alone", "networks_per_s"):
         if k in head:
             out[k] = head[k]
@@ -663,7 +708,7 @@ def main():
             sp = wl.DEFAULT_SPECIAL
             ctx_s = binding.Context(sp.n, sp.q, sp.p, sp.gadget_bits, sp.special)
             others["conv_16x16x128_3x3x128_b16_special_prime"] = conv_config(
-                ctx_s, ctx_s.keygen(0), D, torch, sp, wl.CONV_16x16_128_3x3, 50, args.prewarm_s, 0, special=True)
+                ctx_s, ctx_s.keygen(0), D, torch, sp, wl.CONV_16x16_128_3x3, 50, args.prewarm_s, 0, special=True, compare=False)
             out["also"] = entry_points(ctx, sk, D, torch, par)
     print(json.dumps(out))
 

@@ -295,6 +295,44 @@ int gala_he_conv(const gala_ctx *ctx, void *stream, const gala_conv_plan *plan, 
                  const uint64_t *r, uint64_t mask_seed, uint64_t *ct_out, void *workspace, size_t workspace_bytes,
                  gala_opcount *counts);
 
+/* ---- the paper's comparison schedules on the same operations ------------------------------------------------
+ * The two schedules GALA is measured against in Sec. IV-A, built from the same kernels so that the ratio of the
+ * schedules can be measured on one device.  Results decrypt to the same W x and the same convolution.
+ *
+ * Hybrid matrix-vector product (Sec. III-A(2)): the input ciphertext is rotated by 1..G-1 (HstPerm with one common
+ * DecPerm), each rotation is multiplied by one diagonal vector of W (ScMult) and the products are added; then
+ * log2(n / n_o) rotate-and-sum steps, each a Perm and an Add on the running ciphertext, leave output t in one slot;
+ * the mask (r[t] at that slot, a generator draw in every other slot) is subtracted.  G = max(1, n_i n_o / n).
+ * Shapes as for gala_fc_plan_create; the input is packed as for he_fc (gala_fc_hybrid_pack_input gives the same
+ * slot vector as gala_fc_pack_input); gala_fc_hybrid_unpack reads the n_o result slots of a decrypted vector.
+ * gala_fc_hybrid_plan_rotations lists the input rotations and the rotate-and-sum rotations (GALA_ENOKEY from
+ * bind if one is missing).  Because the input is rotated before ScMult, results decrypt only when the rotation
+ * noise times the weights stays below delta / 2 (Sec. III-C): for G > 1 at a 20-bit p this needs special-prime keys. */
+typedef struct gala_fc_hybrid_plan gala_fc_hybrid_plan;
+int gala_fc_hybrid_plan_create(gala_ctx *ctx, const uint64_t *W, int n_o, int n_i, gala_fc_hybrid_plan **out);
+void gala_fc_hybrid_plan_destroy(gala_fc_hybrid_plan *plan);
+int gala_fc_hybrid_plan_G(const gala_fc_hybrid_plan *plan);
+int gala_fc_hybrid_plan_steps(const gala_fc_hybrid_plan *plan);      /* rotate-and-sum steps = Perms per input */
+int gala_fc_hybrid_plan_rotations(const gala_fc_hybrid_plan *plan, gala_rot *rots, int *nrots);
+int gala_fc_hybrid_plan_bind(gala_fc_hybrid_plan *plan, const gala_gk *gk);
+int gala_fc_hybrid_pack_input(const gala_fc_hybrid_plan *plan, const uint64_t *x /* n_i */, uint64_t *slots /* n */);
+int gala_fc_hybrid_unpack(const gala_fc_hybrid_plan *plan, const uint64_t *slots /* n */, uint64_t *out /* n_o */);
+size_t gala_he_fc_hybrid_workspace(const gala_fc_hybrid_plan *plan, int batch);
+/* Arguments as gala_he_fc.  The rotate-and-sum steps of one input depend on each other, so a call runs them as
+ * log2(n / n_o) launches of `batch` workgroups each. */
+int gala_he_fc_hybrid(const gala_ctx *ctx, void *stream, const gala_fc_hybrid_plan *plan, const uint64_t *ct_in, int batch,
+                      const uint64_t *r, uint64_t mask_seed, uint64_t *ct_out, void *workspace, size_t workspace_bytes,
+                      gala_opcount *counts);
+/* Output-rotation MIMO convolution (Sec. III-B(2)) on a gala_conv_plan: the same packing, encoded kernels, input
+ * rotations, keys and mask as gala_he_conv, but the products of every input ciphertext are summed on their own and
+ * every (output ciphertext, input ciphertext, kernel order) sum is rotated before the additions, i.e.
+ * c_i c_o (c_n - 1) / c_n^2 Perms instead of c_o (c_n - 1) / c_n.  Arguments as gala_he_conv (the multiply-accumulate
+ * runs on the vector ALU). */
+size_t gala_he_conv_outrot_workspace(const gala_conv_plan *plan, int batch);
+int gala_he_conv_outrot(const gala_ctx *ctx, void *stream, const gala_conv_plan *plan, const uint64_t *ct_in, int batch,
+                        const uint64_t *r, uint64_t mask_seed, uint64_t *ct_out, void *workspace, size_t workspace_bytes,
+                        gala_opcount *counts);
+
 /* ---- spatial tiling and stride for images larger than half a ciphertext (host) ---- */
 /* The paper assumes u_w*u_h fits a ciphertext (Sec. III-B(1), footnote) and never mentions stride.
  * Here an in_h x in_w image is cut into overlapping tile_h x tile_w tiles (tile_h*tile_w <= n/2) whose

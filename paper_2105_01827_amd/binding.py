@@ -118,6 +118,18 @@ SIGNATURES = {
     "gala_conv_unpack_share": (_I, [_VP, _I, _U64P, _U64P]),
     "gala_he_conv_workspace": (C.c_size_t, [_VP, _I]),
     "gala_he_conv": (_I, [_VP, _VP, _VP, _U64P, _I, _U64P, C.c_uint64, _U64P, _VP, C.c_size_t, C.POINTER(OpCount)]),
+    "gala_fc_hybrid_plan_create": (_I, [_VP, _U64P, _I, _I, C.POINTER(_VP)]),
+    "gala_fc_hybrid_plan_destroy": (None, [_VP]),
+    "gala_fc_hybrid_plan_G": (_I, [_VP]),
+    "gala_fc_hybrid_plan_steps": (_I, [_VP]),
+    "gala_fc_hybrid_plan_rotations": (_I, [_VP, C.POINTER(Rot), C.POINTER(_I)]),
+    "gala_fc_hybrid_plan_bind": (_I, [_VP, _VP]),
+    "gala_fc_hybrid_pack_input": (_I, [_VP, _U64P, _U64P]),
+    "gala_fc_hybrid_unpack": (_I, [_VP, _U64P, _U64P]),
+    "gala_he_fc_hybrid_workspace": (C.c_size_t, [_VP, _I]),
+    "gala_he_fc_hybrid": (_I, [_VP, _VP, _VP, _U64P, _I, _U64P, C.c_uint64, _U64P, _VP, C.c_size_t, C.POINTER(OpCount)]),
+    "gala_he_conv_outrot_workspace": (C.c_size_t, [_VP, _I]),
+    "gala_he_conv_outrot": (_I, [_VP, _VP, _VP, _U64P, _I, _U64P, C.c_uint64, _U64P, _VP, C.c_size_t, C.POINTER(OpCount)]),
     "gala_conv_tiling_plan": (_I, [_VP, _I, _I, _I, _I, _I, C.POINTER(ConvTiling)]),
     "gala_conv_tile_extract": (_I, [C.POINTER(ConvTiling), _I, _U64P, _I, _U64P]),
     "gala_conv_tile_mask": (_I, [C.POINTER(ConvTiling), _I, _U64P, _I, _U64P]),
@@ -336,6 +348,9 @@ class Context:
     def conv_plan(self, K, u_h, u_w):
         return ConvPlan(self, K, u_h, u_w)
 
+    def fc_hybrid_plan(self, W):
+        return FcHybridPlan(self, W)
+
 
 class SecretKey:
     def __init__(self, ctx, seed):
@@ -436,6 +451,56 @@ class FcPlan:
             self.h = None
 
 
+class FcHybridPlan:
+    """gala_fc_hybrid_plan: the hybrid matrix-vector product of Sec. III-A(2), the paper's comparison schedule."""
+
+    def __init__(self, ctx, W):
+        self.ctx = ctx
+        W, wp = _host(W)
+        self.n_o, self.n_i = W.shape
+        h = C.c_void_p()
+        _check(ctx.lib.gala_fc_hybrid_plan_create(ctx.h, wp, self.n_o, self.n_i, C.byref(h)), "gala_fc_hybrid_plan_create")
+        self.h = h
+        self.G = ctx.lib.gala_fc_hybrid_plan_G(h)
+        self.steps = ctx.lib.gala_fc_hybrid_plan_steps(h)
+
+    def rotations(self):
+        n = C.c_int()
+        _check(self.ctx.lib.gala_fc_hybrid_plan_rotations(self.h, None, C.byref(n)), "gala_fc_hybrid_plan_rotations")
+        arr = (Rot * max(1, n.value))()
+        _check(self.ctx.lib.gala_fc_hybrid_plan_rotations(self.h, arr, C.byref(n)), "gala_fc_hybrid_plan_rotations")
+        return [(arr[i].swap, arr[i].step) for i in range(n.value)]
+
+    def bind(self, gk):
+        _check(self.ctx.lib.gala_fc_hybrid_plan_bind(self.h, gk.h), "gala_fc_hybrid_plan_bind")
+        self._gk = gk
+
+    def pack_input(self, x):
+        x, xp = _host(x); out = np.empty(self.ctx.n, np.uint64)
+        _check(self.ctx.lib.gala_fc_hybrid_pack_input(self.h, xp, out.ctypes.data_as(C.c_void_p)), "gala_fc_hybrid_pack_input")
+        return out
+
+    def unpack(self, slots):
+        s, sp = _host(slots); out = np.empty(self.n_o, np.uint64)
+        _check(self.ctx.lib.gala_fc_hybrid_unpack(self.h, sp, out.ctypes.data_as(C.c_void_p)), "gala_fc_hybrid_unpack")
+        return out
+
+    def workspace_bytes(self, batch):
+        return int(self.ctx.lib.gala_he_fc_hybrid_workspace(self.h, batch))
+
+    def he_fc_hybrid(self, ct_in, batch, r, mask_seed, ct_out, workspace, workspace_bytes, stream=None):
+        cnt = OpCount()
+        _check(self.ctx.lib.gala_he_fc_hybrid(self.ctx.h, _stream(stream), self.h, _dev(ct_in), batch, _dev(r), mask_seed,
+                                              _dev(ct_out), _dev(workspace), workspace_bytes, C.byref(cnt)),
+               "gala_he_fc_hybrid")
+        return cnt.as_dict()
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            self.ctx.lib.gala_fc_hybrid_plan_destroy(self.h)
+            self.h = None
+
+
 class ConvPlan:
     """gala_conv_plan: the kernel-grouping encoding of one convolution layer."""
 
@@ -483,6 +548,16 @@ class ConvPlan:
 
     def workspace_bytes(self, batch):
         return int(self.ctx.lib.gala_he_conv_workspace(self.h, batch))
+
+    def outrot_workspace_bytes(self, batch):
+        return int(self.ctx.lib.gala_he_conv_outrot_workspace(self.h, batch))
+
+    def he_conv_outrot(self, ct_in, batch, r, mask_seed, ct_out, workspace, workspace_bytes, stream=None):
+        cnt = OpCount()
+        _check(self.ctx.lib.gala_he_conv_outrot(self.ctx.h, _stream(stream), self.h, _dev(ct_in), batch, _dev(r), mask_seed,
+                                                _dev(ct_out), _dev(workspace), workspace_bytes, C.byref(cnt)),
+               "gala_he_conv_outrot")
+        return cnt.as_dict()
 
     def he_conv(self, ct_in, batch, r, mask_seed, ct_out, workspace, workspace_bytes, stream=None):
         cnt = OpCount()

@@ -454,3 +454,165 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
     }
     return GALA_OK;
 }
+
+// ---------------------------------------------------------------------------
+// The paper's comparison schedules on the same kernels (Sec. III-A(2), Sec. III-B(2))
+// ---------------------------------------------------------------------------
+namespace {
+struct HybridWorkspace {
+    size_t digits, xrot, s0, s1, total;
+};
+HybridWorkspace hybrid_workspace(const gala_fc_hybrid_plan *pl, int batch) {
+    const gala_ctx *c = pl->ctx;
+    const size_t ct = 2 * (size_t)c->n * sizeof(u64);
+    HybridWorkspace ws{};
+    ws.digits = 0;
+    ws.xrot = ws.digits + (pl->G > 1 ? hoist_digit_bytes(c, (size_t)batch) : 0);
+    ws.s0 = ws.xrot + (pl->G > 1 ? align_up((size_t)batch * pl->G * ct) : 0);
+    ws.s1 = ws.s0 + align_up((size_t)batch * 2 * ct);      // two partial ciphertexts per item in the last step
+    ws.total = ws.s1 + align_up((size_t)batch * 2 * ct);
+    return ws;
+}
+}  // namespace
+
+extern "C" size_t gala_he_fc_hybrid_workspace(const gala_fc_hybrid_plan *pl, int batch) {
+    return (!pl || batch <= 0) ? 0 : hybrid_workspace(pl, batch).total;
+}
+// out = RaS( sum_g ScMult(HstPerm_g(ct), w_g) ) - mask: the input rotations share one DecPerm (gala_rotate_hoisted's
+// kernels), the products are summed by the convolution's multiply-accumulate with a single row, and every
+// rotate-and-sum step is one launch of the rotate-and-accumulate kernel over the pair (identity, rotation) of the
+// running ciphertext; the last step also builds and subtracts the mask.
+extern "C" int gala_he_fc_hybrid(const gala_ctx *c, void *stream, const gala_fc_hybrid_plan *pl, const uint64_t *ct_in,
+                                 int batch, const uint64_t *r, uint64_t mask_seed, uint64_t *ct_out, void *workspace,
+                                 size_t workspace_bytes, gala_opcount *counts) {
+    if (!c || !pl || pl->ctx != c || !ct_in || !ct_out || !r || batch <= 0) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    const int steps = (int)pl->ras_gal.size(), G = pl->G, n = c->n;
+    if ((G > 1 || steps > 0) && !pl->bound) return GALA_ENOKEY;
+    const HybridWorkspace ws = hybrid_workspace(pl, batch);
+    if (!workspace || workspace_bytes < ws.total) return GALA_ENOMEM;
+    char *base = (char *)workspace;
+    u64 *digits = (u64 *)(base + ws.digits), *xrot = (u64 *)(base + ws.xrot);
+    u64 *buf[2] = {(u64 *)(base + ws.s0), (u64 *)(base + ws.s1)};
+    const u64 *keys = pl->bound ? pl->bound->d_keys : nullptr, *keys2 = pl->bound ? pl->bound->d_keys2 : nullptr;
+    const int which = c->prof_which;     // the measurement aid brackets the rotate-and-sum launches only
+    const u64 *mac_in = ct_in;
+    if (G > 1) {
+        const TermList terms{1, G, pl->d_in_ct, pl->d_in_gal, pl->d_in_key};
+        c->prof_which = -1;
+        const int rc = hoist_terms(c, stream, ct_in, batch, terms, true, keys, keys2, digits, xrot);
+        c->prof_which = which;
+        if (rc) return GALA_EHIP;
+        mac_in = xrot;
+    }
+    if (launch_conv_mac(c, stream, pl->d_w, mac_in, batch, 1, 1, G, buf[0])) return GALA_EHIP;
+    int cur = 0;
+    for (int k = 0; k < std::max(steps, 1); ++k) {
+        const bool last = k + 1 >= steps;
+        PermJob job{};
+        job.ct_in = buf[cur];
+        job.in_item_stride = 2 * (size_t)n;
+        job.in_g_stride = 0;                       // both entries read the running ciphertext
+        job.w = nullptr;
+        job.gal = pl->d_ras_gal + 2 * k; job.key_idx = pl->d_ras_key + 2 * k;
+        job.keys = keys; job.keys2 = keys2;
+        job.G = steps ? 2 : 1; job.items = batch; job.nchunks = 1;
+        job.slots = last ? 2 : 1;
+        job.partial = buf[cur ^ 1];
+        if (!last) {
+            if (launch_perm_accumulate(c, stream, job)) return GALA_EHIP;
+        } else {
+            FinalizeJob fin{};
+            fin.partial = job.partial;
+            fin.items = batch; fin.nchunks = 1; fin.slots = 2; fin.nout = 1;
+            fin.r = r; fin.r_stride = (size_t)pl->n_o;
+            fin.mask_seed = mask_seed;
+            fin.mask = pl->mask_d;
+            fin.ct_out = ct_out;
+            if (launch_perm_finalize(c, stream, job, fin)) return GALA_EHIP;
+        }
+        cur ^= 1;
+    }
+    if (counts) {
+        counts->perm = (int64_t)batch * steps;
+        counts->decperm_in = G > 1 ? batch : 0;
+        counts->hstperm_in = (int64_t)batch * (G - 1);
+        counts->scmult = (int64_t)batch * G;
+        counts->add = (int64_t)batch * (G - 1 + steps);
+    }
+    return GALA_OK;
+}
+
+namespace {
+struct OutrotWorkspace {
+    size_t digits, xrot, acc, partial, total;
+    int chunks;
+};
+OutrotWorkspace outrot_workspace(const gala_conv_plan *pl, int batch) {
+    const gala_ctx *c = pl->ctx;
+    const size_t ct = 2 * (size_t)c->n * sizeof(u64);
+    OutrotWorkspace ws{};
+    ws.chunks = choose_chunks(c, batch * pl->nout, pl->cn * pl->nin);
+    ws.digits = 0;
+    ws.xrot = ws.digits + hoist_digit_bytes(c, (size_t)batch * pl->nin);
+    ws.acc = ws.xrot + align_up((size_t)batch * pl->nterm * ct);
+    ws.partial = ws.acc + align_up((size_t)batch * pl->nout * pl->cn * pl->nin * ct);
+    ws.total = ws.partial + align_up((size_t)batch * pl->nout * (ws.chunks + 1) * ct);
+    return ws;
+}
+}  // namespace
+
+extern "C" size_t gala_he_conv_outrot_workspace(const gala_conv_plan *pl, int batch) {
+    return (!pl || batch <= 0) ? 0 : outrot_workspace(pl, batch).total;
+}
+// The same plan, keys, input rotations and encoded kernels as gala_he_conv; the products are summed per input
+// ciphertext (segments of the term list) and every (output ciphertext, input ciphertext, kernel order) sum is rotated
+// on its own before the additions: nin times the Perms of gala_he_conv.
+extern "C" int gala_he_conv_outrot(const gala_ctx *c, void *stream, const gala_conv_plan *pl, const uint64_t *ct_in,
+                                   int batch, const uint64_t *r, uint64_t mask_seed, uint64_t *ct_out, void *workspace,
+                                   size_t workspace_bytes, gala_opcount *counts) {
+    if (!c || !pl || pl->ctx != c || !ct_in || !ct_out || !r || batch <= 0) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    if ((pl->nrot_terms > 0 || pl->cn > 1) && !pl->bound) return GALA_ENOKEY;
+    const OutrotWorkspace ws = outrot_workspace(pl, batch);
+    if (!workspace || workspace_bytes < ws.total) return GALA_ENOMEM;
+    char *base = (char *)workspace;
+    u64 *digits = (u64 *)(base + ws.digits), *xrot = (u64 *)(base + ws.xrot), *acc = (u64 *)(base + ws.acc),
+        *partial = (u64 *)(base + ws.partial);
+    const int n = c->n, nin = pl->nin;
+    const u64 *keys = pl->bound ? pl->bound->d_keys : nullptr, *keys2 = pl->bound ? pl->bound->d_keys2 : nullptr;
+    const TermList terms{nin, pl->nterm, pl->d_term_ct, pl->d_term_gal, pl->d_term_key};
+    const int which = c->prof_which;
+    c->prof_which = -1;
+    const int rc = hoist_terms(c, stream, ct_in, batch, terms, pl->nrot_terms > 0, keys, keys2, digits, xrot);
+    c->prof_which = which;
+    if (rc) return GALA_EHIP;
+    if (launch_conv_mac(c, stream, pl->d_w, xrot, batch, pl->nout, pl->cn, pl->nterm, acc, pl->d_seg_ptr, nin))
+        return GALA_EHIP;
+    PermJob job{};
+    job.ct_in = acc;
+    job.in_item_stride = (size_t)pl->cn * nin * 2 * n;
+    job.in_g_stride = 2 * (size_t)n;
+    job.w = nullptr;
+    job.gal = pl->d_or_gal; job.key_idx = pl->d_or_key;
+    job.keys = keys; job.keys2 = keys2;
+    job.G = pl->cn * nin; job.items = batch * pl->nout; job.nchunks = ws.chunks; job.slots = ws.chunks + 1;
+    job.partial = partial;
+    FinalizeJob fin{};
+    fin.partial = partial;
+    fin.items = job.items; fin.nchunks = ws.chunks; fin.slots = ws.chunks + 1; fin.nout = pl->nout;
+    fin.r = r; fin.r_stride = (size_t)pl->c_o * pl->u_h * pl->u_w;
+    fin.mask_seed = mask_seed;
+    fin.mask = pl->mask_d;
+    fin.ct_out = ct_out;
+    if (launch_perm_finalize(c, stream, job, fin)) return GALA_EHIP;
+    if (counts) {
+        const int64_t nt = pl->nterm;
+        counts->decperm_in = (int64_t)batch * pl->nrot_cts;
+        counts->hstperm_in = (int64_t)batch * pl->nrot_terms;
+        counts->scmult = (int64_t)batch * pl->nout * pl->cn * nt;
+        counts->perm = (int64_t)batch * pl->nout * nin * (pl->cn - 1);
+        counts->add = (int64_t)batch * pl->nout * (pl->cn * (nt - nin) + nin * (pl->cn - 1) + (nin - 1));
+    }
+    return GALA_OK;
+}

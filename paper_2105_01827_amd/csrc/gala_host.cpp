@@ -753,6 +753,116 @@ extern "C" int gala_fc_unpack_share(const gala_fc_plan *pl, const uint64_t *slot
 }
 
 // ===========================================================================
+// hybrid FC plan (Sec. III-A(2)): the comparison schedule, on the same operations
+// ===========================================================================
+// Layout on the 2 x n/2 slot torus.  n_i <= n/2: every half-row holds n/(2 n_i) copies of x; copy c owns the
+// R = max(1, n_i n_o / n) output rows c*R .. c*R+R-1 and slot j of the copy collects row c*R + (j mod R); the G = R
+// diagonal vectors w_g[(h,k)] = W[row(h,k)][(j+g) mod n_i] multiply the input rotated left by g, and rotate-and-sum
+// steps by n_i/2, .., R finish row c*R + j in slot j < R of copy c.  n_i = n: half h holds x[h*n/2 ..], slot (h,k)
+// collects row k mod n_o over the columns of its half (G = n_o), steps by n/4, .., n_o and one row swap.
+namespace {
+int hy_slot_row(const gala_fc_hybrid_plan *pl, int h, int k) {
+    const int n = pl->ctx->n, half = n / 2;
+    if (pl->big) return k % pl->nop;
+    const int copy = h * (half / pl->nip) + k / pl->nip, j = k % pl->nip;
+    if ((long)pl->nip * pl->nop < n && copy >= pl->nop) return -1;
+    return copy * pl->R + j % pl->R;
+}
+}  // namespace
+extern "C" int gala_fc_hybrid_plan_create(gala_ctx *c, const uint64_t *W, int n_o, int n_i, gala_fc_hybrid_plan **out) {
+    if (!c || !W || !out || n_o < 1 || n_i < 1) return GALA_EARG;
+    if (!c->has_device) return GALA_EHIP;
+    const int n = c->n, half = n / 2;
+    gala_fc_hybrid_plan *pl = new (std::nothrow) gala_fc_hybrid_plan;
+    if (!pl) return GALA_ENOMEM;
+    pl->ctx = c; pl->n_o = n_o; pl->n_i = n_i;
+    pl->nop = pow2_ceil(n_o); pl->nip = pow2_ceil(n_i);
+    if (pl->nip > n || pl->nop > n) { delete pl; return GALA_ESHAPE; }
+    pl->big = pl->nip == n;
+    if (pl->big) {
+        if (pl->nop > half) { delete pl; return GALA_ESHAPE; }
+        pl->R = pl->nop;
+    } else {
+        const long prod = (long)pl->nip * pl->nop;
+        pl->R = prod >= n ? (int)(prod / n) : 1;
+    }
+    const int G = pl->G = pl->R;
+    pl->in_gal.resize(G);
+    for (int g = 0; g < G; ++g) pl->in_gal[g] = galois_element(n, 0, g);
+    for (int rho = (pl->big ? half : pl->nip) / 2; rho >= pl->R; rho /= 2) pl->ras_gal.push_back(galois_element(n, 0, rho));
+    if (pl->big) pl->ras_gal.push_back(galois_element(n, 1, 0));
+    pl->result_slot.resize(n_o);
+    for (int t = 0; t < n_o; ++t) {
+        if (pl->big) { pl->result_slot[t] = t; continue; }
+        const int copy = t / pl->R, per_row = half / pl->nip;
+        pl->result_slot[t] = (copy / per_row) * half + (copy % per_row) * pl->nip + t % pl->R;
+    }
+    std::vector<u64> w((size_t)G * n);
+    parallel_for((size_t)G, [&](size_t g) {
+        std::vector<u64> slots(n);
+        for (int h = 0; h < 2; ++h)
+            for (int k = 0; k < half; ++k) {
+                const int row = hy_slot_row(pl, h, k);
+                const int col = pl->big ? h * half + (k + (int)g) % half : (k % pl->nip + (int)g) % pl->nip;
+                slots[h * half + k] = (row >= 0 && row < n_o && col < n_i) ? W[(size_t)row * n_i + col] % c->p : 0;
+            }
+        encode_weight_hat(c, slots.data(), w.data() + g * n);
+    });
+    // mask layout: every real output is a row of one slot (its result slot); all other slots are drawn
+    MaskLayoutHost &mh = pl->mask_h;
+    mh.nout = 1;
+    mh.nrows = {n_o};
+    mh.row_ptr.assign(n + 1, 0);
+    mh.row_slots.assign(n, 0);
+    mh.row_rindex.assign(n, 0);
+    mh.is_first.assign(n, 0);
+    for (int t = 0; t < n_o; ++t) {
+        mh.row_ptr[t] = t;
+        mh.row_slots[t] = pl->result_slot[t];
+        mh.row_rindex[t] = t;
+        mh.is_first[pl->result_slot[t]] = 1;
+    }
+    for (int t = n_o; t <= n; ++t) mh.row_ptr[t] = n_o;
+    const int steps = (int)pl->ras_gal.size();
+    std::vector<int> zeros(G, 0), in_key(G, -1), ras_gal(2 * std::max(steps, 1), 1), ras_key(2 * std::max(steps, 1), -1);
+    for (int k = 0; k < steps; ++k) ras_gal[2 * k + 1] = pl->ras_gal[k];
+    int rc = upload(&pl->d_w, w);
+    if (!rc) rc = upload(&pl->d_in_ct, zeros);
+    if (!rc) rc = upload(&pl->d_in_gal, pl->in_gal);
+    if (!rc) rc = upload(&pl->d_in_key, in_key);
+    if (!rc) rc = upload(&pl->d_ras_gal, ras_gal);
+    if (!rc) rc = upload(&pl->d_ras_key, ras_key);
+    if (!rc) rc = upload_mask_layout(c, mh, &pl->mask_d);
+    if (rc) { gala_fc_hybrid_plan_destroy(pl); return rc; }
+    *out = pl;
+    return GALA_OK;
+}
+extern "C" void gala_fc_hybrid_plan_destroy(gala_fc_hybrid_plan *pl) {
+    if (!pl) return;
+    hipFree(pl->d_w); hipFree(pl->d_in_ct); hipFree(pl->d_in_gal); hipFree(pl->d_in_key);
+    hipFree(pl->d_ras_gal); hipFree(pl->d_ras_key);
+    free_mask_layout(&pl->mask_d);
+    delete pl;
+}
+extern "C" int gala_fc_hybrid_plan_G(const gala_fc_hybrid_plan *pl) { return pl ? pl->G : GALA_EARG; }
+extern "C" int gala_fc_hybrid_plan_steps(const gala_fc_hybrid_plan *pl) { return pl ? (int)pl->ras_gal.size() : GALA_EARG; }
+extern "C" int gala_fc_hybrid_pack_input(const gala_fc_hybrid_plan *pl, const uint64_t *x, uint64_t *slots) {
+    if (!pl || !x || !slots) return GALA_EARG;
+    const int half = pl->ctx->n / 2;
+    for (int h = 0; h < 2; ++h)
+        for (int k = 0; k < half; ++k) {
+            const int col = pl->big ? h * half + k : k % pl->nip;
+            slots[h * half + k] = col < pl->n_i ? x[col] % pl->ctx->p : 0;
+        }
+    return GALA_OK;
+}
+extern "C" int gala_fc_hybrid_unpack(const gala_fc_hybrid_plan *pl, const uint64_t *slots, uint64_t *out) {
+    if (!pl || !slots || !out) return GALA_EARG;
+    for (int t = 0; t < pl->n_o; ++t) out[t] = slots[pl->result_slot[t]] % pl->ctx->p;
+    return GALA_OK;
+}
+
+// ===========================================================================
 // he_conv plan: kernel grouping (Sec. III-B(3))
 // ===========================================================================
 extern "C" int gala_conv_plan_create(gala_ctx *c, const uint64_t *K, int c_o, int c_i, int k_h, int k_w, int u_h,
@@ -856,6 +966,16 @@ extern "C" int gala_conv_plan_create(gala_ctx *c, const uint64_t *K, int c_o, in
     if (!rc) rc = upload(&pl->d_term_key, term_key);
     if (!rc) rc = upload(&pl->d_grp_gal, pl->grp_gal);
     if (!rc) rc = upload(&pl->d_grp_key, grp_key);
+    {
+        std::vector<int> or_gal((size_t)cn * nin), or_key((size_t)cn * nin, -1), seg(nin + 1, 0);
+        for (int gam = 0; gam < cn; ++gam)
+            for (int I = 0; I < nin; ++I) or_gal[(size_t)gam * nin + I] = pl->grp_gal[gam];
+        for (int e = 0; e < nterm; ++e) ++seg[pl->term_ct[e] + 1];
+        for (int I = 0; I < nin; ++I) seg[I + 1] += seg[I];
+        if (!rc) rc = upload(&pl->d_or_gal, or_gal);
+        if (!rc) rc = upload(&pl->d_or_key, or_key);
+        if (!rc) rc = upload(&pl->d_seg_ptr, seg);
+    }
     if (!rc) rc = upload_mask_layout(c, mh, &pl->mask_d);
     if (rc) { gala_conv_plan_destroy(pl); return rc; }
     *out = pl;
@@ -882,6 +1002,7 @@ extern "C" void gala_conv_plan_destroy(gala_conv_plan *pl) {
     if (!pl) return;
     hipFree(pl->d_w); hipFree(pl->d_wl); hipFree(pl->d_term_ct); hipFree(pl->d_term_gal); hipFree(pl->d_term_key);
     hipFree(pl->d_grp_gal); hipFree(pl->d_grp_key);
+    hipFree(pl->d_or_gal); hipFree(pl->d_or_key); hipFree(pl->d_seg_ptr);
     free_mask_layout(&pl->mask_d);
     delete pl;
 }
@@ -934,8 +1055,44 @@ extern "C" int gala_conv_plan_bind(gala_conv_plan *pl, const gala_gk *gk) {
         if (it == gk->index_of.end()) return GALA_ENOKEY;
         gkey[g] = it->second;
     }
+    std::vector<int> okey((size_t)pl->cn * pl->nin);
+    for (int g = 0; g < pl->cn; ++g)
+        for (int I = 0; I < pl->nin; ++I) okey[(size_t)g * pl->nin + I] = gkey[g];
     if (hipMemcpy(pl->d_term_key, tk.data(), sizeof(int) * pl->nterm, hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(pl->d_grp_key, gkey.data(), sizeof(int) * pl->cn, hipMemcpyHostToDevice) != hipSuccess)
+        hipMemcpy(pl->d_grp_key, gkey.data(), sizeof(int) * pl->cn, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(pl->d_or_key, okey.data(), sizeof(int) * okey.size(), hipMemcpyHostToDevice) != hipSuccess)
+        return GALA_EHIP;
+    pl->bound = gk;
+    return GALA_OK;
+}
+// rotations of a hybrid FC plan: the input rotations by 1..G-1, then the rotate-and-sum rotations (duplicates left out)
+extern "C" int gala_fc_hybrid_plan_rotations(const gala_fc_hybrid_plan *pl, gala_rot *rots, int *nrots) {
+    if (!pl || !nrots) return GALA_EARG;
+    std::vector<int> els;
+    for (int g : pl->in_gal) if (g != 1 && std::find(els.begin(), els.end(), g) == els.end()) els.push_back(g);
+    for (int g : pl->ras_gal) if (g != 1 && std::find(els.begin(), els.end(), g) == els.end()) els.push_back(g);
+    *nrots = (int)els.size();
+    if (rots)
+        for (size_t i = 0; i < els.size(); ++i) rots[i] = rot_of(pl->ctx, els[i]);
+    return GALA_OK;
+}
+extern "C" int gala_fc_hybrid_plan_bind(gala_fc_hybrid_plan *pl, const gala_gk *gk) {
+    if (!pl || !gk) return GALA_EARG;
+    if (gk->n != pl->ctx->n || gk->ndigits != pl->ctx->ndigits || gk->polys != pl->ctx->key_polys()) return GALA_EARG;
+    const int steps = (int)pl->ras_gal.size();
+    std::vector<int> in_key(pl->G, -1), ras_key(2 * std::max(steps, 1), -1);
+    for (int g = 1; g < pl->G; ++g) {
+        auto it = gk->index_of.find(pl->in_gal[g]);
+        if (it == gk->index_of.end()) return GALA_ENOKEY;
+        in_key[g] = it->second;
+    }
+    for (int k = 0; k < steps; ++k) {
+        auto it = gk->index_of.find(pl->ras_gal[k]);
+        if (it == gk->index_of.end()) return GALA_ENOKEY;
+        ras_key[2 * k + 1] = it->second;
+    }
+    if (hipMemcpy(pl->d_in_key, in_key.data(), sizeof(int) * in_key.size(), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(pl->d_ras_key, ras_key.data(), sizeof(int) * ras_key.size(), hipMemcpyHostToDevice) != hipSuccess)
         return GALA_EHIP;
     pl->bound = gk;
     return GALA_OK;

@@ -154,6 +154,23 @@ struct gala_fc_plan {
     MaskLayoutDev mask_d;
 };
 
+// The hybrid matrix-vector product of Sec. III-A(2) (comparison schedule): G diagonal vectors that multiply the
+// input rotated by 0..G-1, then rotate-and-sum steps on the running ciphertext.
+struct gala_fc_hybrid_plan {
+    gala_ctx *ctx = nullptr;
+    int n_o = 0, n_i = 0, nop = 0, nip = 0, G = 0, R = 0;
+    bool big = false;
+    std::vector<int> in_gal;           // Galois elements of the input rotations g = 0..G-1 (in_gal[0] = 1)
+    std::vector<int> ras_gal;          // Galois elements of the rotate-and-sum steps, in order
+    std::vector<int> result_slot;      // slot that holds output t after the last step
+    gala::u64 *d_w = nullptr;          // G x n diagonal vectors, evaluation domain
+    int *d_in_ct = nullptr, *d_in_gal = nullptr, *d_in_key = nullptr;   // G each: the term list of the input rotations
+    int *d_ras_gal = nullptr, *d_ras_key = nullptr;   // per step the pair (1, gal) / (-1, key index): 2 ints each
+    const gala_gk *bound = nullptr;
+    MaskLayoutHost mask_h;
+    MaskLayoutDev mask_d;
+};
+
 struct gala_conv_plan {
     gala_ctx *ctx = nullptr;
     int c_o = 0, c_i = 0, k_h = 0, k_w = 0, u_h = 0, u_w = 0;
@@ -167,6 +184,10 @@ struct gala_conv_plan {
     gala::u64 *d_w = nullptr;          // nout x cn x nterm x n encoded kernels, evaluation domain
     gala::u64 *d_wl = nullptr;         // the same as balanced base-256 digit planes for the matrix-core path, or null
     int *d_grp_gal = nullptr, *d_grp_key = nullptr;   // cn
+    // output-rotation schedule (Sec. III-B(2)): entry gam * nin + I of an output ciphertext's sum is the block of input
+    // ciphertext I in kernel order gam; seg_ptr[I] .. seg_ptr[I+1]-1 are the terms of input ciphertext I
+    int *d_or_gal = nullptr, *d_or_key = nullptr;     // cn * nin
+    int *d_seg_ptr = nullptr;                          // nin + 1
     const gala_gk *bound = nullptr;
     MaskLayoutHost mask_h;
     MaskLayoutDev mask_d;
@@ -282,8 +303,10 @@ struct TermList {
 int launch_hstperm_taps(const gala_ctx *ctx, void *stream, const u64 *ct_in, const u64 *digits, int batch,
                         const TermList &terms, const u64 *keys, u64 *xrot);
 // acc[b][O][gam] = sum_{I,tap} w[O][gam][I][tap] (.) xrot[b][I][tap]   (both polynomials)
+// seg_ptr (device, nseg + 1 ints) cuts the terms into nseg consecutive ranges with sums of their own:
+//   acc[b][O][gam][s] = sum over the terms of range s; nullptr: one sum over all terms (nseg ignored)
 int launch_conv_mac(const gala_ctx *ctx, void *stream, const u64 *w, const u64 *xrot, int batch, int nout, int cn,
-                    int nterm, u64 *acc);
+                    int nterm, u64 *acc, const int *seg_ptr = nullptr, int nseg = 1);
 
 // Matrix-core path of the convolution's multiply-accumulate (gala_conv_mfma.hip): digit-plane images of the
 // encoded kernels (built once per plan) and of the rotated inputs (built per call), then one MFMA kernel.

@@ -579,14 +579,19 @@ __device__ __forceinline__ void mac128(u64 &lo, u64 &hi, u64 x, u64 w) {
 // nterm terms (the plan's active (input ciphertext, tap) pairs); groups = nout*cn; cols = 2*batch (input-major, c0 then c1).
 // A workgroup is WM x WN wavefronts on the same 64 coefficients: the wavefronts of a row read the same
 // weight words and those of a column the same input words, so those reads hit in the CU's vector cache.
+// Segments (seg_ptr != nullptr, nseg of them): the terms are cut into consecutive ranges seg_ptr[s] .. seg_ptr[s+1]-1
+// and every range gets sums of its own, acc row (m, s) = m * nseg + s: the per-input-ciphertext sums that the
+// output-rotation schedule of Sec. III-B(2) rotates one by one.  Without segments there is one sum per row.
 template <int TM, int TN, int WM, int WN, int U>
 __global__ __launch_bounds__(64 * WM * WN) void conv_mac_kernel(const u64 *w, const u64 *xrot, int cols, int groups,
                                                                 int nterm, u64 *acc, Modulus mod, int n,
-                                                                int flush_every) {
+                                                                int flush_every, const int *seg_ptr, int nseg) {
     const int i = blockIdx.x * 64 + (threadIdx.x & 63);
     if (i >= n) return;
     const int wave = threadIdx.x >> 6;
-    const int m0 = (blockIdx.y * WM + wave % WM) * TM, c0 = (blockIdx.z * WN + wave / WM) * TN;
+    const int seg = seg_ptr ? (int)(blockIdx.y % (unsigned)nseg) : 0, by = seg_ptr ? (int)(blockIdx.y / (unsigned)nseg) : (int)blockIdx.y;
+    const int e_begin = seg_ptr ? seg_ptr[seg] : 0, e_end = seg_ptr ? seg_ptr[seg + 1] : nterm;
+    const int m0 = (by * WM + wave % WM) * TM, c0 = (blockIdx.z * WN + wave / WM) * TN;
     // rows / columns past the end repeat the last valid one; their sums are computed but not stored
     const u64 *wp[TM], *xp[TN];
 #pragma unroll
@@ -603,8 +608,8 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mac_kernel(const u64 *w, co
         for (int b = 0; b < TN; ++b) lo[a][b] = hi[a][b] = 0;
     // U terms per step, all their loads issued before the first product: a wavefront that waits for one load at
     // a time reaches about half of the memory rate that several loads in flight do.
-    int pending = 0, e = 0;
-    for (; e + U <= nterm; e += U) {
+    int pending = 0, e = e_begin;
+    for (; e + U <= e_end; e += U) {
         u64 wv[U][TM], xv[U][TN];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -631,7 +636,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mac_kernel(const u64 *w, co
             pending = 1;
         }
     }
-    for (; e < nterm; ++e) {               // fewer than U terms left: there is room for them (pending + U <= flush_every)
+    for (; e < e_end; ++e) {               // fewer than U terms left: there is room for them (pending + U <= flush_every)
         u64 wv[TM], xv[TN];
 #pragma unroll
         for (int a = 0; a < TM; ++a) wv[a] = wp[a][(size_t)e * n];
@@ -648,7 +653,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mac_kernel(const u64 *w, co
         for (int b = 0; b < TN; ++b) {
             const int m = m0 + a, col = c0 + b;
             if (m < groups && col < cols)
-                acc[(((size_t)(col >> 1) * groups + m) * 2 + (col & 1)) * n + i] = reduce128(hi[a][b], lo[a][b], mod);
+                acc[((((size_t)(col >> 1) * groups + m) * nseg + seg) * 2 + (col & 1)) * n + i] = reduce128(hi[a][b], lo[a][b], mod);
         }
 }
 
@@ -983,8 +988,9 @@ int launch_hstperm_taps(const gala_ctx *c, void *stream, const u64 *ct_in, const
     return last_error();
 }
 int launch_conv_mac(const gala_ctx *c, void *stream, const u64 *w, const u64 *xrot, int batch, int nout, int cn,
-                    int nterm, u64 *acc) {
+                    int nterm, u64 *acc, const int *seg_ptr, int nseg) {
     if (batch <= 0) return 0;
+    if (!seg_ptr) nseg = 1;
     const int groups = nout * cn, cols = 2 * batch;
     // products are below q^2: 255 of them fit 128 bits when q < 2^60, 63 when q < 2^61
     const int flush_every = c->q < (1ull << 60) ? 255 : 63;
@@ -995,14 +1001,14 @@ int launch_conv_mac(const gala_ctx *c, void *stream, const u64 *w, const u64 *xr
     // kernel of its own.
     const unsigned iblocks = (unsigned)((c->n + 63) / 64);
     auto wgs = [&](int tm, int tn, int wm, int wn) {
-        return (size_t)iblocks * ((groups + tm * wm - 1) / (tm * wm)) * ((cols + tn * wn - 1) / (tn * wn));
+        return (size_t)iblocks * ((groups + tm * wm - 1) / (tm * wm)) * nseg * ((cols + tn * wn - 1) / (tn * wn));
     };
     const size_t enough = 1024;
 #define GALA_MAC(TM, TN, WM, WN)                                                                                      \
     hipLaunchKernelGGL((conv_mac_kernel<TM, TN, WM, WN, 1>),                                                         \
-                       dim3(iblocks, (unsigned)((groups + TM * WM - 1) / (TM * WM)), (unsigned)((cols + TN * WN - 1) / (TN * WN))), \
-                       dim3(64 * WM * WN), 0, st, w, xrot, cols, groups, nterm, acc, c->dev_q.mod, c->n, flush_every)
-    if (cols <= 2) {
+                       dim3(iblocks, (unsigned)((groups + TM * WM - 1) / (TM * WM) * nseg), (unsigned)((cols + TN * WN - 1) / (TN * WN))), \
+                       dim3(64 * WM * WN), 0, st, w, xrot, cols, groups, nterm, acc, c->dev_q.mod, c->n, flush_every, seg_ptr, nseg)
+    if (cols <= 2 && !seg_ptr) {
         // one input: the streaming kernel, with the tallest row tile that still gives every compute unit a workgroup
         const size_t per_cu = 256;
 #define GALA_MACS(TM, KS)                                                                                             \
