@@ -609,6 +609,15 @@ def entry_points(ctx, sk, D, torch, par):
     prewarm(fn, torch, 0.05)
     t = wall_ms(fn, torch, 30)
     res["decrypt_4096_cts"] = {"ms": t, "ciphertexts_per_s": count * 1e3 / t}
+    # Plain forward transforms (the import of coefficient-form ciphertexts): the rate at which encoded kernels could
+    # be produced on the fly from 4-byte coefficients, to set against the rate at which the stored 8-byte evaluation
+    # form streams from HBM in the multiply-accumulate (bytes_per_step / kernel_ms_total of resnet18_b1).
+    d_coef = D.to_dev(rng.integers(0, par.q, size=(count, 2 * par.n), dtype=np.uint64))
+    fn = lambda: ctx.ct_import(d_coef, count, d_ct)
+    prewarm(fn, torch, 0.05)
+    t = wall_ms(fn, torch, 30)
+    res["forward_transform_8192_polys"] = {"ms": t, "polynomials_per_s": 2 * count * 1e3 / t,
+                                           "evaluation_form_bytes_per_s": 2 * count * par.n * 8 * 1e3 / t}
     return res
 
 

@@ -231,7 +231,12 @@ void gala_fc_plan_destroy(gala_fc_plan *plan);
 int gala_fc_plan_G(const gala_fc_plan *plan);
 /* Writes the G-1 rotations the plan needs (rots may be NULL to query *nrots). */
 int gala_fc_plan_rotations(const gala_fc_plan *plan, gala_rot *rots, int *nrots);
-/* Resolves the plan's rotations against a key set (offline; GALA_ENOKEY if one is missing). */
+/* Resolves the plan's rotations against a key set (offline; GALA_ENOKEY if one is missing, GALA_EARG if the keys
+ * were generated for another context).  The plan keeps a pointer to the key set: the key set must outlive every
+ * call that uses the plan, and is destroyed by the caller after the plan (or after binding another key set).
+ * Binding copies a small index table to the device with a blocking copy: do not bind while calls that use the
+ * plan are still in flight on other streams.  The same holds for gala_conv_plan_bind and
+ * gala_fc_hybrid_plan_bind. */
 int gala_fc_plan_bind(gala_fc_plan *plan, const gala_gk *gk);
 /* Client side: slot vector holding n/n_i copies of x (host). */
 int gala_fc_pack_input(const gala_fc_plan *plan, const uint64_t *x /* n_i */, uint64_t *slots /* n */);

@@ -332,12 +332,16 @@ ConvWorkspace conv_workspace(const gala_conv_plan *pl, int batch) {
     const size_t n = c->n, w = sizeof(u64);
     ConvWorkspace ws{};
     ws.chunks = choose_chunks(c, batch * pl->nout, pl->cn);
+    ws.mfma = pl->d_wl && batch >= 2;    // from two inputs on (4 of a workgroup's 32 columns) the matrix cores win
+    // the one-prime n = 2048 path writes the rotated inputs straight into the product's column image and the Perm
+    // kernel reads the product in place: neither the rotated inputs nor the per-ciphertext sums are materialised
+    const bool rotates = pl->nrot_terms > 0;
+    const bool direct = ws.mfma && !c->special && uses_fast_hoist(c) && (!rotates || (pl->bound && pl->bound->d_keys2));
     ws.digits = 0;
     ws.xrot = ws.digits + hoist_digit_bytes(c, (size_t)batch * pl->nin);
-    ws.acc = ws.xrot + align_up((size_t)batch * pl->nterm * 2 * n * w);
-    ws.partial = ws.acc + align_up((size_t)batch * pl->nout * pl->cn * 2 * n * w);
+    ws.acc = ws.xrot + (direct ? 0 : align_up((size_t)batch * pl->nterm * 2 * n * w));
+    ws.partial = ws.acc + (direct ? 0 : align_up((size_t)batch * pl->nout * pl->cn * 2 * n * w));
     ws.xl = ws.partial + align_up((size_t)batch * pl->nout * (ws.chunks + 1) * 2 * n * w);
-    ws.mfma = pl->d_wl && batch >= 2;    // from two inputs on (4 of a workgroup's 32 columns) the matrix cores win
     size_t xl_bytes = 0, tmp_bytes = 0;
     if (ws.mfma) {
         int mt, nt, kb;

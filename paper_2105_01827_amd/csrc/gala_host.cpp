@@ -450,7 +450,7 @@ extern "C" int gala_galois_keygen(gala_ctx *c, const gala_sk *sk, const gala_rot
     const int n = c->n, L = c->ndigits;
     gala_gk *gk = new (std::nothrow) gala_gk;
     if (!gk) return GALA_ENOMEM;
-    gk->n = n; gk->ndigits = L; gk->polys = c->key_polys();
+    gk->ctx = c; gk->n = n; gk->ndigits = L; gk->polys = c->key_polys();
     for (int i = 0; i < nrots; ++i) {
         if (rots[i].step < 0 || rots[i].step >= n / 2 || (rots[i].swap & ~1)) { delete gk; return GALA_EARG; }
         int g = galois_element(n, rots[i].swap, rots[i].step);
@@ -635,6 +635,32 @@ int fc_slot_col(const gala_fc_plan *pl, int h, int k) {
 }
 }  // namespace
 
+namespace {
+// Encoded weights of an FC plan, built on the device: W and the slot -> row table go up once, one kernel writes the G
+// slot vectors and the plaintext encoder takes them to the evaluation domain (centred lift, as ScMult expects).
+// *d_w receives G x n words.
+int encode_fc_weights_on_device(const gala_ctx *c, const uint64_t *W, int n_o, int n_i, int nip, bool big, bool rotate_output,
+                                const std::vector<int> &slot_row_padded, int G, u64 **d_w) {
+    const int n = c->n;
+    u64 *d_W = nullptr, *d_slots = nullptr;
+    int *d_row = nullptr;
+    int rc = GALA_OK;
+    const size_t words = (size_t)n_o * n_i;
+    if (hipMalloc((void **)&d_W, words * sizeof(u64)) != hipSuccess ||
+        hipMalloc((void **)&d_slots, (size_t)G * n * sizeof(u64)) != hipSuccess ||
+        hipMalloc((void **)d_w, (size_t)G * n * sizeof(u64)) != hipSuccess)
+        rc = GALA_ENOMEM;
+    if (!rc) rc = upload(&d_row, slot_row_padded);
+    if (!rc && hipMemcpy(d_W, W, words * sizeof(u64), hipMemcpyHostToDevice) != hipSuccess) rc = GALA_EHIP;
+    const FcGeom geo{n, n_o, n_i, nip, big ? 1 : 0, rotate_output ? 1 : 0, c->p};
+    if (!rc && (launch_fc_weight_slots(c, nullptr, d_W, geo, d_row, G, d_slots) ||
+                launch_encode_plain(c, nullptr, d_slots, G, 0, *d_w) || hipDeviceSynchronize() != hipSuccess))
+        rc = GALA_EHIP;
+    hipFree(d_W); hipFree(d_slots); hipFree(d_row);
+    return rc;
+}
+}  // namespace
+
 extern "C" int gala_fc_plan_create(gala_ctx *c, const uint64_t *W, int n_o, int n_i, gala_fc_plan **out) {
     if (!c || !W || !out || n_o < 1 || n_i < 1) return GALA_EARG;
     if (!c->has_device) return GALA_EHIP;
@@ -661,16 +687,13 @@ extern "C" int gala_fc_plan_create(gala_ctx *c, const uint64_t *W, int n_o, int 
     pl->gal.resize(G);
     for (int g = 0; g < G; ++g) pl->gal[g] = galois_element(n, 0, g);
     // encoded weights: before the left rotation by g, slot (h,k) holds W[row(h,k-g)][col(h,k)]
-    std::vector<u64> w((size_t)G * n);
-    parallel_for((size_t)G, [&](size_t g) {
-        std::vector<u64> slots(n);
-        for (int h = 0; h < 2; ++h)
-            for (int k = 0; k < half; ++k) {
-                int row = fc_slot_row(pl, h, ((k - (int)g) % half + half) % half), col = fc_slot_col(pl, h, k);
-                slots[h * half + k] = (row >= 0 && row < n_o && col < n_i) ? W[(size_t)row * n_i + col] % c->p : 0;
-            }
-        encode_weight_hat(c, slots.data(), w.data() + g * n);
-    });
+    std::vector<int> row_padded(n);
+    for (int s = 0; s < n; ++s) row_padded[s] = fc_slot_row(pl, s / half, s % half);
+    const size_t wsize = (size_t)G * n;
+    {
+        const int erc = encode_fc_weights_on_device(c, W, n_o, n_i, pl->nip, pl->big, true, row_padded, G, &pl->d_w);
+        if (erc) { gala_fc_plan_destroy(pl); return erc; }
+    }
     // mask layout: one output ciphertext, rows = real outputs
     MaskLayoutHost &mh = pl->mask_h;
     mh.nout = 1;
@@ -691,12 +714,12 @@ extern "C" int gala_fc_plan_create(gala_ctx *c, const uint64_t *W, int n_o, int 
     }
     for (int t = n_o; t <= n; ++t) mh.row_ptr[t] = pos;
     std::vector<int> key_idx(G, -1);
-    int rc = upload(&pl->d_w, w);
+    int rc = GALA_OK;
     if (!rc && uses_fast_perm(c)) {
         // pairs in natural order, then once more in the order the Perm kernel's threads own them
-        if (hipMalloc((void **)&pl->d_w2, 4 * w.size() * sizeof(u64)) != hipSuccess) rc = GALA_ENOMEM;
-        if (!rc && (launch_pair_pack(c, nullptr, pl->d_w, pl->d_w2, w.size(), 2) ||
-                    launch_owner_order_2048(nullptr, pl->d_w2, pl->d_w2 + 2 * w.size(), (size_t)G) ||
+        if (hipMalloc((void **)&pl->d_w2, 4 * wsize * sizeof(u64)) != hipSuccess) rc = GALA_ENOMEM;
+        if (!rc && (launch_pair_pack(c, nullptr, pl->d_w, pl->d_w2, wsize, 2) ||
+                    launch_owner_order_2048(nullptr, pl->d_w2, pl->d_w2 + 2 * wsize, (size_t)G) ||
                     hipDeviceSynchronize() != hipSuccess))
             rc = GALA_EHIP;
     }
@@ -722,7 +745,7 @@ extern "C" int gala_fc_plan_rotations(const gala_fc_plan *pl, gala_rot *rots, in
     return GALA_OK;
 }
 extern "C" int gala_fc_plan_bind(gala_fc_plan *pl, const gala_gk *gk) {
-    if (!pl || !gk) return GALA_EARG;
+    if (!pl || !gk || gk->ctx != pl->ctx) return GALA_EARG;
     std::vector<int> idx(pl->G, -1);
     for (int g = 1; g < pl->G; ++g) {
         auto it = gk->index_of.find(pl->gal[g]);
@@ -797,17 +820,12 @@ extern "C" int gala_fc_hybrid_plan_create(gala_ctx *c, const uint64_t *W, int n_
         const int copy = t / pl->R, per_row = half / pl->nip;
         pl->result_slot[t] = (copy / per_row) * half + (copy % per_row) * pl->nip + t % pl->R;
     }
-    std::vector<u64> w((size_t)G * n);
-    parallel_for((size_t)G, [&](size_t g) {
-        std::vector<u64> slots(n);
-        for (int h = 0; h < 2; ++h)
-            for (int k = 0; k < half; ++k) {
-                const int row = hy_slot_row(pl, h, k);
-                const int col = pl->big ? h * half + (k + (int)g) % half : (k % pl->nip + (int)g) % pl->nip;
-                slots[h * half + k] = (row >= 0 && row < n_o && col < n_i) ? W[(size_t)row * n_i + col] % c->p : 0;
-            }
-        encode_weight_hat(c, slots.data(), w.data() + g * n);
-    });
+    std::vector<int> row_padded(n);
+    for (int s = 0; s < n; ++s) row_padded[s] = hy_slot_row(pl, s / half, s % half);
+    {
+        const int erc = encode_fc_weights_on_device(c, W, n_o, n_i, pl->nip, pl->big, false, row_padded, G, &pl->d_w);
+        if (erc) { gala_fc_hybrid_plan_destroy(pl); return erc; }
+    }
     // mask layout: every real output is a row of one slot (its result slot); all other slots are drawn
     MaskLayoutHost &mh = pl->mask_h;
     mh.nout = 1;
@@ -826,8 +844,7 @@ extern "C" int gala_fc_hybrid_plan_create(gala_ctx *c, const uint64_t *W, int n_
     const int steps = (int)pl->ras_gal.size();
     std::vector<int> zeros(G, 0), in_key(G, -1), ras_gal(2 * std::max(steps, 1), 1), ras_key(2 * std::max(steps, 1), -1);
     for (int k = 0; k < steps; ++k) ras_gal[2 * k + 1] = pl->ras_gal[k];
-    int rc = upload(&pl->d_w, w);
-    if (!rc) rc = upload(&pl->d_in_ct, zeros);
+    int rc = upload(&pl->d_in_ct, zeros);
     if (!rc) rc = upload(&pl->d_in_gal, pl->in_gal);
     if (!rc) rc = upload(&pl->d_in_key, in_key);
     if (!rc) rc = upload(&pl->d_ras_gal, ras_gal);
@@ -1040,7 +1057,7 @@ extern "C" int gala_conv_plan_rotations(const gala_conv_plan *pl, gala_rot *rots
     return GALA_OK;
 }
 extern "C" int gala_conv_plan_bind(gala_conv_plan *pl, const gala_gk *gk) {
-    if (!pl || !gk) return GALA_EARG;
+    if (!pl || !gk || gk->ctx != pl->ctx) return GALA_EARG;
     std::vector<int> tk(pl->nterm, -1), gkey(pl->cn, -1);
     for (int e = 0; e < pl->nterm; ++e) {
         const int g = pl->tap_gal[pl->term_tap[e]];
@@ -1077,8 +1094,7 @@ extern "C" int gala_fc_hybrid_plan_rotations(const gala_fc_hybrid_plan *pl, gala
     return GALA_OK;
 }
 extern "C" int gala_fc_hybrid_plan_bind(gala_fc_hybrid_plan *pl, const gala_gk *gk) {
-    if (!pl || !gk) return GALA_EARG;
-    if (gk->n != pl->ctx->n || gk->ndigits != pl->ctx->ndigits || gk->polys != pl->ctx->key_polys()) return GALA_EARG;
+    if (!pl || !gk || gk->ctx != pl->ctx) return GALA_EARG;
     const int steps = (int)pl->ras_gal.size();
     std::vector<int> in_key(pl->G, -1), ras_key(2 * std::max(steps, 1), -1);
     for (int g = 1; g < pl->G; ++g) {

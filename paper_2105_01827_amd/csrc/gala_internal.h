@@ -107,6 +107,7 @@ struct gala_sk {
 };
 
 struct gala_gk {
+    const gala_ctx *ctx = nullptr;     // the context the keys were generated for (plans of another context refuse them)
     int n = 0, ndigits = 0, polys = 2; // polynomials per digit: (b, a) mod q, then (b, a) mod P with a special prime
     std::map<int, int> index_of;       // Galois element -> key index
     std::vector<int> elements;
@@ -227,6 +228,16 @@ struct ConvGeom {
 };
 int launch_conv_weight_slots(const gala_ctx *ctx, void *stream, const u64 *K, const ConvGeom &g, const int *term_ct,
                              const int *term_tap, size_t first, size_t count, u64 *slots);
+// "encode" of an FC plan on the device: slot vectors of the encoded weights g = 0..count-1 from W (n_o x n_i, device)
+// and the plan's slot -> padded row table (n ints, device; -1: the slot carries no weight).  rotate_output: GALA's
+// row-wise encoding (the product is rotated by g afterwards); otherwise the hybrid method's diagonals (the input is
+// rotated by g before the product).
+struct FcGeom {
+    int n, n_o, n_i, nip, big, rotate_output;
+    u64 p;
+};
+int launch_fc_weight_slots(const gala_ctx *ctx, void *stream, const u64 *W, const FcGeom &g, const int *slot_row, int count,
+                           u64 *slots);
 // out[b][rindex of row t] = sum of the row's slots mod p, for `count` items of nout slot vectors each
 int launch_unpack_share(const gala_ctx *ctx, void *stream, const u64 *slots, int count, int nout, const MaskLayoutDev &layout,
                         size_t out_stride, u64 *out);

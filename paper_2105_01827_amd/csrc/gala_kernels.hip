@@ -785,6 +785,28 @@ __global__ void conv_weight_slots_kernel(const u64 *K, ConvGeom g, const int *te
     }
 }
 
+// Slot vectors of an FC plan's encoded weights ("encode-rowwise", Sec. III-A(3); also the diagonal vectors of the
+// hybrid method, Sec. III-A(2)): vector g holds W[row][col] at slot s, with row = slot_row[(h, (k - shift*g) mod n/2)]
+// (shift = 1: the vector is rotated left by g after the product; shift = 0: the input was rotated instead) and
+// col = slot_col[s] (+ g mod col_period when the input was rotated); zero where row or column do not exist.
+// One workgroup per vector.
+__global__ void fc_weight_slots_kernel(const u64 *W, FcGeom g, const int *slot_row, u64 *slots) {
+    const int gi = blockIdx.x, half = g.n / 2;
+    u64 *out = slots + (size_t)gi * g.n;
+    for (int s = threadIdx.x; s < g.n; s += blockDim.x) {
+        const int h = s / half, k = s % half;
+        int row, col;
+        if (g.rotate_output) {      // GALA: row of the slot the value moves to, column of the slot it sits in
+            row = slot_row[h * half + ((k - gi) % half + half) % half];
+            col = g.big ? h * half + k : k % g.nip;
+        } else {                    // hybrid: row of this slot, column of the input entry rotated into it
+            row = slot_row[s];
+            col = g.big ? h * half + (k + gi) % half : (k % g.nip + gi) % g.nip;
+        }
+        out[s] = (row >= 0 && row < g.n_o && col < g.n_i) ? W[(size_t)row * g.n_i + col] % g.p : 0;
+    }
+}
+
 // The plaintext half of share generation: every output is the sum of its row's slots mod p (Sec. III-A(3); a
 // convolution's rows are single slots).  One workgroup per slot vector; the row sums meet in LDS as plain integers.
 __global__ void unpack_share_kernel(const u64 *slots, int nout, int n, u64 p, const int *slot_rowid, const int *row_rindex,
@@ -848,6 +870,13 @@ int launch_conv_weight_slots(const gala_ctx *c, void *stream, const u64 *K, cons
     if (!count) return 0;
     hipLaunchKernelGGL(conv_weight_slots_kernel, dim3((unsigned)count), dim3(block_threads(c->n)), 0, (hipStream_t)stream, K, g,
                        term_ct, term_tap, first, slots);
+    return last_error();
+}
+int launch_fc_weight_slots(const gala_ctx *c, void *stream, const u64 *W, const FcGeom &g, const int *slot_row, int count,
+                           u64 *slots) {
+    if (count <= 0) return 0;
+    hipLaunchKernelGGL(fc_weight_slots_kernel, dim3((unsigned)count), dim3(block_threads(c->n)), 0, (hipStream_t)stream, W, g,
+                       slot_row, slots);
     return last_error();
 }
 int launch_unpack_share(const gala_ctx *c, void *stream, const u64 *slots, int count, int nout, const MaskLayoutDev &layout,
