@@ -339,8 +339,9 @@ ConvWorkspace conv_workspace(const gala_conv_plan *pl, int batch) {
     const bool direct = ws.mfma && !c->special && uses_fast_hoist(c) && (!rotates || (pl->bound && pl->bound->d_keys2));
     ws.digits = 0;
     ws.xrot = ws.digits + hoist_digit_bytes(c, (size_t)batch * pl->nin);
+    const bool in8 = ws.mfma && uses_fast_perm(c);
     ws.acc = ws.xrot + (direct ? 0 : align_up((size_t)batch * pl->nterm * 2 * n * w));
-    ws.partial = ws.acc + (direct ? 0 : align_up((size_t)batch * pl->nout * pl->cn * 2 * n * w));
+    ws.partial = ws.acc + (in8 ? 0 : align_up((size_t)batch * pl->nout * pl->cn * 2 * n * w));
     ws.xl = ws.partial + align_up((size_t)batch * pl->nout * (ws.chunks + 1) * 2 * n * w);
     size_t xl_bytes = 0, tmp_bytes = 0;
     if (ws.mfma) {
@@ -387,11 +388,12 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
         if (end) ++c->prof_used;
     };
     auto mark = [&](int end) { mark_as(1, end); };
-    // The one-prime n = 2048 Perm kernel reads the product's sums in their own blocks of eight coefficients: no
-    // transposition pass in between.
-    const bool in8 = ws.mfma && fast_hoist && !c->special;
+    // The n = 2048 Perm kernels read the product's sums in their own blocks of eight coefficients: no transposition
+    // pass in between.  With one-prime keys the rotated inputs also go straight into the product's column image.
+    const bool direct = ws.mfma && fast_hoist && !c->special;
+    const bool in8 = ws.mfma && uses_fast_perm(c);      // both n = 2048 Perm kernels read the blocks of eight
     const u64 *perm_in = acc;
-    if (ws.mfma && fast_hoist && !c->special) {
+    if (direct) {
         // the rotated inputs go straight into the column image of the matrix-core product
         u64 *xl = (u64 *)(base + ws.xl), *tmp = (u64 *)(base + ws.tmp);
         mark_as(2, 0);
@@ -411,9 +413,10 @@ extern "C" int gala_he_conv(const gala_ctx *c, void *stream, const gala_conv_pla
             u64 *xl = (u64 *)(base + ws.xl), *tmp = (u64 *)(base + ws.tmp);
             if (launch_limb_pack(c, stream, xrot, 1, 2 * batch, nterm, xl)) return GALA_EHIP;
             mark(0);
-            if (launch_conv_mfma(c, stream, pl->d_wl, xl, batch, groups, nterm, tmp)) return GALA_EHIP;
+            if (launch_conv_mfma(c, stream, pl->d_wl, xl, batch, groups, nterm, tmp, in8)) return GALA_EHIP;
             mark(1);
-            if (launch_conv_untranspose(c, stream, tmp, batch, groups, acc)) return GALA_EHIP;
+            if (in8) perm_in = tmp;
+            else if (launch_conv_untranspose(c, stream, tmp, batch, groups, acc)) return GALA_EHIP;
         } else {
             mark(0);
             if (launch_conv_mac(c, stream, pl->d_w, xrot, batch, pl->nout, pl->cn, nterm, acc)) return GALA_EHIP;

@@ -775,7 +775,8 @@ struct SpecialJob {
     ulonglong2 Pq, Pinv;    // P mod q and P^-1 mod q with companions
 };
 
-template <bool HAS_W>
+// IN8: the inputs lie in blocks of eight coefficients (PermJob::in8_S), as the matrix-core product leaves them.
+template <bool HAS_W, bool IN8 = false>
 __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob job, Tables2048 T, SpecialJob S, MaskJob mj,
                                                                       int gadget_bits, int ndigits) {
     __shared__ u64 bufA[LDS_WORDS], bufB[LDS_WORDS];
@@ -805,15 +806,19 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
     for (int s = 0; s < 15; ++s) Rl[s * NT + tid] = 0;
 
     for (int g = g0; g < g1; ++g) {
-        const u64 *c0 = job.ct_in + (size_t)item * job.in_item_stride + (size_t)g * job.in_g_stride;
-        const u64 *c1 = c0 + N;
+        const u64 *c0 = IN8 ? job.ct_in + (size_t)(item % job.in8_nout) * job.in8_o_stride + (size_t)(item / job.in8_nout) * 16 +
+                                  (size_t)g * job.in_g_stride
+                            : job.ct_in + (size_t)item * job.in_item_stride + (size_t)g * job.in_g_stride;
+        const u64 *c1 = IN8 ? c0 + 8 : c0 + N;
+        const size_t S8 = IN8 ? job.in8_S : 0;
+        auto at = [&](const u64 *poly, int i) -> u64 { return IN8 ? poly[(size_t)(i >> 3) * S8 + (i & 7)] : poly[i]; };
         const ulonglong2 *w = HAS_W ? reinterpret_cast<const ulonglong2 *>(job.w2) + (size_t)g * N : nullptr;
         const int gal = job.gal[g];
         if (gal == 1) {   // rotation by zero: ScMult and Add only, times P
 #pragma unroll
             for (int k = 0; k < PER; ++k) {
                 const int i = tid + k * NT;
-                u64 x0 = c0[i], x1 = c1[i];
+                u64 x0 = at(c0, i), x1 = at(c1, i);
                 if (HAS_W) {
                     const ulonglong2 ww = w[i];
                     x0 = mul_const<true>(x0, ww.x, ww.y, q);
@@ -831,7 +836,7 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
         for (int k = 0; k < PER; ++k) src[k] = galois_index11(tid + k * NT, gal);
         u64 a[PER];
         {
-            const ulonglong2 *c1v = reinterpret_cast<const ulonglong2 *>(c1 + 8 * tid);
+            const ulonglong2 *c1v = reinterpret_cast<const ulonglong2 *>(IN8 ? c1 + (size_t)tid * S8 : c1 + 8 * tid);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const ulonglong2 cv = c1v[k];
@@ -851,7 +856,7 @@ __global__ __launch_bounds__(NT, 2) void perm_accumulate_special_2048(PermJob jo
         // the c0 part, times P
 #pragma unroll
         for (int k = 0; k < PER; ++k) {
-            u64 x = c0[src[k]];
+            u64 x = at(c0, src[k]);
             if (HAS_W) {
                 const ulonglong2 ww = w[src[k]];
                 x = mul_const<true>(x, ww.x, ww.y, q);
@@ -1116,13 +1121,16 @@ static int launch_2048(const gala_ctx *c, void *stream, const PermJob &job, cons
     const Tables2048 T = make_tables(c, c->d_tw2, c->dev_q);
     const dim3 grid((unsigned)(job.items * job.nchunks + (mj.enabled ? job.items : 0)));
     if (c->special) {
-        if (job.in8_S) return (int)hipErrorInvalidValue;
+        if (job.in8_S && job.w) return (int)hipErrorInvalidValue;
         SpecialJob S;
         S.TP = make_tables(c, c->d_tw2P, c->dev_P);
         S.Pq = make_ulonglong2(c->Pq, c->Pq_s);
         S.Pinv = make_ulonglong2(c->Pinv, c->Pinv_s);
         if (job.w)
             hipLaunchKernelGGL(perm_accumulate_special_2048<true>, grid, dim3(NT), 0, st, job, T, S, mj, c->gadget_bits, c->ndigits);
+        else if (job.in8_S)
+            hipLaunchKernelGGL((perm_accumulate_special_2048<false, true>), grid, dim3(NT), 0, st, job, T, S, mj, c->gadget_bits,
+                               c->ndigits);
         else
             hipLaunchKernelGGL(perm_accumulate_special_2048<false>, grid, dim3(NT), 0, st, job, T, S, mj, c->gadget_bits, c->ndigits);
         return (int)hipGetLastError();
