@@ -45,7 +45,8 @@ typedef enum {
     GALA_EHIP = -5       /* a HIP call failed                                   */
 } gala_status;
 
-/* BFV parameters of Sec. II-C(1) / Sec. IV: n slots (power of two, 8..2048),
+/* BFV parameters of Sec. II-C(1) / Sec. IV: n slots (power of two, 8..8192; n = 2048, the paper's ring, has kernels
+ * of its own, every other ring runs on kernels written for any n),
  * ciphertext prime q (2^40 <= q < 2^61, q = 1 mod 2n), plaintext prime p
  * (p = 1 mod 2n, p < 2^31, p < q), key-switching digit width gadget_bits
  * (digits = ceil(bitlen(q-1)/gadget_bits) <= 32).  The error distribution is the

@@ -11,7 +11,7 @@
 namespace gala {
 
 constexpr int kMaxDigits = 32;
-constexpr int kMaxN = 2048;
+constexpr int kMaxN = 8192;   // rings above 2048 run on the any-n kernels (512 or 1024 threads per polynomial)
 constexpr int kGaussBound = 19;
 
 // Cumulative table of the discrete Gaussian (passed to kernels by value) and the draw from it: one 64-bit word

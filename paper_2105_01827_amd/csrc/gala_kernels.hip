@@ -5,6 +5,8 @@
 // 2^61; there is no floating point on this path.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include <cstdlib>
 
 #include "gala_internal.h"
@@ -825,7 +827,19 @@ __global__ void unpack_share_kernel(const u64 *slots, int nout, int n, u64 p, co
     for (int t = threadIdx.x; t < nrows[O]; t += blockDim.x) out[(size_t)b * out_stride + row_rindex[(size_t)O * n + t]] = acc[t] % p;
 }
 
-inline int block_threads(int n) { return n >= 512 ? 256 : 64; }
+// Threads of the one-workgroup-per-polynomial kernels: every thread owns at most kMaxPer = 8 coefficients, so rings of
+// 4096 and 8192 take 512 and 1024 threads (LDS image of n words: 32 and 64 KiB).
+inline int block_threads(int n) { return n >= 8192 ? 1024 : n >= 4096 ? 512 : n >= 512 ? 256 : 64; }
+// calls f with the thread count as a compile-time constant
+template <class F>
+inline void by_threads(int n, F f) {
+    switch (block_threads(n)) {
+        case 1024: f(std::integral_constant<int, 1024>{}); break;
+        case 512: f(std::integral_constant<int, 512>{}); break;
+        case 256: f(std::integral_constant<int, 256>{}); break;
+        default: f(std::integral_constant<int, 64>{}); break;
+    }
+}
 inline int last_error() { return (int)hipGetLastError(); }
 
 }  // namespace
@@ -837,10 +851,10 @@ int launch_ntt_mod(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, si
     if (!count) return 0;
     hipStream_t st = (hipStream_t)stream;
     const size_t lds = sizeof(u64) * c->n;
-    if (block_threads(c->n) == 256)
-        hipLaunchKernelGGL(ntt_kernel<256>, dim3((unsigned)count), dim3(256), lds, st, src, dst, c->n, c->logn, T, inverse);
-    else
-        hipLaunchKernelGGL(ntt_kernel<64>, dim3((unsigned)count), dim3(64), lds, st, src, dst, c->n, c->logn, T, inverse);
+    by_threads(c->n, [&](auto nt) {
+        constexpr int NT = decltype(nt)::value;
+        hipLaunchKernelGGL(ntt_kernel<NT>, dim3((unsigned)count), dim3(NT), lds, st, src, dst, c->n, c->logn, T, inverse);
+    });
     return last_error();
 }
 int launch_ntt(const gala_ctx *c, void *stream, const u64 *src, u64 *dst, size_t count, int inverse) {
@@ -850,12 +864,11 @@ int launch_encode_plain(const gala_ctx *c, void *stream, const u64 *slots, int c
     if (!count) return 0;
     const size_t lds = sizeof(u64) * c->n;
     hipStream_t st = (hipStream_t)stream;
-    if (block_threads(c->n) == 256)
-        hipLaunchKernelGGL(encode_plain_kernel<256>, dim3((unsigned)count), dim3(256), lds, st, slots, plain, c->dev_q, c->dev_p,
+    by_threads(c->n, [&](auto nt) {
+        constexpr int NT = decltype(nt)::value;
+        hipLaunchKernelGGL(encode_plain_kernel<NT>, dim3((unsigned)count), dim3(NT), lds, st, slots, plain, c->dev_q, c->dev_p,
                            c->d_slot_to_idx, c->n, c->logn, mode, c->delta, c->delta_s);
-    else
-        hipLaunchKernelGGL(encode_plain_kernel<64>, dim3((unsigned)count), dim3(64), lds, st, slots, plain, c->dev_q, c->dev_p,
-                           c->d_slot_to_idx, c->n, c->logn, mode, c->delta, c->delta_s);
+    });
     return last_error();
 }
 int launch_ct_op(const gala_ctx *c, void *stream, int op, const u64 *a, const u64 *b, size_t b_stride, int count, u64 *out) {
@@ -895,12 +908,11 @@ int launch_encrypt(const gala_ctx *c, void *stream, const u64 *s_hat, const u64 
     for (int i = 0; i < 2 * kGaussBound; ++i) cdf.t[i] = gauss_cdf_table()[i];
     const size_t lds = sizeof(u64) * c->n;
     hipStream_t st = (hipStream_t)stream;
-    if (block_threads(c->n) == 256)
-        hipLaunchKernelGGL(encrypt_kernel<256>, dim3((unsigned)count), dim3(256), lds, st, slots, seeds, s_hat, ct_out, c->dev_q,
+    by_threads(c->n, [&](auto nt) {
+        constexpr int NT = decltype(nt)::value;
+        hipLaunchKernelGGL(encrypt_kernel<NT>, dim3((unsigned)count), dim3(NT), lds, st, slots, seeds, s_hat, ct_out, c->dev_q,
                            c->dev_p, c->d_slot_to_idx, cdf, c->n, c->logn, c->qbits, c->delta, c->delta_s);
-    else
-        hipLaunchKernelGGL(encrypt_kernel<64>, dim3((unsigned)count), dim3(64), lds, st, slots, seeds, s_hat, ct_out, c->dev_q,
-                           c->dev_p, c->d_slot_to_idx, cdf, c->n, c->logn, c->qbits, c->delta, c->delta_s);
+    });
     return last_error();
 }
 int launch_decrypt(const gala_ctx *c, void *stream, const u64 *s_hat, const u64 *ct_in, int count, u64 *slots) {
@@ -910,12 +922,11 @@ int launch_decrypt(const gala_ctx *c, void *stream, const u64 *s_hat, const u64 
     for (int i = 0; i < 6; ++i) inv *= 2 - c->q * inv;
     const size_t lds = sizeof(u64) * c->n;
     hipStream_t st = (hipStream_t)stream;
-    if (block_threads(c->n) == 256)
-        hipLaunchKernelGGL(decrypt_kernel<256>, dim3((unsigned)count), dim3(256), lds, st, ct_in, s_hat, slots, c->dev_q, c->dev_p,
+    by_threads(c->n, [&](auto nt) {
+        constexpr int NT = decltype(nt)::value;
+        hipLaunchKernelGGL(decrypt_kernel<NT>, dim3((unsigned)count), dim3(NT), lds, st, ct_in, s_hat, slots, c->dev_q, c->dev_p,
                            c->d_slot_to_idx, c->n, c->logn, inv);
-    else
-        hipLaunchKernelGGL(decrypt_kernel<64>, dim3((unsigned)count), dim3(64), lds, st, ct_in, s_hat, slots, c->dev_q, c->dev_p,
-                           c->d_slot_to_idx, c->n, c->logn, inv);
+    });
     return last_error();
 }
 int launch_key_finish(const gala_ctx *c, void *stream, u64 *pairs, const u64 *s_hat, size_t npairs, const Modulus &mod) {
@@ -961,21 +972,15 @@ int launch_perm_accumulate(const gala_ctx *c, void *stream, const PermJob &job) 
         return rc;
     }
     const SpecialConst sc{c->Pq, c->Pinv};
-    const bool big = block_threads(c->n) == 256;
-    if (c->special) {
-        if (big)
-            hipLaunchKernelGGL((perm_accumulate_kernel<256, true>), grid, dim3(256), lds, st, job, c->dev_q, c->dev_P, sc, c->n,
+    by_threads(c->n, [&](auto nt) {
+        constexpr int NT = decltype(nt)::value;
+        if (c->special)
+            hipLaunchKernelGGL((perm_accumulate_kernel<NT, true>), grid, dim3(NT), lds, st, job, c->dev_q, c->dev_P, sc, c->n,
                                c->logn, c->gadget_bits, c->ndigits);
         else
-            hipLaunchKernelGGL((perm_accumulate_kernel<64, true>), grid, dim3(64), lds, st, job, c->dev_q, c->dev_P, sc, c->n,
+            hipLaunchKernelGGL((perm_accumulate_kernel<NT, false>), grid, dim3(NT), lds, st, job, c->dev_q, c->dev_q, sc, c->n,
                                c->logn, c->gadget_bits, c->ndigits);
-    } else if (big) {
-        hipLaunchKernelGGL((perm_accumulate_kernel<256, false>), grid, dim3(256), lds, st, job, c->dev_q, c->dev_q, sc, c->n,
-                           c->logn, c->gadget_bits, c->ndigits);
-    } else {
-        hipLaunchKernelGGL((perm_accumulate_kernel<64, false>), grid, dim3(64), lds, st, job, c->dev_q, c->dev_q, sc, c->n,
-                           c->logn, c->gadget_bits, c->ndigits);
-    }
+    });
     if (timed) (void)hipEventRecord((hipEvent_t)c->prof_events[2 * c->prof_used++ + 1], st);
     return last_error();
 }
@@ -983,12 +988,11 @@ int launch_finalize(const gala_ctx *c, void *stream, const FinalizeJob &job) {
     if (job.items <= 0) return 0;
     hipStream_t st = (hipStream_t)stream;
     const size_t lds = sizeof(u64) * c->n;
-    if (block_threads(c->n) == 256)
-        hipLaunchKernelGGL(finalize_kernel<256>, dim3(job.items), dim3(256), lds, st, job, c->dev_q, c->dev_p,
+    by_threads(c->n, [&](auto nt) {
+        constexpr int NT = decltype(nt)::value;
+        hipLaunchKernelGGL(finalize_kernel<NT>, dim3(job.items), dim3(NT), lds, st, job, c->dev_q, c->dev_p,
                            c->d_slot_to_idx, c->n, c->logn, c->pbits, c->delta, c->delta_s);
-    else
-        hipLaunchKernelGGL(finalize_kernel<64>, dim3(job.items), dim3(64), lds, st, job, c->dev_q, c->dev_p,
-                           c->d_slot_to_idx, c->n, c->logn, c->pbits, c->delta, c->delta_s);
+    });
     return last_error();
 }
 int launch_perm_finalize(const gala_ctx *c, void *stream, const PermJob &job, const FinalizeJob &fin) {
@@ -1001,12 +1005,11 @@ int launch_decperm(const gala_ctx *c, void *stream, const u64 *ct_in, size_t cou
     if (!count) return 0;
     hipStream_t st = (hipStream_t)stream;
     const size_t lds = sizeof(u64) * c->n;
-    if (block_threads(c->n) == 256)
-        hipLaunchKernelGGL(decperm_kernel<256>, dim3((unsigned)count), dim3(256), lds, st, ct_in, digits, c->dev_q, c->n,
+    by_threads(c->n, [&](auto nt) {
+        constexpr int NT = decltype(nt)::value;
+        hipLaunchKernelGGL(decperm_kernel<NT>, dim3((unsigned)count), dim3(NT), lds, st, ct_in, digits, c->dev_q, c->n,
                            c->logn, c->gadget_bits, c->ndigits);
-    else
-        hipLaunchKernelGGL(decperm_kernel<64>, dim3((unsigned)count), dim3(64), lds, st, ct_in, digits, c->dev_q, c->n,
-                           c->logn, c->gadget_bits, c->ndigits);
+    });
     return last_error();
 }
 int launch_hstperm_taps(const gala_ctx *c, void *stream, const u64 *ct_in, const u64 *digits, int batch,

@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_bad_parameters_are_rejected():
     lib = binding.load()
-    for n, q, p, gb in [(100, wl.Q, wl.P, 20), (4096, wl.Q, wl.P, 20), (2048, wl.Q + 2, wl.P, 20),
+    for n, q, p, gb in [(100, wl.Q, wl.P, 20), (4096, wl.Q, wl.P, 20), (16384, wl.find_prime_below(1 << 60, 32768 * 65537), 65537, 20), (2048, wl.Q + 2, wl.P, 20),
                         (2048, wl.Q, wl.P + 4096, 20), (2048, wl.Q, wl.P, 0), (2048, wl.Q, wl.P, 1),
                         (2048, 12289, 12289, 4)]:
         with pytest.raises(binding.GalaError) as e:
