@@ -594,7 +594,7 @@ extern "C" int gala_he_conv_outrot(const gala_ctx *c, void *stream, const gala_c
     const int rc = hoist_terms(c, stream, ct_in, batch, terms, pl->nrot_terms > 0, keys, keys2, digits, xrot);
     c->prof_which = which;
     if (rc) return GALA_EHIP;
-    if (launch_conv_mac(c, stream, pl->d_w, xrot, batch, pl->nout, pl->cn, pl->nterm, acc, pl->d_seg_ptr, nin))
+    if (launch_conv_mac(c, stream, pl->d_w, xrot, batch, pl->nout, pl->cn, pl->nterm, acc, pl->d_seg_ptr, pl->d_seg_terms, nin))
         return GALA_EHIP;
     PermJob job{};
     job.ct_in = acc;

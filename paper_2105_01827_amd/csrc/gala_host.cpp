@@ -910,8 +910,8 @@ extern "C" int gala_conv_plan_create(gala_ctx *c, const uint64_t *K, int c_o, in
     // Terms: an (input ciphertext, tap) pair takes part when some kernel value it carries is non-zero mod p and the
     // tap reaches inside the image; every (input channel, output channel) pair sits in exactly one kernel order, so
     // this is the set of pairs with a non-zero encoded kernel.  An all-zero layer keeps one term.
-    for (int I = 0; I < nin; ++I)
-        for (int tap = 0; tap < ntap; ++tap) {
+    for (int tap = 0; tap < ntap; ++tap)
+        for (int I = 0; I < nin; ++I) {
             const int dy = tap / k_w - k_h / 2, dx = tap % k_w - k_w / 2;
             bool active = false;
             if (std::abs(dy) < u_h && std::abs(dx) < u_w)
@@ -987,11 +987,14 @@ extern "C" int gala_conv_plan_create(gala_ctx *c, const uint64_t *K, int c_o, in
         std::vector<int> or_gal((size_t)cn * nin), or_key((size_t)cn * nin, -1), seg(nin + 1, 0);
         for (int gam = 0; gam < cn; ++gam)
             for (int I = 0; I < nin; ++I) or_gal[(size_t)gam * nin + I] = pl->grp_gal[gam];
+        std::vector<int> seg_terms(nterm), fill(nin, 0);
         for (int e = 0; e < nterm; ++e) ++seg[pl->term_ct[e] + 1];
         for (int I = 0; I < nin; ++I) seg[I + 1] += seg[I];
+        for (int e = 0; e < nterm; ++e) seg_terms[seg[pl->term_ct[e]] + fill[pl->term_ct[e]]++] = e;
         if (!rc) rc = upload(&pl->d_or_gal, or_gal);
         if (!rc) rc = upload(&pl->d_or_key, or_key);
         if (!rc) rc = upload(&pl->d_seg_ptr, seg);
+        if (!rc) rc = upload(&pl->d_seg_terms, seg_terms);
     }
     if (!rc) rc = upload_mask_layout(c, mh, &pl->mask_d);
     if (rc) { gala_conv_plan_destroy(pl); return rc; }
@@ -1019,7 +1022,7 @@ extern "C" void gala_conv_plan_destroy(gala_conv_plan *pl) {
     if (!pl) return;
     hipFree(pl->d_w); hipFree(pl->d_wl); hipFree(pl->d_term_ct); hipFree(pl->d_term_gal); hipFree(pl->d_term_key);
     hipFree(pl->d_grp_gal); hipFree(pl->d_grp_key);
-    hipFree(pl->d_or_gal); hipFree(pl->d_or_key); hipFree(pl->d_seg_ptr);
+    hipFree(pl->d_or_gal); hipFree(pl->d_or_key); hipFree(pl->d_seg_ptr); hipFree(pl->d_seg_terms);
     free_mask_layout(&pl->mask_d);
     delete pl;
 }

@@ -178,7 +178,8 @@ struct gala_conv_plan {
     int T = 0, cn = 0, hpos = 0, nin = 0, nout = 0, ntap = 0, centre = 0;
     std::vector<int> tap_gal, grp_gal; // Galois elements of taps (ntap) and kernel orders (cn)
     // Terms of the multiply-accumulate: the (input ciphertext, tap) pairs whose encoded kernels are not all zero,
-    // in (input, tap) order.  A dense kernel has nin*ntap of them.
+    // in (tap, input) order: consecutive terms share their tap, i.e. their rotation and key, which the kernel that
+    // rotates the inputs sixteen terms at a time loads once.  A dense kernel has nin*ntap of them.
     int nterm = 0, nrot_terms = 0, nrot_cts = 0;   // terms; those that rotate; input ciphertexts with a rotating term
     std::vector<int> term_ct, term_tap;
     int *d_term_ct = nullptr, *d_term_gal = nullptr, *d_term_key = nullptr;   // nterm each (key valid once bound)
@@ -188,7 +189,7 @@ struct gala_conv_plan {
     // output-rotation schedule (Sec. III-B(2)): entry gam * nin + I of an output ciphertext's sum is the block of input
     // ciphertext I in kernel order gam; seg_ptr[I] .. seg_ptr[I+1]-1 are the terms of input ciphertext I
     int *d_or_gal = nullptr, *d_or_key = nullptr;     // cn * nin
-    int *d_seg_ptr = nullptr;                          // nin + 1
+    int *d_seg_ptr = nullptr, *d_seg_terms = nullptr;  // nin + 1 offsets into the nterm term numbers grouped by input ciphertext
     const gala_gk *bound = nullptr;
     MaskLayoutHost mask_h;
     MaskLayoutDev mask_d;
@@ -314,10 +315,10 @@ struct TermList {
 int launch_hstperm_taps(const gala_ctx *ctx, void *stream, const u64 *ct_in, const u64 *digits, int batch,
                         const TermList &terms, const u64 *keys, u64 *xrot);
 // acc[b][O][gam] = sum_{I,tap} w[O][gam][I][tap] (.) xrot[b][I][tap]   (both polynomials)
-// seg_ptr (device, nseg + 1 ints) cuts the terms into nseg consecutive ranges with sums of their own:
-//   acc[b][O][gam][s] = sum over the terms of range s; nullptr: one sum over all terms (nseg ignored)
+// seg_ptr (device, nseg + 1 ints) and seg_terms (device, term numbers) give nseg groups of terms sums of their own:
+//   acc[b][O][gam][s] = sum over the terms seg_terms[seg_ptr[s] .. seg_ptr[s+1]-1]; nullptr: one sum over all terms
 int launch_conv_mac(const gala_ctx *ctx, void *stream, const u64 *w, const u64 *xrot, int batch, int nout, int cn,
-                    int nterm, u64 *acc, const int *seg_ptr = nullptr, int nseg = 1);
+                    int nterm, u64 *acc, const int *seg_ptr = nullptr, const int *seg_terms = nullptr, int nseg = 1);
 
 // Matrix-core path of the convolution's multiply-accumulate (gala_conv_mfma.hip): digit-plane images of the
 // encoded kernels (built once per plan) and of the rotated inputs (built per call), then one MFMA kernel.

@@ -581,13 +581,14 @@ __device__ __forceinline__ void mac128(u64 &lo, u64 &hi, u64 x, u64 w) {
 // nterm terms (the plan's active (input ciphertext, tap) pairs); groups = nout*cn; cols = 2*batch (input-major, c0 then c1).
 // A workgroup is WM x WN wavefronts on the same 64 coefficients: the wavefronts of a row read the same
 // weight words and those of a column the same input words, so those reads hit in the CU's vector cache.
-// Segments (seg_ptr != nullptr, nseg of them): the terms are cut into consecutive ranges seg_ptr[s] .. seg_ptr[s+1]-1
-// and every range gets sums of its own, acc row (m, s) = m * nseg + s: the per-input-ciphertext sums that the
-// output-rotation schedule of Sec. III-B(2) rotates one by one.  Without segments there is one sum per row.
+// Segments (seg_ptr != nullptr, nseg of them): segment s owns the terms seg_terms[seg_ptr[s] .. seg_ptr[s+1]-1] and gets
+// sums of its own, acc row (m, s) = m * nseg + s: the per-input-ciphertext sums that the output-rotation schedule of
+// Sec. III-B(2) rotates one by one.  Without segments there is one sum per row over all terms.
 template <int TM, int TN, int WM, int WN, int U>
 __global__ __launch_bounds__(64 * WM * WN) void conv_mac_kernel(const u64 *w, const u64 *xrot, int cols, int groups,
                                                                 int nterm, u64 *acc, Modulus mod, int n,
-                                                                int flush_every, const int *seg_ptr, int nseg) {
+                                                                int flush_every, const int *seg_ptr, const int *seg_terms,
+                                                                int nseg) {
     const int i = blockIdx.x * 64 + (threadIdx.x & 63);
     if (i >= n) return;
     const int wave = threadIdx.x >> 6;
@@ -610,15 +611,17 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mac_kernel(const u64 *w, co
         for (int b = 0; b < TN; ++b) lo[a][b] = hi[a][b] = 0;
     // U terms per step, all their loads issued before the first product: a wavefront that waits for one load at
     // a time reaches about half of the memory rate that several loads in flight do.
+    auto term = [&](int k) -> size_t { return (size_t)(seg_ptr ? seg_terms[k] : k); };
     int pending = 0, e = e_begin;
     for (; e + U <= e_end; e += U) {
         u64 wv[U][TM], xv[U][TN];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
+            const size_t et = term(e + u);
 #pragma unroll
-            for (int a = 0; a < TM; ++a) wv[u][a] = wp[a][(size_t)(e + u) * n];
+            for (int a = 0; a < TM; ++a) wv[u][a] = wp[a][et * n];
 #pragma unroll
-            for (int b = 0; b < TN; ++b) xv[u][b] = xp[b][(size_t)(e + u) * 2 * n];
+            for (int b = 0; b < TN; ++b) xv[u][b] = xp[b][et * 2 * n];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -640,10 +643,11 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mac_kernel(const u64 *w, co
     }
     for (; e < e_end; ++e) {               // fewer than U terms left: there is room for them (pending + U <= flush_every)
         u64 wv[TM], xv[TN];
+        const size_t et = term(e);
 #pragma unroll
-        for (int a = 0; a < TM; ++a) wv[a] = wp[a][(size_t)e * n];
+        for (int a = 0; a < TM; ++a) wv[a] = wp[a][et * n];
 #pragma unroll
-        for (int b = 0; b < TN; ++b) xv[b] = xp[b][(size_t)e * 2 * n];
+        for (int b = 0; b < TN; ++b) xv[b] = xp[b][et * 2 * n];
 #pragma unroll
         for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -1020,7 +1024,7 @@ int launch_hstperm_taps(const gala_ctx *c, void *stream, const u64 *ct_in, const
     return last_error();
 }
 int launch_conv_mac(const gala_ctx *c, void *stream, const u64 *w, const u64 *xrot, int batch, int nout, int cn,
-                    int nterm, u64 *acc, const int *seg_ptr, int nseg) {
+                    int nterm, u64 *acc, const int *seg_ptr, const int *seg_terms, int nseg) {
     if (batch <= 0) return 0;
     if (!seg_ptr) nseg = 1;
     const int groups = nout * cn, cols = 2 * batch;
@@ -1039,7 +1043,7 @@ int launch_conv_mac(const gala_ctx *c, void *stream, const u64 *w, const u64 *xr
 #define GALA_MAC(TM, TN, WM, WN)                                                                                      \
     hipLaunchKernelGGL((conv_mac_kernel<TM, TN, WM, WN, 1>),                                                         \
                        dim3(iblocks, (unsigned)((groups + TM * WM - 1) / (TM * WM) * nseg), (unsigned)((cols + TN * WN - 1) / (TN * WN))), \
-                       dim3(64 * WM * WN), 0, st, w, xrot, cols, groups, nterm, acc, c->dev_q.mod, c->n, flush_every, seg_ptr, nseg)
+                       dim3(64 * WM * WN), 0, st, w, xrot, cols, groups, nterm, acc, c->dev_q.mod, c->n, flush_every, seg_ptr, seg_terms, nseg)
     if (cols <= 2 && !seg_ptr) {
         // one input: the streaming kernel, with the tallest row tile that still gives every compute unit a workgroup
         const size_t per_cu = 256;

@@ -623,42 +623,65 @@ __global__ __launch_bounds__(NT) void hstperm_pack_2048(const u64 *ct_in, const 
     const int nterm = terms.nterm, ndigits = ND ? ND : ndigits_rt;
     const NegQ q = T.nq;
     const size_t key_pairs = (size_t)ndigits * 2 * N;
-    // A term past the end repeats the last one and is zeroed; a rotation by zero reads its own digits and the
-    // first key and multiplies by zero: every term runs the same straight code with the digit loop unrolled.
+    // Terms come in (tap, input ciphertext) order, so the sixteen terms of a thread share their rotation in runs: the
+    // automorphism's source index and the key pairs of the tap are fetched when the rotation changes (a decision all
+    // lanes share), not per term; what differs from term to term is the input ciphertext, i.e. c0 and the digits at
+    // the source index.  Terms of the central tap (no rotation) are copies.  A term past the end repeats the last
+    // one and is zeroed.
     u64 D0[16], D1[16];     // balanced digits of the 16 terms' c0 and c1 values
+    constexpr int KD = ND ? ND : 1;
+    ulonglong2 kwb[KD], kwa[KD];
+    const ulonglong2 *key = nullptr;
+    int cur_gal = 0, src = i;
+    bool ident = true;
 #pragma unroll
     for (int t = 0; t < 16; ++t) {
         const int e = min(eb * 16 + t, nterm - 1);
         const bool live = eb * 16 + t < nterm;
         const int gal = terms.gal[e];
-        const bool ident = gal == 1;
-        const size_t ct = (size_t)b * terms.nin + terms.ct[e];
-        const u64 *c0 = ct_in + ct * 2 * N;
-        const ulonglong2 *key = reinterpret_cast<const ulonglong2 *>(keys2) + (size_t)max(terms.key[e], 0) * key_pairs;
-        const u64 *dsrc = digits + ct * ndigits * N;
-        const int src = ident ? i : galois_index11(i, gal);
-        u64 s0 = c0[src], s1 = ident ? c0[N + i] : 0;
-        if (ANY_ROT) {
-            if (ND) {
+        if (gal != cur_gal) {          // the same for every lane
+            cur_gal = gal;
+            ident = gal == 1;
+            src = ident ? i : galois_index11(i, gal);
+            if (ANY_ROT && !ident) {
+                key = reinterpret_cast<const ulonglong2 *>(keys2) + (size_t)terms.key[e] * key_pairs;
+                if (ND) {
 #pragma unroll
-                for (int j = 0; j < (ND ? ND : 1); ++j) {
-                    const u64 dl = dsrc[(size_t)j * N + src];
-                    const u64 d = ident ? 0 : dl;
-                    const ulonglong2 kb = key[(size_t)(2 * j) * N + i], ka = key[(size_t)(2 * j + 1) * N + i];
-                    s0 += mul_const(d, kb.x, kb.y, q);      // each product is below 2q: at most 7q in all
-                    s1 += mul_const(d, ka.x, ka.y, q);
-                }
-            } else {
-                for (int j = 0; j < ndigits; ++j) {
-                    const u64 dl = dsrc[(size_t)j * N + src];
-                    const u64 d = ident ? 0 : dl;
-                    const ulonglong2 kb = key[(size_t)(2 * j) * N + i], ka = key[(size_t)(2 * j + 1) * N + i];
-                    s0 += mul_const(d, kb.x, kb.y, q);
-                    s1 += mul_const(d, ka.x, ka.y, q);
+                    for (int j = 0; j < KD; ++j) {
+                        kwb[j] = key[(size_t)(2 * j) * N + i];
+                        kwa[j] = key[(size_t)(2 * j + 1) * N + i];
+                    }
                 }
             }
         }
-        const u64 v0 = live ? reduce64(s0, T.mod) : 0, v1 = live ? reduce64(s1, T.mod) : 0;
+        const size_t ct = (size_t)b * terms.nin + terms.ct[e];
+        const u64 *c0 = ct_in + ct * 2 * N;
+        u64 v0, v1;
+        if (!ANY_ROT || ident) {
+            v0 = c0[i];
+            v1 = c0[N + i];
+        } else {
+            const u64 *dsrc = digits + ct * ndigits * N;
+            u64 s0 = c0[src], s1 = 0;
+            if (ND) {
+#pragma unroll
+                for (int j = 0; j < KD; ++j) {
+                    const u64 d = dsrc[(size_t)j * N + src];
+                    s0 += mul_const(d, kwb[j].x, kwb[j].y, q);      // each product is below 2q: at most 7q in all
+                    s1 += mul_const(d, kwa[j].x, kwa[j].y, q);
+                }
+            } else {
+                for (int j = 0; j < ndigits; ++j) {
+                    const u64 d = dsrc[(size_t)j * N + src];
+                    const ulonglong2 wb = key[(size_t)(2 * j) * N + i], wa = key[(size_t)(2 * j + 1) * N + i];
+                    s0 += mul_const(d, wb.x, wb.y, q);
+                    s1 += mul_const(d, wa.x, wa.y, q);
+                }
+            }
+            v0 = reduce64(s0, T.mod);
+            v1 = reduce64(s1, T.mod);
+        }
+        if (!live) v0 = v1 = 0;
         const u64 k80 = 0x8080808080808080ull;   // bytes of x + 0x80..80 are the balanced digits plus 128
         D0[t] = (v0 + k80) ^ k80;
         D1[t] = (v1 + k80) ^ k80;
