@@ -10,7 +10,6 @@ sample of the same inputs, whose ciphertexts must equal the GPU's.  Prints ONE J
 """
 import argparse
 import concurrent.futures
-import ctypes
 import json
 import os
 import re
@@ -633,6 +632,8 @@ def main():
                     help="wall time every workload runs untimed before its measurements, on top of --warmup")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="measure the headline workload only")
+    ap.add_argument("--no-compare", action="store_true",
+                    help="skip the paper's comparison schedules (hybrid FC, output-rotation convolution) beside each workload")
     ap.add_argument("--vector-mac", action="store_true",
                     help="convolution: keep the multiply-accumulate on the vector ALU instead of the matrix cores")
     ap.add_argument("--special-prime", action="store_true",
@@ -673,10 +674,11 @@ def main():
         if name in fc_shapes:
             sample, repeat = fc_sample[name]
             return fc_config(ctx, sk, D, torch, par, fc_shapes[name], steps, pre, sample if cpu else 0, repeat,
-                             special=args.special_prime, warmup=warmup)
+                             special=args.special_prime, warmup=warmup, compare=not args.no_compare)
         if name.startswith("conv"):
             return conv_config(ctx, sk, D, torch, par, wl.CONV_16x16_128_3x3, steps, pre, 16 if cpu else 0,
-                               special=args.special_prime, vector_mac=args.vector_mac, warmup=warmup)
+                               special=args.special_prime, vector_mac=args.vector_mac, warmup=warmup,
+                               compare=not args.no_compare)
         return resnet18_config(ctx, sk, D, torch, par, steps, pre, 3 if cpu else 0, args.stride_by_subsampling,
                                warmup=warmup)
 

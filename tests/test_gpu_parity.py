@@ -534,3 +534,27 @@ def test_he_conv_matrix_cores_long_sums_stay_exact(n, c_i, u):
     shape = (n // (u * u), c_i, 1, 1, u, u)
     ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, shape, 2, [(0, 0), (1, 0)], seed=n, matrix_cores=True)
     assert plan.nterm == c_i * u * u // n and plan.nterm >= 2048 and plan.nout == 1
+
+
+def test_edge_cases_empty_counts_and_largest_fc_shapes():
+    """Nothing to do is not an error for the element-wise and Perm entry points (count = 0 launches nothing and leaves
+    the output untouched); the largest matrices one ciphertext block holds (n_o = n with n_i = n/2, and n_o = n/2
+    with n_i = n: 1024 encoded rows, 1023 rotations) against the oracle."""
+    import torch
+    H = harness()
+    par = wl.DEFAULT
+    ctx, o = both(par)
+    sk = ctx.keygen(1)
+    gk = ctx.galois_keygen(sk, [(0, 1)], seed=2)
+    d_in = H.dev_empty(2 * par.n)
+    d_out = torch.full((2 * par.n,), 7, dtype=torch.int64, device="cuda")
+    ctx.rotate(gk, d_in, 0, (0, 1), d_out)
+    ctx.ct_import(d_in, 0, d_out)
+    ctx.ct_export(d_in, 0, d_out)
+    torch.cuda.synchronize()
+    assert bool((d_out == 7).all())
+    for n_o, n_i in ((2048, 1024), (1024, 2048)):
+        ctx2, o2, plan, sk2, W, x, r, got = fc_case(par, n_o, n_i, 1, [0], seed=n_o)
+        assert plan.G == 1024
+        share = plan.unpack_share(ctx2.decrypt(sk2, got[0]))
+        assert np.array_equal((share + r[0]) % np.uint64(par.p), (W @ x[0]) % np.uint64(par.p))
