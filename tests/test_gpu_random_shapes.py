@@ -1,0 +1,77 @@
+"""GPU parity on layer shapes drawn by a seeded generator: he_fc and he_conv against the oracle, bit for bit.
+
+The hand-picked shapes of test_gpu_parity.py cover the cases someone thought of; these cover ragged
+sizes nobody picked (odd channel counts, non-square images, 1 x k kernels, batches that leave a column
+tile of the matrix-core product partly empty).  Every output ciphertext of every case is recomputed by
+the oracle, and the FC cases also decrypt to W x.  A third of the cases use special-prime keys; those
+convolutions decrypt to the plain convolution as well.
+"""
+import numpy as np
+import pytest
+
+from oracle.oracle import Oracle
+from tests.helpers import small_params
+from tests.test_gpu_parity import conv_case, fc_case, plain_conv, plain_matvec
+from tests.test_gpu_special import with_special
+
+pytestmark = pytest.mark.gpu
+
+
+def fc_shapes(count, seed):
+    """(n, n_o, n_i, batch, special): padded sizes within what a plan accepts (n_i <= n; n_o <= n/2 when n_i fills the ring)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        n = int(rng.choice([32, 64, 128, 256, 512]))
+        n_i = int(rng.integers(1, n + 1))
+        nip = 1 << (n_i - 1).bit_length()
+        n_o = int(rng.integers(1, (n // 2 if nip == n else n) + 1))
+        out.append((n, n_o, n_i, int(rng.integers(1, 5)), bool(rng.integers(0, 3) == 0)))
+    return out
+
+
+def conv_shapes(count, seed):
+    """(n, shape, batch, matrix_cores, special): odd kernel sides, an image of at most n/2 pixels."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        n = int(rng.choice([32, 64, 128, 256, 512]))
+        uh = int(rng.integers(1, 9))
+        uw = int(rng.integers(1, 9))
+        if uh * uw > n // 2:
+            continue
+        kh, kw = int(rng.choice([1, 3, 5])), int(rng.choice([1, 3, 5]))
+        co, ci = int(rng.integers(1, 20)), int(rng.integers(1, 20))
+        batch = int(rng.integers(1, 7))
+        out.append((n, (co, ci, kh, kw, uh, uw), batch, bool(batch >= 2 and rng.integers(0, 2)),
+                    bool(rng.integers(0, 3) == 0)))
+    return out
+
+
+@pytest.mark.parametrize("n,n_o,n_i,batch,special", fc_shapes(60, seed=20210501))
+def test_he_fc_on_drawn_shapes(n, n_o, n_i, batch, special):
+    par = small_params(n)
+    if special:
+        par = with_special(par)
+    ctx, o, plan, sk, W, x, r, got = fc_case(par, n_o, n_i, batch, list(range(batch)), seed=7 * n_o + n_i)
+    for b in range(batch):
+        share = plan.unpack_share(ctx.decrypt(sk, got[b]))
+        assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_matvec(W, x[b], par.p))
+
+
+@pytest.mark.parametrize("n,shape,batch,matrix_cores,special", conv_shapes(60, seed=20210502))
+def test_he_conv_on_drawn_shapes(n, shape, batch, matrix_cores, special):
+    par = small_params(n, p_limit=1 << 14, gadget_bits=4)
+    if special:
+        par = with_special(par)
+    nout = Oracle(par.n, par.q, par.p, par.gadget_bits).conv_geometry(*shape)["nout"]
+    ctx, o, plan, sk, K, x, r, got, cnt = conv_case(par, shape, batch, [(b, O) for b in range(batch) for O in range(nout)],
+                                                    seed=n + shape[0], matrix_cores=matrix_cores)
+    if not special:
+        return
+    co, ci, kh, kw, uh, uw = shape
+    for b in range(batch):
+        share = np.zeros((co, uh, uw), np.uint64)
+        for O in range(plan.nout):
+            plan.unpack_share(O, ctx.decrypt(sk, got[b, O]), share)
+        assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_conv(K, x[b], par.p))
