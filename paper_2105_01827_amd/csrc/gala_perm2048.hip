@@ -90,7 +90,9 @@ __device__ __forceinline__ u64 mul_const(u64 y, u64 w, u64 ws, NegQ nq) {
 // wait state between an inline-asm statement and any statement that reads one of its results; inside a block
 // there is none.  A block ends where the next step needs one half of a 64-bit result (halves cannot be named
 // inside a block).  The two chains alternate, so no instruction reads the result of the one before it.  Carry-outs
-// go to vcc except the one that is read through a scalar pair.
+// go to vcc except the one that is read through a scalar pair; each of the two carries that are used is read two
+// wait states after the multiply-add that wrote it (the spacing the compiler itself keeps between a vector
+// instruction that writes a scalar register and one that reads it).
 // Measured, this form is 4.5 % faster where both constants already sit in registers (the packed convolution's
 // key products), makes no difference in the transforms, and is a tenth slower where each product waits for its
 // own loads (the Perm kernel's key products): only the first kind uses it.
@@ -106,6 +108,7 @@ __device__ __forceinline__ void mul_const2(u64 &ra, u64 &rb, u64 ya, const ulong
         "v_mad_u64_u32 %[Cb], vcc, %[b0], %[sb1], %[A1b]\n\t"
         "v_mad_u64_u32 %[Ca], vcc, %[a1], %[sa0], %[Ca]\n\t"
         "v_mad_u64_u32 %[Cb], %[kb], %[b1], %[sb0], %[Cb]\n\t"
+        "s_nop 0\n\t"
         "v_cndmask_b32_e64 %[topa], 0, 1, vcc\n\t"
         "v_cndmask_b32_e64 %[topb], 0, 1, %[kb]"
         : [Ca] "=&v"(Ca), [Cb] "=&v"(Cb), [topa] "=v"(topa), [topb] "=v"(topb), [kb] "=&s"(kb)
