@@ -47,3 +47,36 @@ def rotate_slots(v, step, swap=False):
 def centred(v, q):
     v = int(v)
     return v - q if v > q // 2 else v
+
+
+# Layer shapes drawn by a seeded generator: ragged sizes nobody picked by hand (odd channel counts, non-square
+# images, 1 x k kernels).  The oracle is pinned on them by its decryption identities, the GPU library by the oracle.
+def fc_shapes(count, seed):
+    """(n, n_o, n_i, batch, special): padded sizes within what a plan accepts (n_i <= n; n_o <= n/2 when n_i fills the ring)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        n = int(rng.choice([32, 64, 128, 256, 512]))
+        n_i = int(rng.integers(1, n + 1))
+        nip = 1 << (n_i - 1).bit_length()
+        n_o = int(rng.integers(1, (n // 2 if nip == n else n) + 1))
+        out.append((n, n_o, n_i, int(rng.integers(1, 5)), bool(rng.integers(0, 3) == 0)))
+    return out
+
+
+def conv_shapes(count, seed):
+    """(n, shape, batch, matrix_cores, special): odd kernel sides, an image of at most n/2 pixels."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        n = int(rng.choice([32, 64, 128, 256, 512]))
+        uh = int(rng.integers(1, 9))
+        uw = int(rng.integers(1, 9))
+        if uh * uw > n // 2:
+            continue
+        kh, kw = int(rng.choice([1, 3, 5])), int(rng.choice([1, 3, 5]))
+        co, ci = int(rng.integers(1, 20)), int(rng.integers(1, 20))
+        batch = int(rng.integers(1, 7))
+        out.append((n, (co, ci, kh, kw, uh, uw), batch, bool(batch >= 2 and rng.integers(0, 2)),
+                    bool(rng.integers(0, 3) == 0)))
+    return out

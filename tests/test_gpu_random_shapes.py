@@ -10,42 +10,11 @@ import numpy as np
 import pytest
 
 from oracle.oracle import Oracle
-from tests.helpers import small_params
+from tests.helpers import conv_shapes, fc_shapes, small_params
 from tests.test_gpu_parity import conv_case, fc_case, plain_conv, plain_matvec
 from tests.test_gpu_special import with_special
 
 pytestmark = pytest.mark.gpu
-
-
-def fc_shapes(count, seed):
-    """(n, n_o, n_i, batch, special): padded sizes within what a plan accepts (n_i <= n; n_o <= n/2 when n_i fills the ring)."""
-    rng = np.random.default_rng(seed)
-    out = []
-    while len(out) < count:
-        n = int(rng.choice([32, 64, 128, 256, 512]))
-        n_i = int(rng.integers(1, n + 1))
-        nip = 1 << (n_i - 1).bit_length()
-        n_o = int(rng.integers(1, (n // 2 if nip == n else n) + 1))
-        out.append((n, n_o, n_i, int(rng.integers(1, 5)), bool(rng.integers(0, 3) == 0)))
-    return out
-
-
-def conv_shapes(count, seed):
-    """(n, shape, batch, matrix_cores, special): odd kernel sides, an image of at most n/2 pixels."""
-    rng = np.random.default_rng(seed)
-    out = []
-    while len(out) < count:
-        n = int(rng.choice([32, 64, 128, 256, 512]))
-        uh = int(rng.integers(1, 9))
-        uw = int(rng.integers(1, 9))
-        if uh * uw > n // 2:
-            continue
-        kh, kw = int(rng.choice([1, 3, 5])), int(rng.choice([1, 3, 5]))
-        co, ci = int(rng.integers(1, 20)), int(rng.integers(1, 20))
-        batch = int(rng.integers(1, 7))
-        out.append((n, (co, ci, kh, kw, uh, uw), batch, bool(batch >= 2 and rng.integers(0, 2)),
-                    bool(rng.integers(0, 3) == 0)))
-    return out
 
 
 @pytest.mark.parametrize("n,n_o,n_i,batch,special", fc_shapes(60, seed=20210501))
