@@ -558,3 +558,48 @@ def test_edge_cases_empty_counts_and_largest_fc_shapes():
         assert plan.G == 1024
         share = plan.unpack_share(ctx2.decrypt(sk2, got[0]))
         assert np.array_equal((share + r[0]) % np.uint64(par.p), (W @ x[0]) % np.uint64(par.p))
+
+
+@pytest.mark.parametrize("gb", [60, 30, 15, 12, 7])
+def test_n2048_kernels_with_other_digit_counts(gb):
+    """The n = 2048 kernels are written for any number of gadget digits but every other full-size test uses three
+    (or two with a special prime): one, two, four, five and nine digits here, through Perm, hoisted rotations,
+    he_fc and he_conv on both multiply-accumulate paths, ciphertexts equal to the oracle's."""
+    import dataclasses
+    H = harness()
+    par = dataclasses.replace(wl.DEFAULT, gadget_bits=gb)
+    ctx, o = both(par)
+    n = par.n
+    sk, osk = ctx.keygen(3), o.keygen(3)
+    rng = np.random.default_rng(gb)
+    slots = rng.integers(0, par.p, size=(2, n), dtype=np.uint64)
+    cts = np.stack([ctx.encrypt(sk, slots[i], seed=10 + i) for i in range(2)])
+    rots = [(0, 5), (1, 77)]
+    gk = ctx.galois_keygen(sk, rots, seed=42)
+    d_in = H.import_cts(ctx, cts)
+    for swap, step in rots:
+        d_out = H.dev_empty(2 * 2 * n)
+        ctx.rotate(gk, d_in, 2, (swap, step), d_out)
+        got = H.export_cts(ctx, d_out, 2)
+        g = o.galois_elt(swap, step)
+        for i in range(2):
+            assert np.array_equal(got[i], o.perm(cts[i], g, o.galois_key(osk, g, 42))), (swap, step, i)
+    d_out = H.dev_empty(2 * len(rots) * 2 * n)
+    wsb = ctx.rotate_hoisted_workspace(2)
+    ws = torch_empty(wsb)
+    ctx.rotate_hoisted(gk, d_in, 2, d_out, ws, wsb)
+    got = H.export_cts(ctx, d_out, 2 * len(rots)).reshape(2, len(rots), 2 * n)
+    for i in range(2):
+        digits = o.decperm(cts[i][n:])
+        for k, (swap, step) in enumerate(rots):
+            g = o.galois_elt(swap, step)
+            assert np.array_equal(got[i, k], o.hstperm(cts[i][:n], digits, g, o.galois_key(osk, g, 42))), (i, swap, step)
+    fc_case(par, 64, 512, 2, [0, 1], seed=gb)                                   # G = 16
+    shape = (10, 12, 3, 3, 16, 16)                                               # c_n = 8: two input, two output ciphertexts
+    conv_case(par, shape, 1, [(0, 0), (0, 1)], seed=gb)
+    conv_case(par, shape, 3, [(0, 1), (2, 0)], seed=gb, matrix_cores=True)
+
+
+def torch_empty(nbytes):
+    import torch
+    return torch.empty(max(nbytes, 8), dtype=torch.uint8, device="cuda")

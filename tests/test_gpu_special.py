@@ -182,3 +182,37 @@ def test_resnet_3x3_layers_decrypt_at_full_size(c, hw):
     for O in range(plan.nout):
         plan.unpack_share(O, ctx.decrypt(sk, got[0, O]), share)
     assert np.array_equal((share + r[0]) % np.uint64(par.p), fast_plain_conv(K, x[0], par.p))
+
+
+@pytest.mark.parametrize("gb", [60, 20, 15, 9])
+def test_n2048_special_prime_kernels_with_other_digit_counts(gb):
+    """Every other full-size special-prime test uses two digits of 30 bits: one, three, four and seven digits here,
+    through Perm, hoisted rotations, he_fc and he_conv on both multiply-accumulate paths, against the oracle."""
+    H = harness()
+    par = dataclasses.replace(wl.DEFAULT_SPECIAL, gadget_bits=gb)
+    ctx, o = both(par)
+    n = par.n
+    sk, osk = ctx.keygen(3), o.keygen(3)
+    rng = np.random.default_rng(gb)
+    slots = rng.integers(0, par.p, size=(2, n), dtype=np.uint64)
+    cts = np.stack([ctx.encrypt(sk, slots[i], seed=10 + i) for i in range(2)])
+    rots = [(0, 5), (1, 77)]
+    gk = ctx.galois_keygen(sk, rots, seed=42)
+    d_in = H.import_cts(ctx, cts)
+    for swap, step in rots:
+        d_out = H.dev_empty(2 * 2 * n)
+        ctx.rotate(gk, d_in, 2, (swap, step), d_out)
+        got = H.export_cts(ctx, d_out, 2)
+        g = o.galois_elt(swap, step)
+        for i in range(2):
+            assert np.array_equal(got[i], o.perm(cts[i], g, o.galois_key(osk, g, 42))), (swap, step, i)
+            assert np.array_equal(ctx.decrypt(sk, got[i]), rotate_slots(slots[i], step, bool(swap)))
+    fc_case(par, 64, 512, 2, [0, 1], seed=gb)
+    shape = (10, 12, 3, 3, 16, 16)
+    conv_case(par, shape, 1, [(0, 0), (0, 1)], seed=gb)
+    ctx2, o2, plan, sk2, K, x, r, got, cnt = conv_case(par, shape, 3, [(0, 1), (2, 0)], seed=gb, matrix_cores=True)
+    for b in range(3):     # with the special prime the 3x3 layer decrypts at p ~ 2^20
+        share = np.zeros((10, 16, 16), np.uint64)
+        for O in range(plan.nout):
+            plan.unpack_share(O, ctx2.decrypt(sk2, got[b, O]), share)
+        assert np.array_equal((share + r[b]) % np.uint64(par.p), plain_conv(K, x[b], par.p))
