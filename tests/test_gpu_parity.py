@@ -603,3 +603,41 @@ def test_n2048_kernels_with_other_digit_counts(gb):
 def torch_empty(nbytes):
     import torch
     return torch.empty(max(nbytes, 8), dtype=torch.uint8, device="cuda")
+
+
+@pytest.mark.parametrize("qbits,p,special", [(60, 12289, False), (60, 65537, True), (50, 1032193, False), (44, 12289, True),
+                                             (59, 40961, False)])
+def test_n2048_kernels_with_other_moduli(qbits, p, special):
+    """Every other full-size test on the n = 2048 kernels uses the default q and p: other plaintext moduli (mask
+    draws, the transform mod p) and shorter ciphertext moduli (fewer digits, other reduction constants) here, with
+    and without a special prime, through Perm, he_fc and he_conv on both multiply-accumulate paths."""
+    import dataclasses
+    H = harness()
+    n = 2048
+    q = wl.find_prime_below(1 << qbits, 2 * n * p)
+    par = wl.Params(n=n, q=q, p=p, gadget_bits=20)
+    if special:
+        P = wl.find_prime_below(1 << 60, 2 * n)
+        par = dataclasses.replace(par, special=P if P != q else wl.find_prime_below(P, 2 * n))
+    ctx, o = both(par)
+    sk, osk = ctx.keygen(3), o.keygen(3)
+    rng = np.random.default_rng(qbits)
+    slots = rng.integers(0, par.p, size=(2, n), dtype=np.uint64)
+    cts = np.stack([ctx.encrypt(sk, slots[i], seed=10 + i) for i in range(2)])
+    for i in range(2):
+        assert np.array_equal(cts[i], o.encrypt(osk, slots[i], seed=10 + i))
+        assert np.array_equal(ctx.decrypt(sk, cts[i]), slots[i])
+    rots = [(0, 9), (1, 300)]
+    gk = ctx.galois_keygen(sk, rots, seed=42)
+    d_in = H.import_cts(ctx, cts)
+    for swap, step in rots:
+        d_out = H.dev_empty(2 * 2 * n)
+        ctx.rotate(gk, d_in, 2, (swap, step), d_out)
+        got = H.export_cts(ctx, d_out, 2)
+        g = o.galois_elt(swap, step)
+        for i in range(2):
+            assert np.array_equal(got[i], o.perm(cts[i], g, o.galois_key(osk, g, 42))), (swap, step, i)
+    fc_case(par, 64, 512, 2, [0, 1], seed=qbits)
+    shape = (10, 12, 3, 3, 16, 16)
+    conv_case(par, shape, 1, [(0, 0), (0, 1)], seed=qbits)
+    conv_case(par, shape, 3, [(0, 1), (2, 0)], seed=qbits, matrix_cores=True)
