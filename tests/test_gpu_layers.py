@@ -193,28 +193,33 @@ def test_resnet18_strided_layers_as_polyphase_layers():
         del plan
 
 
-def test_he_fc_and_he_conv_replay_from_a_hip_graph():
+@pytest.mark.parametrize("which", ["n256", "n2048", "n2048_special"])
+def test_he_fc_and_he_conv_replay_from_a_hip_graph(which):
     """The layer entry points allocate nothing, wait for nothing and clear memory with kernels only, so a caller
     can capture them in a HIP graph.  Captured once, replayed three times on fresh inputs with eager work and
-    synchronisations in between; every replay must equal the eager result of the same inputs."""
+    synchronisations in between; every replay must equal the eager result of the same inputs.  On the any-n
+    kernels (n = 256) and on the n = 2048 kernels with the matrix-core product, one-prime and special-prime keys."""
     import torch
     from tests import gpu_harness as Hn
-    par = small_params(256, p_limit=1 << 13, gadget_bits=8)
-    ctx = binding.Context(par.n, par.q, par.p, par.gadget_bits)
+    par = {"n256": small_params(256, p_limit=1 << 13, gadget_bits=8), "n2048": wl.DEFAULT,
+           "n2048_special": wl.DEFAULT_SPECIAL}[which]
+    ctx = binding.Context(par.n, par.q, par.p, par.gadget_bits, par.special)
     sk = ctx.keygen(0)
     rng = np.random.default_rng(3)
     n, batch = par.n, 4
-    W = rng.integers(0, par.p, size=(16, 64), dtype=np.uint64)
+    W = rng.integers(0, par.p, size=(16, 64), dtype=np.uint64) if n == 256 else \
+        rng.integers(0, par.p, size=(64, 512), dtype=np.uint64)
     fplan = ctx.fc_plan(W)
     fplan.bind(ctx.galois_keygen(sk, fplan.rotations(), seed=1))
     K = rng.integers(0, par.p, size=(8, 8, 3, 3), dtype=np.uint64)
-    cplan = ctx.conv_plan(K, 4, 4)
+    cplan = ctx.conv_plan(K, 4, 4) if n == 256 else ctx.conv_plan(K, 16, 16)
     cplan.bind(ctx.galois_keygen(sk, cplan.rotations(), seed=2))
     cplan.prepare_batched()
     d_fin, d_fout = Hn.dev_empty(batch * 2 * n), Hn.dev_empty(batch * 2 * n)
     d_cin, d_cout = Hn.dev_empty(batch * cplan.nin * 2 * n), Hn.dev_empty(batch * cplan.nout * 2 * n)
-    d_fr = Hn.to_dev(rng.integers(0, par.p, size=(batch, 16), dtype=np.uint64))
-    d_cr = Hn.to_dev(rng.integers(0, par.p, size=(batch, 8, 4, 4), dtype=np.uint64))
+    d_fr = Hn.to_dev(rng.integers(0, par.p, size=(batch, W.shape[0]), dtype=np.uint64))
+    u = 4 if n == 256 else 16
+    d_cr = Hn.to_dev(rng.integers(0, par.p, size=(batch, 8, u, u), dtype=np.uint64))
     fwsb, cwsb = fplan.workspace_bytes(batch), cplan.workspace_bytes(batch)
     fws = torch.empty(fwsb, dtype=torch.uint8, device="cuda")
     cws = torch.empty(cwsb, dtype=torch.uint8, device="cuda")
