@@ -120,3 +120,31 @@ def test_conv_unpack_share_batch_matches_oracle(n, shape):
             o.conv_unpack_share(shape, O, slots[i, O] % np.uint64(par.p), want)
             plan.unpack_share(O, slots[i, O], mine)
         assert np.array_equal(got[i], want) and np.array_equal(mine, want), i
+
+
+@pytest.mark.parametrize("qbits,p", [(60, 12289), (50, 1032193), (44, 65537), (59, 40961)])
+def test_client_steps_on_the_n2048_kernels_with_other_moduli(qbits, p):
+    """encrypt_2048 / decrypt_2048 at other ciphertext and plaintext moduli (uniform draws of other bit lengths, the
+    transform mod p, the rounding of decryption) against the oracle, junk ciphertexts included."""
+    H = harness()
+    n, count = 2048, 3
+    par = wl.Params(n=n, q=wl.find_prime_below(1 << qbits, 2 * n * p), p=p, gadget_bits=20)
+    ctx, o = both(par)
+    sk, osk = ctx.keygen(9), o.keygen(9)
+    rng = np.random.default_rng(qbits)
+    slots = rng.integers(0, par.p, size=(count, n), dtype=np.uint64)
+    seeds = np.array([7 + 100 * i for i in range(count)], dtype=np.uint64)
+    d_ct = H.dev_empty(count * 2 * n)
+    ctx.encrypt_batch(sk, H.to_dev(slots), H.to_dev(seeds), count, d_ct)
+    got = H.export_cts(ctx, d_ct, count)
+    for i in range(count):
+        assert np.array_equal(got[i], o.encrypt(osk, slots[i], int(seeds[i]))), i
+    junk = rng.integers(0, par.q, size=(2, 2 * n), dtype=np.uint64)
+    allc = np.concatenate([got, junk])
+    d_slots = H.dev_empty((count + 2) * n)
+    ctx.decrypt_batch(sk, H.import_cts(ctx, allc), count + 2, d_slots)
+    dec = H.to_host(d_slots).reshape(count + 2, n)
+    for i in range(count):
+        assert np.array_equal(dec[i], slots[i])
+    for i in range(count + 2):
+        assert np.array_equal(dec[i], o.decrypt(osk, allc[i])), i
