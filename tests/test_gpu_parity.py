@@ -641,3 +641,37 @@ def test_n2048_kernels_with_other_moduli(qbits, p, special):
     shape = (10, 12, 3, 3, 16, 16)
     conv_case(par, shape, 1, [(0, 0), (0, 1)], seed=qbits)
     conv_case(par, shape, 3, [(0, 1), (2, 0)], seed=qbits, matrix_cores=True)
+
+
+@pytest.mark.parametrize("n,c_i,u", [(16, 16 * 4096, 1), (2048, 8 * 512, 16), (2048, 8 * 144, 16)])
+def test_he_conv_matrix_cores_worst_case_residues(n, c_i, u):
+    """Random data never reaches the bounds the matrix-core product is built on (int32 digit sums, the 128-bit
+    recombined value, the running sums between two reductions): here every residue of every operand is q - 1.
+    Kernels whose weights are all p - 1 encode to the constant polynomial -1 (every evaluation q - 1), and the
+    ciphertext (q - 1, q - 1) of constant polynomials has every evaluation q - 1 too; 1x1 kernels, so the inputs
+    reach the product as they are.  4096, 512 (reduced every 192 terms) and 144 terms (one reduction at the end)."""
+    H = harness()
+    par = small_params(n, p_limit=1 << 7, gadget_bits=4) if n != 2048 else wl.DEFAULT
+    ctx, o = both(par)
+    cn = n // (u * u)
+    shape = (cn, c_i, 1, 1, u, u)
+    batch = 2
+    K = np.full((cn, c_i, 1, 1), par.p - 1, dtype=np.uint64)
+    r = np.random.default_rng(n).integers(0, par.p, size=(batch, cn, u, u), dtype=np.uint64)
+    sk, osk = ctx.keygen(0), o.keygen(0)
+    plan = ctx.conv_plan(K, u, u)
+    assert plan.nterm == c_i // cn and plan.nout == 1
+    plan.bind(ctx.galois_keygen(sk, plan.rotations(), seed=8))
+    plan.prepare_batched()
+    cts = np.full((batch, plan.nin, 2 * n), 0, dtype=np.uint64)
+    cts[:, :, 0] = par.q - 1                  # c0 = the constant polynomial q - 1
+    cts[:, :, n] = par.q - 1                  # c1 likewise
+    # the operands of the product really are all q - 1: the encoded kernel of a group and term, the input's evaluations
+    w_poly = o.encode_weight(o.conv_weight_slots(shape, K, 0, cn - 1, plan.nin - 1, 0))
+    assert np.all(o.eval_q(w_poly) == np.uint64(par.q - 1)) and np.all(o.eval_q(cts[0, 0, :n]) == np.uint64(par.q - 1))
+    got, cnt = H.gpu_he_conv(ctx, plan, cts, r, mask_seed=3)
+    tk, gkk = o.conv_keys(osk, shape, seed=8)
+    for b in range(batch):
+        xrot, ready = np.empty(plan.nin * plan.ntap * 2 * n, np.uint64), ctypes.c_int(0)
+        want = o.he_conv_block(shape, K, 0, cts[b], tk, gkk, o.conv_mask_slots(shape, r[b], 3, b, 0), xrot, ready)[0]
+        assert np.array_equal(got[b, 0], want), b
