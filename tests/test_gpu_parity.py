@@ -643,26 +643,29 @@ def test_n2048_kernels_with_other_moduli(qbits, p, special):
     conv_case(par, shape, 3, [(0, 1), (2, 0)], seed=qbits, matrix_cores=True)
 
 
+@pytest.mark.parametrize("path,batch", [("matrix cores", 2), ("vector", 2), ("one input", 1)])
 @pytest.mark.parametrize("n,c_i,u", [(16, 16 * 4096, 1), (2048, 8 * 512, 16), (2048, 8 * 144, 16)])
-def test_he_conv_matrix_cores_worst_case_residues(n, c_i, u):
+def test_he_conv_worst_case_residues(n, c_i, u, path, batch):
     """Random data never reaches the bounds the matrix-core product is built on (int32 digit sums, the 128-bit
     recombined value, the running sums between two reductions): here every residue of every operand is q - 1.
     Kernels whose weights are all p - 1 encode to the constant polynomial -1 (every evaluation q - 1), and the
     ciphertext (q - 1, q - 1) of constant polynomials has every evaluation q - 1 too; 1x1 kernels, so the inputs
-    reach the product as they are.  4096, 512 (reduced every 192 terms) and 144 terms (one reduction at the end)."""
+    reach the product as they are.  4096, 512 (reduced every 192 terms) and 144 terms (one reduction at the end); the
+    same sums on the vector multiply-accumulate (128-bit accumulators flushed every 255 terms) and on the kernel
+    that streams the encoded kernels for a single input."""
     H = harness()
     par = small_params(n, p_limit=1 << 7, gadget_bits=4) if n != 2048 else wl.DEFAULT
     ctx, o = both(par)
     cn = n // (u * u)
     shape = (cn, c_i, 1, 1, u, u)
-    batch = 2
     K = np.full((cn, c_i, 1, 1), par.p - 1, dtype=np.uint64)
     r = np.random.default_rng(n).integers(0, par.p, size=(batch, cn, u, u), dtype=np.uint64)
     sk, osk = ctx.keygen(0), o.keygen(0)
     plan = ctx.conv_plan(K, u, u)
     assert plan.nterm == c_i // cn and plan.nout == 1
     plan.bind(ctx.galois_keygen(sk, plan.rotations(), seed=8))
-    plan.prepare_batched()
+    if path == "matrix cores":
+        plan.prepare_batched()
     cts = np.full((batch, plan.nin, 2 * n), 0, dtype=np.uint64)
     cts[:, :, 0] = par.q - 1                  # c0 = the constant polynomial q - 1
     cts[:, :, n] = par.q - 1                  # c1 likewise
@@ -675,3 +678,37 @@ def test_he_conv_matrix_cores_worst_case_residues(n, c_i, u):
         xrot, ready = np.empty(plan.nin * plan.ntap * 2 * n, np.uint64), ctypes.c_int(0)
         want = o.he_conv_block(shape, K, 0, cts[b], tk, gkk, o.conv_mask_slots(shape, r[b], 3, b, 0), xrot, ready)[0]
         assert np.array_equal(got[b, 0], want), b
+
+
+@pytest.mark.parametrize("n,n_o,n_i", [(64, 8, 32), (2048, 128, 1024), (2048, 16, 128)])
+def test_he_fc_and_perm_with_extreme_residues(n, n_o, n_i):
+    """The lazy arithmetic of the Perm kernels (sums kept below 8q, transforms on values below 16q) at the edge of
+    its input range: ciphertexts whose every evaluation is q - 1 (constant polynomials), and others whose every
+    coefficient is q - 1, rotated and pushed through he_fc with weights that all encode to q - 1."""
+    H = harness()
+    par = small_params(n) if n != 2048 else wl.DEFAULT
+    ctx, o = both(par)
+    sk, osk = ctx.keygen(0), o.keygen(0)
+    cts = np.zeros((2, 2 * n), dtype=np.uint64)
+    cts[0, 0] = cts[0, n] = par.q - 1                # constant polynomials: every evaluation is q - 1
+    cts[1, :] = par.q - 1                            # every coefficient is q - 1
+    rots = [(0, 1), (1, 3)]
+    gk = ctx.galois_keygen(sk, rots, seed=42)
+    d_in = H.import_cts(ctx, cts)
+    for swap, step in rots:
+        d_out = H.dev_empty(2 * 2 * n)
+        ctx.rotate(gk, d_in, 2, (swap, step), d_out)
+        got = H.export_cts(ctx, d_out, 2)
+        g = o.galois_elt(swap, step)
+        for i in range(2):
+            assert np.array_equal(got[i], o.perm(cts[i], g, o.galois_key(osk, g, 42))), (swap, step, i)
+    W = np.full((n_o, n_i), par.p - 1, dtype=np.uint64)
+    r = np.random.default_rng(n).integers(0, par.p, size=(2, n_o), dtype=np.uint64)
+    plan = ctx.fc_plan(W)
+    plan.bind(ctx.galois_keygen(sk, plan.rotations(), seed=1))
+    got, cnt = H.gpu_he_fc(ctx, plan, cts, r, mask_seed=17)
+    wpoly = o.fc_encode_rowwise(W)
+    ksk = o.fc_keys(osk, n_o, n_i, seed=1)
+    for b in range(2):
+        want = o.he_fc(wpoly, cts[b], ksk, o.fc_mask_slots(n_o, n_i, r[b], 17, b))[0]
+        assert np.array_equal(got[b], want), b
