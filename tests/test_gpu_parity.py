@@ -712,3 +712,15 @@ def test_he_fc_and_perm_with_extreme_residues(n, n_o, n_i):
     for b in range(2):
         want = o.he_fc(wpoly, cts[b], ksk, o.fc_mask_slots(n_o, n_i, r[b], 17, b))[0]
         assert np.array_equal(got[b], want), b
+
+
+@pytest.mark.parametrize("c_o,batch", [(72, 3), (136, 2), (8, 9)])
+def test_he_conv_matrix_cores_with_ragged_row_tiles_n2048(c_o, batch):
+    """Row counts of the matrix-core product that end inside a row tile and inside a workgroup's group of four
+    tiles (72 rows = 4.5 tiles, 136 rows = 8.5 tiles), and a single tile (8 rows) with 18 columns, at n = 2048:
+    first, middle and last output ciphertext of the first and the last input against the oracle."""
+    par = wl.DEFAULT
+    shape = (c_o, 16, 3, 3, 16, 16)
+    nout = (c_o + 7) // 8
+    picks = sorted({(b, O) for b in (0, batch - 1) for O in (0, nout // 2, nout - 1)})
+    conv_case(par, shape, batch, picks, seed=c_o, matrix_cores=True)
