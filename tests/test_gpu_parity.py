@@ -724,3 +724,11 @@ def test_he_conv_matrix_cores_with_ragged_row_tiles_n2048(c_o, batch):
     nout = (c_o + 7) // 8
     picks = sorted({(b, O) for b in (0, batch - 1) for O in (0, nout // 2, nout - 1)})
     conv_case(par, shape, batch, picks, seed=c_o, matrix_cores=True)
+
+
+@pytest.mark.parametrize("n_o,n_i,batch", [(128, 1024, 7), (128, 1024, 33), (128, 1024, 100), (16, 2048, 13), (1000, 2048, 3)])
+def test_he_fc_other_batch_sizes_n2048(n_o, n_i, batch):
+    """The number of chunks a sum is cut into follows the batch size (and with it the workgroup-to-chunk mapping and
+    the kernel that adds the partial ciphertexts up): batches other than the benchmarked ones, first, middle and
+    last input against the oracle."""
+    fc_case(wl.DEFAULT, n_o, n_i, batch, sorted({0, batch // 2, batch - 1}), seed=batch)
