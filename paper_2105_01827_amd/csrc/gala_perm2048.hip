@@ -70,8 +70,10 @@ __device__ __forceinline__ u64 mulhi64_dev(u64 y, u64 s) {
 struct NegQ { u32 lo, hi; };
 // y*w mod q up to one extra q (a value in [0,2q)) for any 64-bit y, w a constant with companion ws:
 // y*w - h*q = y*w + h*(-q) mod 2^64 as one chain for the low word and one for the high word.
-template <bool CM = false>
-__device__ __forceinline__ u64 mul_const(u64 y, u64 w, u64 ws, NegQ nq) {
+// ADD: x is added to the product in the same instructions (the first multiply-add of the low chain takes it as its
+// addend), so x + (y*w mod q) costs no more than the product; the sum is exact modulo 2^64.
+template <bool CM = false, bool ADD = false>
+__device__ __forceinline__ u64 mul_const(u64 y, u64 w, u64 ws, NegQ nq, u64 x = 0) {
     const u64 h = mulhi64_dev<CM>(y, ws);
     const u32 y0 = (u32)y, y1 = (u32)(y >> 32), w0 = (u32)w, w1 = (u32)(w >> 32);
     const u32 h0 = (u32)h, h1 = (u32)(h >> 32);
@@ -79,7 +81,7 @@ __device__ __forceinline__ u64 mul_const(u64 y, u64 w, u64 ws, NegQ nq) {
     u = mad_u64<CM>(y1, w0, u);
     u = mad_u64<CM>(h0, nq.hi, u);
     u = mad_u64<CM>(h1, nq.lo, u);
-    u64 t = mul_u64<CM>(y0, w0);
+    u64 t = ADD ? mad_u64<CM>(y0, w0, x) : mul_u64<CM>(y0, w0);
     t = mad_u64<CM>(h0, nq.lo, t);
     u32 hi;
     asm("v_add_u32 %0, %1, %2" : "=v"(hi) : "v"((u32)(t >> 32)), "v"((u32)u));
@@ -165,9 +167,9 @@ __device__ __forceinline__ u64 csub_dev(u64 x, u64 c) {
 // x,y -> x + w*y, x - w*y + 2q  without any correction (bound grows by 2q per stage)
 template <bool CM = false>
 __device__ __forceinline__ void bf_fwd(u64 &x, u64 &y, const ulonglong2 t, NegQ nq, u64 q2) {
-    const u64 v = mul_const<CM>(y, t.x, t.y, nq);
-    y = x - v + q2;
-    x = x + v;
+    const u64 s = mul_const<CM, true>(y, t.x, t.y, nq, x);      // x + w*y
+    y = (x << 1) + q2 - s;                                      // x - w*y + 2q = 2x + 2q - (x + w*y)
+    x = s;
 }
 // x,y in [0,2q) -> x + y (below 2q), (x - y)*w (below 2q)
 template <bool CM = false>
