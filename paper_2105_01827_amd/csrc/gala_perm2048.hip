@@ -490,8 +490,8 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
                 const int i = tid + k * NT;
                 if (HAS_W) {
                     const ulonglong2 ww = w[i];
-                    sum0[k] = csub_dev(sum0[k] + mul_const(c0[i], ww.x, ww.y, q), q8);
-                    sum1[k] = csub_dev(sum1[k] + mul_const(c1[i], ww.x, ww.y, q), q8);
+                    sum0[k] = csub_dev(mul_const<false, true>(c0[i], ww.x, ww.y, q, sum0[k]), q8);
+                    sum1[k] = csub_dev(mul_const<false, true>(c1[i], ww.x, ww.y, q, sum1[k]), q8);
                 } else {
                     sum0[k] = csub_dev(sum0[k] + at(c0, i), q8);
                     sum1[k] = csub_dev(sum1[k] + at(c1, i), q8);
@@ -535,7 +535,7 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
         for (int k = 0; k < PER; ++k) {
             if (HAS_W) {
                 const ulonglong2 ww = w[src[k]];
-                sum0[k] += mul_const(c0[src[k]], ww.x, ww.y, q);
+                sum0[k] = mul_const<false, true>(c0[src[k]], ww.x, ww.y, q, sum0[k]);
             } else {
                 sum0[k] += at(c0, src[k]);
             }
@@ -559,8 +559,8 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
                 const int i = tid + k * NT;
                 const u64 d = bufA[pad(src[k])];
                 const ulonglong2 b = kb[i], aa = ka[i];
-                sum0[k] += mul_const(d, b.x, b.y, q);
-                sum1[k] += mul_const(d, aa.x, aa.y, q);
+                sum0[k] = mul_const<false, true>(d, b.x, b.y, q, sum0[k]);       // the sum rides on the product
+                sum1[k] = mul_const<false, true>(d, aa.x, aa.y, q, sum1[k]);
             }
             ++pending;
         }
@@ -742,8 +742,8 @@ __global__ __launch_bounds__(NT) void hstperm_pack_2048(const u64 *ct_in, const 
                 for (int j = 0; j < ndigits; ++j) {
                     const u64 d = dsrc[(size_t)j * N + src];
                     const ulonglong2 wb = key[(size_t)(2 * j) * N + i], wa = key[(size_t)(2 * j + 1) * N + i];
-                    s0 += mul_const(d, wb.x, wb.y, q);
-                    s1 += mul_const(d, wa.x, wa.y, q);
+                    s0 = mul_const<false, true>(d, wb.x, wb.y, q, s0);
+                    s1 = mul_const<false, true>(d, wa.x, wa.y, q, s1);
                 }
             }
             v0 = reduce64(s0, T.mod);
