@@ -171,11 +171,13 @@ __device__ __forceinline__ void bf_fwd(u64 &x, u64 &y, const ulonglong2 t, NegQ 
     y = (x << 1) + q2 - s;                                      // x - w*y + 2q = 2x + 2q - (x + w*y)
     x = s;
 }
-// x,y in [0,2q) -> x + y (below 2q), (x - y)*w (below 2q)
+// x, y -> x + y, (x - y + off)*w.  The sum is left uncorrected (its bound is the sum of the operands'), and `off`, a
+// multiple of q above y's bound, keeps the difference non-negative.  The product is below 2q whatever comes in, so
+// only the sums grow; a radix-8 pass lets them (2q -> 4q -> 8q -> 16q < 2^64) and corrects at its end.
 template <bool CM = false>
-__device__ __forceinline__ void bf_inv(u64 &x, u64 &y, const ulonglong2 t, NegQ nq, u64 q2) {
-    const u64 s = x + y, d = x - y + q2;
-    x = csub_dev(s, q2);
+__device__ __forceinline__ void bf_inv_lazy(u64 &x, u64 &y, const ulonglong2 t, NegQ nq, u64 off) {
+    const u64 s = x + y, d = x - y + off;
+    x = s;
     y = mul_const<CM>(d, t.x, t.y, nq);
 }
 
@@ -231,16 +233,24 @@ __device__ __forceinline__ void fwd_pass(u64 (&a)[8], const Tw7 &w, NegQ q, u64 
 // Radix-8 inverse pass (bit 0 of k first), same block layout on the inverse table.
 template <bool CM = false>
 __device__ __forceinline__ void inv_pass(u64 (&a)[8], const Tw7 &w, NegQ q, u64 q2) {
-    bf_inv<CM>(a[0], a[1], w.t[3], q, q2);
-    bf_inv<CM>(a[2], a[3], w.t[4], q, q2);
-    bf_inv<CM>(a[4], a[5], w.t[5], q, q2);
-    bf_inv<CM>(a[6], a[7], w.t[6], q, q2);
-    bf_inv<CM>(a[0], a[2], w.t[1], q, q2);
-    bf_inv<CM>(a[1], a[3], w.t[1], q, q2);
-    bf_inv<CM>(a[4], a[6], w.t[2], q, q2);
-    bf_inv<CM>(a[5], a[7], w.t[2], q, q2);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) bf_inv<CM>(a[k], a[k + 4], w.t[0], q, q2);
+    // all eight below 2q on entry; bounds after each stage in the comments
+    const u64 q4 = 2 * q2, q8 = 4 * q2;
+    bf_inv_lazy<CM>(a[0], a[1], w.t[3], q, q2);
+    bf_inv_lazy<CM>(a[2], a[3], w.t[4], q, q2);
+    bf_inv_lazy<CM>(a[4], a[5], w.t[5], q, q2);
+    bf_inv_lazy<CM>(a[6], a[7], w.t[6], q, q2);      // a0 a2 a4 a6 < 4q, the products a1 a3 a5 a7 < 2q
+    bf_inv_lazy<CM>(a[0], a[2], w.t[1], q, q4);
+    bf_inv_lazy<CM>(a[1], a[3], w.t[1], q, q2);
+    bf_inv_lazy<CM>(a[4], a[6], w.t[2], q, q4);
+    bf_inv_lazy<CM>(a[5], a[7], w.t[2], q, q2);      // a0 a4 < 8q, a1 a5 < 4q, a2 a3 a6 a7 < 2q
+    bf_inv_lazy<CM>(a[0], a[4], w.t[0], q, q8);
+    bf_inv_lazy<CM>(a[1], a[5], w.t[0], q, q4);
+    bf_inv_lazy<CM>(a[2], a[6], w.t[0], q, q2);
+    bf_inv_lazy<CM>(a[3], a[7], w.t[0], q, q2);      // a0 < 16q, a1 < 8q, a2 a3 < 4q, a4 .. a7 < 2q
+    a[0] = csub_dev(csub_dev(csub_dev(a[0], q8), q4), q2);
+    a[1] = csub_dev(csub_dev(a[1], q4), q2);
+    a[2] = csub_dev(a[2], q2);
+    a[3] = csub_dev(a[3], q2);
 }
 
 // Store the 8 registers at index(k) = base_out | (k << SH_OUT), barrier, load index(k) = base_in | (k << SH_IN).
@@ -327,15 +337,15 @@ __device__ __forceinline__ void inverse_in_regs(u64 (&a)[8], u64 *bufA, u64 *buf
     const ulonglong2 t2a = T.itw[1], t2b = T.itw[2];      // level 1: constants 1 and 2 of block 1
     exchange<6, 8>(a, bufA, ((tid >> 6) << 9) | (tid & 63), tid);
     // bits 9-10 (register bits 1,2; register bit 0 is index bit 8), n^-1 folded into the last stage
-    bf_inv<CM>(a[0], a[2], t2a, q, q2);
-    bf_inv<CM>(a[1], a[3], t2a, q, q2);
-    bf_inv<CM>(a[4], a[6], t2b, q, q2);
-    bf_inv<CM>(a[5], a[7], t2b, q, q2);
+    bf_inv_lazy<CM>(a[0], a[2], t2a, q, q2);
+    bf_inv_lazy<CM>(a[1], a[3], t2a, q, q2);
+    bf_inv_lazy<CM>(a[4], a[6], t2b, q, q2);
+    bf_inv_lazy<CM>(a[5], a[7], t2b, q, q2);         // the sums a0 a1 a4 a5 < 4q, the products a2 a3 a6 a7 < 2q
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const u64 x = a[k], y = a[k + 4];
         a[k] = csub_dev(mul_const<CM>(x + y, T.ninv.x, T.ninv.y, q), T.mod.q);
-        a[k + 4] = csub_dev(mul_const<CM>(x - y + q2, T.itw1n.x, T.itw1n.y, q), T.mod.q);
+        a[k + 4] = csub_dev(mul_const<CM>(x - y + 2 * q2, T.itw1n.x, T.itw1n.y, q), T.mod.q);
     }
 }
 
