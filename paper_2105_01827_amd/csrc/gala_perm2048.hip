@@ -87,6 +87,20 @@ __device__ __forceinline__ u64 mul_const(u64 y, u64 w, u64 ws, NegQ nq, u64 x = 
     asm("v_add_u32 %0, %1, %2" : "=v"(hi) : "v"((u32)(t >> 32)), "v"((u32)u));
     return ((u64)hi << 32) | (u32)t;
 }
+// The same for y below 2^32 (a gadget digit): the quotient estimate floor(y*ws / 2^64) is the high word of
+// y*ws1 + hi32(y*ws0) and fits one word, so five of the twelve instructions have nothing to do.  Same value as mul_const.
+template <bool ADD = false>
+__device__ __forceinline__ u64 mul_const_small(u32 y, u64 w, u64 ws, NegQ nq, u64 x = 0) {
+    const u32 w0 = (u32)w, w1 = (u32)(w >> 32), s0 = (u32)ws, s1 = (u32)(ws >> 32);
+    const u32 h = (u32)(mad_u64(y, s1, (u64)__umulhi(y, s0)) >> 32);
+    u64 u = mul_u64(y, w1);
+    u = mad_u64(h, nq.hi, u);
+    u64 t = ADD ? mad_u64(y, w0, x) : mul_u64(y, w0);
+    t = mad_u64(h, nq.lo, t);
+    u32 hi;
+    asm("v_add_u32 %0, %1, %2" : "=v"(hi) : "v"((u32)(t >> 32)), "v"((u32)u));
+    return ((u64)hi << 32) | (u32)t;
+}
 // Two independent constant multiplications, written as three blocks of instructions instead of one statement per
 // instruction.  The compiler cannot know that v_mad_u64_u32 forwards its result without a hazard, so it puts a
 // wait state between an inline-asm statement and any statement that reads one of its results; inside a block
@@ -171,6 +185,12 @@ __device__ __forceinline__ void bf_fwd(u64 &x, u64 &y, const ulonglong2 t, NegQ 
     y = (x << 1) + q2 - s;                                      // x - w*y + 2q = 2x + 2q - (x + w*y)
     x = s;
 }
+// the forward butterfly when y is below 2^32
+__device__ __forceinline__ void bf_fwd_small(u64 &x, u64 &y, const ulonglong2 t, NegQ nq, u64 q2) {
+    const u64 s = mul_const_small<true>((u32)y, t.x, t.y, nq, x);
+    y = (x << 1) + q2 - s;
+    x = s;
+}
 // x, y -> x + y, (x - y + off)*w.  The sum is left uncorrected (its bound is the sum of the operands'), and `off`, a
 // multiple of q above y's bound, keeps the difference non-negative.  The product is below 2q whatever comes in, so
 // only the sums grow; a radix-8 pass lets them (2q -> 4q -> 8q -> 16q < 2^64) and corrects at its end.
@@ -210,11 +230,18 @@ __device__ __forceinline__ Tw7 tw_level(const ulonglong2 *__restrict__ table, un
     for (int e = 0; e < 7; ++e) w.t[e] = *reinterpret_cast<const ulonglong2 *>(level + (size_t)(e * COUNT * 16) + off);
     return w;
 }
+// small_in (the same for every thread): all eight inputs are below 2^32, as gadget digits are; the first stage then
+// multiplies with mul_const_small.
 template <bool FIRST, bool CORRECT, bool CM = false>
-__device__ __forceinline__ void fwd_pass(u64 (&a)[8], const Tw7 &w, NegQ q, u64 q2) {
+__device__ __forceinline__ void fwd_pass(u64 (&a)[8], const Tw7 &w, NegQ q, u64 q2, bool small_in = false) {
     if (FIRST) {
+        if (!CM && small_in) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) bf_fwd<CM>(a[k], a[k + 4], w.t[0], q, q2);
+            for (int k = 0; k < 4; ++k) bf_fwd_small(a[k], a[k + 4], w.t[0], q, q2);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) bf_fwd<CM>(a[k], a[k + 4], w.t[0], q, q2);
+        }
     }
     if (CORRECT) {   // seven stages done: everything is below 15q, bring it below 8q
         const u64 q8 = 4 * q2;
@@ -298,12 +325,13 @@ __device__ __forceinline__ int fresh(int tid) {
 // Forward transform of the 8 registers (ownership t + 256k, values below q); the result is left in
 // LDS buffer `res` (natural index, padded), values below 16q.  LDS phases: other, res, other, res.
 template <bool CM = false>
-__device__ __forceinline__ void forward_to_lds(u64 (&a)[8], u64 *res, u64 *other, const Tables2048 &T, int tid_) {
+__device__ __forceinline__ void forward_to_lds(u64 (&a)[8], u64 *res, u64 *other, const Tables2048 &T, int tid_,
+                                               bool small_in = false) {
     const int tid = fresh(tid_);
     const NegQ q = T.nq;
     const u64 q2 = T.mod.q2;
     Tw7 w = tw_level<1>(T.tw, 0);
-    fwd_pass<true, false, CM>(a, w, q, q2);                                              // bits 8-10
+    fwd_pass<true, false, CM>(a, w, q, q2, small_in);                                    // bits 8-10
     w = tw_level<8>(T.tw, (unsigned)tid >> 5);
     exchange<8, 5>(a, other, tid, ((tid >> 5) << 8) | (tid & 31));
     fwd_pass<true, false, CM>(a, w, q, q2);                                              // bits 5-7
@@ -554,7 +582,9 @@ __global__ __launch_bounds__(NT) void perm_accumulate_2048(PermJob job, Tables20
         for (int j = 0; j < ndigits; ++j) {
 #pragma unroll
             for (int k = 0; k < PER; ++k) a[k] = (stash[tid + k * NT] >> (j * gadget_bits)) & digit_mask;
-            forward_to_lds(a, bufA, bufB, T, tid);   // result in bufA, any 64-bit value below 16q
+            // result in bufA, any 64-bit value below 16q.  The cheaper first stage for digits below 2^32 only where
+            // the registers allow it: in the variants without weights it pushes the count past three workgroups per CU
+            forward_to_lds(a, bufA, bufB, T, tid, HAS_W && gadget_bits <= 32);
             const ulonglong2 *kb = key + (size_t)(2 * j) * N, *ka = kb + N;
             if (pending == 4) {
 #pragma unroll
@@ -614,7 +644,7 @@ __global__ __launch_bounds__(NT) void decperm_2048(const u64 *ct_in, u64 *digits
     const u64 digit_mask = (1ull << gadget_bits) - 1;
 #pragma unroll
     for (int k = 0; k < PER; ++k) a[k] = (a[k] >> (j * gadget_bits)) & digit_mask;
-    forward_to_lds(a, bufA, bufB, T, tid);       // LDS phases B A B A, ends on a barrier
+    forward_to_lds(a, bufA, bufB, T, tid, gadget_bits <= 32);       // LDS phases B A B A, ends on a barrier
     u64 *out = digits + ((size_t)ct * ndigits + j) * N;
 #pragma unroll
     for (int k = 0; k < PER; ++k) out[tid + k * NT] = bufA[pad(tid + k * NT)];
